@@ -1,0 +1,154 @@
+/*
+ * a2d — per-device compute of Attention2D (arXiv 2503.15758) on MI355X (gfx950).
+ *
+ * The paper splits self-attention over a sqrt(P) x sqrt(P) device grid along both
+ * the query and the key/value dimension.  What one device computes on its share
+ * is (i) exact attention of one block of queries against one block of keys and
+ * values, kept as an UNNORMALISED partial triple (M, N, D) (Sec. 3.1, Eq. (3);
+ * the FlashAttn call of Alg. 1 line 4), (ii) the AttnFix merge of the sqrt(P)
+ * partials of a query block followed by the division by D (Alg. 2; Alg. 1
+ * lines 5-6), (iii) the per-tile gradient call of Alg. 3 line 3 and (iv) the
+ * summing reductions of Alg. 3 lines 4-5.  This header is the whole boundary:
+ * four compute entry points plus a workspace query and error reporting.
+ *
+ * Conventions shared by every call
+ *  - Every pointer is caller-owned DEVICE memory unless stated otherwise; the
+ *    library allocates nothing and keeps no pointer after a call returns.
+ *  - Matrices are row-major [heads][rows][H] with H contiguous and no padding;
+ *    per-row statistics are [heads][rows].  heads = batch * number of heads (the
+ *    method works per head, Sec. 2.1 / Sec. 5).
+ *  - Scores are s = scale * <q, k> (the 1/sqrt(H) factor the paper's footnote in
+ *    Sec. 2.1 leaves out is the explicit `scale`), then the causal mask of
+ *    Sec. 2.1: key r is hidden from query i iff q_off + i < kv_off + r, where
+ *    q_off / kv_off are the GLOBAL indices of row 0 / key 0 of the tile.  The
+ *    paper's cyclic index sets (Sec. 3.2) map to (q_off, kv_off) = (0, 0) for a
+ *    tile with grid row >= grid column and (0, 1) otherwise.
+ *  - m, l, lse are in natural-log units of the scaled scores.  A row that sees no
+ *    key has m = -inf, l = 0, N = 0; AttnFix gives such a partial weight 0; a row
+ *    whose k partials are all empty gets O = 0, lse = -inf.
+ *  - Calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL =
+ *    the default stream) and return; they do not synchronise.  Outputs are
+ *    fully overwritten.  Same inputs give bitwise identical outputs.
+ *  - On error a negative status is returned, nothing has been enqueued, and
+ *    a2d_last_error() describes the cause (thread-local, host memory owned by
+ *    the library).
+ *  - Alignment: every device pointer must be 16-byte aligned.
+ */
+#ifndef A2D_H_
+#define A2D_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  A2D_OK = 0,
+  A2D_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, k out of range          */
+  A2D_ERR_UNSUPPORTED = -2, /* dtype / head size the kernels do not cover               */
+  A2D_ERR_MISALIGNED = -3,  /* a device pointer is not 16-byte aligned                  */
+  A2D_ERR_WORKSPACE = -4,   /* workspace missing or smaller than a2d_workspace_bytes()  */
+  A2D_ERR_HIP = -5          /* the HIP runtime refused a launch                         */
+} a2d_status;
+
+typedef enum { A2D_F32 = 0, A2D_BF16 = 1 } a2d_dtype;
+
+typedef enum {
+  A2D_OP_PARTIAL_FWD = 0,
+  A2D_OP_FIX = 1,
+  A2D_OP_PARTIAL_BWD = 2,
+  A2D_OP_FIX_BWD = 3
+} a2d_op;
+
+/* Most partials one a2d_fix / a2d_fix_bwd call can merge (sqrt(P) in the paper). */
+#define A2D_MAX_PARTS 32
+
+/* One tile problem: a block of nq queries against a block of nkv keys/values. */
+typedef struct {
+  int32_t heads;   /* B * M, >= 1                                                     */
+  int32_t nq;      /* query rows of the tile, >= 1                                    */
+  int32_t nkv;     /* key/value rows of the tile, >= 1                                */
+  int32_t hdim;    /* H: 64 or 128                                                    */
+  int64_t q_off;   /* global index of query row 0 (used only when causal != 0)        */
+  int64_t kv_off;  /* global index of key row 0   (used only when causal != 0)        */
+  int32_t causal;  /* 0: no mask; 1: hide key r from query i iff q_off+i < kv_off+r   */
+  float scale;     /* multiplies <q, k>; 1/sqrt(H) in the paper's setting             */
+  int32_t dtype;   /* a2d_dtype of Q, K, V, O, dO                                     */
+} a2d_tile_desc;
+
+/*
+ * Bytes of device workspace the given op needs for this tile (0 if none).
+ * Only A2D_OP_PARTIAL_BWD needs any (the per-row sums delta = rowsum(dO o O)).
+ * `k` is ignored for the tile ops.  Returns 0 for a NULL or invalid descriptor.
+ */
+size_t a2d_workspace_bytes(const a2d_tile_desc* desc, int op, int k);
+
+/*
+ * Partial attention of one tile (Sec. 3.1, Eq. (3); Alg. 1 line 4).
+ *   in : Q [heads][nq][H], K, V [heads][nkv][H] in desc->dtype
+ *   out: O_part [heads][nq][H] fp32 = n' (unnormalised), m [heads][nq] fp32 = m'
+ *        (the true maximum of the visible scaled scores), l [heads][nq] fp32 = d'.
+ * bf16 inputs: products accumulate in fp32, the softmax runs in fp32, the
+ * probabilities are rounded to bf16 (nearest-even) before the P*V contraction.
+ * fp32 inputs: fp32 throughout.  workspace may be NULL (none is needed).
+ */
+a2d_status a2d_partial_fwd(const a2d_tile_desc* desc, const void* Q, const void* K,
+                           const void* V, float* O_part, float* m, float* l,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * AttnFix over k partials of the same query block, then normalisation
+ * (Alg. 2 folded over k inputs; O = Diag(D^-1) N of Alg. 1 line 6; the statistic
+ * L = M + log D of the footnote in Sec. 3.2).
+ *   in : O_parts, m, l: HOST arrays of k device pointers, each as written by
+ *        a2d_partial_fwd for `rows` = heads * nq rows of head size hdim
+ *   out: O [rows][hdim] in out_dtype (rounded once, nearest-even), lse [rows] fp32.
+ * One pass: M = max_k m_k, w_k = exp(m_k - M), sums taken in index order 0..k-1.
+ * 1 <= k <= A2D_MAX_PARTS; hdim a multiple of 4.
+ */
+a2d_status a2d_fix(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
+                   const float* const* O_parts, const float* const* m,
+                   const float* const* l, void* O, float* lse, void* stream);
+
+/*
+ * Gradient share of one tile (the BwdFlashAttn call of Alg. 3 line 3).
+ *   in : Q, K, V as for the forward; O [heads][nq][H] and lse [heads][nq]: the
+ *        FINAL merged output and log-sum-exp of the query block (what Alg. 1
+ *        line 7 saves), not the tile's own partial; dO [heads][nq][H].
+ *   out: dQ_part [heads][nq][H], dK_part, dV_part [heads][nkv][H], fp32:
+ *        P = exp(S - lse), delta = rowsum(dO o O), dV = P^T dO, dP = dO V^T,
+ *        dS = P o (dP - delta), dQ = scale dS K, dK = scale dS^T Q.
+ * bf16 inputs: P and dS are rounded to bf16 before their contractions.
+ * workspace: a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD, 0) bytes, contents
+ * undefined on entry and exit; calls sharing one workspace must be ordered on
+ * one stream.
+ */
+a2d_status a2d_partial_bwd(const a2d_tile_desc* desc, const void* Q, const void* K,
+                           const void* V, const void* O, const void* dO,
+                           const float* lse, float* dQ_part, float* dK_part,
+                           float* dV_part, void* workspace, size_t workspace_bytes,
+                           void* stream);
+
+/*
+ * Sum of k gradient partials (the reduce-scatters of Alg. 3 lines 4-5 use plain
+ * summation): out[i] = sum_k parts[k][i], added in index order in fp32, rounded
+ * once to out_dtype.  parts: HOST array of k device pointers to n fp32 values;
+ * n a multiple of 4.  Call once each for dQ (over a grid row), dK and dV (over a
+ * grid column).
+ */
+a2d_status a2d_fix_bwd(int k, int64_t n, int32_t out_dtype, const float* const* parts,
+                       void* out, void* stream);
+
+/* Static string for a status code. */
+const char* a2d_status_str(a2d_status status);
+/* Detail of the calling thread's last failed call ("" if none). */
+const char* a2d_last_error(void);
+/* Library version, "major.minor". */
+const char* a2d_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* A2D_H_ */

@@ -1,0 +1,185 @@
+"""ctypes binding of liba2d.so: the same four calls as include/a2d.h, on torch tensors.
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  torch supplies device memory and the current stream.  If the library
+has not been built (python -m paper_2503_15758_amd.build) every call raises.
+"""
+import ctypes
+import math
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "liba2d.so")
+
+A2D_F32, A2D_BF16 = 0, 1
+OP_PARTIAL_FWD, OP_FIX, OP_PARTIAL_BWD, OP_FIX_BWD = 0, 1, 2, 3
+MAX_PARTS = 32
+
+EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
+           "a2d_status_str", "a2d_last_error", "a2d_version")
+
+
+class TileDesc(ctypes.Structure):
+    _fields_ = [("heads", ctypes.c_int32), ("nq", ctypes.c_int32), ("nkv", ctypes.c_int32),
+                ("hdim", ctypes.c_int32), ("q_off", ctypes.c_int64), ("kv_off", ctypes.c_int64),
+                ("causal", ctypes.c_int32), ("scale", ctypes.c_float), ("dtype", ctypes.c_int32)]
+
+
+class A2DError(RuntimeError):
+    def __init__(self, status, detail):
+        super().__init__("a2d status %d: %s" % (status, detail))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("liba2d.so is missing at %s: build it with "
+                               "`python -m paper_2503_15758_amd.build`" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, fp = ctypes.c_void_p, ctypes.c_void_p
+        L.a2d_workspace_bytes.restype = ctypes.c_size_t
+        L.a2d_workspace_bytes.argtypes = [ctypes.POINTER(TileDesc), ctypes.c_int, ctypes.c_int]
+        L.a2d_partial_fwd.restype = ctypes.c_int
+        L.a2d_partial_fwd.argtypes = [ctypes.POINTER(TileDesc), vp, vp, vp, fp, fp, fp, vp,
+                                      ctypes.c_size_t, vp]
+        L.a2d_fix.restype = ctypes.c_int
+        L.a2d_fix.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                              ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, fp, vp]
+        L.a2d_partial_bwd.restype = ctypes.c_int
+        L.a2d_partial_bwd.argtypes = [ctypes.POINTER(TileDesc), vp, vp, vp, vp, vp, fp, fp, fp, fp,
+                                      vp, ctypes.c_size_t, vp]
+        L.a2d_fix_bwd.restype = ctypes.c_int
+        L.a2d_fix_bwd.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(vp),
+                                  vp, vp]
+        L.a2d_status_str.restype = ctypes.c_char_p
+        L.a2d_status_str.argtypes = [ctypes.c_int]
+        L.a2d_last_error.restype = ctypes.c_char_p
+        L.a2d_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != 0:
+        raise A2DError(status, lib().a2d_last_error().decode())
+
+
+def _dtype_code(t):
+    if t == torch.float32:
+        return A2D_F32
+    if t == torch.bfloat16:
+        return A2D_BF16
+    raise A2DError(-2, "dtype %s not supported" % t)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _ptr_array(ts):
+    return (ctypes.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+
+
+def _dev3(t, name):
+    if not (t.is_cuda and t.is_contiguous() and t.dim() == 3):
+        raise A2DError(-1, "%s must be a contiguous [heads][rows][H] device tensor" % name)
+
+
+def tile_desc(Q, K, q_off, kv_off, causal, scale):
+    heads, nq, H = Q.shape
+    return TileDesc(heads, nq, K.shape[1], H, int(q_off), int(kv_off), int(bool(causal)),
+                    float(scale if scale is not None else 1.0 / math.sqrt(H)), _dtype_code(Q.dtype))
+
+
+def workspace_bytes(desc, op, k=0):
+    return int(lib().a2d_workspace_bytes(ctypes.byref(desc), op, k))
+
+
+def partial_fwd(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None):
+    """a2d_partial_fwd. Returns (O_part fp32 [heads][nq][H], m, l fp32 [heads][nq])."""
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
+        _dev3(t, n)
+    if K.shape != V.shape or K.shape[0] != Q.shape[0] or K.shape[2] != Q.shape[2] or \
+            K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise A2DError(-1, "Q, K, V shapes / dtypes do not match")
+    d = tile_desc(Q, K, q_off, kv_off, causal, scale)
+    if out is None:
+        O_part = torch.empty(Q.shape, dtype=torch.float32, device=Q.device)
+        m = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
+        l = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
+    else:
+        O_part, m, l = out
+    _check(lib().a2d_partial_fwd(ctypes.byref(d), _ptr(Q), _ptr(K), _ptr(V), _ptr(O_part), _ptr(m),
+                                 _ptr(l), None, 0, _stream()))
+    return O_part, m, l
+
+
+def fix(O_parts, ms, ls, out_dtype=torch.bfloat16, out=None):
+    """a2d_fix over k partial triples. Returns (O [heads][nq][H] in out_dtype, lse fp32)."""
+    k = len(O_parts)
+    if k < 1 or len(ms) != k or len(ls) != k:
+        raise A2DError(-1, "need k >= 1 partial triples")
+    shape = O_parts[0].shape
+    rows = 1
+    for s in shape[:-1]:
+        rows *= s
+    if out is None:
+        O = torch.empty(shape, dtype=out_dtype, device=O_parts[0].device)
+        lse = torch.empty(shape[:-1], dtype=torch.float32, device=O_parts[0].device)
+    else:
+        O, lse = out
+    _check(lib().a2d_fix(k, rows, shape[-1], _dtype_code(O.dtype), _ptr_array(O_parts),
+                         _ptr_array(ms), _ptr_array(ls), _ptr(O), _ptr(lse), _stream()))
+    return O, lse
+
+
+def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None, out=None,
+                workspace=None):
+    """a2d_partial_bwd. Returns (dQ_part, dK_part, dV_part), all fp32."""
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _dev3(t, n)
+    if O.shape != Q.shape or dO.shape != Q.shape or O.dtype != Q.dtype or dO.dtype != Q.dtype or \
+            lse.shape != Q.shape[:2] or lse.dtype != torch.float32 or K.shape != V.shape:
+        raise A2DError(-1, "O, dO, lse do not match Q")
+    d = tile_desc(Q, K, q_off, kv_off, causal, scale)
+    need = workspace_bytes(d, OP_PARTIAL_BWD)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    if out is None:
+        dQ = torch.empty(Q.shape, dtype=torch.float32, device=Q.device)
+        dK = torch.empty(K.shape, dtype=torch.float32, device=Q.device)
+        dV = torch.empty(K.shape, dtype=torch.float32, device=Q.device)
+    else:
+        dQ, dK, dV = out
+    _check(lib().a2d_partial_bwd(ctypes.byref(d), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO),
+                                 _ptr(lse), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream()))
+    return dQ, dK, dV
+
+
+def fix_bwd(parts, out_dtype=torch.bfloat16, out=None):
+    """a2d_fix_bwd: sum of k fp32 partials, rounded once to out_dtype."""
+    k = len(parts)
+    if k < 1:
+        raise A2DError(-1, "need k >= 1 partials")
+    if out is None:
+        out = torch.empty(parts[0].shape, dtype=out_dtype, device=parts[0].device)
+    _check(lib().a2d_fix_bwd(k, parts[0].numel(), _dtype_code(out.dtype), _ptr_array(parts), _ptr(out),
+                             _stream()))
+    return out
+
+
+def version():
+    return lib().a2d_version().decode()

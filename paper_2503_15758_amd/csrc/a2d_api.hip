@@ -1,0 +1,195 @@
+// C-ABI layer of liba2d: argument validation, kernel selection, error reporting.
+// No arithmetic happens here; see include/a2d.h for the contract of every call.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "a2d_common.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+a2d_status fail(a2d_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// A2D_FORCE_GENERIC=1 routes every tile call to the generic kernels (debugging aid).
+bool force_generic() {
+  static const bool v = [] {
+    const char* e = getenv("A2D_FORCE_GENERIC");
+    return e && e[0] == '1';
+  }();
+  return v;
+}
+
+a2d_status check_desc(const a2d_tile_desc* d, const char* who) {
+  if (!d) return fail(A2D_ERR_INVALID_ARG, "%s: descriptor is NULL", who);
+  if (d->heads < 1 || d->nq < 1 || d->nkv < 1)
+    return fail(A2D_ERR_INVALID_ARG, "%s: heads=%d nq=%d nkv=%d must all be >= 1", who, d->heads,
+                d->nq, d->nkv);
+  if (d->dtype != A2D_F32 && d->dtype != A2D_BF16)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: dtype %d is neither A2D_F32 nor A2D_BF16", who, d->dtype);
+  if (d->hdim != 64 && d->hdim != 128)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: head size %d not supported (64 or 128)", who, d->hdim);
+  if (!(d->scale > 0.f) || !std::isfinite(d->scale))
+    return fail(A2D_ERR_INVALID_ARG, "%s: scale must be finite and > 0", who);
+  if (d->causal != 0 && d->causal != 1)
+    return fail(A2D_ERR_INVALID_ARG, "%s: causal must be 0 or 1", who);
+  if (d->heads > 65535) return fail(A2D_ERR_INVALID_ARG, "%s: heads=%d exceeds 65535", who, d->heads);
+  const int64_t lim = (int64_t)1 << 40;
+  if (d->q_off < -lim || d->q_off > lim || d->kv_off < -lim || d->kv_off > lim)
+    return fail(A2D_ERR_INVALID_ARG, "%s: offsets out of range", who);
+  return A2D_OK;
+}
+
+a2d_status check_ptr(const void* p, const char* who, const char* name) {
+  if (!p) return fail(A2D_ERR_INVALID_ARG, "%s: %s is NULL", who, name);
+  if (!aligned16(p)) return fail(A2D_ERR_MISALIGNED, "%s: %s is not 16-byte aligned", who, name);
+  return A2D_OK;
+}
+
+#define A2D_TRY(expr)                   \
+  do {                                  \
+    a2d_status st__ = (expr);           \
+    if (st__ != A2D_OK) return st__;    \
+  } while (0)
+
+a2d_status hip_result(hipError_t e, const char* who) {
+  if (e == hipSuccess) return A2D_OK;
+  return fail(A2D_ERR_HIP, "%s: HIP error %d (%s)", who, (int)e, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t a2d_workspace_bytes(const a2d_tile_desc* desc, int op, int /*k*/) {
+  if (!desc || desc->heads < 1 || desc->nq < 1) return 0;
+  if (op != A2D_OP_PARTIAL_BWD) return 0;
+  const size_t rows = (size_t)desc->heads * (size_t)desc->nq;
+  return ((rows * sizeof(float) + 255) / 256) * 256;
+}
+
+a2d_status a2d_partial_fwd(const a2d_tile_desc* desc, const void* Q, const void* K, const void* V,
+                           float* O_part, float* m, float* l, void* /*workspace*/,
+                           size_t /*workspace_bytes*/, void* stream) {
+  const char* who = "a2d_partial_fwd";
+  A2D_TRY(check_desc(desc, who));
+  A2D_TRY(check_ptr(Q, who, "Q"));
+  A2D_TRY(check_ptr(K, who, "K"));
+  A2D_TRY(check_ptr(V, who, "V"));
+  A2D_TRY(check_ptr(O_part, who, "O_part"));
+  A2D_TRY(check_ptr(m, who, "m"));
+  A2D_TRY(check_ptr(l, who, "l"));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!force_generic() && a2d::fwd_mfma_supported(*desc))
+    return hip_result(a2d::launch_fwd_mfma(*desc, Q, K, V, O_part, m, l, s), who);
+  return hip_result(a2d::launch_fwd_generic(*desc, Q, K, V, O_part, m, l, s), who);
+}
+
+a2d_status a2d_fix(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
+                   const float* const* O_parts, const float* const* m, const float* const* l,
+                   void* O, float* lse, void* stream) {
+  const char* who = "a2d_fix";
+  if (k < 1 || k > A2D_MAX_PARTS)
+    return fail(A2D_ERR_INVALID_ARG, "%s: k=%d outside 1..%d", who, k, A2D_MAX_PARTS);
+  if (rows < 1) return fail(A2D_ERR_INVALID_ARG, "%s: rows=%lld must be >= 1", who, (long long)rows);
+  if (hdim < 4 || hdim % 4 != 0 || hdim > 1024)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: hdim=%d must be a multiple of 4 in 4..1024", who, hdim);
+  if (out_dtype != A2D_F32 && out_dtype != A2D_BF16)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: out_dtype %d not supported", who, out_dtype);
+  if (rows * (int64_t)(hdim / 4) > ((int64_t)1 << 39))
+    return fail(A2D_ERR_INVALID_ARG, "%s: rows * hdim too large", who);
+  if (!O_parts || !m || !l) return fail(A2D_ERR_INVALID_ARG, "%s: pointer array is NULL", who);
+  A2D_TRY(check_ptr(O, who, "O"));
+  A2D_TRY(check_ptr(lse, who, "lse"));
+  a2d::FixPtrs p;
+  memset(&p, 0, sizeof(p));
+  for (int x = 0; x < k; ++x) {
+    A2D_TRY(check_ptr(O_parts[x], who, "O_parts[x]"));
+    A2D_TRY(check_ptr(m[x], who, "m[x]"));
+    A2D_TRY(check_ptr(l[x], who, "l[x]"));
+    p.o[x] = O_parts[x]; p.m[x] = m[x]; p.l[x] = l[x];
+  }
+  return hip_result(a2d::launch_fix(k, rows, hdim, out_dtype, p, O, lse,
+                                    static_cast<hipStream_t>(stream)), who);
+}
+
+a2d_status a2d_partial_bwd(const a2d_tile_desc* desc, const void* Q, const void* K, const void* V,
+                           const void* O, const void* dO, const float* lse, float* dQ_part,
+                           float* dK_part, float* dV_part, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+  const char* who = "a2d_partial_bwd";
+  A2D_TRY(check_desc(desc, who));
+  A2D_TRY(check_ptr(Q, who, "Q"));
+  A2D_TRY(check_ptr(K, who, "K"));
+  A2D_TRY(check_ptr(V, who, "V"));
+  A2D_TRY(check_ptr(O, who, "O"));
+  A2D_TRY(check_ptr(dO, who, "dO"));
+  A2D_TRY(check_ptr(lse, who, "lse"));
+  A2D_TRY(check_ptr(dQ_part, who, "dQ_part"));
+  A2D_TRY(check_ptr(dK_part, who, "dK_part"));
+  A2D_TRY(check_ptr(dV_part, who, "dV_part"));
+  const size_t need = a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD, 0);
+  if (!workspace || workspace_bytes < need)
+    return fail(A2D_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need,
+                workspace ? workspace_bytes : (size_t)0);
+  if (!aligned16(workspace)) return fail(A2D_ERR_MISALIGNED, "%s: workspace is not 16-byte aligned", who);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* delta = static_cast<float*>(workspace);
+  A2D_TRY(hip_result(a2d::launch_delta(desc->dtype, (int64_t)desc->heads * desc->nq, desc->hdim, O,
+                                       dO, delta, s), who));
+  if (!force_generic() && a2d::bwd_mfma_supported(*desc))
+    return hip_result(a2d::launch_bwd_mfma(*desc, Q, K, V, dO, lse, delta, dQ_part, dK_part,
+                                           dV_part, s), who);
+  return hip_result(a2d::launch_bwd_generic(*desc, Q, K, V, dO, lse, delta, dQ_part, dK_part,
+                                            dV_part, s), who);
+}
+
+a2d_status a2d_fix_bwd(int k, int64_t n, int32_t out_dtype, const float* const* parts, void* out,
+                       void* stream) {
+  const char* who = "a2d_fix_bwd";
+  if (k < 1 || k > A2D_MAX_PARTS)
+    return fail(A2D_ERR_INVALID_ARG, "%s: k=%d outside 1..%d", who, k, A2D_MAX_PARTS);
+  if (n < 4 || n % 4 != 0)
+    return fail(A2D_ERR_INVALID_ARG, "%s: n=%lld must be a positive multiple of 4", who, (long long)n);
+  if (n > ((int64_t)1 << 41)) return fail(A2D_ERR_INVALID_ARG, "%s: n too large", who);
+  if (out_dtype != A2D_F32 && out_dtype != A2D_BF16)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: out_dtype %d not supported", who, out_dtype);
+  if (!parts) return fail(A2D_ERR_INVALID_ARG, "%s: parts is NULL", who);
+  A2D_TRY(check_ptr(out, who, "out"));
+  a2d::SumPtrs p;
+  memset(&p, 0, sizeof(p));
+  for (int x = 0; x < k; ++x) {
+    A2D_TRY(check_ptr(parts[x], who, "parts[x]"));
+    p.p[x] = parts[x];
+  }
+  return hip_result(a2d::launch_fix_bwd(k, n, out_dtype, p, out, static_cast<hipStream_t>(stream)), who);
+}
+
+const char* a2d_status_str(a2d_status status) {
+  switch (status) {
+    case A2D_OK: return "ok";
+    case A2D_ERR_INVALID_ARG: return "invalid argument";
+    case A2D_ERR_UNSUPPORTED: return "unsupported dtype or shape";
+    case A2D_ERR_MISALIGNED: return "misaligned pointer";
+    case A2D_ERR_WORKSPACE: return "workspace missing or too small";
+    case A2D_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+const char* a2d_last_error(void) { return g_err; }
+
+const char* a2d_version(void) { return "0.1"; }
+
+}  // extern "C"

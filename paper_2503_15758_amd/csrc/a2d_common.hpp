@@ -1,0 +1,72 @@
+// Shared device-side helpers and the launcher interface between the C-ABI layer
+// (a2d_api.hip) and the kernel translation units.  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "a2d.h"
+
+namespace a2d {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return (float)x; }
+
+// 2^x and log2(x) on the hardware transcendental unit (about 1 ulp).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+template <typename T> struct dtype_of;
+template <> struct dtype_of<float> { static constexpr int value = A2D_F32; };
+template <> struct dtype_of<bf16_t> { static constexpr int value = A2D_BF16; };
+
+// ---- launchers (each returns the launch's hipError_t; none synchronises) ----
+
+// Generic tile kernels: fp32 arithmetic on the vector ALUs for fp32 or bf16
+// inputs, any nq / nkv, H in {64, 128}.
+hipError_t launch_fwd_generic(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+                              float* O_part, float* m, float* l, hipStream_t s);
+hipError_t launch_bwd_generic(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+                              const void* dO, const float* lse, const float* delta, float* dQ,
+                              float* dK, float* dV, hipStream_t s);
+
+// delta[row] = sum_j dO[row][j] * O[row][j]
+hipError_t launch_delta(int dtype, int64_t rows, int hdim, const void* O, const void* dO,
+                        float* delta, hipStream_t s);
+
+// bf16 MFMA tile kernels (H = 128).  `supported` tells whether the shape is covered.
+bool fwd_mfma_supported(const a2d_tile_desc& d);
+hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+                           float* O_part, float* m, float* l, hipStream_t s);
+bool bwd_mfma_supported(const a2d_tile_desc& d);
+hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+                           const void* dO, const float* lse, const float* delta, float* dQ,
+                           float* dK, float* dV, hipStream_t s);
+
+struct FixPtrs {
+  const float* o[A2D_MAX_PARTS];
+  const float* m[A2D_MAX_PARTS];
+  const float* l[A2D_MAX_PARTS];
+};
+struct SumPtrs {
+  const float* p[A2D_MAX_PARTS];
+};
+hipError_t launch_fix(int k, int64_t rows, int hdim, int out_dtype, const FixPtrs& p, void* O,
+                      float* lse, hipStream_t s);
+hipError_t launch_fix_bwd(int k, int64_t n, int out_dtype, const SumPtrs& p, void* out,
+                          hipStream_t s);
+
+}  // namespace a2d

@@ -1,0 +1,320 @@
+"""GPU parity: every C-ABI call against the fp64 oracle on the same seeded inputs.
+
+Small cases compare every element; the paper-sized workloads (synth.WORKLOADS) run in the
+launch configuration the benchmark times and compare whole heads or sampled rows.
+Tolerances (the benchmark spec): max abs error <= 1e-4 (fp32), <= 2e-2 (bf16 in / fp32 accumulate).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_15758_amd import synth
+from helpers import TOL, assert_close, grid_backward, grid_forward, np64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def a2d():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2503_15758_amd import binding
+    binding.lib()          # raises if the HIP library has not been built
+    return binding
+
+
+def dev(t):
+    return t.to("cuda")
+
+
+DT = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def check_partial(a2d, Q, K, V, q_off, kv_off, causal, scale, what):
+    dtype = Q.dtype
+    Np, m, l = a2d.partial_fwd(dev(Q), dev(K), dev(V), q_off, kv_off, causal, scale)
+    torch.cuda.synchronize()
+    Nr, mr, lr = oracle.partial_fwd(np64(Q), np64(K), np64(V), q_off, kv_off, causal, scale)
+    Ng, mg, lg = np64(Np), np64(m), np64(l)
+    empty = np.isinf(mr)
+    # rows that see no key: exact conventions
+    assert np.array_equal(np.isinf(mg) & (mg < 0), empty), what + ": set of empty rows differs"
+    assert np.all(lg[empty] == 0.0) and np.all(Ng[empty] == 0.0), what + ": empty rows not zero"
+    ok = ~empty
+    if ok.any():
+        assert_close(mg[ok], mr[ok], dtype, what + " m", rel=False)
+        assert_close(Ng[ok] / lg[ok][:, None], Nr[ok] / lr[ok][:, None], dtype, what + " N/l")
+        assert_close(mg[ok] + np.log(lg[ok]), mr[ok] + np.log(lr[ok]), dtype, what + " m+ln l", rel=False)
+        assert_close(Ng[ok], Nr[ok], dtype, what + " N (per-row scaled)", rel=False, scale_rows=True)
+        assert np.all(lg[ok] >= 1.0 - 1e-3), what + ": l < 1 on a non-empty row"
+    return Np, m, l
+
+
+# ----------------------------------------------------------------------------- partial_fwd
+FWD_CASES = [
+    # heads, nq, nkv, H, causal, q_off, kv_off
+    (2, 128, 128, 64, False, 0, 0),
+    (1, 100, 77, 64, False, 0, 0),
+    (3, 257, 190, 128, False, 0, 0),
+    (1, 1, 1, 128, False, 0, 0),
+    (2, 256, 256, 128, True, 0, 0),          # diagonal tile
+    (2, 130, 300, 128, True, 170, 0),        # below the diagonal, ragged
+    (1, 200, 131, 128, True, 0, 5),          # first rows see no key
+    (1, 96, 64, 64, True, 0, 1),             # the cyclic layout's r < c tile
+    (1, 64, 64, 128, True, 0, 1000),         # wholly above the diagonal
+    (2, 384, 512, 128, True, 256, 128),      # several blocks, offset diagonal
+]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("case", FWD_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_partial_fwd_small(a2d, dt, case):
+    heads, nq, nkv, H, causal, q_off, kv_off = case
+    Q = synth.normal((heads, nq, H), 11, 0, 1.0, dt)
+    K = synth.normal((heads, nkv, H), 11, 1, 1.0, dt)
+    V = synth.normal((heads, nkv, H), 11, 2, 1.0, dt)
+    check_partial(a2d, Q, K, V, q_off, kv_off, causal, 1.0 / math.sqrt(H), "fwd %s %s" % (dt, case))
+
+
+def test_partial_fwd_peaky_logits(a2d):
+    """sigma = 4 queries/keys (the prefill workload): row maxima near 80, heavy rescaling."""
+    H = 128
+    Q = synth.normal((2, 192, H), 12, 0, 4.0, "bf16")
+    K = synth.normal((2, 320, H), 12, 1, 4.0, "bf16")
+    V = synth.normal((2, 320, H), 12, 2, 1.0, "bf16")
+    check_partial(a2d, Q, K, V, 0, 0, False, 1.0 / math.sqrt(H), "peaky")
+
+
+# ----------------------------------------------------------------------------- fix / fix_bwd
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 16, 32])
+@pytest.mark.parametrize("H,out", [(128, "bf16"), (64, "f32"), (80, "f32")])
+def test_fix_vs_oracle(a2d, k, H, out):
+    rows = 333
+    g = torch.Generator().manual_seed(100 + k)
+    Ns = [torch.randn(rows, H, generator=g) * 3 for _ in range(k)]
+    ms = [torch.randn(rows, generator=g) * 20 for _ in range(k)]
+    ls = [torch.rand(rows, generator=g) * 50 + 1 for _ in range(k)]
+    for x in range(k):                      # sprinkle empty partials, one row empty everywhere
+        emp = torch.rand(rows, generator=g) < 0.2
+        emp[7] = True
+        ms[x][emp] = -float("inf"); ls[x][emp] = 0.0; Ns[x][emp] = 0.0
+    O, lse = a2d.fix([dev(n) for n in Ns], [dev(m) for m in ms], [dev(l) for l in ls], DT[out])
+    torch.cuda.synchronize()
+    Or, lr = oracle.fix([np64(n) for n in Ns], [np64(m) for m in ms], [np64(l) for l in ls])
+    assert_close(O, Or, DT[out], "fix O k=%d" % k)
+    assert_close(lse, lr, DT[out], "fix lse k=%d" % k, rel=False)
+    assert np64(lse)[7] == -np.inf and np.all(np64(O)[7] == 0.0)
+
+
+@pytest.mark.parametrize("k", [1, 2, 5, 8, 32])
+@pytest.mark.parametrize("out", ["bf16", "f32"])
+def test_fix_bwd_vs_oracle(a2d, k, out):
+    g = torch.Generator().manual_seed(200 + k)
+    # sums stay O(1) so that the single bf16 rounding of the output is inside the tolerance
+    parts = [torch.randn(3, 50, 64, generator=g) * (0.5 / math.sqrt(k)) for _ in range(k)]
+    got = a2d.fix_bwd([dev(p) for p in parts], DT[out])
+    torch.cuda.synchronize()
+    ref = oracle.fix_bwd([np64(p) for p in parts])
+    if out == "f32" and k <= 2:
+        assert np.array_equal(np64(got), ref.astype(np.float32).astype(np.float64))
+    assert_close(got, ref, DT[out], "fix_bwd k=%d" % k)
+
+
+# ----------------------------------------------------------------------------- partial_bwd
+BWD_CASES = [
+    (2, 128, 128, 64, False, 0, 0),
+    (1, 100, 77, 64, False, 0, 0),
+    (2, 257, 190, 128, False, 0, 0),
+    (2, 256, 256, 128, True, 0, 0),
+    (1, 130, 300, 128, True, 170, 0),
+    (1, 200, 131, 128, True, 0, 5),
+    (1, 64, 64, 128, True, 0, 1000),
+    (1, 384, 512, 128, True, 256, 128),
+]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("case", BWD_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_partial_bwd_small(a2d, dt, case):
+    """The tile is one of two key blocks of the row: O and lse are the FINAL ones over both blocks,
+    so the test also checks that the kernel uses them and not tile-local statistics."""
+    heads, nq, nkv, H, causal, q_off, kv_off = case
+    scale = 1.0 / math.sqrt(H)
+    extra = 96                                # keys of the "other" tile, always visible
+    Q = synth.normal((heads, nq, H), 13, 0, 1.0, dt)
+    K = synth.normal((heads, nkv, H), 13, 1, 1.0, dt)
+    V = synth.normal((heads, nkv, H), 13, 2, 1.0, dt)
+    K2 = synth.normal((heads, extra, H), 13, 3, 1.0, dt)
+    V2 = synth.normal((heads, extra, H), 13, 4, 1.0, dt)
+    dO = synth.normal((heads, nq, H), 13, 5, 1.0, dt)
+    t1 = oracle.partial_fwd(np64(Q), np64(K), np64(V), q_off, kv_off, causal, scale)
+    t2 = oracle.partial_fwd(np64(Q), np64(K2), np64(V2), 0, 0, False, scale)
+    Of, lsef = oracle.fix([t1[0], t2[0]], [t1[1], t2[1]], [t1[2], t2[2]])
+    O_in = torch.from_numpy(Of).to(DT[dt])            # what the forward would have stored
+    lse_in = torch.from_numpy(lsef).to(torch.float32)
+    dQ, dK, dV = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, kv_off, causal, scale)
+    torch.cuda.synchronize()
+    rQ, rK, rV = oracle.partial_bwd(np64(Q), np64(K), np64(V), np64(O_in), np64(dO), np64(lse_in),
+                                    q_off, kv_off, causal, scale)
+    what = "bwd %s %s" % (dt, case)
+    for got, ref, name in ((dQ, rQ, "dQ"), (dK, rK, "dK"), (dV, rV, "dV")):
+        assert_close(got, ref, DT[dt], what + " " + name, rel=bool(np.abs(ref).max() > 0))
+
+
+# ----------------------------------------------------------------------------- workloads
+def test_c1_fp32_grid_forward_all_elements(a2d):
+    w = synth.WORKLOADS["c1"]
+    T, scale = w.tile, 1.0 / math.sqrt(w.hdim)
+    Qb = [synth.q_block(w, r) for r in range(w.grid)]
+    Kb = [synth.k_block(w, c) for c in range(w.grid)]
+    Vb = [synth.v_block(w, c) for c in range(w.grid)]
+    parts, fixed = grid_forward(a2d, [dev(x) for x in Qb], [dev(x) for x in Kb], [dev(x) for x in Vb],
+                                T, w.causal, scale, torch.float32)
+    torch.cuda.synchronize()
+    Q, K, V = (np.concatenate([np64(x) for x in b], axis=1) for b in (Qb, Kb, Vb))
+    O, lse = oracle.attention_fwd(Q, K, V, scale, w.causal)
+    for r in range(w.grid):
+        assert_close(fixed[r][0], O[:, r * T:(r + 1) * T], torch.float32, "c1 O block %d" % r)
+        assert_close(fixed[r][1], lse[:, r * T:(r + 1) * T], torch.float32, "c1 lse block %d" % r, rel=False)
+        for c in range(w.grid):
+            Nr, mr, lr = oracle.partial_fwd(np64(Qb[r]), np64(Kb[c]), np64(Vb[c]), r * T, c * T, False, scale)
+            Np, m, l = parts[r][c]
+            assert_close(m, mr, torch.float32, "c1 m tile %d,%d" % (r, c), rel=False)
+            assert_close(np64(Np) / np64(l)[..., None], Nr / lr[..., None], torch.float32, "c1 N/l tile")
+
+
+def test_c2_bf16_grid_fwd_bwd_two_heads(a2d):
+    """Full 4 x 4 grid, all 16 heads on the GPU; the oracle checks heads 0 and 15 completely."""
+    w = synth.WORKLOADS["c2"]
+    T, scale, G = w.tile, 1.0 / math.sqrt(w.hdim), w.grid
+    Qb = [synth.q_block(w, r) for r in range(G)]
+    Kb = [synth.k_block(w, c) for c in range(G)]
+    Vb = [synth.v_block(w, c) for c in range(G)]
+    dOb = [synth.do_block(w, r) for r in range(G)]
+    dQb, dKb, dVb, dOd = ([dev(x) for x in b] for b in (Qb, Kb, Vb, dOb))
+    parts, fixed = grid_forward(a2d, dQb, dKb, dVb, T, w.causal, scale, torch.bfloat16)
+    Ob = [f[0] for f in fixed]
+    lseb = [f[1] for f in fixed]
+    _, gQ, gK, gV = grid_backward(a2d, dQb, dKb, dVb, Ob, dOd, lseb, T, w.causal, scale, torch.bfloat16)
+    torch.cuda.synchronize()
+    # run to run: bitwise identical lse and O
+    _, fixed2 = grid_forward(a2d, dQb, dKb, dVb, T, w.causal, scale, torch.bfloat16)
+    torch.cuda.synchronize()
+    for r in range(G):
+        assert torch.equal(fixed[r][1], fixed2[r][1]) and torch.equal(fixed[r][0], fixed2[r][0])
+    hs = [0, w.heads - 1]
+    Q, K, V, dO = (np.concatenate([np64(x[hs]) for x in b], axis=1) for b in (Qb, Kb, Vb, dOb))
+    O, lse = oracle.attention_fwd(Q, K, V, scale, w.causal)
+    Og = np.concatenate([np64(x[hs]) for x in Ob], axis=1)
+    lg = np.concatenate([np64(x[hs]) for x in lseb], axis=1)
+    assert_close(Og, O, torch.bfloat16, "c2 O")
+    assert_close(lg, lse, torch.bfloat16, "c2 lse", rel=False)
+    rQ, rK, rV = oracle.attention_bwd(Q, K, V, dO, scale, w.causal)
+    for got, ref, name in ((gQ, rQ, "dQ"), (gK, rK, "dK"), (gV, rV, "dV")):
+        gg = np.concatenate([np64(x[hs]) for x in got], axis=1)
+        # the oracle's gradient is of the exact O; the GPU's dO*O term uses its bf16-rounded O: same bar
+        assert_close(gg, ref, torch.bfloat16, "c2 " + name, rel=False)
+        from helpers import rel_fro
+        assert rel_fro(gg, ref) < 3e-2, "c2 %s relative error %.3e" % (name, rel_fro(gg, ref))
+
+
+def _sample_rows(T):
+    step = max(1, T // 256)
+    rows = sorted(set(list(range(0, T, step)) + list(range(8)) + list(range(T - 8, T))))
+    return np.array(rows)
+
+
+def test_c3_causal_tiles_full_heads(a2d):
+    """GPT-3-like causal workload: query block r = 7 against all 8 key blocks at 96 heads (the
+    benchmark's launch shape); oracle on head 0 and head 95 rows sampled, bwd of the diagonal and one
+    unmasked tile on head 0."""
+    w = synth.WORKLOADS["c3"]
+    T, scale, G, r = w.tile, 1.0 / math.sqrt(w.hdim), w.grid, w.grid - 1
+    Qr = synth.q_block(w, r)
+    dOr = synth.do_block(w, r)
+    Kb = [synth.k_block(w, c) for c in range(G)]
+    Vb = [synth.v_block(w, c) for c in range(G)]
+    Qd, dOd = dev(Qr), dev(dOr)
+    Kd, Vd = [dev(x) for x in Kb], [dev(x) for x in Vb]
+    parts = [a2d.partial_fwd(Qd, Kd[c], Vd[c], r * T, c * T, True, scale) for c in range(G)]
+    O, lse = a2d.fix([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], torch.bfloat16)
+    torch.cuda.synchronize()
+    parts2 = a2d.partial_fwd(Qd, Kd[r], Vd[r], r * T, r * T, True, scale)
+    O2, lse2 = a2d.fix([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], torch.bfloat16)
+    torch.cuda.synchronize()
+    assert torch.equal(lse, lse2) and torch.equal(O, O2) and torch.equal(parts2[1], parts[r][1])
+    rows = _sample_rows(T)
+    for h in (0, w.heads - 1):
+        trip = [oracle.partial_fwd(np64(Qr[h:h + 1, rows]), np64(Kb[c][h:h + 1]), np64(Vb[c][h:h + 1]),
+                                   0, 0, False, scale) if c < r else None for c in range(G)]
+        # the diagonal block needs per-row offsets: evaluate the sampled rows one contiguous run at a time
+        Nd = np.empty((1, len(rows), w.hdim)); md = np.empty((1, len(rows))); ld = np.empty((1, len(rows)))
+        for i, row in enumerate(rows):
+            a, b, c_ = oracle.partial_fwd(np64(Qr[h:h + 1, row:row + 1]), np64(Kb[r][h:h + 1]), np64(Vb[r][h:h + 1]),
+                                          r * T + row, r * T, True, scale)
+            Nd[0, i], md[0, i], ld[0, i] = a[0, 0], b[0, 0], c_[0, 0]
+        trip[r] = (Nd, md, ld)
+        Or, lr = oracle.fix([t[0] for t in trip], [t[1] for t in trip], [t[2] for t in trip])
+        assert_close(np64(O[h:h + 1, rows]), Or, torch.bfloat16, "c3 O head %d" % h)
+        assert_close(np64(lse[h:h + 1, rows]), lr, torch.bfloat16, "c3 lse head %d" % h, rel=False)
+        for c in (0, r):
+            assert_close(np64(parts[c][1][h:h + 1, rows]), trip[c][1], torch.bfloat16, "c3 m", rel=False)
+            assert_close(np64(parts[c][0][h:h + 1, rows]) / np64(parts[c][2][h:h + 1, rows])[..., None],
+                         trip[c][0] / trip[c][2][..., None], torch.bfloat16, "c3 N/l tile %d" % c)
+    # backward of the diagonal tile and of the unmasked tile (r, 0), all heads on the GPU, head 0 checked
+    for c in (r, 0):
+        dQ, dK, dV = a2d.partial_bwd(Qd, Kd[c], Vd[c], O, dOd, lse, r * T, c * T, True, scale)
+        torch.cuda.synchronize()
+        rQ, rK, rV = oracle.partial_bwd(np64(Qr[:1]), np64(Kb[c][:1]), np64(Vb[c][:1]), np64(O[:1]), np64(dOr[:1]),
+                                        np64(lse[:1]), r * T, c * T, True, scale)
+        for got, ref, name in ((dQ, rQ, "dQ"), (dK, rK, "dK"), (dV, rV, "dV")):
+            assert_close(got[:1], ref, torch.bfloat16, "c3 bwd tile (7,%d) %s" % (c, name))
+
+
+@pytest.mark.parametrize("name", ["c4", "c5"])
+def test_long_context_tiles_sampled(a2d, name):
+    """16384 x 16384 tiles at the workload's head count; AttnFix over all sqrt(P) partials of query
+    block 0; oracle on sampled rows of the first and last head against every key of the sequence."""
+    w = synth.WORKLOADS[name]
+    T, scale, G = w.tile, 1.0 / math.sqrt(w.hdim), w.grid
+    Q0 = synth.q_block(w, 0)
+    Qd = dev(Q0)
+    rows = _sample_rows(T)[::4]
+    hs = [0, w.heads - 1]
+    parts, trips = [], []
+    for c in range(G):
+        Kc, Vc = synth.k_block(w, c), synth.v_block(w, c)
+        parts.append(a2d.partial_fwd(Qd, dev(Kc), dev(Vc), 0, c * T, False, scale))
+        trips.append(oracle.partial_fwd(np64(Q0[hs][:, rows]), np64(Kc[hs]), np64(Vc[hs]), 0, 0, False, scale))
+        if c == 0:
+            K0, V0 = Kc, Vc
+    O, lse = a2d.fix([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], torch.bfloat16)
+    torch.cuda.synchronize()
+    Or, lr = oracle.fix([t[0] for t in trips], [t[1] for t in trips], [t[2] for t in trips])
+    assert_close(np64(O[hs][:, rows]), Or, torch.bfloat16, name + " O")
+    assert_close(np64(lse[hs][:, rows]), lr, torch.bfloat16, name + " lse", rel=False)
+    for c in (0, G - 1):
+        assert_close(np64(parts[c][1][hs][:, rows]), trips[c][1], torch.bfloat16, name + " m", rel=False)
+        assert_close(np64(parts[c][0][hs][:, rows]) / np64(parts[c][2][hs][:, rows])[..., None],
+                     trips[c][0] / trips[c][2][..., None], torch.bfloat16, name + " N/l")
+    if not w.backward:
+        return
+    # backward of tile (0, 0) at full head count; oracle on a 2048 x 2048 corner of head 0 is not a
+    # valid sub-problem (gradients couple all rows), so check dQ on sampled query rows (needs all keys
+    # of the tile) and dK/dV through their sums over keys, which need only per-row quantities.
+    dO0 = synth.do_block(w, 0)
+    dQ, dK, dV = a2d.partial_bwd(Qd, dev(K0), dev(V0), O, dev(dO0), lse, 0, 0, False, scale)
+    torch.cuda.synchronize()
+    sub = rows[:48]
+    rQ, _, _ = oracle.partial_bwd(np64(Q0[:1, sub]), np64(K0[:1]), np64(V0[:1]), np64(O[:1, sub]), np64(dO0[:1, sub]),
+                                  np64(lse[:1, sub]), 0, 0, False, scale)
+    assert_close(np64(dQ[:1, sub]), rQ, torch.bfloat16, name + " dQ sampled rows")
+    # dK, dV of sampled KEY rows need every query row: oracle with the key block cut to those rows
+    ksub = rows[:24]
+    _, rK, rV = oracle.partial_bwd(np64(Q0[:1]), np64(K0[:1, ksub]), np64(V0[:1, ksub]), np64(O[:1]), np64(dO0[:1]),
+                                   np64(lse[:1]), 0, 0, False, scale)
+    assert_close(np64(dK[:1, ksub]), rK, torch.bfloat16, name + " dK sampled keys")
+    assert_close(np64(dV[:1, ksub]), rV, torch.bfloat16, name + " dV sampled keys")

@@ -1,0 +1,102 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2503_15758_amd import binding as b
+    if not os.path.exists(b.LIB_PATH):
+        from paper_2503_15758_amd import build
+        build.build(verbose=False)
+    b.lib()
+    return b
+
+
+def test_header_symbols_are_exported(binding):
+    text = open(os.path.join(ROOT, "include", "a2d.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(a2d_[a-z_]+)\s*\(", text))
+    assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
+    L = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert binding.version() == "0.1"
+
+
+def test_descriptor_layout(binding):
+    assert ctypes.sizeof(binding.TileDesc) == 48
+    assert binding.TileDesc.q_off.offset == 16 and binding.TileDesc.dtype.offset == 40
+
+
+def _desc(b, **kw):
+    d = dict(heads=2, nq=128, nkv=128, hdim=128, q_off=0, kv_off=0, causal=0, scale=0.1, dtype=b.A2D_BF16)
+    d.update(kw)
+    return b.TileDesc(**d)
+
+
+def test_workspace_bytes(binding):
+    b = binding
+    assert b.workspace_bytes(_desc(b), b.OP_PARTIAL_FWD) == 0
+    assert b.workspace_bytes(_desc(b), b.OP_FIX, 8) == 0
+    assert b.workspace_bytes(_desc(b), b.OP_PARTIAL_BWD) == 2 * 128 * 4
+    assert b.workspace_bytes(_desc(b, heads=3, nq=5), b.OP_PARTIAL_BWD) == 256
+    assert b.lib().a2d_workspace_bytes(None, b.OP_PARTIAL_BWD, 0) == 0
+
+
+def test_argument_errors_enqueue_nothing(binding):
+    """Every call below fails validation, so no pointer is dereferenced and no kernel is launched."""
+    b, L = binding, binding.lib()
+    P = ctypes.c_void_p(0x10000)       # aligned, never dereferenced
+    odd = ctypes.c_void_p(0x10004)
+    fwd = lambda d, q=P, o=P: L.a2d_partial_fwd(ctypes.byref(d) if d else None, q, P, P, o, P, P, None, 0, None)
+    assert fwd(None) == -1 and b"NULL" in L.a2d_last_error()
+    assert fwd(_desc(b, hdim=80)) == -2
+    assert fwd(_desc(b, dtype=7)) == -2
+    assert fwd(_desc(b, nq=0)) == -1
+    assert fwd(_desc(b, scale=0.0)) == -1
+    assert fwd(_desc(b, scale=float("nan"))) == -1
+    assert fwd(_desc(b, causal=2)) == -1
+    assert fwd(_desc(b), q=None) == -1
+    assert fwd(_desc(b), q=odd) == -3 and b"aligned" in L.a2d_last_error()
+    assert fwd(_desc(b), o=odd) == -3
+    # backward: workspace missing / too small
+    d = _desc(b)
+    bwd = lambda ws, n: L.a2d_partial_bwd(ctypes.byref(d), P, P, P, P, P, P, P, P, P, ws, n, None)
+    assert bwd(None, 0) == -4
+    assert bwd(P, 16) == -4 and b"1024" in L.a2d_last_error()
+    # fix / fix_bwd
+    arr = (ctypes.c_void_p * 2)(0x10000, 0x20000)
+    assert L.a2d_fix(0, 10, 128, b.A2D_BF16, arr, arr, arr, P, P, None) == -1
+    assert L.a2d_fix(33, 10, 128, b.A2D_BF16, arr, arr, arr, P, P, None) == -1
+    assert L.a2d_fix(2, 0, 128, b.A2D_BF16, arr, arr, arr, P, P, None) == -1
+    assert L.a2d_fix(2, 10, 126, b.A2D_BF16, arr, arr, arr, P, P, None) == -2
+    assert L.a2d_fix(2, 10, 128, 9, arr, arr, arr, P, P, None) == -2
+    assert L.a2d_fix(2, 10, 128, b.A2D_BF16, None, arr, arr, P, P, None) == -1
+    bad = (ctypes.c_void_p * 2)(0x10000, 0x20002)
+    assert L.a2d_fix(2, 10, 128, b.A2D_BF16, bad, arr, arr, P, P, None) == -3
+    assert L.a2d_fix_bwd(2, 10, b.A2D_BF16, arr, P, None) == -1          # n not a multiple of 4
+    assert L.a2d_fix_bwd(2, 16, b.A2D_BF16, arr, None, None) == -1
+    assert L.a2d_fix_bwd(40, 16, b.A2D_BF16, arr, P, None) == -1
+    assert L.a2d_status_str(-4) == b"workspace missing or too small"
+    assert L.a2d_status_str(0) == b"ok"
+
+
+def test_binding_fails_loudly_without_library(binding, monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/liba2d.so")
+    with pytest.raises(RuntimeError, match="liba2d.so is missing"):
+        binding.lib()
+
+
+def test_binding_rejects_cpu_tensors(binding):
+    import torch
+    x = torch.zeros(1, 4, 128, dtype=torch.bfloat16)
+    with pytest.raises(binding.A2DError):
+        binding.partial_fwd(x, x, x)
