@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the Attention2D per-device hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic tiles of the chosen
+workload (default: the GPT-3-like causal workload, 4096 x 4096 x H128 tiles, 96 heads):
+  partial_fwd (diagonal tile) + partial_fwd (unmasked tile)  ->  fix over the sqrt(P) partials
+  ->  partial_bwd of both tiles  ->  fix_bwd for dQ (grid row) and dK, dV (grid column).
+All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+  value            = algorithmic tile FLOPs of the step / wall time of the step (TFLOP/s)
+  roofline         = the dominant kernel (the backward tile kernel) against the bf16 MFMA peak,
+                     its duration measured with events on the launch stream inside the timed region
+  kernels          = the same for every call of the step (fix / fix_bwd against the HBM peak)
+  cpu_baseline     = the fp64 oracle timed on the host cores on a bounded sample
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def tile_flops(w, nq, nkv, causal_diag):
+    """Algorithmic FLOPs of one tile, all heads: fwd 4 Nq Nkv H, bwd 10 Nq Nkv H per head; a
+    diagonal causal tile counts its visible fraction (T + 1) / (2 T)."""
+    frac = (nq + 1) / (2.0 * nq) if causal_diag else 1.0
+    base = w.heads * nq * nkv * w.hdim * frac
+    return 4.0 * base, 10.0 * base
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the sqrt(P) x sqrt(P) grid is emulated as "
+                 "independent tiles on one device); --gpus %d is not supported" % args.gpus)
+
+    import torch
+    from paper_2503_15758_amd import binding as a2d, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    a2d.lib()
+    w = synth.WORKLOADS[args.workload]
+    T, G, H = w.tile, w.grid, w.hdim
+    scale = 1.0 / math.sqrt(H)
+    dt = synth.torch_dtype(w.dtype)
+    r = G - 1                                   # the query block with every partial non-empty
+    # tiles of the step: (key block c, is_diagonal)
+    tiles = [(r, True), (0, False)] if w.causal else [(0, False)]
+
+    dev = lambda t: t.to("cuda")
+    Q = dev(synth.q_block(w, r))
+    dO = dev(synth.do_block(w, r)) if w.backward else None
+    Kc = {c: dev(synth.k_block(w, c)) for c, _ in tiles}
+    Vc = {c: dev(synth.v_block(w, c)) for c, _ in tiles}
+
+    f32 = dict(dtype=torch.float32, device="cuda")
+    # sqrt(P) partial triples of the query block; the tiles of the step are recomputed every step,
+    # the others are produced once here (same kernels, other key blocks)
+    parts = [(torch.empty(w.heads, T, H, **f32), torch.empty(w.heads, T, **f32),
+              torch.empty(w.heads, T, **f32)) for _ in range(G)]
+    timed_cols = {c for c, _ in tiles}
+    for c in range(G):
+        if c not in timed_cols:
+            a2d.partial_fwd(Q, dev(synth.k_block(w, c)), dev(synth.v_block(w, c)), r * T, c * T, w.causal,
+                            scale, out=parts[c])
+    O = torch.empty(w.heads, T, H, dtype=dt, device="cuda")
+    lse = torch.empty(w.heads, T, **f32)
+    if w.backward:
+        ws = torch.empty(a2d.workspace_bytes(a2d.tile_desc(Q, Kc[tiles[0][0]], 0, 0, w.causal, scale),
+                                             a2d.OP_PARTIAL_BWD), dtype=torch.uint8, device="cuda")
+        # gradient partials: dQ over the grid row (one per key block), dK / dV over the grid column
+        dq_parts = [torch.zeros(w.heads, T, H, **f32) for _ in range(G)]
+        dk_parts = [torch.zeros(w.heads, T, H, **f32) for _ in range(G)]
+        dv_parts = [torch.zeros(w.heads, T, H, **f32) for _ in range(G)]
+        for x in range(G):   # untimed partials hold plausible values
+            dq_parts[x].normal_(); dk_parts[x].normal_(); dv_parts[x].normal_()
+        dQ = torch.empty(w.heads, T, H, dtype=dt, device="cuda")
+        dK = torch.empty(w.heads, T, H, dtype=dt, device="cuda")
+        dV = torch.empty(w.heads, T, H, dtype=dt, device="cuda")
+    torch.cuda.synchronize()
+
+    names = []
+    calls = []      # (name, fn)
+    for i, (c, diag) in enumerate(tiles):
+        tag = "diag" if diag else "full"
+        calls.append(("partial_fwd_" + tag, lambda c=c: a2d.partial_fwd(
+            Q, Kc[c], Vc[c], r * T, c * T, w.causal, scale, out=parts[c])))
+    calls.append(("fix", lambda: a2d.fix([p[0] for p in parts], [p[1] for p in parts],
+                                         [p[2] for p in parts], out=(O, lse))))
+    if w.backward:
+        for i, (c, diag) in enumerate(tiles):
+            tag = "diag" if diag else "full"
+            calls.append(("partial_bwd_" + tag, lambda c=c, i=i: a2d.partial_bwd(
+                Q, Kc[c], Vc[c], O, dO, lse, r * T, c * T, w.causal, scale,
+                out=(dq_parts[c], dk_parts[i], dv_parts[i]), workspace=ws)))
+        calls.append(("fix_bwd_dq", lambda: a2d.fix_bwd(dq_parts, out=dQ)))
+        calls.append(("fix_bwd_dk", lambda: a2d.fix_bwd(dk_parts, out=dK)))
+        calls.append(("fix_bwd_dv", lambda: a2d.fix_bwd(dv_parts, out=dV)))
+    names = [n for n, _ in calls]
+
+    def step(events=None):
+        for i, (_, fn) in enumerate(calls):
+            if events is not None:
+                events[i][0].record()
+            fn()
+            if events is not None:
+                events[i][1].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in calls] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(ev[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    avg_ms = {n: sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)) / args.steps
+              for i, n in enumerate(names)}
+
+    # ---- algorithmic work of each call
+    flops = {}
+    for c, diag in tiles:
+        tag = "diag" if diag else "full"
+        f, b = tile_flops(w, T, T, diag)
+        flops["partial_fwd_" + tag] = f
+        if w.backward:
+            flops["partial_bwd_" + tag] = b
+    out_b = 2 if w.dtype == "bf16" else 4
+    rows = w.heads * T
+    bytes_ = {"fix": rows * (G * (H + 2) * 4 + H * out_b + 4)}
+    if w.backward:
+        for n in ("fix_bwd_dq", "fix_bwd_dk", "fix_bwd_dv"):
+            bytes_[n] = rows * (G * H * 4 + H * out_b)
+    total_flops = sum(flops.values())
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+
+    kernels = {}
+    for n in names:
+        if n in flops:
+            ach = flops[n] / (avg_ms[n] * 1e-3) / 1e12
+            kernels[n] = {"avg_ms": round(avg_ms[n], 4), "bound": "mfma", "achieved": round(ach, 2),
+                          "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4)}
+        else:
+            ach = bytes_[n] / (avg_ms[n] * 1e-3) / 1e9
+            kernels[n] = {"avg_ms": round(avg_ms[n], 4), "bound": "hbm", "achieved": round(ach, 1),
+                          "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4)}
+    dom = max((n for n in names if n in flops), key=lambda n: avg_ms[n])
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["achieved"],
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": kernels[dom]["frac"],
+                "avg_ms": kernels[dom]["avg_ms"], "traffic": None}
+
+    result = {
+        "metric": "fwd+bwd attention TFLOP/s per tile + % bf16 MFMA peak; AttnFix GB/s",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %s tiles %dx%dxH%d, %d heads, sqrtP=%d, %s" % (
+            w.name, "causal" if w.causal else "non-causal", T, T, H, w.heads, G,
+            "fwd+bwd" if w.backward else "fwd only"),
+            "tiles_per_step": [("diagonal" if d else "unmasked") for _, d in tiles], "fix_k": G},
+        "frac_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "attnfix_gbs": kernels["fix"]["achieved"], "attnfix_frac_hbm": kernels["fix"]["frac"],
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, scale)
+    print(json.dumps(result))
+
+
+def cpu_baseline(w, scale):
+    """The fp64 oracle on the host cores, on a bounded sample of the same workload: one head of an
+    unmasked tile, the first `nq_s` query rows against all T keys, partial forward + partial backward."""
+    import numpy as np
+    import oracle
+    from paper_2503_15758_amd import synth
+    T, H = w.tile, w.hdim
+    nq_s = max(64, min(T, int(2.0e10 / (14.0 * T * H))))     # about 20 GFLOP of algorithmic work
+    one = synth.Workload(w.name, w.dtype, 1, H, w.seq, w.grid, w.causal, w.backward, w.sigma_qk, w.seed)
+    n64 = lambda t: t.double().numpy()
+    Q = n64(synth.q_block(one, w.grid - 1, nq_s)); K = n64(synth.k_block(one, 0)); V = n64(synth.v_block(one, 0))
+    dO = n64(synth.do_block(one, w.grid - 1, nq_s))
+    t0 = time.perf_counter()
+    N, m, l = oracle.partial_fwd(Q, K, V, 0, 0, False, scale)
+    O, lse = oracle.fix([N], [m], [l])
+    fl = 4.0 * nq_s * T * H
+    if w.backward:
+        oracle.partial_bwd(Q, K, V, O, dO, lse, 0, 0, False, scale)
+        fl += 10.0 * nq_s * T * H
+    sec = time.perf_counter() - t0
+    return {"value": round(fl / sec / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(sec, 2),
+            "sample": "one head, %d query rows x %d keys x H%d of an unmasked tile, fp64 partial "
+                      "fwd%s" % (nq_s, T, H, "+bwd" if w.backward else "")}
+
+
+if __name__ == "__main__":
+    main()

@@ -15,46 +15,26 @@
 //                   may be permuted freely as long as A uses the same permutation),
 //                   A = V^T fragment read from the row-major V tile with the LDS
 //                   transpose read ds_read_b64_tr_b16.
-// LDS: K and V tiles double-buffered; rows padded (K: 272 B, V: 320 B) so that the
-// 128-bit K reads and the transposing V reads are bank-conflict free.
-#include "a2d_common.hpp"
+// LDS: K and V tiles double-buffered in the swizzled layout of a2d_mfma.hpp, which
+// keeps both the 128-bit K reads and the transposing V reads bank-conflict free.
+#include "a2d_mfma.hpp"
 
 namespace a2d {
 namespace {
 
-constexpr int H = 128;
+using namespace mfma;
+
 constexpr int BM = 128;            // query rows per workgroup
 constexpr int BN = 64;             // keys per step
-constexpr int KLD = H + 8;         // K tile row stride (bf16 elements) = 272 B
-constexpr int VLD = H + 32;        // V tile row stride = 320 B
-constexpr int K_TILE = BN * KLD;   // elements
-constexpr int V_TILE = BN * VLD;
 constexpr int kThreads = 256;
-
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
-__device__ __forceinline__ bf16x8 lds_read_tr_pair(const bf16_t* p_lo, const bf16_t* p_hi) {
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p_lo);
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p_hi);
-  typedef short s16x8 __attribute__((ext_vector_type(8)));
-  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-__device__ __forceinline__ bf16x8 pack_bf16x8(const f32x16& s, int base) {
-  bf16x8 r;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) r[e] = (bf16_t)s[base + e];
-  return r;
-}
+constexpr int kLdsBytes = 4 * TILE64_BYTES;   // K, V x two buffers
 
 __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
     a2d_tile_desc d, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, float* __restrict__ O_part, float* __restrict__ m_out,
     float* __restrict__ l_out) {
-  extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
-  bf16_t* Ks = lds;                 // [2][BN][KLD]
-  bf16_t* Vs = lds + 2 * K_TILE;    // [2][BN][VLD]
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  // [buf] K tile at buf * 2 * TILE64_BYTES, V tile right after it
 
   const int head = blockIdx.y;
   // heavy (late) query blocks first: under a causal mask they walk more key blocks
@@ -66,6 +46,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
   Q += (int64_t)head * d.nq * H;
   K += (int64_t)head * d.nkv * H;
   V += (int64_t)head * d.nkv * H;
+  FragAddr fa;
+  fa.init(lane);
 
   // ---- Q^T fragments: lane holds query row (l32), h = 16*step + 8*half + 0..7
   const int q_row = q0 + wave * 32 + l32;
@@ -81,89 +63,56 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
     }
   }
 
-  // ---- visibility bounds (all in local key indices of this tile)
-  // vis_hi(i) = number of leading keys query row i can see
-  const int64_t rel = d.q_off - d.kv_off;   // query i sees key r iff r <= i + rel
-  auto vis_count = [&](int i) -> int {
+  // ---- visibility bounds in local key indices: query i sees key r iff r <= i + rel
+  const int64_t rel = d.q_off - d.kv_off;
+  auto vis_count = [&](int i) -> int {      // number of leading keys query row i can see
     if (!d.causal) return d.nkv;
     const int64_t v = (int64_t)i + rel + 1;
     return v <= 0 ? 0 : (v < d.nkv ? (int)v : d.nkv);
   };
   const int blk_last = min(q0 + BM, d.nq) - 1;
-  const int nvis_blk = vis_count(blk_last);
-  const int nblk = (nvis_blk + BN - 1) / BN;
+  const int nblk = (vis_count(blk_last) + BN - 1) / BN;
   const int w_first = q0 + wave * 32;
   const int w_last = min(w_first + 31, d.nq - 1);
   const int nvis_wave = (w_first < d.nq) ? vis_count(w_last) : 0;     // keys any row of the wave sees
   const int nfull_wave = (w_first < d.nq) ? vis_count(w_first) : 0;   // keys every row of the wave sees
-
-  // ---- global -> LDS staging: thread moves 16 B chunks (row = tid/16 + 16p, chunk = tid%16)
-  const int ld_row = tid >> 4, ld_chunk = tid & 15;
-  u32x4 kreg[4], vreg[4];
-  auto load_tile_regs = [&](int k0) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int r = k0 + ld_row + 16 * p;
-      if (r < d.nkv) {
-        kreg[p] = *reinterpret_cast<const u32x4*>(K + (int64_t)r * H + ld_chunk * 8);
-        vreg[p] = *reinterpret_cast<const u32x4*>(V + (int64_t)r * H + ld_chunk * 8);
-      } else {
-        kreg[p] = u32x4{0, 0, 0, 0};
-        vreg[p] = u32x4{0, 0, 0, 0};
-      }
-    }
-  };
-  auto store_tile_lds = [&](int buf) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int r = ld_row + 16 * p;
-      *reinterpret_cast<u32x4*>(&Ks[buf * K_TILE + r * KLD + ld_chunk * 8]) = kreg[p];
-      *reinterpret_cast<u32x4*>(&Vs[buf * V_TILE + r * VLD + ld_chunk * 8]) = vreg[p];
-    }
-  };
+  const int my_vis = (q_row < d.nq) ? vis_count(q_row) : 0;
 
   f32x16 o[4];
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
+  for (int t = 0; t < 4; ++t) o[t] = zero16();
   float m_run = -INFINITY;   // running max of the RAW dot products (scale applied on output)
   float l_run = 0.f;         // this lane's share of the running row sum
   const float c = d.scale * kLog2e;
 
-  // V^T fragment addressing for the transposing read (see file header)
-  const int g16 = lane >> 4, j16 = lane & 15;
-  const int v_row_off = 4 * (g16 >> 1) + (j16 >> 2);
-  const int v_col_off = 16 * (g16 & 1) + 4 * (j16 & 3);
-
+  Stage64 kst, vst;
   if (nblk > 0) {
-    load_tile_regs(0);
-    store_tile_lds(0);
+    kst.load(K, 0, d.nkv, tid);
+    vst.load(V, 0, d.nkv, tid);
+    kst.store(lds, tid);
+    vst.store(lds + TILE64_BYTES, tid);
   }
   __syncthreads();
 
   for (int j = 0; j < nblk; ++j) {
-    const int buf = j & 1;
     const int k0 = j * BN;
-    if (j + 1 < nblk) load_tile_regs(k0 + BN);
+    const char* ks = lds + (j & 1) * 2 * TILE64_BYTES;
+    const char* vs = ks + TILE64_BYTES;
+    if (j + 1 < nblk) {
+      kst.load(K, k0 + BN, d.nkv, tid);
+      vst.load(V, k0 + BN, d.nkv, tid);
+    }
 
     if (k0 < nvis_wave) {
-      const bf16_t* ks = &Ks[buf * K_TILE];
-      const bf16_t* vs = &Vs[buf * V_TILE];
       f32x16 s[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
+        s[t] = zero16();
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
-#pragma unroll
-        for (int st = 0; st < 8; ++st) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(ks + (32 * t + l32) * KLD + 16 * st + 8 * half);
-          s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[st], s[t], 0, 0, 0);
-        }
+        for (int st = 0; st < 8; ++st) s[t] = mma(read_nat(ks, fa, 32 * t, st), qf[st], s[t]);
       }
       // mask (only blocks that straddle the diagonal or the end of the tile)
       if (k0 + BN > nfull_wave) {
-        const int my_vis = (q_row < d.nq) ? vis_count(q_row) : 0;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -200,17 +149,16 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
 
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const bf16x8 pb = pack_bf16x8(s[u >> 1], 8 * (u & 1));
-        const int kbase = 32 * (u >> 1) + 16 * (u & 1);
+        const bf16x8 pb = pack8(s[u >> 1], 8 * (u & 1));
 #pragma unroll
-        for (int ht = 0; ht < 4; ++ht) {
-          const bf16_t* p_lo = vs + (kbase + v_row_off) * VLD + 32 * ht + v_col_off;
-          const bf16x8 a = lds_read_tr_pair(p_lo, p_lo + 8 * VLD);
-          o[ht] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[ht], 0, 0, 0);
-        }
+        for (int ht = 0; ht < 4; ++ht) o[ht] = mma(read_tr(vs, fa, 16 * u, ht), pb, o[ht]);
       }
     }
-    if (j + 1 < nblk) store_tile_lds(buf ^ 1);
+    if (j + 1 < nblk) {
+      char* nk = lds + ((j + 1) & 1) * 2 * TILE64_BYTES;
+      kst.store(nk, tid);
+      vst.store(nk + TILE64_BYTES, tid);
+    }
     __syncthreads();
   }
 
@@ -236,17 +184,16 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
 }  // namespace
 
 bool fwd_mfma_supported(const a2d_tile_desc& d) {
-  return d.dtype == A2D_BF16 && d.hdim == H;
+  return d.dtype == A2D_BF16 && d.hdim == mfma::H;
 }
 
 hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
                            float* O_part, float* m, float* l, hipStream_t s) {
-  constexpr size_t lds_bytes = sizeof(bf16_t) * 2 * (K_TILE + V_TILE);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_mfma_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
   if (e != hipSuccess) return e;
   dim3 grid((d.nq + BM - 1) / BM, d.heads), block(kThreads);
-  hipLaunchKernelGGL(fwd_mfma_kernel, grid, block, lds_bytes, s, d, (const bf16_t*)Q, (const bf16_t*)K,
+  hipLaunchKernelGGL(fwd_mfma_kernel, grid, block, kLdsBytes, s, d, (const bf16_t*)Q, (const bf16_t*)K,
                      (const bf16_t*)V, O_part, m, l);
   return hipGetLastError();
 }
