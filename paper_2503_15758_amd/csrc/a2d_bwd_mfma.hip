@@ -49,8 +49,9 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ delta, float* __restrict__ dK, float* __restrict__ dV) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  const int head = blockIdx.y;
-  const int k0 = blockIdx.x * BK;
+  int head, blk;
+  if (!xcd_map(d.heads, (d.nkv + BK - 1) / BK, head, blk)) return;
+  const int k0 = blk * BK;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int half = lane >> 5, l32 = lane & 31;
@@ -78,6 +79,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(
       vf[st] = __builtin_bit_cast(bf16x8, b);
     }
   }
+  wait_vmem_all();
   f32x16 dk[4], dv[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) { dk[t] = zero16(); dv[t] = zero16(); }
@@ -194,9 +196,10 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ delta, float* __restrict__ dQ) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  const int head = blockIdx.y;
-  const int qb = gridDim.x - 1 - blockIdx.x;      // heavy blocks first under a causal mask
-  const int q0 = qb * BK;
+  const int nqb = (d.nq + BK - 1) / BK;
+  int head, blk;
+  if (!xcd_map(d.heads, nqb, head, blk)) return;
+  const int q0 = (nqb - 1 - blk) * BK;            // heavy blocks first under a causal mask
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int half = lane >> 5, l32 = lane & 31;
@@ -227,6 +230,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(
     lse2 = (v == -INFINITY) ? INFINITY : v * kLog2e;
     del = delta[(int64_t)head * d.nq + q_row];
   }
+  wait_vmem_all();
 
   const int64_t rel = d.q_off - d.kv_off;
   auto vis_count = [&](int i) -> int {
@@ -315,7 +319,7 @@ hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K,
                           hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
   if (e != hipSuccess) return e;
   dim3 block(kThreads);
-  dim3 grid_kv((d.nkv + BK - 1) / BK, d.heads), grid_q((d.nq + BK - 1) / BK, d.heads);
+  dim3 grid_kv(xcd_grid(d.heads, (d.nkv + BK - 1) / BK)), grid_q(xcd_grid(d.heads, (d.nq + BK - 1) / BK));
   hipLaunchKernelGGL(bwd_dkdv_kernel, grid_kv, block, DKDV_LDS, s, d, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV);
   e = hipGetLastError();

@@ -15,8 +15,15 @@
 //                   may be permuted freely as long as A uses the same permutation),
 //                   A = V^T fragment read from the row-major V tile with the LDS
 //                   transpose read ds_read_b64_tr_b16.
-// LDS: K and V tiles double-buffered in the swizzled layout of a2d_mfma.hpp, which
-// keeps both the 128-bit K reads and the transposing V reads bank-conflict free.
+// LDS: K and V tiles double-buffered, rows padded (K: 272 B, V: 320 B) so that the
+// 128-bit K reads and the transposing V reads are bank-conflict free and every
+// fragment address is one per-lane base register plus an immediate.  Two workgroups
+// share a compute unit, so one's MFMAs overlap the other's softmax arithmetic.
+//
+// Rescaling is lazy: the exponent reference m_ref of a row follows its true running
+// maximum only when that has grown by more than 2^8 (in the exponent's units); the
+// true maximum is tracked separately and the outputs are brought to it at the end,
+// so (N, m, l) leave the kernel exactly as Eq. (3) defines them.
 #include "a2d_mfma.hpp"
 
 namespace a2d {
@@ -27,41 +34,130 @@ using namespace mfma;
 constexpr int BM = 128;            // query rows per workgroup
 constexpr int BN = 64;             // keys per step
 constexpr int kThreads = 256;
-constexpr int kLdsBytes = 4 * TILE64_BYTES;   // K, V x two buffers
+constexpr int KLD = 272;           // K tile row stride, bytes
+constexpr int VLD = 320;           // V tile row stride, bytes
+constexpr int K_BYTES = BN * KLD;
+constexpr int V_BYTES = BN * VLD;
+constexpr int BUF_BYTES = K_BYTES + V_BYTES;
+constexpr int kLdsBytes = 2 * BUF_BYTES;
+constexpr float kRescaleThreshold = 8.0f;   // log2 units
+
+struct FwdState {
+  f32x16 o[4];
+  float m_run;    // true running max of the raw dot products
+  float m_ref;    // reference the exponentials are taken against (raw units)
+  float l_run;    // this lane's share of the row sum, relative to m_ref
+};
+
+// One 64-key block for one wavefront.  k_rd / v_rd: per-lane LDS byte addresses of the
+// natural K fragment (t = 0, st = 0) and of the transposing V read (u = 0, ht = 0, low rows).
+template <bool MASK>
+__device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], unsigned k_rd, unsigned v_rd,
+                                          int k0, int my_vis, int half, float c) {
+  // K fragments are requested a full tile (8 MFMAs) ahead of their use
+  f32x16 s[2];
+  bf16x8 ka[8], kb[8];
+#pragma unroll
+  for (int x = 0; x < 8; ++x) ka[x] = lds_load_b128(k_rd + x * 32);
+  s[0] = zero16();
+  s[1] = zero16();
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    kb[x] = lds_load_b128(k_rd + 32 * KLD + x * 32);
+    s[0] = mma(ka[x], qf[x], s[0]);
+  }
+#pragma unroll
+  for (int x = 0; x < 8; ++x) s[1] = mma(kb[x], qf[x], s[1]);
+  if (MASK) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = k0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (key >= my_vis) s[t][r] = -INFINITY;
+      }
+  }
+  float mx = s[0][0];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float m_new = fmaxf(st.m_run, mx);
+  st.m_run = m_new;
+  // (m_new - m_ref) is +inf on the first visible block, NaN (-> false) while nothing is visible
+  const bool grow = (m_new - st.m_ref) * c > kRescaleThreshold;
+  if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+    asm volatile("" ::: "memory");   // keep this a real (rarely taken) branch: no if-conversion
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = fast_exp2((st.m_ref - m_use) * c);    // m_ref = -inf gives 0
+    st.m_ref = m_new;
+    st.l_run *= alpha;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.o[t][r] *= alpha;
+  }
+  const float mc = (st.m_ref == -INFINITY) ? 0.f : st.m_ref * c;
+  // V^T fragments of the first 32 keys are requested before the exponentials, those of the
+  // last 32 keys while the first half's MFMAs run
+  bf16x8 va[8], vb[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const unsigned a = v_rd + (i >> 2) * 16 * VLD + (i & 3) * 64;
+    va[i] = lds_load_tr(a, a + 8 * VLD);
+  }
+  float psum = 0.f;
+  bf16x8 pb[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float p = fast_exp2(fmaf(s[u >> 1][8 * (u & 1) + e], c, -mc));
+      psum += p;
+      pb[u][e] = (bf16_t)p;
+    }
+  st.l_run += psum;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const unsigned a = v_rd + (2 + (i >> 2)) * 16 * VLD + (i & 3) * 64;
+    vb[i] = lds_load_tr(a, a + 8 * VLD);
+    st.o[i & 3] = mma(va[i], pb[i >> 2], st.o[i & 3]);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) st.o[i & 3] = mma(vb[i], pb[2 + (i >> 2)], st.o[i & 3]);
+}
 
 __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
     a2d_tile_desc d, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, float* __restrict__ O_part, float* __restrict__ m_out,
     float* __restrict__ l_out) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  // [buf] K tile at buf * 2 * TILE64_BYTES, V tile right after it
+  // [buf]{ K tile (BN x KLD), V tile (BN x VLD) }
+  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
-  const int head = blockIdx.y;
+  const int nqb = (d.nq + BM - 1) / BM;
+  int head, blk;
+  if (!xcd_map(d.heads, nqb, head, blk)) return;
   // heavy (late) query blocks first: under a causal mask they walk more key blocks
-  const int qb = gridDim.x - 1 - blockIdx.x;
-  const int q0 = qb * BM;
+  const int q0 = (nqb - 1 - blk) * BM;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int half = lane >> 5, l32 = lane & 31;
   Q += (int64_t)head * d.nq * H;
   K += (int64_t)head * d.nkv * H;
   V += (int64_t)head * d.nkv * H;
-  FragAddr fa;
-  fa.init(lane);
 
-  // ---- Q^T fragments: lane holds query row (l32), h = 16*step + 8*half + 0..7
+  // ---- Q^T fragments: lane holds query row (l32), h = 16*step + 8*half + 0..7.
+  // Rows beyond nq re-read the last row (their results are never stored).
   const int q_row = q0 + wave * 32 + l32;
   bf16x8 qf[8];
   {
-    const bool ok = q_row < d.nq;
-    const bf16_t* qp = Q + (int64_t)(ok ? q_row : 0) * H + 8 * half;
+    const bf16_t* qp = Q + (int64_t)min(q_row, d.nq - 1) * H + 8 * half;
 #pragma unroll
-    for (int st = 0; st < 8; ++st) {
-      u32x4 w = *reinterpret_cast<const u32x4*>(qp + 16 * st);
-      if (!ok) w = u32x4{0, 0, 0, 0};
-      qf[st] = __builtin_bit_cast(bf16x8, w);
-    }
+    for (int x = 0; x < 8; ++x) qf[x] = *reinterpret_cast<const bf16x8*>(qp + 16 * x);
   }
+  wait_vmem_all();
 
   // ---- visibility bounds in local key indices: query i sees key r iff r <= i + rel
   const int64_t rel = d.q_off - d.kv_off;
@@ -72,98 +168,72 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
   };
   const int blk_last = min(q0 + BM, d.nq) - 1;
   const int nblk = (vis_count(blk_last) + BN - 1) / BN;
-  const int w_first = q0 + wave * 32;
-  const int w_last = min(w_first + 31, d.nq - 1);
-  const int nvis_wave = (w_first < d.nq) ? vis_count(w_last) : 0;     // keys any row of the wave sees
-  const int nfull_wave = (w_first < d.nq) ? vis_count(w_first) : 0;   // keys every row of the wave sees
-  const int my_vis = (q_row < d.nq) ? vis_count(q_row) : 0;
+  const int w_first = min(q0 + wave * 32, d.nq - 1);
+  const int w_last = min(q0 + wave * 32 + 31, d.nq - 1);
+  const int nvis_wave = vis_count(w_last);      // keys any row of the wave sees
+  const int nfull_wave = vis_count(w_first);    // keys every row of the wave sees
+  const int my_vis = vis_count(min(q_row, d.nq - 1));
 
-  f32x16 o[4];
+  FwdState st;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) o[t] = zero16();
-  float m_run = -INFINITY;   // running max of the RAW dot products (scale applied on output)
-  float l_run = 0.f;         // this lane's share of the running row sum
+  for (int t = 0; t < 4; ++t) st.o[t] = zero16();
+  st.m_run = -INFINITY;
+  st.m_ref = -INFINITY;
+  st.l_run = 0.f;
   const float c = d.scale * kLog2e;
 
-  Stage64 kst, vst;
+  // ---- staging: thread moves the 16-byte chunk (tid & 15) of rows (tid >> 4) + 16 p.
+  // Rows beyond nkv re-read the last row: finite values, masked out of the scores.
+  const int ld_row = tid >> 4, ld_chunk = tid & 15;
+  const int k_wr = ld_row * KLD + ld_chunk * 16;
+  const int v_wr = K_BYTES + ld_row * VLD + ld_chunk * 16;
+  u32x4 kreg[4], vreg[4];
+  auto load_tile = [&](int k0) {
+    const char* kb = reinterpret_cast<const char*>(K + (int64_t)k0 * H);   // wave-uniform bases
+    const char* vb = reinterpret_cast<const char*>(V + (int64_t)k0 * H);
+    const int last = d.nkv - 1 - k0;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const unsigned off = (unsigned)(min(ld_row + 16 * p, last) * (H * 2) + ld_chunk * 16);
+      kreg[p] = *reinterpret_cast<const u32x4*>(kb + off);
+      vreg[p] = *reinterpret_cast<const u32x4*>(vb + off);
+    }
+  };
+  auto store_tile = [&](int boff) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      *reinterpret_cast<u32x4*>(lds + boff + k_wr + p * 16 * KLD) = kreg[p];
+      *reinterpret_cast<u32x4*>(lds + boff + v_wr + p * 16 * VLD) = vreg[p];
+    }
+  };
+  // fragment read bases (buffer 0)
+  const unsigned k_rd0 = lds_base + l32 * KLD + half * 16;
+  const int g16 = lane >> 4, j16 = lane & 15;
+  const unsigned v_rd0 =
+      lds_base + K_BYTES + (4 * (g16 >> 1) + (j16 >> 2)) * VLD + (16 * (g16 & 1) + 4 * (j16 & 3)) * 2;
+
   if (nblk > 0) {
-    kst.load(K, 0, d.nkv, tid);
-    vst.load(V, 0, d.nkv, tid);
-    kst.store(lds, tid);
-    vst.store(lds + TILE64_BYTES, tid);
+    load_tile(0);
+    store_tile(0);
   }
   __syncthreads();
 
   for (int j = 0; j < nblk; ++j) {
     const int k0 = j * BN;
-    const char* ks = lds + (j & 1) * 2 * TILE64_BYTES;
-    const char* vs = ks + TILE64_BYTES;
-    if (j + 1 < nblk) {
-      kst.load(K, k0 + BN, d.nkv, tid);
-      vst.load(V, k0 + BN, d.nkv, tid);
-    }
-
+    const int boff = (j & 1) * BUF_BYTES;
+    const bool more = j + 1 < nblk;
+    if (more) load_tile(k0 + BN);
     if (k0 < nvis_wave) {
-      f32x16 s[2];
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        s[t] = zero16();
-#pragma unroll
-        for (int st = 0; st < 8; ++st) s[t] = mma(read_nat(ks, fa, 32 * t, st), qf[st], s[t]);
-      }
-      // mask (only blocks that straddle the diagonal or the end of the tile)
-      if (k0 + BN > nfull_wave) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = k0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (key >= my_vis) s[t][r] = -INFINITY;
-          }
-      }
-      float mx = -INFINITY;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = fast_exp2((m_run - m_use) * c);
-      const float mc = m_use * c;
-      float psum = 0.f;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = fast_exp2(fmaf(s[t][r], c, -mc));
-          s[t][r] = p;
-          psum += p;
-        }
-      l_run = fmaf(l_run, alpha, psum);
-      m_run = m_new;
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
-
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const bf16x8 pb = pack8(s[u >> 1], 8 * (u & 1));
-#pragma unroll
-        for (int ht = 0; ht < 4; ++ht) o[ht] = mma(read_tr(vs, fa, 16 * u, ht), pb, o[ht]);
-      }
+      if (k0 + BN > nfull_wave) fwd_block<true>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
+      else fwd_block<false>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
     }
-    if (j + 1 < nblk) {
-      char* nk = lds + ((j + 1) & 1) * 2 * TILE64_BYTES;
-      kst.store(nk, tid);
-      vst.store(nk + TILE64_BYTES, tid);
-    }
+    if (more) store_tile(BUF_BYTES - boff);
     __syncthreads();
   }
 
-  // ---- epilogue: N (unnormalised), m (scaled units), l
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  // ---- epilogue: bring N and l to the true maximum, store N, m (scaled units), l
+  const float f = (st.m_run == -INFINITY) ? 0.f : fast_exp2((st.m_ref - st.m_run) * c);
+  const float l_tot = (st.l_run + __shfl_xor(st.l_run, 32, 64)) * f;
   if (q_row < d.nq) {
     const int64_t row = (int64_t)head * d.nq + q_row;
     float* op = O_part + row * H + 4 * half;
@@ -171,11 +241,12 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
     for (int ht = 0; ht < 4; ++ht)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        f32x4 v = {o[ht][4 * g], o[ht][4 * g + 1], o[ht][4 * g + 2], o[ht][4 * g + 3]};
+        f32x4 v = {st.o[ht][4 * g] * f, st.o[ht][4 * g + 1] * f, st.o[ht][4 * g + 2] * f,
+                   st.o[ht][4 * g + 3] * f};
         *reinterpret_cast<f32x4*>(op + 32 * ht + 8 * g) = v;
       }
     if (half == 0) {
-      m_out[row] = m_run * d.scale;   // -inf stays -inf (scale > 0)
+      m_out[row] = st.m_run * d.scale;   // -inf stays -inf (scale > 0)
       l_out[row] = l_tot;
     }
   }
@@ -192,7 +263,7 @@ hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K,
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_mfma_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
   if (e != hipSuccess) return e;
-  dim3 grid((d.nq + BM - 1) / BM, d.heads), block(kThreads);
+  dim3 grid(xcd_grid(d.heads, (d.nq + BM - 1) / BM)), block(kThreads);
   hipLaunchKernelGGL(fwd_mfma_kernel, grid, block, kLdsBytes, s, d, (const bf16_t*)Q, (const bf16_t*)K,
                      (const bf16_t*)V, O_part, m, l);
   return hipGetLastError();

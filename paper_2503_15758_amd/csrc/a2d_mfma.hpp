@@ -46,6 +46,23 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& s, int base) {
   return r;
 }
 
+// s_waitcnt vmcnt(0) only (gfx9 encoding: lgkmcnt and expcnt fields left at their maxima).
+// Placed after a prologue's one-off global loads it tells the compiler's wait-count insertion that
+// those registers are complete, so that uses inside the main loop do not have to be guarded by
+// waits that would also cover the loop's own freshly issued prefetches.
+__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// LDS reads by byte address (address space 3)
+__device__ __forceinline__ bf16x8 lds_load_b128(unsigned addr) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>((uintptr_t)addr);
+}
+__device__ __forceinline__ bf16x8 lds_load_tr(unsigned addr_lo, unsigned addr_hi) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)addr_lo);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)addr_hi);
+  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
 // Per-lane constants of the fragment reads; rows are relative to a row base that is a
 // multiple of 16 (so the swizzle term depends on the lane only).
 struct FragAddr {
@@ -103,6 +120,23 @@ struct Stage64 {
 };
 
 constexpr int TILE64_BYTES = 64 * ROW_BYTES;
+
+// XCD-aware work mapping.  MI355X has 8 XCDs, each with its own L2, and hands consecutive
+// workgroup ids to consecutive XCDs (id % 8).  All blocks of one head read the same K / V (or
+// Q / dO) rows, so they are placed on ONE XCD, back to back in its dispatch order: the k-th
+// workgroup of XCD x (id = 8 k + x) works on head 8 * (k / nblocks) + x, block k % nblocks.
+// Grid size: 8 * ceil(heads / 8) * nblocks; workgroups whose head is out of range exit.
+constexpr int kXcds = 8;
+__host__ __device__ inline int xcd_grid(int heads, int nblocks) {
+  return kXcds * ((heads + kXcds - 1) / kXcds) * nblocks;
+}
+__device__ __forceinline__ bool xcd_map(int heads, int nblocks, int& head, int& block) {
+  const int id = blockIdx.x;
+  const int x = id % kXcds, k = id / kXcds;
+  head = kXcds * (k / nblocks) + x;
+  block = k % nblocks;
+  return head < heads;
+}
 
 }  // namespace mfma
 }  // namespace a2d
