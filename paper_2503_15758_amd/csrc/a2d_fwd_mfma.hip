@@ -9,8 +9,8 @@
 // needed between them (v_mfma_f32_32x32x16_bf16, D = A * B, A: 32 x 16, B: 16 x 32):
 //   S^T = K * Q^T : A = K fragment (LDS, 128-bit reads), B = Q^T fragment (registers,
 //                   loaded once).  In D a lane holds 16 keys of ONE query column, so
-//                   row max / row sum are in-lane reductions plus one exchange with
-//                   lane ^ 32.
+//                   row max / row sum are in-lane reductions; the two lanes of a row
+//                   (lane, lane ^ 32) are combined only when needed.
 //   O^T += V^T * P^T : B = P^T is exactly the D layout of S^T (the contraction index
 //                   may be permuted freely as long as A uses the same permutation),
 //                   A = V^T fragment read from the row-major V tile with the LDS
@@ -20,10 +20,12 @@
 // fragment address is one per-lane base register plus an immediate.  Two workgroups
 // share a compute unit, so one's MFMAs overlap the other's softmax arithmetic.
 //
-// Rescaling is lazy: the exponent reference m_ref of a row follows its true running
-// maximum only when that has grown by more than 2^8 (in the exponent's units); the
-// true maximum is tracked separately and the outputs are brought to it at the end,
-// so (N, m, l) leave the kernel exactly as Eq. (3) defines them.
+// Rescaling is lazy: a row's exponent reference m_ref follows its running maximum
+// only when a score exceeds it by more than 2^8 (in the exponent's units) - a rare,
+// wave-uniform branch, and the only place where the two lanes of a row talk to each
+// other.  Each lane tracks the true maximum of its own scores; at the end the halves
+// are combined and N, l are brought to the true row maximum, so (N, m, l) leave the
+// kernel exactly as Eq. (3) defines them.
 #include "a2d_mfma.hpp"
 
 namespace a2d {
@@ -44,8 +46,8 @@ constexpr float kRescaleThreshold = 8.0f;   // log2 units
 
 struct FwdState {
   f32x16 o[4];
-  float m_run;    // true running max of the raw dot products
-  float m_ref;    // reference the exponentials are taken against (raw units)
+  float m_lane;   // true running max of this lane's raw dot products
+  float m_ref;    // reference the exponentials are taken against (raw units, same in both lanes of a row)
   float l_run;    // this lane's share of the row sum, relative to m_ref
 };
 
@@ -82,16 +84,15 @@ __device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], u
   for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-  const float m_new = fmaxf(st.m_run, mx);
-  st.m_run = m_new;
-  // (m_new - m_ref) is +inf on the first visible block, NaN (-> false) while nothing is visible
-  const bool grow = (m_new - st.m_ref) * c > kRescaleThreshold;
+  st.m_lane = fmaxf(st.m_lane, mx);
+  // (m_lane - m_ref) is +inf on the first visible block, NaN (-> false) while nothing is visible
+  const bool grow = (st.m_lane - st.m_ref) * c > kRescaleThreshold;
   if (__builtin_amdgcn_ballot_w64(grow) != 0) {
     asm volatile("" ::: "memory");   // keep this a real (rarely taken) branch: no if-conversion
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float m_row = fmaxf(st.m_lane, __shfl_xor(st.m_lane, 32, 64));
+    const float m_use = (m_row == -INFINITY) ? 0.f : m_row;
     const float alpha = fast_exp2((st.m_ref - m_use) * c);    // m_ref = -inf gives 0
-    st.m_ref = m_new;
+    st.m_ref = m_row;
     st.l_run *= alpha;
 #pragma unroll
     for (int t = 0; t < 4; ++t)
@@ -177,7 +178,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
   FwdState st;
 #pragma unroll
   for (int t = 0; t < 4; ++t) st.o[t] = zero16();
-  st.m_run = -INFINITY;
+  st.m_lane = -INFINITY;
   st.m_ref = -INFINITY;
   st.l_run = 0.f;
   const float c = d.scale * kLog2e;
@@ -189,8 +190,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
   const int v_wr = K_BYTES + ld_row * VLD + ld_chunk * 16;
   u32x4 kreg[4], vreg[4];
   auto load_tile = [&](int k0) {
-    const char* kb = reinterpret_cast<const char*>(K + (int64_t)k0 * H);   // wave-uniform bases
-    const char* vb = reinterpret_cast<const char*>(V + (int64_t)k0 * H);
+    const char* kb = uniform_ptr(reinterpret_cast<const char*>(K + (int64_t)k0 * H));   // scalar bases
+    const char* vb = uniform_ptr(reinterpret_cast<const char*>(V + (int64_t)k0 * H));
     const int last = d.nkv - 1 - k0;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
@@ -231,8 +232,9 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
     __syncthreads();
   }
 
-  // ---- epilogue: bring N and l to the true maximum, store N, m (scaled units), l
-  const float f = (st.m_run == -INFINITY) ? 0.f : fast_exp2((st.m_ref - st.m_run) * c);
+  // ---- epilogue: bring N and l to the true row maximum, store N, m (scaled units), l
+  const float m_row = fmaxf(st.m_lane, __shfl_xor(st.m_lane, 32, 64));
+  const float f = (m_row == -INFINITY) ? 0.f : fast_exp2((st.m_ref - m_row) * c);
   const float l_tot = (st.l_run + __shfl_xor(st.l_run, 32, 64)) * f;
   if (q_row < d.nq) {
     const int64_t row = (int64_t)head * d.nq + q_row;
@@ -246,7 +248,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
         *reinterpret_cast<f32x4*>(op + 32 * ht + 8 * g) = v;
       }
     if (half == 0) {
-      m_out[row] = st.m_run * d.scale;   // -inf stays -inf (scale > 0)
+      m_out[row] = m_row * d.scale;      // -inf stays -inf (scale > 0)
       l_out[row] = l_tot;
     }
   }
