@@ -4,27 +4,29 @@
 //
 // Two kernels, so that every output has exactly one writer and no atomics are needed
 // (bitwise reproducible results):
-//   bwd_dkdv_kernel  owns key rows.   Workgroup = 128 keys (32 per wavefront, K and V
-//                    fragments resident in registers); walks the query blocks, 64 rows
-//                    per step, staged through LDS together with dO, lse and delta.
-//                    S = Q K^T and dP = dO V^T leave a lane holding ONE key column, so
-//                    P and dS feed dV^T += dO^T P and dK^T += Q^T dS directly as B
-//                    operands; dO^T / Q^T come from the LDS transpose read.
-//   bwd_dq_kernel    owns query rows. Workgroup = 128 queries (32 per wavefront, Q and
-//                    dO fragments in registers); walks the key blocks, 64 keys per step.
-//                    S^T = K Q^T and dP^T = V dO^T leave a lane holding ONE query
-//                    column; dQ^T += K^T dS^T with K^T from the LDS transpose read.
-// The score recomputation is done in both kernels (7 contractions for 5 counted ones).
+//   bwd_dkdv_kernel  owns key rows.  Workgroup = 4 wavefronts = 128 keys (32 per
+//                    wavefront, K and V fragments resident in registers); walks
+//                    the query blocks, 64 rows per step, staged through LDS together with
+//                    dO, lse and delta.  S = Q K^T and dP = dO V^T leave a lane holding
+//                    ONE key column, so P and dS feed dV^T += dO^T P and dK^T += Q^T dS
+//                    directly as B operands; dO^T / Q^T come from the LDS transpose read.
+//   bwd_dq_kernel    owns query rows.  Workgroup = 4 wavefronts = 128 queries (32 per
+//                    wavefront, Q and dO fragments in registers), two workgroups per
+//                    compute unit; walks the key blocks, 64 keys per step.  S^T = K Q^T
+//                    and dP^T = V dO^T leave a lane holding ONE query column;
+//                    dQ^T += K^T dS^T with K^T from the LDS transpose read.
+// The dK/dV kernel needs more than 256 VGPRs (128 of accumulators alone) and runs one
+// wavefront per SIMD; the dQ kernel keeps two, so one's MFMAs overlap the other's
+// exponentials (a single wavefront cannot overlap the two).  In the dK/dV kernel the tiles
+// read both ways live in the "dual" LDS layout of a2d_mfma.hpp (every fragment address is a
+// per-lane base plus an immediate); the dQ kernel uses the XOR-swizzled layout.  The score recomputation is done in both kernels (7 contractions
+// for 5 counted ones).
 #include "a2d_mfma.hpp"
 
 namespace a2d {
 namespace {
 
 using namespace mfma;
-
-constexpr int kThreads = 256;
-constexpr int BK = 128;   // keys per workgroup (dkdv) / queries per workgroup (dq)
-constexpr int BS = 64;    // rows of the streamed operand per step
 
 // stores a transposed accumulator (lane = one output row, registers = 4-column groups)
 __device__ __forceinline__ void store_acc_t(float* __restrict__ out_row, const f32x16 (&acc)[4],
@@ -39,155 +41,225 @@ __device__ __forceinline__ void store_acc_t(float* __restrict__ out_row, const f
     }
 }
 
-// ------------------------------------------------------------------ dK, dV
-// LDS: [buf]{ Q tile 16 KB, dO tile 16 KB, lse*log2e [64] f32, delta [64] f32 }
-constexpr int DKDV_BUF = 2 * TILE64_BYTES + 2 * BS * 4;
-constexpr int DKDV_LDS = 2 * DKDV_BUF;
+__device__ __forceinline__ f32x4 lds_load_f32x4(unsigned addr) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>((uintptr_t)addr);
+}
 
-__global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(
+// natural fragment x of a dual tile (rows RB .. RB+31 relative to the per-lane bases in `a`)
+template <int X>
+__device__ __forceinline__ bf16x8 dual_nat(const DualAddr& a, int extra) {
+  return lds_load_b128(((X & 1) ? a.nat_o : a.nat_e) + 64 * (X >> 1) + extra);
+}
+
+// ------------------------------------------------------------------ dK, dV
+constexpr int DK_THREADS = 256;
+constexpr int DK_KEYS = 128;      // keys per workgroup
+constexpr int BQ = 64;            // query rows per step
+constexpr int VT_LD = 272;        // V tile row stride (natural reads only)
+// LDS: [buf]{ Q tile, dO tile } (dual layout) | [buf]{ lse*log2e [64], delta [64] }
+constexpr int DK_BUF = 2 * DUAL64_BYTES;
+constexpr int DK_STAT = 2 * DK_BUF;
+constexpr int DK_LDS = DK_STAT + 2 * 2 * BQ * 4;
+
+struct DkCtx {
+  f32x16 dk[4], dv[4];
+  bf16x8 kf[8], vf[8];  // K^T / V^T fragments of this wavefront's 32 keys
+  DualAddr qa;          // Q tile of the current buffer; the dO tile is DUAL64_BYTES further
+  unsigned stat;        // lse / delta rows of the current buffer, offset by 16 * half
+  float c;
+  int my_first;         // first local query row that sees this lane's key
+  int half;
+};
+
+// One 32-query x 32-key piece; SUB selects the half of the 64-row step.
+// A single wavefront per SIMD runs this kernel, so nothing hides LDS latency but the
+// instruction order: every fragment is requested about four MFMA pairs before its use
+// (rolling prefetch; the LDS wait counter only tracks 15 operations in flight).
+template <int SUB, bool MASK>
+__device__ __forceinline__ void dkdv_piece(DkCtx& cx, int qs0) {
+  constexpr int RB = SUB * 32 * DUAL_LD;
+  constexpr int GO = DUAL64_BYTES;            // dO tile behind the Q tile
+  bf16x8 qn[4], gn[4];                        // ring of natural fragments, four steps deep
+#define A2D_LD1(X) qn[(X) & 3] = dual_nat<X>(cx.qa, RB); gn[(X) & 3] = dual_nat<X>(cx.qa, RB + GO);
+#define A2D_SDP(X) s = mma(qn[(X) & 3], cx.kf[X], s); dp = mma(gn[(X) & 3], cx.vf[X], dp);
+  A2D_LD1(0) A2D_LD1(1) A2D_LD1(2) A2D_LD1(3)
+  f32x16 s = zero16(), dp = zero16();
+  A2D_SDP(0) A2D_LD1(4)
+  A2D_SDP(1) A2D_LD1(5)
+  A2D_SDP(2) A2D_LD1(6)
+  A2D_SDP(3) A2D_LD1(7)
+  // transposed fragments of the first 16 query rows: on their way during the exponentials
+  bf16x8 gt[4], qt[4];
+#define A2D_LD2(HT, U)                                                                                   \
+  gt[HT] = lds_load_tr(cx.qa.tr_lo + GO + RB + (U) * 16 * DUAL_LD + 64 * (HT),                            \
+                       cx.qa.tr_hi + GO + RB + (U) * 16 * DUAL_LD + 64 * (HT));                           \
+  qt[HT] = lds_load_tr(cx.qa.tr_lo + RB + (U) * 16 * DUAL_LD + 64 * (HT),                                 \
+                       cx.qa.tr_hi + RB + (U) * 16 * DUAL_LD + 64 * (HT));
+  A2D_SDP(4) A2D_LD2(0, 0)
+  A2D_SDP(5) A2D_LD2(1, 0)
+  A2D_SDP(6) A2D_LD2(2, 0)
+  A2D_SDP(7) A2D_LD2(3, 0)
+#undef A2D_SDP
+#undef A2D_LD1
+  // register r <-> query qs0 + 8*(r>>2) + 4*half + (r&3); lane <-> key
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const f32x4 l4 = lds_load_f32x4(cx.stat + (SUB * 32 + 8 * g) * 4);
+    const f32x4 d4 = lds_load_f32x4(cx.stat + (BQ + SUB * 32 + 8 * g) * 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int r = 4 * g + e;
+      float p = fast_exp2(fmaf(s[r], cx.c, -l4[e]));
+      if (MASK && (qs0 + 8 * g + 4 * cx.half + e < cx.my_first)) p = 0.f;
+      s[r] = p;
+      dp[r] = p * (dp[r] - d4[e]);
+    }
+  }
+  bf16x8 pb[2], dsb[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) { pb[u] = pack8(s, 8 * u); dsb[u] = pack8(dp, 8 * u); }
+#define A2D_DVDK(HT, U) cx.dv[HT] = mma(gt[HT], pb[U], cx.dv[HT]); cx.dk[HT] = mma(qt[HT], dsb[U], cx.dk[HT]);
+  A2D_DVDK(0, 0) A2D_LD2(0, 1)
+  A2D_DVDK(1, 0) A2D_LD2(1, 1)
+  A2D_DVDK(2, 0) A2D_LD2(2, 1)
+  A2D_DVDK(3, 0) A2D_LD2(3, 1)
+  A2D_DVDK(0, 1) A2D_DVDK(1, 1) A2D_DVDK(2, 1) A2D_DVDK(3, 1)
+#undef A2D_DVDK
+#undef A2D_LD2
+}
+
+__global__ __launch_bounds__(DK_THREADS, 1) void bwd_dkdv_kernel(
     a2d_tile_desc d, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ delta, float* __restrict__ dK, float* __restrict__ dV) {
-  extern __shared__ __attribute__((aligned(16))) char lds[];
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
   int head, blk;
-  if (!xcd_map(d.heads, (d.nkv + BK - 1) / BK, head, blk)) return;
-  const int k0 = blk * BK;
+  if (!xcd_map(d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS, head, blk)) return;
+  const int k0 = blk * DK_KEYS;
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
-  const int half = lane >> 5, l32 = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int l32 = lane & 31;
   Q += (int64_t)head * d.nq * H;
   dO += (int64_t)head * d.nq * H;
   K += (int64_t)head * d.nkv * H;
   V += (int64_t)head * d.nkv * H;
   lse += (int64_t)head * d.nq;
   delta += (int64_t)head * d.nq;
-  FragAddr fa;
-  fa.init(lane);
 
-  // ---- K^T / V^T B fragments of this wave's 32 keys: lane = key, h = 16 st + 8 half + 0..7
+  DkCtx cx;
+  cx.half = lane >> 5;
+  cx.c = d.scale * kLog2e;
+  // ---- K^T / V^T B fragments of this wave's 32 keys: lane = key, h = 16 x + 8 half + 0..7.
+  // Keys beyond nkv re-read the last key; the mask zeroes their probabilities.
   const int key = k0 + wave * 32 + l32;
-  bf16x8 kf[8], vf[8];
   {
-    const bool ok = key < d.nkv;
-    const int64_t off = (int64_t)(ok ? key : 0) * H + 8 * half;
+    const int64_t off = (int64_t)min(key, d.nkv - 1) * H + 8 * cx.half;
 #pragma unroll
-    for (int st = 0; st < 8; ++st) {
-      u32x4 a = *reinterpret_cast<const u32x4*>(K + off + 16 * st);
-      u32x4 b = *reinterpret_cast<const u32x4*>(V + off + 16 * st);
-      if (!ok) { a = u32x4{0, 0, 0, 0}; b = u32x4{0, 0, 0, 0}; }
-      kf[st] = __builtin_bit_cast(bf16x8, a);
-      vf[st] = __builtin_bit_cast(bf16x8, b);
+    for (int x = 0; x < 8; ++x) {
+      cx.kf[x] = *reinterpret_cast<const bf16x8*>(K + off + 16 * x);
+      cx.vf[x] = *reinterpret_cast<const bf16x8*>(V + off + 16 * x);
     }
   }
   wait_vmem_all();
-  f32x16 dk[4], dv[4];
 #pragma unroll
-  for (int t = 0; t < 4; ++t) { dk[t] = zero16(); dv[t] = zero16(); }
+  for (int t = 0; t < 4; ++t) { cx.dk[t] = zero16(); cx.dv[t] = zero16(); }
 
   // query i sees key r iff i >= r - rel  (local indices), rel = q_off - kv_off
   const int64_t rel = d.q_off - d.kv_off;
-  int i_begin = 0;                      // first query row that sees key k0 (the block's first key)
-  if (d.causal) {
-    const int64_t f = (int64_t)k0 - rel;
-    i_begin = f <= 0 ? 0 : (f >= d.nq ? d.nq : (int)f);
-  }
-  const int i_start = (i_begin / BS) * BS;
-  const int nsteps = (d.nq - i_start + BS - 1) / BS;     // 0 if no row sees the block
+  auto first_row = [&](int r) -> int {          // first local query row that sees local key r
+    if (!d.causal) return 0;
+    const int64_t f = (int64_t)r - rel;
+    return f <= 0 ? 0 : (f >= d.nq ? d.nq : (int)f);
+  };
+  const int i_start = (first_row(k0) / BQ) * BQ;
+  const int nsteps = (d.nq - i_start + BQ - 1) / BQ;
   const int wk_first = k0 + wave * 32, wk_last = wk_first + 31;
-  // first query row seeing this lane's key (rows below it are masked); nq if the key is padding
-  int my_first = 0;
-  if (d.causal) {
-    const int64_t f = (int64_t)key - rel;
-    my_first = f <= 0 ? 0 : (f >= d.nq ? d.nq : (int)f);
-  }
-  if (key >= d.nkv) my_first = d.nq;
-  const float c = d.scale * kLog2e;
+  cx.my_first = (key < d.nkv) ? first_row(key) : d.nq;       // padding keys see nothing
+  const int w_any = first_row(wk_first);                      // rows below see none of the wave's keys
+  const int w_all = (wk_last < d.nkv) ? first_row(wk_last) : d.nq;   // rows from here see all of them
 
-  Stage64 qst, gst;
+  cx.qa.init(lane, lds_base);
+  cx.stat = lds_base + DK_STAT + 16 * cx.half;
+
+  // ---- staging of a 64-row step: thread moves chunk (tid & 15) of rows (tid >> 4) + 16 p
+  constexpr int ST_ROWS = DK_THREADS / 16, ST_N = BQ / ST_ROWS;
+  const int st_row = tid >> 4, st_ch = tid & 15;
+  u32x4 qreg[ST_N], greg[ST_N];
   float stat = 0.f;
+  bool stat_ok = false;
   auto load_step = [&](int i0) {
-    qst.load(Q, i0, d.nq, tid);
-    gst.load(dO, i0, d.nq, tid);
-    if (tid < BS) {
-      const int i = i0 + tid;
-      const float v = (i < d.nq) ? lse[i] : INFINITY;
-      stat = (v == -INFINITY) ? INFINITY : v * kLog2e;     // +inf makes exp2(s - stat) = 0
-    } else if (tid < 2 * BS) {
-      const int i = i0 + tid - BS;
-      stat = (i < d.nq) ? delta[i] : 0.f;
+    const char* qb = uniform_ptr(reinterpret_cast<const char*>(Q + (int64_t)i0 * H));
+    const char* gb = uniform_ptr(reinterpret_cast<const char*>(dO + (int64_t)i0 * H));
+    const int last = d.nq - 1 - i0;
+#pragma unroll
+    for (int p = 0; p < ST_N; ++p) {
+      const unsigned off = (unsigned)(min(st_row + ST_ROWS * p, last) * (H * 2) + st_ch * 16);
+      qreg[p] = *reinterpret_cast<const u32x4*>(qb + off);
+      greg[p] = *reinterpret_cast<const u32x4*>(gb + off);
+    }
+    // raw loads only: converting here would make the wave wait for everything just issued
+    if (tid < 2 * BQ) {
+      const int i = min(i0 + (tid & (BQ - 1)), d.nq - 1);
+      stat = (tid < BQ) ? lse[i] : delta[i];
+      stat_ok = (i0 + (tid & (BQ - 1))) < d.nq;
     }
   };
-  auto store_step = [&](char* buf) {
-    qst.store(buf, tid);
-    gst.store(buf + TILE64_BYTES, tid);
-    if (tid < 2 * BS) reinterpret_cast<float*>(buf + 2 * TILE64_BYTES)[tid] = stat;
+  auto store_step = [&](int buf) {
+    char* b = lds + buf * DK_BUF;
+#pragma unroll
+    for (int p = 0; p < ST_N; ++p) {
+      const int off = dual_store_off(st_row + ST_ROWS * p, st_ch);
+      *reinterpret_cast<u32x4*>(b + off) = qreg[p];
+      *reinterpret_cast<u32x4*>(b + DUAL64_BYTES + off) = greg[p];
+    }
+    if (tid < 2 * BQ) {
+      float v = stat;
+      // rows beyond nq and rows with lse = -inf get +inf, which makes exp2(s - lse) = 0
+      if (tid < BQ) v = (!stat_ok || v == -INFINITY) ? INFINITY : v * kLog2e;
+      else v = stat_ok ? v : 0.f;
+      reinterpret_cast<float*>(lds + DK_STAT + buf * 2 * BQ * 4)[tid] = v;
+    }
   };
 
   if (nsteps > 0) {
     load_step(i_start);
-    store_step(lds);
+    store_step(0);
   }
   __syncthreads();
 
   for (int j = 0; j < nsteps; ++j) {
-    const int i0 = i_start + j * BS;
-    const char* qs = lds + (j & 1) * DKDV_BUF;
-    const char* gs = qs + TILE64_BYTES;
-    const float* lse_s = reinterpret_cast<const float*>(qs + 2 * TILE64_BYTES);
-    const float* del_s = lse_s + BS;
-    if (j + 1 < nsteps) load_step(i0 + BS);
-
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      const int qs0 = i0 + 32 * sub;                          // first query row of the sub-block
-      // skip when no (query, key) pair of this 32 x 32 piece is visible
-      const bool any_vis = !d.causal || ((int64_t)qs0 + 31 + rel >= wk_first);
-      if (qs0 < d.nq && any_vis) {
-        f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-        for (int st = 0; st < 8; ++st) {
-          s = mma(read_nat(qs, fa, 32 * sub, st), kf[st], s);
-          dp = mma(read_nat(gs, fa, 32 * sub, st), vf[st], dp);
-        }
-        // register r <-> query qs0 + 8*(r>>2) + 4*half + (r&3); lane <-> key
-        const bool need_mask = (wk_last >= d.nkv) || (d.causal && ((int64_t)qs0 + rel < wk_last));
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + 32 * sub + 8 * g + 4 * half);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(del_s + 32 * sub + 8 * g + 4 * half);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = 4 * g + e;
-            float p = fast_exp2(fmaf(s[r], c, -l4[e]));
-            if (need_mask && (qs0 + 8 * g + 4 * half + e < my_first)) p = 0.f;
-            s[r] = p;
-            dp[r] = p * (dp[r] - d4[e]);
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const bf16x8 pb = pack8(s, 8 * u);
-          const bf16x8 dsb = pack8(dp, 8 * u);
-#pragma unroll
-          for (int ht = 0; ht < 4; ++ht) {
-            dv[ht] = mma(read_tr(gs, fa, 32 * sub + 16 * u, ht), pb, dv[ht]);
-            dk[ht] = mma(read_tr(qs, fa, 32 * sub + 16 * u, ht), dsb, dk[ht]);
-          }
-        }
-      }
+    const int i0 = i_start + j * BQ;
+    const bool more = j + 1 < nsteps;
+    if (more) load_step(i0 + BQ);
+    // piece (SUB): rows i0 + 32 SUB .. +31.  Skipped when no row of it sees any key of the wave
+    // or it lies beyond nq; masked unless every row sees every key.
+    if (i0 + 31 >= w_any && i0 < d.nq) {
+      if (i0 >= w_all && i0 + 32 <= d.nq) dkdv_piece<0, false>(cx, i0);
+      else dkdv_piece<0, true>(cx, i0);
     }
-    if (j + 1 < nsteps) store_step(lds + ((j + 1) & 1) * DKDV_BUF);
+    if (i0 + 63 >= w_any && i0 + 32 < d.nq) {
+      if (i0 + 32 >= w_all && i0 + 64 <= d.nq) dkdv_piece<1, false>(cx, i0 + 32);
+      else dkdv_piece<1, true>(cx, i0 + 32);
+    }
+    if (more) store_step((j + 1) & 1);
+    const int tog = (j & 1) ? -DK_BUF : DK_BUF;
+    cx.qa.shift(tog);
+    cx.stat += (j & 1) ? -2 * BQ * 4 : 2 * BQ * 4;
     __syncthreads();
   }
 
   if (key < d.nkv) {
     const int64_t row = (int64_t)head * d.nkv + key;
-    store_acc_t(dK + row * H, dk, half, d.scale);
-    store_acc_t(dV + row * H, dv, half, 1.0f);
+    store_acc_t(dK + row * H, cx.dk, cx.half, d.scale);
+    store_acc_t(dV + row * H, cx.dv, cx.half, 1.0f);
   }
 }
 
 // ---------------------------------------------------------------------- dQ
+constexpr int kThreads = 256;
+constexpr int BK = 128;   // query rows per workgroup
+constexpr int BS = 64;    // keys per step
 // LDS: [buf]{ K tile 16 KB, V tile 16 KB }
 constexpr int DQ_LDS = 4 * TILE64_BYTES;
 
@@ -313,19 +385,19 @@ hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K,
                            const void* dO, const float* lse, const float* delta, float* dQ,
                            float* dK, float* dV, hipStream_t s) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, DKDV_LDS);
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, DK_LDS);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
   if (e != hipSuccess) return e;
-  dim3 block(kThreads);
-  dim3 grid_kv(xcd_grid(d.heads, (d.nkv + BK - 1) / BK)), grid_q(xcd_grid(d.heads, (d.nq + BK - 1) / BK));
-  hipLaunchKernelGGL(bwd_dkdv_kernel, grid_kv, block, DKDV_LDS, s, d, (const bf16_t*)Q,
+  dim3 grid_kv(xcd_grid(d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS));
+  dim3 grid_q(xcd_grid(d.heads, (d.nq + BK - 1) / BK));
+  hipLaunchKernelGGL(bwd_dkdv_kernel, grid_kv, dim3(DK_THREADS), DK_LDS, s, d, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bwd_dq_kernel, grid_q, block, DQ_LDS, s, d, (const bf16_t*)Q, (const bf16_t*)K,
-                     (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
+  hipLaunchKernelGGL(bwd_dq_kernel, grid_q, dim3(kThreads), DQ_LDS, s, d, (const bf16_t*)Q,
+                     (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
   return hipGetLastError();
 }
 

@@ -131,6 +131,39 @@ struct Stage64 {
 
 constexpr int TILE64_BYTES = 64 * ROW_BYTES;
 
+// "Dual" LDS tile layout for tiles read BOTH ways (natural and transposed) with
+// immediate-only addressing: rows of 320 B (256 B data + 64 B pad), and within a row the
+// 16-byte chunk c sits at position c ^ ((row >> 2) & 3).
+//   - the 64 B pad shifts consecutive rows by 16 banks, so the four rows of a transposing
+//     32-lane pass use four disjoint 16-bank windows;
+//   - the XOR on the two low chunk bits separates the rows r, r+4, r+8, r+12 that share a
+//     window in a 16-row natural (128-bit) pass.
+// Every fragment address is then one of four per-lane bases plus a compile-time constant:
+//   natural fragment x of rows RB + (lane & 31), RB a multiple of 32:
+//       (x & 1 ? nat_o : nat_e) + 64 * (x >> 1) + RB * 320
+//   transposing reads of column tile ct, rows RB + {0..7 | 8..15}, RB a multiple of 16:
+//       (tr_lo | tr_hi) + 64 * ct + RB * 320
+constexpr int DUAL_LD = 320;
+constexpr int DUAL64_BYTES = 64 * DUAL_LD;
+struct DualAddr {
+  unsigned nat_e, nat_o, tr_lo, tr_hi;
+  __device__ __forceinline__ void init(int lane, unsigned tile_base) {
+    const int l32 = lane & 31, half = lane >> 5;
+    const int kap = (l32 >> 2) & 3;
+    nat_e = tile_base + l32 * DUAL_LD + 32 * (kap >> 1) + 16 * (half ^ (kap & 1));
+    nat_o = nat_e ^ 32;      // bit 5 of the address is exactly the (x & 1) ^ (kap >> 1) term
+    const int g16 = lane >> 4, j16 = lane & 15;
+    const int row = 4 * (g16 >> 1) + (j16 >> 2);           // 0..7, (row >> 2) & 3 = g16 >> 1
+    const int cl = 2 * (g16 & 1) + ((j16 & 3) >> 1);       // logical chunk within a 64-byte column tile
+    const int sub = 8 * (j16 & 1);
+    tr_lo = tile_base + row * DUAL_LD + 16 * (cl ^ (g16 >> 1)) + sub;
+    tr_hi = tile_base + (row + 8) * DUAL_LD + 16 * (cl ^ ((g16 >> 1) + 2)) + sub;
+  }
+  __device__ __forceinline__ void shift(int delta) { nat_e += delta; nat_o += delta; tr_lo += delta; tr_hi += delta; }
+};
+// byte offset inside a dual tile at which the 16-byte chunk `c` of row `r` is stored
+__device__ __forceinline__ int dual_store_off(int r, int c) { return r * DUAL_LD + ((c ^ ((r >> 2) & 3)) << 4); }
+
 // XCD-aware work mapping.  MI355X has 8 XCDs, each with its own L2, and hands consecutive
 // workgroup ids to consecutive XCDs (id % 8).  All blocks of one head read the same K / V (or
 // Q / dO) rows, so they are placed on ONE XCD, back to back in its dispatch order: the k-th
