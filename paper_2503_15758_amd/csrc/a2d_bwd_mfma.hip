@@ -80,7 +80,10 @@ __device__ __forceinline__ void dkdv_piece(DkCtx& cx, int qs0) {
   constexpr int RB = SUB * 32 * DUAL_LD;
   constexpr int GO = DUAL64_BYTES;            // dO tile behind the Q tile
   bf16x8 qn[4], gn[4];                        // ring of natural fragments, four steps deep
-#define A2D_LD1(X) qn[(X) & 3] = dual_nat<X>(cx.qa, RB); gn[(X) & 3] = dual_nat<X>(cx.qa, RB + GO);
+  // (the scheduling fences keep the compiler from sinking the requests back to their uses)
+#define A2D_LD1(X)                                                                  \
+  qn[(X) & 3] = dual_nat<X>(cx.qa, RB); gn[(X) & 3] = dual_nat<X>(cx.qa, RB + GO); \
+  __builtin_amdgcn_sched_barrier(0);
 #define A2D_SDP(X) s = mma(qn[(X) & 3], cx.kf[X], s); dp = mma(gn[(X) & 3], cx.vf[X], dp);
   A2D_LD1(0) A2D_LD1(1) A2D_LD1(2) A2D_LD1(3)
   f32x16 s = zero16(), dp = zero16();
@@ -94,7 +97,8 @@ __device__ __forceinline__ void dkdv_piece(DkCtx& cx, int qs0) {
   gt[HT] = lds_load_tr(cx.qa.tr_lo + GO + RB + (U) * 16 * DUAL_LD + 64 * (HT),                            \
                        cx.qa.tr_hi + GO + RB + (U) * 16 * DUAL_LD + 64 * (HT));                           \
   qt[HT] = lds_load_tr(cx.qa.tr_lo + RB + (U) * 16 * DUAL_LD + 64 * (HT),                                 \
-                       cx.qa.tr_hi + RB + (U) * 16 * DUAL_LD + 64 * (HT));
+                       cx.qa.tr_hi + RB + (U) * 16 * DUAL_LD + 64 * (HT));                                \
+  __builtin_amdgcn_sched_barrier(0);
   A2D_SDP(4) A2D_LD2(0, 0)
   A2D_SDP(5) A2D_LD2(1, 0)
   A2D_SDP(6) A2D_LD2(2, 0)

@@ -56,20 +56,23 @@ struct FwdState {
 template <bool MASK>
 __device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], unsigned k_rd, unsigned v_rd,
                                           int k0, int my_vis, int half, float c) {
-  // K fragments are requested a full tile (8 MFMAs) ahead of their use
+  // K fragments go through a ring four deep: each is requested four MFMAs before its use (the
+  // scheduling fences keep the compiler from sinking the requests back to their uses)
   f32x16 s[2];
-  bf16x8 ka[8], kb[8];
-#pragma unroll
-  for (int x = 0; x < 8; ++x) ka[x] = lds_load_b128(k_rd + x * 32);
   s[0] = zero16();
   s[1] = zero16();
-#pragma unroll
-  for (int x = 0; x < 8; ++x) {
-    kb[x] = lds_load_b128(k_rd + 32 * KLD + x * 32);
-    s[0] = mma(ka[x], qf[x], s[0]);
-  }
-#pragma unroll
-  for (int x = 0; x < 8; ++x) s[1] = mma(kb[x], qf[x], s[1]);
+  bf16x8 kr[4];
+#define A2D_LDK(I) kr[(I) & 3] = lds_load_b128(k_rd + ((I) >> 3) * 32 * KLD + ((I) & 7) * 32);
+#define A2D_S(I)                                              \
+  s[(I) >> 3] = mma(kr[(I) & 3], qf[(I) & 7], s[(I) >> 3]);   \
+  if ((I) + 4 < 16) { A2D_LDK(((I) + 4) & 15) }               \
+  __builtin_amdgcn_sched_barrier(0);
+  A2D_LDK(0) A2D_LDK(1) A2D_LDK(2) A2D_LDK(3)
+  __builtin_amdgcn_sched_barrier(0);
+  A2D_S(0) A2D_S(1) A2D_S(2) A2D_S(3) A2D_S(4) A2D_S(5) A2D_S(6) A2D_S(7)
+  A2D_S(8) A2D_S(9) A2D_S(10) A2D_S(11) A2D_S(12) A2D_S(13) A2D_S(14) A2D_S(15)
+#undef A2D_S
+#undef A2D_LDK
   if (MASK) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -100,14 +103,16 @@ __device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], u
       for (int r = 0; r < 16; ++r) st.o[t][r] *= alpha;
   }
   const float mc = (st.m_ref == -INFINITY) ? 0.f : st.m_ref * c;
-  // V^T fragments of the first 32 keys are requested before the exponentials, those of the
-  // last 32 keys while the first half's MFMAs run
-  bf16x8 va[8], vb[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const unsigned a = v_rd + (i >> 2) * 16 * VLD + (i & 3) * 64;
-    va[i] = lds_load_tr(a, a + 8 * VLD);
+  // V^T fragments (i = 4 u + ht) go through a ring four deep as well; the first four are
+  // requested before the exponentials
+  bf16x8 vr[4];
+#define A2D_LDV(I)                                                          \
+  {                                                                         \
+    const unsigned a = v_rd + ((I) >> 2) * 16 * VLD + ((I) & 3) * 64;       \
+    vr[(I) & 3] = lds_load_tr(a, a + 8 * VLD);                              \
   }
+  A2D_LDV(0) A2D_LDV(1) A2D_LDV(2) A2D_LDV(3)
+  __builtin_amdgcn_sched_barrier(0);
   float psum = 0.f;
   bf16x8 pb[4];
 #pragma unroll
@@ -119,14 +124,15 @@ __device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], u
       pb[u][e] = (bf16_t)p;
     }
   st.l_run += psum;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const unsigned a = v_rd + (2 + (i >> 2)) * 16 * VLD + (i & 3) * 64;
-    vb[i] = lds_load_tr(a, a + 8 * VLD);
-    st.o[i & 3] = mma(va[i], pb[i >> 2], st.o[i & 3]);
-  }
-#pragma unroll
-  for (int i = 0; i < 8; ++i) st.o[i & 3] = mma(vb[i], pb[2 + (i >> 2)], st.o[i & 3]);
+  __builtin_amdgcn_sched_barrier(0);
+#define A2D_PV(I)                                                  \
+  st.o[(I) & 3] = mma(vr[(I) & 3], pb[(I) >> 2], st.o[(I) & 3]);   \
+  if ((I) + 4 < 16) A2D_LDV(((I) + 4) & 15)                        \
+  __builtin_amdgcn_sched_barrier(0);
+  A2D_PV(0) A2D_PV(1) A2D_PV(2) A2D_PV(3) A2D_PV(4) A2D_PV(5) A2D_PV(6) A2D_PV(7)
+  A2D_PV(8) A2D_PV(9) A2D_PV(10) A2D_PV(11) A2D_PV(12) A2D_PV(13) A2D_PV(14) A2D_PV(15)
+#undef A2D_PV
+#undef A2D_LDV
 }
 
 __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
