@@ -27,6 +27,17 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# HBM bytes per launch of each call, from rocprofv3 PMC runs of this script (FETCH_SIZE and WRITE_SIZE,
+# each scaled by the reading of a 1 GiB copy: profiles/bench_c3_hbm_traffic.txt).  The tile calls sum
+# their kernels (partial_bwd = delta + dK/dV + dQ kernels).  Only the default workload was counted.
+MIB = float(1 << 20)
+TRAFFIC_BYTES = {"c3": {
+    "partial_fwd_diag": (289.8 + 197.4) * MIB, "partial_fwd_full": (289.8 + 197.4) * MIB,
+    "partial_bwd_diag": (192.0 + 387.2 + 391.0 + 1.5 + 391.7 + 193.7) * MIB,
+    "partial_bwd_full": (192.0 + 387.2 + 391.0 + 1.5 + 391.7 + 193.7) * MIB,
+    "fix": (1632.0 + 97.5) * MIB, "fix_bwd_dq": (1536.0 + 96.0) * MIB,
+    "fix_bwd_dk": (1536.0 + 96.0) * MIB, "fix_bwd_dv": (1536.0 + 96.0) * MIB}}
+
 
 def tile_flops(w, nq, nkv, causal_diag):
     """Algorithmic FLOPs of one tile, all heads: fwd 4 Nq Nkv H, bwd 10 Nq Nkv H per head; a
@@ -43,6 +54,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="after the timed steps run one plain 1 GiB device copy (torch copy_), so that a "
+                         "rocprofv3 --pmc run of this command also holds the counter reading of a copy of "
+                         "known size (the scale factor for FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the sqrt(P) x sqrt(P) grid is emulated as "
@@ -133,6 +148,12 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     avg_ms = {n: sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)) / args.steps
               for i, n in enumerate(names)}
@@ -167,7 +188,8 @@ def main():
     dom = max((n for n in names if n in flops), key=lambda n: avg_ms[n])
     roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["achieved"],
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": kernels[dom]["frac"],
-                "avg_ms": kernels[dom]["avg_ms"], "traffic": None}
+                "avg_ms": kernels[dom]["avg_ms"],
+                "traffic": TRAFFIC_BYTES.get(w.name, {}).get(dom)}
 
     result = {
         "metric": "fwd+bwd attention TFLOP/s per tile + % bf16 MFMA peak; AttnFix GB/s",
@@ -188,29 +210,31 @@ def main():
 
 
 def cpu_baseline(w, scale):
-    """The fp64 oracle on the host cores, on a bounded sample of the same workload: one head of an
-    unmasked tile, the first `nq_s` query rows against all T keys, partial forward + partial backward."""
-    import numpy as np
+    """The fp64 oracle, as it stands, on the host cores: partial forward + AttnFix (k = 1) + partial
+    backward of an unmasked tile for a bounded number of heads (about 6e11 algorithmic FLOPs, some
+    10-20 s on 16 cores)."""
     import oracle
     from paper_2503_15758_amd import synth
     T, H = w.tile, w.hdim
-    nq_s = max(64, min(T, int(2.0e10 / (14.0 * T * H))))     # about 20 GFLOP of algorithmic work
-    one = synth.Workload(w.name, w.dtype, 1, H, w.seq, w.grid, w.causal, w.backward, w.sigma_qk, w.seed)
+    per_head = (14.0 if w.backward else 4.0) * T * T * H
+    nh = int(max(1, min(w.heads, round(6.0e11 / per_head))))
+    nq_s = T if per_head <= 6.0e11 else max(64, int(6.0e11 / ((14.0 if w.backward else 4.0) * T * H)))
+    sub = synth.Workload(w.name, w.dtype, nh, H, w.seq, w.grid, w.causal, w.backward, w.sigma_qk, w.seed)
     n64 = lambda t: t.double().numpy()
-    Q = n64(synth.q_block(one, w.grid - 1, nq_s)); K = n64(synth.k_block(one, 0)); V = n64(synth.v_block(one, 0))
-    dO = n64(synth.do_block(one, w.grid - 1, nq_s))
+    Q = n64(synth.q_block(sub, w.grid - 1, nq_s)); K = n64(synth.k_block(sub, 0)); V = n64(synth.v_block(sub, 0))
+    dO = n64(synth.do_block(sub, w.grid - 1, nq_s))
     t0 = time.perf_counter()
     N, m, l = oracle.partial_fwd(Q, K, V, 0, 0, False, scale)
     O, lse = oracle.fix([N], [m], [l])
-    fl = 4.0 * nq_s * T * H
+    fl = 4.0 * nh * nq_s * T * H
     if w.backward:
         oracle.partial_bwd(Q, K, V, O, dO, lse, 0, 0, False, scale)
-        fl += 10.0 * nq_s * T * H
+        fl += 10.0 * nh * nq_s * T * H
     sec = time.perf_counter() - t0
     return {"value": round(fl / sec / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": round(sec, 2),
-            "sample": "one head, %d query rows x %d keys x H%d of an unmasked tile, fp64 partial "
-                      "fwd%s" % (nq_s, T, H, "+bwd" if w.backward else "")}
+            "sample": "%d head(s), %d query rows x %d keys x H%d of an unmasked tile, fp64 partial "
+                      "fwd + fix%s" % (nh, nq_s, T, H, " + partial bwd" if w.backward else "")}
 
 
 if __name__ == "__main__":
