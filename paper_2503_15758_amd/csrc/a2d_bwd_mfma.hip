@@ -193,14 +193,14 @@ __global__ __launch_bounds__(DK_THREADS, 1) void bwd_dkdv_kernel(
   float stat = 0.f;
   bool stat_ok = false;
   auto load_step = [&](int i0) {
-    const char* qb = uniform_ptr(reinterpret_cast<const char*>(Q + (int64_t)i0 * H));
-    const char* gb = uniform_ptr(reinterpret_cast<const char*>(dO + (int64_t)i0 * H));
+    const gptr_t qb = uniform_gptr(Q + (int64_t)i0 * H);
+    const gptr_t gb = uniform_gptr(dO + (int64_t)i0 * H);
     const int last = d.nq - 1 - i0;
 #pragma unroll
     for (int p = 0; p < ST_N; ++p) {
       const unsigned off = (unsigned)(min(st_row + ST_ROWS * p, last) * (H * 2) + st_ch * 16);
-      qreg[p] = *reinterpret_cast<const u32x4*>(qb + off);
-      greg[p] = *reinterpret_cast<const u32x4*>(gb + off);
+      qreg[p] = gload_b128(qb, off);
+      greg[p] = gload_b128(gb, off);
     }
     // raw loads only: converting here would make the wave wait for everything just issued
     if (tid < 2 * BQ) {

@@ -196,14 +196,14 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_mfma_kernel(
   const int v_wr = K_BYTES + ld_row * VLD + ld_chunk * 16;
   u32x4 kreg[4], vreg[4];
   auto load_tile = [&](int k0) {
-    const char* kb = uniform_ptr(reinterpret_cast<const char*>(K + (int64_t)k0 * H));   // scalar bases
-    const char* vb = uniform_ptr(reinterpret_cast<const char*>(V + (int64_t)k0 * H));
+    const gptr_t kb = uniform_gptr(K + (int64_t)k0 * H);   // scalar bases
+    const gptr_t vb = uniform_gptr(V + (int64_t)k0 * H);
     const int last = d.nkv - 1 - k0;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       const unsigned off = (unsigned)(min(ld_row + 16 * p, last) * (H * 2) + ld_chunk * 16);
-      kreg[p] = *reinterpret_cast<const u32x4*>(kb + off);
-      vreg[p] = *reinterpret_cast<const u32x4*>(vb + off);
+      kreg[p] = gload_b128(kb, off);
+      vreg[p] = gload_b128(vb, off);
     }
   };
   auto store_tile = [&](int boff) {

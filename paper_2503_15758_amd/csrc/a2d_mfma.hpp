@@ -52,14 +52,19 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& s, int base) {
 // waits that would also cover the loop's own freshly issued prefetches.
 __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
-// Marks a pointer that is the same in every lane as such, so that global loads use the
-// scalar-base + 32-bit-lane-offset addressing form (no per-lane 64-bit address arithmetic).
-template <typename T>
-__device__ __forceinline__ const T* uniform_ptr(const T* p) {
+// Global-memory pointer that is the same in every lane, held in scalar registers, so that loads
+// through it use the scalar-base + 32-bit-lane-offset addressing form (no per-lane 64-bit address
+// arithmetic).  It carries the global address space: a generic pointer rebuilt from integers would
+// turn the loads into FLAT ones, which also count on the LDS wait counter.
+typedef const __attribute__((address_space(1))) char* gptr_t;
+__device__ __forceinline__ gptr_t uniform_gptr(const void* p) {
   const uint64_t v = reinterpret_cast<uint64_t>(p);
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
   const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-  return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
+  return reinterpret_cast<gptr_t>(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ u32x4 gload_b128(gptr_t base, unsigned byte_off) {
+  return *reinterpret_cast<const __attribute__((address_space(1))) u32x4*>(base + byte_off);
 }
 
 // LDS reads by byte address (address space 3)
