@@ -55,7 +55,6 @@ __device__ __forceinline__ bf16x8 dual_nat(const DualAddr& a, int extra) {
 constexpr int DK_THREADS = 256;
 constexpr int DK_KEYS = 128;      // keys per workgroup
 constexpr int BQ = 64;            // query rows per step
-constexpr int VT_LD = 272;        // V tile row stride (natural reads only)
 // LDS: [buf]{ Q tile, dO tile } (dual layout) | [buf]{ lse*log2e [64], delta [64] }
 constexpr int DK_BUF = 2 * DUAL64_BYTES;
 constexpr int DK_STAT = 2 * DK_BUF;
@@ -261,50 +260,112 @@ __global__ __launch_bounds__(DK_THREADS, 1) void bwd_dkdv_kernel(
 }
 
 // ---------------------------------------------------------------------- dQ
-constexpr int kThreads = 256;
-constexpr int BK = 128;   // query rows per workgroup
-constexpr int BS = 64;    // keys per step
-// LDS: [buf]{ K tile 16 KB, V tile 16 KB }
-constexpr int DQ_LDS = 4 * TILE64_BYTES;
+constexpr int DQ_THREADS = 256;
+constexpr int DQ_ROWS = 128;      // query rows per workgroup
+constexpr int BKS = 64;           // keys per step
+constexpr int VT_LD = 272;        // V tile row stride (natural reads only)
+// LDS: [buf]{ K tile (dual layout), V tile (272-byte rows) }
+constexpr int DQ_VT = DUAL64_BYTES;
+constexpr int DQ_BUF = DUAL64_BYTES + BKS * VT_LD;
+constexpr int DQ_LDS = 2 * DQ_BUF;
+constexpr int DQ_RING = 2;        // fragment ring depth (registers are tight: 256 per wavefront)
 
-__global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(
+struct DqCtx {
+  f32x16 dq[4];
+  bf16x8 qf[8], gf[8];
+  DualAddr ka;          // K tile of the current buffer
+  unsigned vnat;        // natural-fragment base in the V tile of the current buffer
+  float c, lse2, del;
+  int my_vis;           // number of leading local keys this lane's query row sees
+  int half;
+};
+
+// one 32-key x 32-query piece: T selects the half of the 64-key step
+template <int T, bool MASK>
+__device__ __forceinline__ void dq_piece(DqCtx& cx, int key0) {
+  constexpr int RB = T * 32 * DUAL_LD;
+  constexpr int VB = T * 32 * VT_LD;
+  bf16x8 kr[DQ_RING], vr[DQ_RING];
+#define A2D_LD1(X)                                             \
+  kr[(X) % DQ_RING] = dual_nat<X>(cx.ka, RB);                  \
+  vr[(X) % DQ_RING] = lds_load_b128(cx.vnat + VB + 32 * (X));  \
+  __builtin_amdgcn_sched_barrier(0);
+#define A2D_SDP(X) s = mma(kr[(X) % DQ_RING], cx.qf[X], s); dp = mma(vr[(X) % DQ_RING], cx.gf[X], dp);
+  A2D_LD1(0) A2D_LD1(1)
+  f32x16 s = zero16(), dp = zero16();
+  A2D_SDP(0) A2D_LD1(2)
+  A2D_SDP(1) A2D_LD1(3)
+  A2D_SDP(2) A2D_LD1(4)
+  A2D_SDP(3) A2D_LD1(5)
+  A2D_SDP(4) A2D_LD1(6)
+  A2D_SDP(5) A2D_LD1(7)
+  // K^T fragments of the first key rows: on their way during the exponentials
+  bf16x8 kt[DQ_RING];
+#define A2D_LD2(I)                                                                                        \
+  kt[(I) % DQ_RING] = lds_load_tr(cx.ka.tr_lo + RB + ((I) >> 2) * 16 * DUAL_LD + 64 * ((I) & 3),          \
+                                  cx.ka.tr_hi + RB + ((I) >> 2) * 16 * DUAL_LD + 64 * ((I) & 3));         \
+  __builtin_amdgcn_sched_barrier(0);
+  A2D_SDP(6) A2D_LD2(0)
+  A2D_SDP(7) A2D_LD2(1)
+#undef A2D_SDP
+#undef A2D_LD1
+  // register r <-> key key0 + 8*(r>>2) + 4*half + (r&3); lane <-> query
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float p = fast_exp2(fmaf(s[r], cx.c, -cx.lse2));
+    if (MASK && (key0 + 8 * (r >> 2) + 4 * cx.half + (r & 3) >= cx.my_vis)) p = 0.f;
+    dp[r] = p * (dp[r] - cx.del);
+  }
+  bf16x8 dsb[2];
+  dsb[0] = pack8(dp, 0);
+  dsb[1] = pack8(dp, 8);
+  __builtin_amdgcn_sched_barrier(0);
+#define A2D_DQ(I) cx.dq[(I) & 3] = mma(kt[(I) % DQ_RING], dsb[(I) >> 2], cx.dq[(I) & 3]);
+  A2D_DQ(0) A2D_LD2(2)
+  A2D_DQ(1) A2D_LD2(3)
+  A2D_DQ(2) A2D_LD2(4)
+  A2D_DQ(3) A2D_LD2(5)
+  A2D_DQ(4) A2D_LD2(6)
+  A2D_DQ(5) A2D_LD2(7)
+  A2D_DQ(6) A2D_DQ(7)
+#undef A2D_DQ
+#undef A2D_LD2
+}
+
+__global__ __launch_bounds__(DQ_THREADS, 2) void bwd_dq_kernel(
     a2d_tile_desc d, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ delta, float* __restrict__ dQ) {
-  extern __shared__ __attribute__((aligned(16))) char lds[];
-  const int nqb = (d.nq + BK - 1) / BK;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+  const int nqb = (d.nq + DQ_ROWS - 1) / DQ_ROWS;
   int head, blk;
   if (!xcd_map(d.heads, nqb, head, blk)) return;
-  const int q0 = (nqb - 1 - blk) * BK;            // heavy blocks first under a causal mask
+  const int q0 = (nqb - 1 - blk) * DQ_ROWS;            // heavy blocks first under a causal mask
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
-  const int half = lane >> 5, l32 = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int l32 = lane & 31;
   Q += (int64_t)head * d.nq * H;
   dO += (int64_t)head * d.nq * H;
   K += (int64_t)head * d.nkv * H;
   V += (int64_t)head * d.nkv * H;
-  FragAddr fa;
-  fa.init(lane);
 
+  DqCtx cx;
+  cx.half = lane >> 5;
+  cx.c = d.scale * kLog2e;
   const int q_row = q0 + wave * 32 + l32;
   const bool q_ok = q_row < d.nq;
-  bf16x8 qf[8], gf[8];
+  const int q_ld = min(q_row, d.nq - 1);         // rows beyond nq re-read the last row, lse2 = +inf
   {
-    const int64_t off = (int64_t)(q_ok ? q_row : 0) * H + 8 * half;
+    const int64_t off = (int64_t)q_ld * H + 8 * cx.half;
 #pragma unroll
-    for (int st = 0; st < 8; ++st) {
-      u32x4 a = *reinterpret_cast<const u32x4*>(Q + off + 16 * st);
-      u32x4 b = *reinterpret_cast<const u32x4*>(dO + off + 16 * st);
-      if (!q_ok) { a = u32x4{0, 0, 0, 0}; b = u32x4{0, 0, 0, 0}; }
-      qf[st] = __builtin_bit_cast(bf16x8, a);
-      gf[st] = __builtin_bit_cast(bf16x8, b);
+    for (int x = 0; x < 8; ++x) {
+      cx.qf[x] = *reinterpret_cast<const bf16x8*>(Q + off + 16 * x);
+      cx.gf[x] = *reinterpret_cast<const bf16x8*>(dO + off + 16 * x);
     }
-  }
-  float lse2 = INFINITY, del = 0.f;            // +inf: exp2(s - lse2) = 0 for padding / empty rows
-  if (q_ok) {
-    const float v = lse[(int64_t)head * d.nq + q_row];
-    lse2 = (v == -INFINITY) ? INFINITY : v * kLog2e;
-    del = delta[(int64_t)head * d.nq + q_row];
+    const float v = lse[(int64_t)head * d.nq + q_ld];
+    cx.lse2 = (!q_ok || v == -INFINITY) ? INFINITY : v * kLog2e;    // +inf: exp2(s - lse2) = 0
+    cx.del = delta[(int64_t)head * d.nq + q_ld];
   }
   wait_vmem_all();
 
@@ -314,69 +375,69 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(
     const int64_t v = (int64_t)i + rel + 1;
     return v <= 0 ? 0 : (v < d.nkv ? (int)v : d.nkv);
   };
-  const int blk_last = min(q0 + BK, d.nq) - 1;
-  const int nblk = (vis_count(blk_last) + BS - 1) / BS;
-  const int w_first = q0 + wave * 32;
-  const int w_last = min(w_first + 31, d.nq - 1);
-  const int nvis_wave = (w_first < d.nq) ? vis_count(w_last) : 0;
-  const int nfull_wave = (w_first < d.nq) ? vis_count(w_first) : 0;
-  const int my_vis = q_ok ? vis_count(q_row) : 0;
-  const float c = d.scale * kLog2e;
-
-  f32x16 dq[4];
+  const int blk_last = min(q0 + DQ_ROWS, d.nq) - 1;
+  const int nblk = (vis_count(blk_last) + BKS - 1) / BKS;
+  const int w_first = min(q0 + wave * 32, d.nq - 1);
+  const int w_last = min(q0 + wave * 32 + 31, d.nq - 1);
+  const int nvis_wave = vis_count(w_last);
+  const int nfull_wave = vis_count(w_first);
+  cx.my_vis = vis_count(q_ld);
 #pragma unroll
-  for (int t = 0; t < 4; ++t) dq[t] = zero16();
+  for (int t = 0; t < 4; ++t) cx.dq[t] = zero16();
 
-  Stage64 kst, vst;
+  cx.ka.init(lane, lds_base);
+  cx.vnat = lds_base + DQ_VT + l32 * VT_LD + 16 * cx.half;
+
+  // ---- staging, in two halves of 32 key rows so that only 16 registers are in flight: thread
+  // moves chunk (tid & 15) of rows (tid >> 4) + 16 p of a half.  Rows beyond nkv re-read the last
+  // row (finite values, masked out).
+  const int st_row = tid >> 4, st_ch = tid & 15;
+  u32x4 kreg[2], vreg[2];
+  auto load_half = [&](int k0, int hf) {
+    const gptr_t kb = uniform_gptr(K + (int64_t)k0 * H);
+    const gptr_t vb = uniform_gptr(V + (int64_t)k0 * H);
+    const int last = d.nkv - 1 - k0;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const unsigned off = (unsigned)(min(32 * hf + st_row + 16 * p, last) * (H * 2) + st_ch * 16);
+      kreg[p] = gload_b128(kb, off);
+      vreg[p] = gload_b128(vb, off);
+    }
+  };
+  auto store_half = [&](int buf, int hf) {
+    char* b = lds + buf * DQ_BUF;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const int row = 32 * hf + st_row + 16 * p;
+      *reinterpret_cast<u32x4*>(b + dual_store_off(row, st_ch)) = kreg[p];
+      *reinterpret_cast<u32x4*>(b + DQ_VT + row * VT_LD + st_ch * 16) = vreg[p];
+    }
+  };
+
   if (nblk > 0) {
-    kst.load(K, 0, d.nkv, tid);
-    vst.load(V, 0, d.nkv, tid);
-    kst.store(lds, tid);
-    vst.store(lds + TILE64_BYTES, tid);
+    load_half(0, 0); store_half(0, 0);
+    load_half(0, 1); store_half(0, 1);
   }
   __syncthreads();
 
   for (int j = 0; j < nblk; ++j) {
-    const int k0 = j * BS;
-    const char* ks = lds + (j & 1) * 2 * TILE64_BYTES;
-    const char* vs = ks + TILE64_BYTES;
-    if (j + 1 < nblk) {
-      kst.load(K, k0 + BS, d.nkv, tid);
-      vst.load(V, k0 + BS, d.nkv, tid);
-    }
+    const int k0 = j * BKS;
+    const bool more = j + 1 < nblk;
+    if (more) load_half(k0 + BKS, 0);
     if (k0 < nvis_wave) {
-      const bool need_mask = k0 + BS > nfull_wave;
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-        for (int st = 0; st < 8; ++st) {
-          s = mma(read_nat(ks, fa, 32 * t, st), qf[st], s);
-          dp = mma(read_nat(vs, fa, 32 * t, st), gf[st], dp);
-        }
-        // register r <-> key k0 + 32 t + 8*(r>>2) + 4*half + (r&3); lane <-> query
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float p = fast_exp2(fmaf(s[r], c, -lse2));
-          if (need_mask && (k0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3) >= my_vis)) p = 0.f;
-          dp[r] = p * (dp[r] - del);
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const bf16x8 dsb = pack8(dp, 8 * u);
-#pragma unroll
-          for (int ht = 0; ht < 4; ++ht) dq[ht] = mma(read_tr(ks, fa, 32 * t + 16 * u, ht), dsb, dq[ht]);
-        }
-      }
+      if (k0 + 32 > nfull_wave) dq_piece<0, true>(cx, k0); else dq_piece<0, false>(cx, k0);
     }
-    if (j + 1 < nblk) {
-      char* nk = lds + ((j + 1) & 1) * 2 * TILE64_BYTES;
-      kst.store(nk, tid);
-      vst.store(nk + TILE64_BYTES, tid);
+    if (more) { store_half((j + 1) & 1, 0); load_half(k0 + BKS, 1); }
+    if (k0 + 32 < nvis_wave) {
+      if (k0 + 64 > nfull_wave) dq_piece<1, true>(cx, k0 + 32); else dq_piece<1, false>(cx, k0 + 32);
     }
+    if (more) store_half((j + 1) & 1, 1);
+    const int tog = (j & 1) ? -DQ_BUF : DQ_BUF;
+    cx.ka.shift(tog);
+    cx.vnat += tog;
     __syncthreads();
   }
-  if (q_ok) store_acc_t(dQ + ((int64_t)head * d.nq + q_row) * H, dq, half, d.scale);
+  if (q_ok) store_acc_t(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, d.scale);
 }
 
 }  // namespace
@@ -395,12 +456,12 @@ hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K,
                           hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
   if (e != hipSuccess) return e;
   dim3 grid_kv(xcd_grid(d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS));
-  dim3 grid_q(xcd_grid(d.heads, (d.nq + BK - 1) / BK));
+  dim3 grid_q(xcd_grid(d.heads, (d.nq + DQ_ROWS - 1) / DQ_ROWS));
   hipLaunchKernelGGL(bwd_dkdv_kernel, grid_kv, dim3(DK_THREADS), DK_LDS, s, d, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bwd_dq_kernel, grid_q, dim3(kThreads), DQ_LDS, s, d, (const bf16_t*)Q,
+  hipLaunchKernelGGL(bwd_dq_kernel, grid_q, dim3(DQ_THREADS), DQ_LDS, s, d, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
   return hipGetLastError();
 }
