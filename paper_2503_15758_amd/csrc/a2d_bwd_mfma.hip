@@ -185,40 +185,41 @@ __global__ __launch_bounds__(DK_THREADS, 1) void bwd_dkdv_kernel(
   cx.qa.init(lane, lds_base);
   cx.stat = lds_base + DK_STAT + 16 * cx.half;
 
-  // ---- staging of a 64-row step: thread moves chunk (tid & 15) of rows (tid >> 4) + 16 p
-  constexpr int ST_ROWS = DK_THREADS / 16, ST_N = BQ / ST_ROWS;
+  // ---- staging of a 64-row step in two halves of 32 rows (16 registers in flight): thread moves
+  // chunk (tid & 15) of rows (tid >> 4) + 16 p of a half.  Rows beyond nq re-read the last row;
+  // their lse entry is +inf, which makes exp2(s - lse) = 0 (also for rows whose lse is -inf).
+  static_assert(DK_THREADS == 256, "staging map assumes 256 threads");
   const int st_row = tid >> 4, st_ch = tid & 15;
-  u32x4 qreg[ST_N], greg[ST_N];
+  u32x4 qreg[2], greg[2];
   float stat = 0.f;
   bool stat_ok = false;
-  auto load_step = [&](int i0) {
+  auto load_half = [&](int i0, int hf) {
     const gptr_t qb = uniform_gptr(Q + (int64_t)i0 * H);
     const gptr_t gb = uniform_gptr(dO + (int64_t)i0 * H);
     const int last = d.nq - 1 - i0;
 #pragma unroll
-    for (int p = 0; p < ST_N; ++p) {
-      const unsigned off = (unsigned)(min(st_row + ST_ROWS * p, last) * (H * 2) + st_ch * 16);
+    for (int p = 0; p < 2; ++p) {
+      const unsigned off = (unsigned)(min(32 * hf + st_row + 16 * p, last) * (H * 2) + st_ch * 16);
       qreg[p] = gload_b128(qb, off);
       greg[p] = gload_b128(gb, off);
     }
-    // raw loads only: converting here would make the wave wait for everything just issued
-    if (tid < 2 * BQ) {
+    // raw statistic loads only: converting here would make the wave wait for everything just issued
+    if (hf == 0 && tid < 2 * BQ) {
       const int i = min(i0 + (tid & (BQ - 1)), d.nq - 1);
       stat = (tid < BQ) ? lse[i] : delta[i];
       stat_ok = (i0 + (tid & (BQ - 1))) < d.nq;
     }
   };
-  auto store_step = [&](int buf) {
+  auto store_half = [&](int buf, int hf) {
     char* b = lds + buf * DK_BUF;
 #pragma unroll
-    for (int p = 0; p < ST_N; ++p) {
-      const int off = dual_store_off(st_row + ST_ROWS * p, st_ch);
+    for (int p = 0; p < 2; ++p) {
+      const int off = dual_store_off(32 * hf + st_row + 16 * p, st_ch);
       *reinterpret_cast<u32x4*>(b + off) = qreg[p];
       *reinterpret_cast<u32x4*>(b + DUAL64_BYTES + off) = greg[p];
     }
-    if (tid < 2 * BQ) {
+    if (hf == 0 && tid < 2 * BQ) {
       float v = stat;
-      // rows beyond nq and rows with lse = -inf get +inf, which makes exp2(s - lse) = 0
       if (tid < BQ) v = (!stat_ok || v == -INFINITY) ? INFINITY : v * kLog2e;
       else v = stat_ok ? v : 0.f;
       reinterpret_cast<float*>(lds + DK_STAT + buf * 2 * BQ * 4)[tid] = v;
@@ -226,26 +227,27 @@ __global__ __launch_bounds__(DK_THREADS, 1) void bwd_dkdv_kernel(
   };
 
   if (nsteps > 0) {
-    load_step(i_start);
-    store_step(0);
+    load_half(i_start, 0); store_half(0, 0);
+    load_half(i_start, 1); store_half(0, 1);
   }
   __syncthreads();
 
   for (int j = 0; j < nsteps; ++j) {
     const int i0 = i_start + j * BQ;
     const bool more = j + 1 < nsteps;
-    if (more) load_step(i0 + BQ);
+    if (more) load_half(i0 + BQ, 0);
     // piece (SUB): rows i0 + 32 SUB .. +31.  Skipped when no row of it sees any key of the wave
     // or it lies beyond nq; masked unless every row sees every key.
     if (i0 + 31 >= w_any && i0 < d.nq) {
       if (i0 >= w_all && i0 + 32 <= d.nq) dkdv_piece<0, false>(cx, i0);
       else dkdv_piece<0, true>(cx, i0);
     }
+    if (more) { store_half((j + 1) & 1, 0); load_half(i0 + BQ, 1); }
     if (i0 + 63 >= w_any && i0 + 32 < d.nq) {
       if (i0 + 32 >= w_all && i0 + 64 <= d.nq) dkdv_piece<1, false>(cx, i0 + 32);
       else dkdv_piece<1, true>(cx, i0 + 32);
     }
-    if (more) store_step((j + 1) & 1);
+    if (more) store_half((j + 1) & 1, 1);
     const int tog = (j & 1) ? -DK_BUF : DK_BUF;
     cx.qa.shift(tog);
     cx.stat += (j & 1) ? -2 * BQ * 4 : 2 * BQ * 4;

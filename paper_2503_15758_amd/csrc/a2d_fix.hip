@@ -16,94 +16,132 @@ __device__ __forceinline__ void store_out4(bf16_t* O, int64_t off, f32x4 v) {
   *reinterpret_cast<bf16x4*>(O + off) = b;
 }
 
-// One thread owns 4 consecutive columns of one row.  HV = H / 4 threads per row.
+// Each thread handles CPT 16-byte column groups, one per grid-sized stride, and issues the
+// loads of all of them (CPT * k 128-bit loads) before the first use: the amount of data in
+// flight per thread, not the arithmetic, decides how close these kernels get to the HBM rate.
+constexpr int kLoadsInFlight = 32;
+constexpr int chunks_per_thread(int kmax) { return kmax >= kLoadsInFlight ? 1 : kLoadsInFlight / kmax > 4 ? 4 : kLoadsInFlight / kmax; }
+
+// A column group = 4 consecutive columns of one row; hv = H / 4 groups per row.
 // KMAX is the unroll bound (k <= KMAX); loads of absent partials are predicated off.
-template <typename OutT, int KMAX>
+template <typename OutT, int KMAX, int CPT>
 __global__ __launch_bounds__(256) void fix_kernel(FixPtrs p, int k, int64_t rows, int hv,
                                                   OutT* __restrict__ O, float* __restrict__ lse) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t row = idx / hv;
-  const int c = (int)(idx - row * hv);
-  if (row >= rows) return;
-  const int64_t off = (row * hv + c) * 4;
+  const int64_t base = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  const int64_t total = rows * hv;
 
-  f32x4 n[KMAX];
-  float mk[KMAX], lk[KMAX];
+  f32x4 n[CPT][KMAX];
+  float mk[CPT][KMAX], lk[CPT][KMAX];
 #pragma unroll
-  for (int x = 0; x < KMAX; ++x) {
-    if (x < k) {
-      n[x] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p.o[x] + off));
-      mk[x] = p.m[x][row];
-      lk[x] = p.l[x][row];
-    } else {
-      n[x] = f32x4{0.f, 0.f, 0.f, 0.f};
-      mk[x] = -INFINITY;
-      lk[x] = 0.f;
+  for (int c = 0; c < CPT; ++c) {
+    const int64_t idx = base + c * stride;
+    const int64_t row = idx / hv;
+#pragma unroll
+    for (int x = 0; x < KMAX; ++x) {
+      if (x < k && idx < total) {
+        n[c][x] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p.o[x]) + idx);
+        mk[c][x] = p.m[x][row];
+        lk[c][x] = p.l[x][row];
+      } else {
+        n[c][x] = f32x4{0.f, 0.f, 0.f, 0.f};
+        mk[c][x] = -INFINITY;
+        lk[c][x] = 0.f;
+      }
     }
   }
-  float M = -INFINITY;
 #pragma unroll
-  for (int x = 0; x < KMAX; ++x) M = fmaxf(M, mk[x]);
-  float D = 0.f;
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int c = 0; c < CPT; ++c) {
+    const int64_t idx = base + c * stride;
+    if (idx >= total) break;
+    const int64_t row = idx / hv;
+    float M = -INFINITY;
 #pragma unroll
-  for (int x = 0; x < KMAX; ++x) {
-    // weight of partial x: exp(m_x - M); an empty partial (m = -inf) weighs 0
-    const float w = (mk[x] == -INFINITY) ? 0.f : fast_exp2((mk[x] - M) * kLog2e);
-    D = fmaf(w, lk[x], D);
-    acc[0] = fmaf(w, n[x][0], acc[0]);
-    acc[1] = fmaf(w, n[x][1], acc[1]);
-    acc[2] = fmaf(w, n[x][2], acc[2]);
-    acc[3] = fmaf(w, n[x][3], acc[3]);
+    for (int x = 0; x < KMAX; ++x) M = fmaxf(M, mk[c][x]);
+    float D = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int x = 0; x < KMAX; ++x) {
+      // weight of partial x: exp(m_x - M); an empty partial (m = -inf) weighs 0
+      const float w = (mk[c][x] == -INFINITY) ? 0.f : fast_exp2((mk[c][x] - M) * kLog2e);
+      D = fmaf(w, lk[c][x], D);
+      acc[0] = fmaf(w, n[c][x][0], acc[0]);
+      acc[1] = fmaf(w, n[c][x][1], acc[1]);
+      acc[2] = fmaf(w, n[c][x][2], acc[2]);
+      acc[3] = fmaf(w, n[c][x][3], acc[3]);
+    }
+    const float inv = (D > 0.f) ? 1.0f / D : 0.f;
+    acc[0] *= inv; acc[1] *= inv; acc[2] *= inv; acc[3] *= inv;
+    store_out4(O, idx * 4, acc);
+    if (idx == row * hv) lse[row] = (D > 0.f) ? M + logf(D) : -INFINITY;
   }
-  const float inv = (D > 0.f) ? 1.0f / D : 0.f;
-  acc[0] *= inv; acc[1] *= inv; acc[2] *= inv; acc[3] *= inv;
-  store_out4(O, off, acc);
-  if (c == 0) lse[row] = (D > 0.f) ? M + logf(D) : -INFINITY;
+}
+
+template <typename OutT, int KMAX, int CPT>
+__global__ __launch_bounds__(256) void sum_kernel(SumPtrs p, int k, int64_t n4,
+                                                  OutT* __restrict__ out) {
+  const int64_t base = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  f32x4 v[CPT][KMAX];
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    const int64_t idx = base + c * stride;
+#pragma unroll
+    for (int x = 0; x < KMAX; ++x) {
+      if (x < k && idx < n4) v[c][x] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p.p[x]) + idx);
+      else v[c][x] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    const int64_t idx = base + c * stride;
+    if (idx >= n4) break;
+    // left-to-right sum over the partials (absent ones hold zeros)
+    f32x4 acc = v[c][0];
+#pragma unroll
+    for (int x = 1; x < KMAX; ++x) {
+      acc[0] += v[c][x][0]; acc[1] += v[c][x][1]; acc[2] += v[c][x][2]; acc[3] += v[c][x][3];
+    }
+    store_out4(out, idx * 4, acc);
+  }
 }
 
 template <typename OutT, int KMAX>
-__global__ __launch_bounds__(256) void sum_kernel(SumPtrs p, int k, int64_t n4,
-                                                  OutT* __restrict__ out) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= n4) return;
-  f32x4 v[KMAX];
-#pragma unroll
-  for (int x = 0; x < KMAX; ++x) {
-    if (x < k) v[x] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p.p[x]) + idx);
-    else v[x] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-  f32x4 acc = v[0];
-#pragma unroll
-  for (int x = 1; x < KMAX; ++x) {
-    if (x < k) { acc[0] += v[x][0]; acc[1] += v[x][1]; acc[2] += v[x][2]; acc[3] += v[x][3]; }
-  }
-  store_out4(out, idx * 4, acc);
+void fix_launch(int k, int64_t rows, int hv, const FixPtrs& p, OutT* O, float* lse, hipStream_t s) {
+  constexpr int CPT = chunks_per_thread(KMAX);
+  const int64_t per_block = 256 * CPT;
+  const dim3 grid((unsigned)((rows * hv + per_block - 1) / per_block)), block(256);
+  hipLaunchKernelGGL((fix_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, rows, hv, O, lse);
+}
+
+template <typename OutT, int KMAX>
+void sum_launch(int k, int64_t n4, const SumPtrs& p, OutT* out, hipStream_t s) {
+  constexpr int CPT = chunks_per_thread(KMAX);
+  const int64_t per_block = 256 * CPT;
+  const dim3 grid((unsigned)((n4 + per_block - 1) / per_block)), block(256);
+  hipLaunchKernelGGL((sum_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, n4, out);
 }
 
 template <typename OutT>
 hipError_t fix_dispatch(int k, int64_t rows, int hdim, const FixPtrs& p, OutT* O, float* lse,
                         hipStream_t s) {
   const int hv = hdim / 4;
-  const int64_t threads = rows * hv;
-  const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
-  if (k <= 2) hipLaunchKernelGGL((fix_kernel<OutT, 2>), grid, block, 0, s, p, k, rows, hv, O, lse);
-  else if (k <= 4) hipLaunchKernelGGL((fix_kernel<OutT, 4>), grid, block, 0, s, p, k, rows, hv, O, lse);
-  else if (k <= 8) hipLaunchKernelGGL((fix_kernel<OutT, 8>), grid, block, 0, s, p, k, rows, hv, O, lse);
-  else if (k <= 16) hipLaunchKernelGGL((fix_kernel<OutT, 16>), grid, block, 0, s, p, k, rows, hv, O, lse);
-  else hipLaunchKernelGGL((fix_kernel<OutT, 32>), grid, block, 0, s, p, k, rows, hv, O, lse);
+  if (k <= 2) fix_launch<OutT, 2>(k, rows, hv, p, O, lse, s);
+  else if (k <= 4) fix_launch<OutT, 4>(k, rows, hv, p, O, lse, s);
+  else if (k <= 8) fix_launch<OutT, 8>(k, rows, hv, p, O, lse, s);
+  else if (k <= 16) fix_launch<OutT, 16>(k, rows, hv, p, O, lse, s);
+  else fix_launch<OutT, 32>(k, rows, hv, p, O, lse, s);
   return hipGetLastError();
 }
 
 template <typename OutT>
 hipError_t sum_dispatch(int k, int64_t n, const SumPtrs& p, OutT* out, hipStream_t s) {
   const int64_t n4 = n / 4;
-  const dim3 grid((unsigned)((n4 + 255) / 256)), block(256);
-  if (k <= 2) hipLaunchKernelGGL((sum_kernel<OutT, 2>), grid, block, 0, s, p, k, n4, out);
-  else if (k <= 4) hipLaunchKernelGGL((sum_kernel<OutT, 4>), grid, block, 0, s, p, k, n4, out);
-  else if (k <= 8) hipLaunchKernelGGL((sum_kernel<OutT, 8>), grid, block, 0, s, p, k, n4, out);
-  else if (k <= 16) hipLaunchKernelGGL((sum_kernel<OutT, 16>), grid, block, 0, s, p, k, n4, out);
-  else hipLaunchKernelGGL((sum_kernel<OutT, 32>), grid, block, 0, s, p, k, n4, out);
+  if (k <= 2) sum_launch<OutT, 2>(k, n4, p, out, s);
+  else if (k <= 4) sum_launch<OutT, 4>(k, n4, p, out, s);
+  else if (k <= 8) sum_launch<OutT, 8>(k, n4, p, out, s);
+  else if (k <= 16) sum_launch<OutT, 16>(k, n4, p, out, s);
+  else sum_launch<OutT, 32>(k, n4, p, out, s);
   return hipGetLastError();
 }
 
