@@ -4,23 +4,30 @@
 //
 // Two kernels, so that every output has exactly one writer and no atomics are needed
 // (bitwise reproducible results):
-//   bwd_dkdv_kernel  owns key rows.  Workgroup = 4 wavefronts = 128 keys (32 per
-//                    wavefront, K and V fragments resident in registers); walks
-//                    the query blocks, 64 rows per step, staged through LDS together with
-//                    dO, lse and delta.  S = Q K^T and dP = dO V^T leave a lane holding
-//                    ONE key column, so P and dS feed dV^T += dO^T P and dK^T += Q^T dS
-//                    directly as B operands; dO^T / Q^T come from the LDS transpose read.
+//   bwd_dkdv_kernel  owns key rows.  Workgroup = 8 wavefronts = 128 keys: four PAIRS of
+//                    wavefronts (w, w + 4; both on SIMD w), 32 keys per pair.  The "score"
+//                    wave of a pair holds the K^T fragments and the dV^T accumulators and
+//                    computes S = Q K^T, P, dV^T += dO^T P; the "gradient" wave holds the V^T
+//                    fragments and the dK^T accumulators and computes dP = dO V^T,
+//                    dS = P o (dP - delta), dK^T += Q^T dS, with P handed over in fp32
+//                    through LDS.  That halves the accumulators per wavefront (64 registers),
+//                    so two wavefronts fit on a SIMD and one's exponentials overlap the
+//                    other's MFMAs (a single wavefront cannot overlap the two).  The query
+//                    blocks are walked 32 rows per step, staged through LDS together with dO,
+//                    lse and delta; the gradient waves run one step behind the score waves, so
+//                    one barrier per step is the only synchronisation.  S and dP leave a lane
+//                    holding ONE key column, so P and dS feed the second contractions directly
+//                    as B operands; dO^T / Q^T come from the LDS transpose read.
 //   bwd_dq_kernel    owns query rows.  Workgroup = 4 wavefronts = 128 queries (32 per
 //                    wavefront, Q and dO fragments in registers), two workgroups per
 //                    compute unit; walks the key blocks, 64 keys per step.  S^T = K Q^T
 //                    and dP^T = V dO^T leave a lane holding ONE query column;
 //                    dQ^T += K^T dS^T with K^T from the LDS transpose read.
-// The dK/dV kernel needs more than 256 VGPRs (128 of accumulators alone) and runs one
-// wavefront per SIMD; the dQ kernel keeps two, so one's MFMAs overlap the other's
-// exponentials (a single wavefront cannot overlap the two).  In the dK/dV kernel the tiles
-// read both ways live in the "dual" LDS layout of a2d_mfma.hpp (every fragment address is a
-// per-lane base plus an immediate); the dQ kernel uses the XOR-swizzled layout.  The score recomputation is done in both kernels (7 contractions
-// for 5 counted ones).
+// Tiles that are read both ways (natural and transposed fragments) live in the "dual" LDS
+// layout of a2d_mfma.hpp: every fragment address is a per-lane base plus an immediate.  The
+// score recomputation is done in both kernels (7 contractions for 5 counted ones).
+#include <type_traits>
+
 #include "a2d_mfma.hpp"
 
 namespace a2d {
@@ -52,86 +59,130 @@ __device__ __forceinline__ bf16x8 dual_nat(const DualAddr& a, int extra) {
 }
 
 // ------------------------------------------------------------------ dK, dV
-constexpr int DK_THREADS = 256;
+constexpr int DK_THREADS = 512;
 constexpr int DK_KEYS = 128;      // keys per workgroup
-constexpr int BQ = 64;            // query rows per step
-// LDS: [buf]{ Q tile, dO tile } (dual layout) | [buf]{ lse*log2e [64], delta [64] }
-constexpr int DK_BUF = 2 * DUAL64_BYTES;
-constexpr int DK_STAT = 2 * DK_BUF;
-constexpr int DK_LDS = DK_STAT + 2 * 2 * BQ * 4;
+constexpr int BQ = 32;            // query rows per step
+constexpr int DK_NBUF = 3;        // tile buffers: gradient waves' step, score waves' step, incoming
+// LDS: [buf]{ Q tile, dO tile } (dual layout, 32 rows each) | [buf]{ lse*log2e [32], delta [32] } |
+//      [slot][pair] probabilities handed from the score wave to the gradient wave (fp32)
+constexpr int DK_TILE = BQ * DUAL_LD;
+constexpr int DK_BUF = 2 * DK_TILE;
+constexpr int DK_STAT = DK_NBUF * DK_BUF;
+constexpr int DK_STAT_BUF = 2 * BQ * 4;
+constexpr int DK_MBOX = DK_STAT + DK_NBUF * DK_STAT_BUF;
+constexpr int DK_MBOX_PIECE = 32 * 32 * 4;
+constexpr int DK_MBOX_SLOT = 4 * DK_MBOX_PIECE;
+constexpr int DK_LDS = DK_MBOX + 2 * DK_MBOX_SLOT;
 
+// Per-wavefront state.  The two roles run the same contraction code on different operands:
+//   score wave (role 0):    frag = K^T fragments, natural reads from the Q tile,
+//                           transposed reads from the dO tile, acc = dV^T
+//   gradient wave (role 1): frag = V^T fragments, natural reads from the dO tile,
+//                           transposed reads from the Q tile, acc = dK^T
 struct DkCtx {
-  f32x16 dk[4], dv[4];
-  bf16x8 kf[8], vf[8];  // K^T / V^T fragments of this wavefront's 32 keys
-  DualAddr qa;          // Q tile of the current buffer; the dO tile is DUAL64_BYTES further
-  unsigned stat;        // lse / delta rows of the current buffer, offset by 16 * half
+  f32x16 acc[4];
+  bf16x8 frag[8];
+  unsigned nat_e, nat_o, tr_lo, tr_hi;   // dual-layout bases in the tile buffer of this wave's step
+  unsigned stat;        // lse (role 0) or delta (role 1) row of that buffer, + 16 * half
+  unsigned mbox;        // this lane's place in the pair's mailbox, slot of this wave's step
   float c;
   int my_first;         // first local query row that sees this lane's key
   int half;
 };
 
-// One 32-query x 32-key piece; SUB selects the half of the 64-row step.
-// A single wavefront per SIMD runs this kernel, so nothing hides LDS latency but the
-// instruction order: every fragment is requested about four MFMA pairs before its use
-// (rolling prefetch; the LDS wait counter only tracks 15 operations in flight).
-template <int SUB, bool MASK>
-__device__ __forceinline__ void dkdv_piece(DkCtx& cx, int qs0) {
-  constexpr int RB = SUB * 32 * DUAL_LD;
-  constexpr int GO = DUAL64_BYTES;            // dO tile behind the Q tile
-  bf16x8 qn[4], gn[4];                        // ring of natural fragments, four steps deep
-  // (the scheduling fences keep the compiler from sinking the requests back to their uses)
-#define A2D_LD1(X)                                                                  \
-  qn[(X) & 3] = dual_nat<X>(cx.qa, RB); gn[(X) & 3] = dual_nat<X>(cx.qa, RB + GO); \
-  __builtin_amdgcn_sched_barrier(0);
-#define A2D_SDP(X) s = mma(qn[(X) & 3], cx.kf[X], s); dp = mma(gn[(X) & 3], cx.vf[X], dp);
-  A2D_LD1(0) A2D_LD1(1) A2D_LD1(2) A2D_LD1(3)
-  f32x16 s = zero16(), dp = zero16();
-  A2D_SDP(0) A2D_LD1(4)
-  A2D_SDP(1) A2D_LD1(5)
-  A2D_SDP(2) A2D_LD1(6)
-  A2D_SDP(3) A2D_LD1(7)
-  // transposed fragments of the first 16 query rows: on their way during the exponentials
-  bf16x8 gt[4], qt[4];
-#define A2D_LD2(HT, U)                                                                                   \
-  gt[HT] = lds_load_tr(cx.qa.tr_lo + GO + RB + (U) * 16 * DUAL_LD + 64 * (HT),                            \
-                       cx.qa.tr_hi + GO + RB + (U) * 16 * DUAL_LD + 64 * (HT));                           \
-  qt[HT] = lds_load_tr(cx.qa.tr_lo + RB + (U) * 16 * DUAL_LD + 64 * (HT),                                 \
-                       cx.qa.tr_hi + RB + (U) * 16 * DUAL_LD + 64 * (HT));                                \
-  __builtin_amdgcn_sched_barrier(0);
-  A2D_SDP(4) A2D_LD2(0, 0)
-  A2D_SDP(5) A2D_LD2(1, 0)
-  A2D_SDP(6) A2D_LD2(2, 0)
-  A2D_SDP(7) A2D_LD2(3, 0)
-#undef A2D_SDP
-#undef A2D_LD1
-  // register r <-> query qs0 + 8*(r>>2) + 4*half + (r&3); lane <-> key
-#pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    const f32x4 l4 = lds_load_f32x4(cx.stat + (SUB * 32 + 8 * g) * 4);
-    const f32x4 d4 = lds_load_f32x4(cx.stat + (BQ + SUB * 32 + 8 * g) * 4);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int r = 4 * g + e;
-      float p = fast_exp2(fmaf(s[r], cx.c, -l4[e]));
-      if (MASK && (qs0 + 8 * g + 4 * cx.half + e < cx.my_first)) p = 0.f;
-      s[r] = p;
-      dp[r] = p * (dp[r] - d4[e]);
-    }
-  }
-  bf16x8 pb[2], dsb[2];
-#pragma unroll
-  for (int u = 0; u < 2; ++u) { pb[u] = pack8(s, 8 * u); dsb[u] = pack8(dp, 8 * u); }
-#define A2D_DVDK(HT, U) cx.dv[HT] = mma(gt[HT], pb[U], cx.dv[HT]); cx.dk[HT] = mma(qt[HT], dsb[U], cx.dk[HT]);
-  A2D_DVDK(0, 0) A2D_LD2(0, 1)
-  A2D_DVDK(1, 0) A2D_LD2(1, 1)
-  A2D_DVDK(2, 0) A2D_LD2(2, 1)
-  A2D_DVDK(3, 0) A2D_LD2(3, 1)
-  A2D_DVDK(0, 1) A2D_DVDK(1, 1) A2D_DVDK(2, 1) A2D_DVDK(3, 1)
-#undef A2D_DVDK
-#undef A2D_LD2
+// Fragment addresses inside the wave's tile buffer (per-lane base + immediate)
+#define A2D_NAT(X) lds_load_b128((((X) & 1) ? cx.nat_o : cx.nat_e) + 64 * ((X) >> 1))
+#define A2D_TR(U, HT) \
+  lds_load_tr(cx.tr_lo + (U) * 16 * DUAL_LD + 64 * (HT), cx.tr_hi + (U) * 16 * DUAL_LD + 64 * (HT))
+#define A2D_FENCE __builtin_amdgcn_sched_barrier(0);
+
+// First contraction of a 32-query x 32-key step (S = Q K^T or dP = dO V^T): eight MFMAs over
+// H.  The natural fragments travel through a ring of four: dk_first_pre requests fragments
+// 0..3, the body requests 4..7 while it consumes 0..3.  (The fences keep the compiler from
+// sinking the requests down to their uses.)
+__device__ __forceinline__ void dk_first_pre(const DkCtx& cx, bf16x8 (&n)[4]) {
+  n[0] = A2D_NAT(0); n[1] = A2D_NAT(1); n[2] = A2D_NAT(2); n[3] = A2D_NAT(3);
+  A2D_FENCE
+}
+__device__ __forceinline__ f32x16 dk_first(const DkCtx& cx, bf16x8 (&n)[4]) {
+  f32x16 s = zero16();
+#define A2D_MM1(X) s = mma(n[(X) & 3], cx.frag[X], s);
+  A2D_MM1(0) n[0] = A2D_NAT(4); A2D_FENCE
+  A2D_MM1(1) n[1] = A2D_NAT(5); A2D_FENCE
+  A2D_MM1(2) n[2] = A2D_NAT(6); A2D_FENCE
+  A2D_MM1(3) n[3] = A2D_NAT(7); A2D_FENCE
+  A2D_MM1(4) A2D_MM1(5) A2D_MM1(6) A2D_MM1(7)
+#undef A2D_MM1
+  return s;
 }
 
-__global__ __launch_bounds__(DK_THREADS, 1) void bwd_dkdv_kernel(
+// The 32 per-query statistics of the step (lse for the score wave, delta for the gradient wave)
+// and the partner's probabilities, requested ahead of the first contraction.
+__device__ __forceinline__ void dk_stat_pre(const DkCtx& cx, f32x4 (&st)[4]) {
+#pragma unroll
+  for (int g = 0; g < 4; ++g) st[g] = lds_load_f32x4(cx.stat + 8 * g * 4);
+  A2D_FENCE
+}
+__device__ __forceinline__ void dk_mbox_pre(const DkCtx& cx, f32x4 (&pm)[4]) {
+#pragma unroll
+  for (int g = 0; g < 4; ++g) pm[g] = lds_load_f32x4(cx.mbox + g * 1024);
+  A2D_FENCE
+}
+
+// score wave: P = exp2(c S - lse2), masked; handed on in fp32 and kept as bf16 B fragments.
+// register r <-> query qs0 + 8*(r>>2) + 4*half + (r&3); lane <-> key
+template <bool MASK>
+__device__ __forceinline__ void dk_probs(const DkCtx& cx, const f32x4 (&st)[4], f32x16& s,
+                                         bf16x8 (&bf)[2], int qs0) {
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    f32x4 p4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float p = fast_exp2(fmaf(s[4 * g + e], cx.c, -st[g][e]));
+      if (MASK && (qs0 + 8 * g + 4 * cx.half + e < cx.my_first)) p = 0.f;
+      s[4 * g + e] = p;
+      p4[e] = p;
+    }
+    *reinterpret_cast<__attribute__((address_space(3))) f32x4*>((uintptr_t)(cx.mbox + g * 1024)) = p4;
+  }
+#pragma unroll
+  for (int u = 0; u < 2; ++u) bf[u] = pack8(s, 8 * u);
+}
+
+// gradient wave: dS = P o (dP - delta) from the partner's probabilities
+__device__ __forceinline__ void dk_dscores(const f32x4 (&st)[4], const f32x4 (&pm)[4], f32x16& dp,
+                                           bf16x8 (&bf)[2]) {
+#pragma unroll
+  for (int g = 0; g < 4; ++g)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) dp[4 * g + e] = pm[g][e] * (dp[4 * g + e] - st[g][e]);
+#pragma unroll
+  for (int u = 0; u < 2; ++u) bf[u] = pack8(dp, 8 * u);
+}
+
+// Second contraction of a step (dV^T += dO^T P or dK^T += Q^T dS): eight MFMAs, A operands from
+// the LDS transpose read, again through a ring of four fragments (one per 32-column tile of H):
+// dk_second_pre requests those of the first 16 query rows (before the exponentials, so they
+// arrive meanwhile), the body those of the second 16.
+__device__ __forceinline__ void dk_second_pre(const DkCtx& cx, bf16x8 (&t)[4]) {
+  t[0] = A2D_TR(0, 0); t[1] = A2D_TR(0, 1); t[2] = A2D_TR(0, 2); t[3] = A2D_TR(0, 3);
+  A2D_FENCE
+}
+__device__ __forceinline__ void dk_second(DkCtx& cx, bf16x8 (&t)[4], const bf16x8 (&bf)[2]) {
+#define A2D_MM2(HT, U) cx.acc[HT] = mma(t[HT], bf[U], cx.acc[HT]);
+  A2D_MM2(0, 0) t[0] = A2D_TR(1, 0); A2D_FENCE
+  A2D_MM2(1, 0) t[1] = A2D_TR(1, 1); A2D_FENCE
+  A2D_MM2(2, 0) t[2] = A2D_TR(1, 2); A2D_FENCE
+  A2D_MM2(3, 0) t[3] = A2D_TR(1, 3); A2D_FENCE
+  A2D_MM2(0, 1) A2D_MM2(1, 1) A2D_MM2(2, 1) A2D_MM2(3, 1)
+#undef A2D_MM2
+}
+#undef A2D_FENCE
+#undef A2D_TR
+#undef A2D_NAT
+
+__global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
     a2d_tile_desc d, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ delta, float* __restrict__ dK, float* __restrict__ dV) {
@@ -142,6 +193,7 @@ __global__ __launch_bounds__(DK_THREADS, 1) void bwd_dkdv_kernel(
   const int k0 = blk * DK_KEYS;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int pair = wave & 3, role = wave >> 2;   // wavefronts w and w + 4 share 32 keys
   const int l32 = lane & 31;
   Q += (int64_t)head * d.nq * H;
   dO += (int64_t)head * d.nq * H;
@@ -153,20 +205,18 @@ __global__ __launch_bounds__(DK_THREADS, 1) void bwd_dkdv_kernel(
   DkCtx cx;
   cx.half = lane >> 5;
   cx.c = d.scale * kLog2e;
-  // ---- K^T / V^T B fragments of this wave's 32 keys: lane = key, h = 16 x + 8 half + 0..7.
-  // Keys beyond nkv re-read the last key; the mask zeroes their probabilities.
-  const int key = k0 + wave * 32 + l32;
+  // ---- K^T (score wave) or V^T (gradient wave) B fragments of the pair's 32 keys: lane = key,
+  // h = 16 x + 8 half + 0..7.  Keys beyond nkv re-read the last key; the mask zeroes their
+  // probabilities.
+  const int key = k0 + pair * 32 + l32;
   {
-    const int64_t off = (int64_t)min(key, d.nkv - 1) * H + 8 * cx.half;
+    const bf16_t* src = (role ? V : K) + (int64_t)min(key, d.nkv - 1) * H + 8 * cx.half;
 #pragma unroll
-    for (int x = 0; x < 8; ++x) {
-      cx.kf[x] = *reinterpret_cast<const bf16x8*>(K + off + 16 * x);
-      cx.vf[x] = *reinterpret_cast<const bf16x8*>(V + off + 16 * x);
-    }
+    for (int x = 0; x < 8; ++x) cx.frag[x] = *reinterpret_cast<const bf16x8*>(src + 16 * x);
   }
   wait_vmem_all();
 #pragma unroll
-  for (int t = 0; t < 4; ++t) { cx.dk[t] = zero16(); cx.dv[t] = zero16(); }
+  for (int t = 0; t < 4; ++t) cx.acc[t] = zero16();
 
   // query i sees key r iff i >= r - rel  (local indices), rel = q_off - kv_off
   const int64_t rel = d.q_off - d.kv_off;
@@ -177,87 +227,124 @@ __global__ __launch_bounds__(DK_THREADS, 1) void bwd_dkdv_kernel(
   };
   const int i_start = (first_row(k0) / BQ) * BQ;
   const int nsteps = (d.nq - i_start + BQ - 1) / BQ;
-  const int wk_first = k0 + wave * 32, wk_last = wk_first + 31;
+  const int wk_first = k0 + pair * 32, wk_last = wk_first + 31;
   cx.my_first = (key < d.nkv) ? first_row(key) : d.nq;       // padding keys see nothing
-  const int w_any = first_row(wk_first);                      // rows below see none of the wave's keys
+  const int w_any = first_row(wk_first);                      // rows below see none of the pair's keys
   const int w_all = (wk_last < d.nkv) ? first_row(wk_last) : d.nq;   // rows from here see all of them
 
-  cx.qa.init(lane, lds_base);
-  cx.stat = lds_base + DK_STAT + 16 * cx.half;
+  // ---- The gradient waves run ONE STEP BEHIND the score waves: in iteration j the score wave
+  // computes S, P, dV of step j and leaves P in mailbox slot j & 1, while the gradient wave of
+  // the same SIMD computes dP, dS, dK of step j - 1 from slot (j - 1) & 1.  Inside an iteration
+  // the two never wait for each other, so one's exponentials overlap the other's MFMAs; the
+  // single barrier per iteration publishes the mailbox and the next tile.  Step s lives in tile
+  // buffer s % 3 (buffer (j + 1) % 3 is filled during iteration j, while j % 3 and (j - 1) % 3
+  // are being read).  The score wave starts on buffer 0 / slot 0, the gradient wave one behind.
+  {
+    DualAddr a;
+    a.init(lane, lds_base + (role ? (DK_NBUF - 1) * DK_BUF : 0));
+    const unsigned nat_tile = role ? DK_TILE : 0, tr_tile = role ? 0 : DK_TILE;
+    cx.nat_e = a.nat_e + nat_tile; cx.nat_o = a.nat_o + nat_tile;
+    cx.tr_lo = a.tr_lo + tr_tile;  cx.tr_hi = a.tr_hi + tr_tile;
+  }
+  cx.stat = lds_base + DK_STAT + (role ? (DK_NBUF - 1) * DK_STAT_BUF + BQ * 4 : 0) + 16 * cx.half;
+  cx.mbox = lds_base + DK_MBOX + (role ? DK_MBOX_SLOT : 0) + pair * DK_MBOX_PIECE + lane * 16;
+  int cur = role ? DK_NBUF - 1 : 0;   // tile buffer of this wave's step
 
-  // ---- staging of a 64-row step in two halves of 32 rows (16 registers in flight): thread moves
-  // chunk (tid & 15) of rows (tid >> 4) + 16 p of a half.  Rows beyond nq re-read the last row;
-  // their lse entry is +inf, which makes exp2(s - lse) = 0 (also for rows whose lse is -inf).
-  static_assert(DK_THREADS == 256, "staging map assumes 256 threads");
+  // ---- staging of a 32-row step: thread moves chunk (tid & 15) of row (tid >> 4) of both tiles.
+  // Global latency is longer than an iteration, so loads run two steps ahead through two
+  // register sets.  Rows beyond nq re-read the last row; their lse entry is +inf, which makes
+  // exp2(s - lse) = 0 (also for rows whose lse is -inf).  Steps beyond the last re-stage the
+  // last one (into a buffer nobody reads any more): unconditional loads and stores keep the
+  // compiler's wait counters exact.
+  static_assert(DK_THREADS == BQ * 16, "staging map: one 16-byte chunk of each tile per thread");
   const int st_row = tid >> 4, st_ch = tid & 15;
   u32x4 qreg[2], greg[2];
-  float stat = 0.f;
-  bool stat_ok = false;
-  auto load_half = [&](int i0, int hf) {
+  float stat[2] = {0.f, 0.f};
+  bool stat_ok[2] = {false, false};
+  auto load_step = [&](int step, auto set_tag) {
+    constexpr int SET = decltype(set_tag)::value;
+    const int i0 = i_start + min(step, nsteps - 1) * BQ;
     const gptr_t qb = uniform_gptr(Q + (int64_t)i0 * H);
     const gptr_t gb = uniform_gptr(dO + (int64_t)i0 * H);
-    const int last = d.nq - 1 - i0;
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const unsigned off = (unsigned)(min(32 * hf + st_row + 16 * p, last) * (H * 2) + st_ch * 16);
-      qreg[p] = gload_b128(qb, off);
-      greg[p] = gload_b128(gb, off);
-    }
+    const unsigned off = (unsigned)(min(st_row, d.nq - 1 - i0) * (H * 2) + st_ch * 16);
+    qreg[SET] = gload_b128(qb, off);
+    greg[SET] = gload_b128(gb, off);
     // raw statistic loads only: converting here would make the wave wait for everything just issued
-    if (hf == 0 && tid < 2 * BQ) {
+    if (tid < 2 * BQ) {
       const int i = min(i0 + (tid & (BQ - 1)), d.nq - 1);
-      stat = (tid < BQ) ? lse[i] : delta[i];
-      stat_ok = (i0 + (tid & (BQ - 1))) < d.nq;
+      stat[SET] = (tid < BQ) ? lse[i] : delta[i];
+      stat_ok[SET] = (i0 + (tid & (BQ - 1))) < d.nq;
     }
   };
-  auto store_half = [&](int buf, int hf) {
+  auto store_step = [&](int buf, auto set_tag) {
+    constexpr int SET = decltype(set_tag)::value;
     char* b = lds + buf * DK_BUF;
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const int off = dual_store_off(32 * hf + st_row + 16 * p, st_ch);
-      *reinterpret_cast<u32x4*>(b + off) = qreg[p];
-      *reinterpret_cast<u32x4*>(b + DUAL64_BYTES + off) = greg[p];
-    }
-    if (hf == 0 && tid < 2 * BQ) {
-      float v = stat;
-      if (tid < BQ) v = (!stat_ok || v == -INFINITY) ? INFINITY : v * kLog2e;
-      else v = stat_ok ? v : 0.f;
-      reinterpret_cast<float*>(lds + DK_STAT + buf * 2 * BQ * 4)[tid] = v;
+    const int off = dual_store_off(st_row, st_ch);
+    *reinterpret_cast<u32x4*>(b + off) = qreg[SET];
+    *reinterpret_cast<u32x4*>(b + DK_TILE + off) = greg[SET];
+    if (tid < 2 * BQ) {
+      float v = stat[SET];
+      if (tid < BQ) v = (!stat_ok[SET] || v == -INFINITY) ? INFINITY : v * kLog2e;
+      else v = stat_ok[SET] ? v : 0.f;
+      reinterpret_cast<float*>(lds + DK_STAT + buf * DK_STAT_BUF)[tid] = v;
     }
   };
+  using set0 = std::integral_constant<int, 0>;
+  using set1 = std::integral_constant<int, 1>;
 
   if (nsteps > 0) {
-    load_half(i_start, 0); store_half(0, 0);
-    load_half(i_start, 1); store_half(0, 1);
+    load_step(0, set0{});
+    load_step(1, set1{});
+    store_step(0, set0{});
   }
   __syncthreads();
 
-  for (int j = 0; j < nsteps; ++j) {
-    const int i0 = i_start + j * BQ;
-    const bool more = j + 1 < nsteps;
-    if (more) load_half(i0 + BQ, 0);
-    // piece (SUB): rows i0 + 32 SUB .. +31.  Skipped when no row of it sees any key of the wave
-    // or it lies beyond nq; masked unless every row sees every key.
-    if (i0 + 31 >= w_any && i0 < d.nq) {
-      if (i0 >= w_all && i0 + 32 <= d.nq) dkdv_piece<0, false>(cx, i0);
-      else dkdv_piece<0, true>(cx, i0);
+  // One iteration; SET is the register set that receives step j + 2 (it held step j), the
+  // other one holds step j + 1 and is stored at the end.
+  auto iteration = [&](int j, auto set_tag) {
+    constexpr int SET = decltype(set_tag)::value;
+    load_step(j + 2, set_tag);
+    // this wave's step and its first row; a step is skipped (by both wavefronts of the pair)
+    // when none of its rows sees any of the pair's keys, it is masked unless every row sees
+    // every key
+    const int step = j - role;
+    const int i0 = i_start + step * BQ;
+    if (step >= 0 && step < nsteps && i0 + BQ - 1 >= w_any) {
+      bf16x8 n[4], t[4], bf[2];
+      f32x4 st[4], pm[4];
+      dk_first_pre(cx, n);
+      dk_stat_pre(cx, st);
+      if (role == 1) dk_mbox_pre(cx, pm);
+      f32x16 s = dk_first(cx, n);
+      dk_second_pre(cx, t);
+      if (role == 0) {
+        if (i0 >= w_all && i0 + BQ <= d.nq) dk_probs<false>(cx, st, s, bf, i0);
+        else dk_probs<true>(cx, st, s, bf, i0);
+      } else {
+        dk_dscores(st, pm, s, bf);
+      }
+      dk_second(cx, t, bf);
     }
-    if (more) { store_half((j + 1) & 1, 0); load_half(i0 + BQ, 1); }
-    if (i0 + 63 >= w_any && i0 + 32 < d.nq) {
-      if (i0 + 32 >= w_all && i0 + 64 <= d.nq) dkdv_piece<1, false>(cx, i0 + 32);
-      else dkdv_piece<1, true>(cx, i0 + 32);
-    }
-    if (more) store_half((j + 1) & 1, 1);
-    const int tog = (j & 1) ? -DK_BUF : DK_BUF;
-    cx.qa.shift(tog);
-    cx.stat += (j & 1) ? -2 * BQ * 4 : 2 * BQ * 4;
+    store_step((j + 1) % DK_NBUF, std::integral_constant<int, SET ^ 1>{});
+    // advance this wave to its next step's buffer and mailbox slot
+    const int adv = (cur == DK_NBUF - 1) ? -(DK_NBUF - 1) : 1;
+    cur += adv;
+    cx.nat_e += adv * DK_BUF; cx.nat_o += adv * DK_BUF; cx.tr_lo += adv * DK_BUF; cx.tr_hi += adv * DK_BUF;
+    cx.stat += adv * DK_STAT_BUF;
+    cx.mbox += ((SET == 1) != (role == 1)) ? -DK_MBOX_SLOT : DK_MBOX_SLOT;   // slot (step + 1) & 1
     __syncthreads();
+  };
+  if (nsteps > 0) {
+    for (int j = 0; j <= nsteps; j += 2) {    // nsteps + 1 iterations (the gradient wave's last step)
+      iteration(j, set0{});
+      if (j + 1 <= nsteps) iteration(j + 1, set1{});
+    }
   }
 
   if (key < d.nkv) {
     const int64_t row = (int64_t)head * d.nkv + key;
-    store_acc_t(dK + row * H, cx.dk, cx.half, d.scale);
-    store_acc_t(dV + row * H, cx.dv, cx.half, 1.0f);
+    if (role == 0) store_acc_t(dV + row * H, cx.acc, cx.half, 1.0f);
+    else store_acc_t(dK + row * H, cx.acc, cx.half, d.scale);
   }
 }
 
