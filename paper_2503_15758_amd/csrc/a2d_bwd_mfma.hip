@@ -62,7 +62,7 @@ __device__ __forceinline__ bf16x8 dual_nat(const DualAddr& a, int extra) {
 constexpr int DK_THREADS = 512;
 constexpr int DK_KEYS = 128;      // keys per workgroup
 constexpr int BQ = 32;            // query rows per step
-constexpr int DK_NBUF = 3;        // tile buffers: gradient waves' step, score waves' step, incoming
+constexpr int DK_NBUF = 4;        // tile buffers: gradient waves' step, score waves' step, next, incoming
 // LDS: [buf]{ Q tile, dO tile } (dual layout, 32 rows each) | [buf]{ lse*log2e [32], delta [32] } |
 //      [slot][pair] probabilities handed from the score wave to the gradient wave (fp32)
 constexpr int DK_TILE = BQ * DUAL_LD;
@@ -104,16 +104,21 @@ __device__ __forceinline__ void dk_first_pre(const DkCtx& cx, bf16x8 (&n)[4]) {
   n[0] = A2D_NAT(0); n[1] = A2D_NAT(1); n[2] = A2D_NAT(2); n[3] = A2D_NAT(3);
   A2D_FENCE
 }
-__device__ __forceinline__ f32x16 dk_first(const DkCtx& cx, bf16x8 (&n)[4]) {
-  f32x16 s = zero16();
-#define A2D_MM1(X) s = mma(n[(X) & 3], cx.frag[X], s);
+// `init` is the starting value of the sum (zero for S, -delta for dP - delta).  Two accumulators
+// (even / odd 16-wide slices of H): an MFMA that accumulates onto the result of the one issued
+// just before it would wait for that result.
+__device__ __forceinline__ f32x16 dk_first(const DkCtx& cx, bf16x8 (&n)[4], f32x16 init) {
+  f32x16 sa = init, sb = zero16();
+#define A2D_MM1(X) if ((X) & 1) sb = mma(n[(X) & 3], cx.frag[X], sb); else sa = mma(n[(X) & 3], cx.frag[X], sa);
   A2D_MM1(0) n[0] = A2D_NAT(4); A2D_FENCE
   A2D_MM1(1) n[1] = A2D_NAT(5); A2D_FENCE
   A2D_MM1(2) n[2] = A2D_NAT(6); A2D_FENCE
   A2D_MM1(3) n[3] = A2D_NAT(7); A2D_FENCE
   A2D_MM1(4) A2D_MM1(5) A2D_MM1(6) A2D_MM1(7)
 #undef A2D_MM1
-  return s;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) sa[r] += sb[r];
+  return sa;
 }
 
 // The 32 per-query statistics of the step (lse for the score wave, delta for the gradient wave)
@@ -150,13 +155,14 @@ __device__ __forceinline__ void dk_probs(const DkCtx& cx, const f32x4 (&st)[4], 
   for (int u = 0; u < 2; ++u) bf[u] = pack8(s, 8 * u);
 }
 
-// gradient wave: dS = P o (dP - delta) from the partner's probabilities
-__device__ __forceinline__ void dk_dscores(const f32x4 (&st)[4], const f32x4 (&pm)[4], f32x16& dp,
-                                           bf16x8 (&bf)[2]) {
+// gradient wave: dS = P o (dP - delta) from the partner's probabilities; `dpd` is dP - delta
+// already (the contraction started from -delta)
+__device__ __forceinline__ void dk_dscores(const f32x4 (&pm)[4], f32x16& dpd, bf16x8 (&bf)[2]) {
+  f32x16& dp = dpd;
 #pragma unroll
   for (int g = 0; g < 4; ++g)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) dp[4 * g + e] = pm[g][e] * (dp[4 * g + e] - st[g][e]);
+    for (int e = 0; e < 4; ++e) dp[4 * g + e] = pm[g][e] * dp[4 * g + e];
 #pragma unroll
   for (int u = 0; u < 2; ++u) bf[u] = pack8(dp, 8 * u);
 }
@@ -235,10 +241,12 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   // ---- The gradient waves run ONE STEP BEHIND the score waves: in iteration j the score wave
   // computes S, P, dV of step j and leaves P in mailbox slot j & 1, while the gradient wave of
   // the same SIMD computes dP, dS, dK of step j - 1 from slot (j - 1) & 1.  Inside an iteration
-  // the two never wait for each other, so one's exponentials overlap the other's MFMAs; the
-  // single barrier per iteration publishes the mailbox and the next tile.  Step s lives in tile
-  // buffer s % 3 (buffer (j + 1) % 3 is filled during iteration j, while j % 3 and (j - 1) % 3
-  // are being read).  The score wave starts on buffer 0 / slot 0, the gradient wave one behind.
+  // the two never wait for each other; the single barrier per iteration publishes the mailbox
+  // and a tile.  Step s lives in tile buffer s % 4: during iteration j buffers (j - 1) % 4 and
+  // j % 4 are being computed on, (j + 1) % 4 is complete already - so that every wave can
+  // request the first fragments of its NEXT step before the barrier and start the following
+  // iteration with its operands in registers - and (j + 2) % 4 is being filled.  The score wave
+  // starts on buffer 0 / slot 0, the gradient wave one behind.
   {
     DualAddr a;
     a.init(lane, lds_base + (role ? (DK_NBUF - 1) * DK_BUF : 0));
@@ -251,37 +259,36 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   int cur = role ? DK_NBUF - 1 : 0;   // tile buffer of this wave's step
 
   // ---- staging of a 32-row step: thread moves chunk (tid & 15) of row (tid >> 4) of both tiles.
-  // Global latency is longer than an iteration, so loads run two steps ahead through two
-  // register sets.  Rows beyond nq re-read the last row; their lse entry is +inf, which makes
-  // exp2(s - lse) = 0 (also for rows whose lse is -inf).  Steps beyond the last re-stage the
-  // last one (into a buffer nobody reads any more): unconditional loads and stores keep the
-  // compiler's wait counters exact.
+  // Global latency is longer than an iteration: step j + 4 is requested in iteration j and
+  // written to LDS in iteration j + 2, through two register sets.  Rows beyond nq re-read the
+  // last row; their lse entry is +inf, which makes exp2(s - lse) = 0 (also for rows whose lse is
+  // -inf).  Steps beyond the last re-stage the last one (into a buffer nobody reads any more):
+  // unconditional loads and stores keep the compiler's wait counters exact.
   static_assert(DK_THREADS == BQ * 16, "staging map: one 16-byte chunk of each tile per thread");
   const int st_row = tid >> 4, st_ch = tid & 15;
+  const gptr_t q_base = uniform_gptr(Q), g_base = uniform_gptr(dO);
+  const int st_off = dual_store_off(st_row, st_ch);
   u32x4 qreg[2], greg[2];
   float stat[2] = {0.f, 0.f};
   bool stat_ok[2] = {false, false};
   auto load_step = [&](int step, auto set_tag) {
     constexpr int SET = decltype(set_tag)::value;
     const int i0 = i_start + min(step, nsteps - 1) * BQ;
-    const gptr_t qb = uniform_gptr(Q + (int64_t)i0 * H);
-    const gptr_t gb = uniform_gptr(dO + (int64_t)i0 * H);
-    const unsigned off = (unsigned)(min(st_row, d.nq - 1 - i0) * (H * 2) + st_ch * 16);
-    qreg[SET] = gload_b128(qb, off);
-    greg[SET] = gload_b128(gb, off);
-    // raw statistic loads only: converting here would make the wave wait for everything just issued
-    if (tid < 2 * BQ) {
-      const int i = min(i0 + (tid & (BQ - 1)), d.nq - 1);
-      stat[SET] = (tid < BQ) ? lse[i] : delta[i];
-      stat_ok[SET] = (i0 + (tid & (BQ - 1))) < d.nq;
-    }
+    const unsigned off = (unsigned)(min(i0 + st_row, d.nq - 1) * (H * 2) + st_ch * 16);
+    qreg[SET] = gload_b128(q_base, off);
+    greg[SET] = gload_b128(g_base, off);
+    // raw statistic loads only: converting here would make the wave wait for everything just
+    // issued.  Every thread loads one (only the first 64 values are used) so that each set is
+    // the same number of loads in every wavefront.
+    const int i = min(i0 + (tid & (BQ - 1)), d.nq - 1);
+    stat[SET] = (tid & BQ) ? delta[i] : lse[i];
+    stat_ok[SET] = (i0 + (tid & (BQ - 1))) < d.nq;
   };
   auto store_step = [&](int buf, auto set_tag) {
     constexpr int SET = decltype(set_tag)::value;
     char* b = lds + buf * DK_BUF;
-    const int off = dual_store_off(st_row, st_ch);
-    *reinterpret_cast<u32x4*>(b + off) = qreg[SET];
-    *reinterpret_cast<u32x4*>(b + DK_TILE + off) = greg[SET];
+    *reinterpret_cast<u32x4*>(b + st_off) = qreg[SET];
+    *reinterpret_cast<u32x4*>(b + DK_TILE + st_off) = greg[SET];
     if (tid < 2 * BQ) {
       float v = stat[SET];
       if (tid < BQ) v = (!stat_ok[SET] || v == -INFINITY) ? INFINITY : v * kLog2e;
@@ -293,51 +300,89 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   using set1 = std::integral_constant<int, 1>;
 
   if (nsteps > 0) {
-    load_step(0, set0{});
-    load_step(1, set1{});
-    store_step(0, set0{});
+    load_step(0, set0{}); load_step(1, set1{});
+    store_step(0, set0{}); store_step(1, set1{});
+    load_step(2, set0{}); load_step(3, set1{});
   }
   __syncthreads();
 
-  // One iteration; SET is the register set that receives step j + 2 (it held step j), the
-  // other one holds step j + 1 and is stored at the end.
-  auto iteration = [&](int j, auto set_tag) {
-    constexpr int SET = decltype(set_tag)::value;
-    load_step(j + 2, set_tag);
-    // this wave's step and its first row; a step is skipped (by both wavefronts of the pair)
-    // when none of its rows sees any of the pair's keys, it is masked unless every row sees
-    // every key
-    const int step = j - role;
-    const int i0 = i_start + step * BQ;
-    if (step >= 0 && step < nsteps && i0 + BQ - 1 >= w_any) {
-      bf16x8 n[4], t[4], bf[2];
-      f32x4 st[4], pm[4];
-      dk_first_pre(cx, n);
-      dk_stat_pre(cx, st);
-      if (role == 1) dk_mbox_pre(cx, pm);
-      f32x16 s = dk_first(cx, n);
-      dk_second_pre(cx, t);
-      if (role == 0) {
-        if (i0 >= w_all && i0 + BQ <= d.nq) dk_probs<false>(cx, st, s, bf, i0);
-        else dk_probs<true>(cx, st, s, bf, i0);
-      } else {
-        dk_dscores(st, pm, s, bf);
-      }
-      dk_second(cx, t, bf);
-    }
-    store_step((j + 1) % DK_NBUF, std::integral_constant<int, SET ^ 1>{});
-    // advance this wave to its next step's buffer and mailbox slot
+  // A step is skipped (by both wavefronts of its pair) when none of its rows sees any of the
+  // pair's keys; it is masked unless every row sees every key.
+  auto active = [&](int step) { return step >= 0 && step < nsteps && i_start + step * BQ + BQ - 1 >= w_any; };
+  auto advance = [&](int slot_delta) {   // to this wave's next step: tile buffer and mailbox slot
     const int adv = (cur == DK_NBUF - 1) ? -(DK_NBUF - 1) : 1;
     cur += adv;
     cx.nat_e += adv * DK_BUF; cx.nat_o += adv * DK_BUF; cx.tr_lo += adv * DK_BUF; cx.tr_hi += adv * DK_BUF;
     cx.stat += adv * DK_STAT_BUF;
-    cx.mbox += ((SET == 1) != (role == 1)) ? -DK_MBOX_SLOT : DK_MBOX_SLOT;   // slot (step + 1) & 1
-    __syncthreads();
+    cx.mbox += slot_delta;
   };
-  if (nsteps > 0) {
-    for (int j = 0; j <= nsteps; j += 2) {    // nsteps + 1 iterations (the gradient wave's last step)
+
+  // The two roles go through an iteration in opposite phase, so that on every SIMD one wave's
+  // element-wise work coincides with the other's MFMAs:
+  //   score wave     S (8 MFMAs)          | exponentials          | dV (8 MFMAs)
+  //   gradient wave  dS of step j - 1     | dK of step j - 1      | dP of step j (8 MFMAs each)
+  // In iteration j, SET is the register set that holds step j + 2 and then receives step j + 4.
+  if (nsteps > 0 && role == 0) {
+    // first natural fragments and lse values of the coming step, requested an iteration ahead
+    bf16x8 n[4];
+    f32x4 st[4];
+    dk_first_pre(cx, n);
+    dk_stat_pre(cx, st);
+    auto iteration = [&](int j, auto set_tag) {
+      constexpr int SET = decltype(set_tag)::value;
+      store_step((j + 2) % DK_NBUF, set_tag);
+      load_step(j + 4, set_tag);
+      if (active(j)) {
+        const int i0 = i_start + j * BQ;
+        bf16x8 t[4], bf[2];
+        f32x16 s = dk_first(cx, n, zero16());
+        dk_second_pre(cx, t);
+        if (i0 >= w_all && i0 + BQ <= d.nq) dk_probs<false>(cx, st, s, bf, i0);
+        else dk_probs<true>(cx, st, s, bf, i0);
+        dk_second(cx, t, bf);
+      }
+      advance(SET ? -DK_MBOX_SLOT : DK_MBOX_SLOT);
+      dk_first_pre(cx, n);
+      dk_stat_pre(cx, st);
+      __syncthreads();
+    };
+    // nsteps + 1 iterations (the gradient wave's last step), rounded up to an even number: an
+    // iteration beyond that finds no step to compute, and straight-line control flow keeps the
+    // wait counters exact
+    for (int j = 0; j <= nsteps; j += 2) {
       iteration(j, set0{});
-      if (j + 1 <= nsteps) iteration(j + 1, set1{});
+      iteration(j + 1, set1{});
+    }
+  } else if (nsteps > 0) {
+    f32x16 dp = zero16();   // dP - delta of the step whose dS, dK come next iteration
+    auto iteration = [&](int j, auto set_tag) {
+      constexpr int SET = decltype(set_tag)::value;
+      store_step((j + 2) % DK_NBUF, set_tag);
+      load_step(j + 4, set_tag);
+      if (active(j - 1)) {
+        bf16x8 t[4], bf[2];
+        f32x4 pm[4];
+        dk_mbox_pre(cx, pm);
+        dk_second_pre(cx, t);
+        dk_dscores(pm, dp, bf);
+        dk_second(cx, t, bf);
+      }
+      advance(SET ? DK_MBOX_SLOT : -DK_MBOX_SLOT);
+      if (active(j)) {
+        bf16x8 n[4];
+        f32x4 st[4];
+        dk_first_pre(cx, n);
+        dk_stat_pre(cx, st);
+        f32x16 init;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) init[r] = -st[r >> 2][r & 3];
+        dp = dk_first(cx, n, init);
+      }
+      __syncthreads();
+    };
+    for (int j = 0; j <= nsteps; j += 2) {
+      iteration(j, set0{});
+      iteration(j + 1, set1{});
     }
   }
 
