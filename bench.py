@@ -12,6 +12,9 @@ All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
                      its duration measured with events on the launch stream inside the timed region
   kernels          = the same for every call of the step (fix / fix_bwd against the HBM peak)
   cpu_baseline     = the fp64 oracle timed on the host cores on a bounded sample
+  mfma_ceiling     = what the bf16 MFMA units sustain on their own on this chip (diagnostic probe of the
+                     library: register operands, no other work), with random and with constant operands,
+                     and the shader clock during each; context for the roofline fraction, not its peak
 """
 import argparse
 import json
@@ -32,10 +35,10 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # their kernels (partial_bwd = delta + dK/dV + dQ kernels).  Only the default workload was counted.
 MIB = float(1 << 20)
 TRAFFIC_BYTES = {"c3": {
-    "partial_fwd_diag": (289.8 + 197.4) * MIB, "partial_fwd_full": (289.8 + 197.4) * MIB,
-    "partial_bwd_diag": (192.0 + 387.2 + 391.0 + 1.5 + 391.7 + 193.7) * MIB,
-    "partial_bwd_full": (192.0 + 387.2 + 391.0 + 1.5 + 391.7 + 193.7) * MIB,
-    "fix": (1632.0 + 97.5) * MIB, "fix_bwd_dq": (1536.0 + 96.0) * MIB,
+    "partial_fwd_diag": (291.0 + 195.0) * MIB, "partial_fwd_full": (291.0 + 195.0) * MIB,
+    "partial_bwd_diag": (192.0 + 387.2 + 412.0 + 1.5 + 384.2 + 193.6) * MIB,
+    "partial_bwd_full": (192.0 + 387.2 + 412.0 + 1.5 + 384.2 + 193.6) * MIB,
+    "fix": (1632.1 + 97.5) * MIB, "fix_bwd_dq": (1536.0 + 96.0) * MIB,
     "fix_bwd_dk": (1536.0 + 96.0) * MIB, "fix_bwd_dv": (1536.0 + 96.0) * MIB}}
 
 
@@ -54,6 +57,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-probe", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed steps run one plain 1 GiB device copy (torch copy_), so that a "
                          "rocprofv3 --pmc run of this command also holds the counter reading of a copy of "
@@ -204,6 +208,12 @@ def main():
         "attnfix_gbs": kernels["fix"]["achieved"], "attnfix_frac_hbm": kernels["fix"]["frac"],
         "roofline": roofline, "kernels": kernels,
     }
+    if not args.no_mfma_probe:
+        tf_r, mhz_r = a2d.mfma_ceiling(20000, True)
+        tf_c, mhz_c = a2d.mfma_ceiling(20000, False)
+        result["mfma_ceiling"] = {"random_operands": {"tflops": round(tf_r, 1), "shader_mhz": round(mhz_r)},
+                                  "constant_operands": {"tflops": round(tf_c, 1), "shader_mhz": round(mhz_c)},
+                                  "unit": "TFLOP/s", "kind": "MFMA-only probe, register operands"}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, scale)
     print(json.dumps(result))

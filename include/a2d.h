@@ -141,6 +141,22 @@ a2d_status a2d_partial_bwd(const a2d_tile_desc* desc, const void* Q, const void*
 a2d_status a2d_fix_bwd(int k, int64_t n, int32_t out_dtype, const float* const* parts,
                        void* out, void* stream);
 
+/*
+ * Diagnostic, not part of the method: the rate the bf16 MFMA units of the current device
+ * sustain on their own (register operands only, several wavefronts per SIMD, four independent
+ * accumulators per wavefront), for pricing the tile kernels against what the chip delivers
+ * rather than the data-sheet number.  The MFMA rate depends on the operand values (power):
+ * random_data != 0 uses pseudo-random values of unit scale, 0 uses the constant 0.5.
+ * Unlike the compute calls this one is SYNCHRONOUS: it runs on the default stream, waits, and
+ * writes HOST results: *tflops (dense bf16 TFLOP/s over the whole chip) and *shader_mhz (the
+ * shader clock during the run).  scratch: device memory of at least
+ * a2d_mfma_ceiling_scratch_bytes() bytes (0 if the device cannot be queried), overwritten.
+ * iters: MFMA groups of 16 per wavefront, 1 .. 2^22 (20000 is about 10 ms).
+ */
+size_t a2d_mfma_ceiling_scratch_bytes(void);
+a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t scratch_bytes,
+                            double* tflops, double* shader_mhz);
+
 /* Static string for a status code. */
 const char* a2d_status_str(a2d_status status);
 /* Detail of the calling thread's last failed call ("" if none). */

@@ -18,6 +18,7 @@ OP_PARTIAL_FWD, OP_FIX, OP_PARTIAL_BWD, OP_FIX_BWD = 0, 1, 2, 3
 MAX_PARTS = 32
 
 EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
+           "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling",
            "a2d_status_str", "a2d_last_error", "a2d_version")
 
 
@@ -59,6 +60,11 @@ def lib():
         L.a2d_fix_bwd.restype = ctypes.c_int
         L.a2d_fix_bwd.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(vp),
                                   vp, vp]
+        L.a2d_mfma_ceiling_scratch_bytes.restype = ctypes.c_size_t
+        L.a2d_mfma_ceiling_scratch_bytes.argtypes = []
+        L.a2d_mfma_ceiling.restype = ctypes.c_int
+        L.a2d_mfma_ceiling.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t,
+                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.a2d_status_str.restype = ctypes.c_char_p
         L.a2d_status_str.argtypes = [ctypes.c_int]
         L.a2d_last_error.restype = ctypes.c_char_p
@@ -179,6 +185,16 @@ def fix_bwd(parts, out_dtype=torch.bfloat16, out=None):
     _check(lib().a2d_fix_bwd(k, parts[0].numel(), _dtype_code(out.dtype), _ptr_array(parts), _ptr(out),
                              _stream()))
     return out
+
+
+def mfma_ceiling(iters=20000, random_data=True):
+    """Diagnostic (a2d_mfma_ceiling): (dense bf16 TFLOP/s of the MFMA units alone, shader MHz)."""
+    n = int(lib().a2d_mfma_ceiling_scratch_bytes())
+    scratch = torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
+    tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(lib().a2d_mfma_ceiling(int(iters), int(bool(random_data)), _ptr(scratch), scratch.numel(),
+                                  ctypes.byref(tf), ctypes.byref(mhz)))
+    return tf.value, mhz.value
 
 
 def version():

@@ -188,6 +188,53 @@ const char* a2d_status_str(a2d_status status) {
   return "unknown status";
 }
 
+size_t a2d_mfma_ceiling_scratch_bytes(void) {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    return 0;
+  // four workgroups per compute unit: enough wavefronts to keep every SIMD's MFMA pipe full
+  // however the dispatcher spreads them
+  return (size_t)4 * cus * a2d::mfma_probe_threads() * sizeof(float) + 16;
+}
+
+a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t scratch_bytes,
+                            double* tflops, double* shader_mhz) {
+  const char* who = "a2d_mfma_ceiling";
+  if (iters < 1 || iters > (1 << 22)) return fail(A2D_ERR_INVALID_ARG, "%s: iters=%d outside 1..2^22", who, iters);
+  if (!tflops || !shader_mhz) return fail(A2D_ERR_INVALID_ARG, "%s: result pointer is NULL", who);
+  A2D_TRY(check_ptr(scratch, who, "scratch"));
+  const size_t need = a2d_mfma_ceiling_scratch_bytes();
+  if (need == 0) return fail(A2D_ERR_HIP, "%s: cannot query the device", who);
+  if (scratch_bytes < need)
+    return fail(A2D_ERR_WORKSPACE, "%s: scratch of %zu bytes, %zu needed", who, scratch_bytes, need);
+  const int blocks = (int)((need - 16) / (a2d::mfma_probe_threads() * sizeof(float)));
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+    return fail(A2D_ERR_HIP, "%s: hipEventCreate failed", who);
+  float* sc = static_cast<float*>(scratch);
+  hipError_t e = a2d::launch_mfma_probe(blocks, iters, random_data, sc, nullptr);   // warm-up, clocks settle
+  if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+  if (e == hipSuccess) e = hipEventRecord(e0, nullptr);
+  if (e == hipSuccess) e = a2d::launch_mfma_probe(blocks, iters, random_data, sc, nullptr);
+  if (e == hipSuccess) e = hipEventRecord(e1, nullptr);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  unsigned long long clocks[2] = {0, 0};
+  if (e == hipSuccess)
+    e = hipMemcpy(clocks, sc + (size_t)blocks * a2d::mfma_probe_threads(), sizeof(clocks), hipMemcpyDeviceToHost);
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
+  if (e != hipSuccess) return hip_result(e, who);
+  // every wavefront issues iters * 16 MFMAs of 2 * 32 * 32 * 16 flop; 8 wavefronts per workgroup
+  const double flop = (double)blocks * (a2d::mfma_probe_threads() / 64) * iters *
+                      a2d::mfma_probe_mfma_per_iter() * 2.0 * 32 * 32 * 16;
+  *tflops = flop / (ms * 1e-3) / 1e12;
+  *shader_mhz = clocks[1] ? (double)clocks[0] / ((double)clocks[1] / 100.0) : 0.0;   // 100 MHz wall counter
+  return A2D_OK;
+}
+
 const char* a2d_last_error(void) { return g_err; }
 
 const char* a2d_version(void) { return "0.1"; }

@@ -69,4 +69,9 @@ hipError_t launch_fix(int k, int64_t rows, int hdim, int out_dtype, const FixPtr
 hipError_t launch_fix_bwd(int k, int64_t n, int out_dtype, const SumPtrs& p, void* out,
                           hipStream_t s);
 
+// MFMA-only ceiling probe (diagnostic)
+hipError_t launch_mfma_probe(int blocks, int iters, int random_data, float* scratch, hipStream_t s);
+int mfma_probe_threads();
+int mfma_probe_mfma_per_iter();
+
 }  // namespace a2d

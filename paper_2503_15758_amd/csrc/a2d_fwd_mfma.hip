@@ -62,9 +62,11 @@ __device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], u
   s[0] = zero16();
   s[1] = zero16();
   bf16x8 kr[4];
-#define A2D_LDK(I) kr[(I) & 3] = lds_load_b128(k_rd + ((I) >> 3) * 32 * KLD + ((I) & 7) * 32);
+  // step I works on key tile I & 1, slice I >> 1 of H: the two accumulators alternate, so that no
+  // MFMA accumulates onto the result of the one issued just before it
+#define A2D_LDK(I) kr[(I) & 3] = lds_load_b128(k_rd + ((I) & 1) * 32 * KLD + ((I) >> 1) * 32);
 #define A2D_S(I)                                              \
-  s[(I) >> 3] = mma(kr[(I) & 3], qf[(I) & 7], s[(I) >> 3]);   \
+  s[(I) & 1] = mma(kr[(I) & 3], qf[(I) >> 1], s[(I) & 1]);    \
   if ((I) + 4 < 16) { A2D_LDK(((I) + 4) & 15) }               \
   __builtin_amdgcn_sched_barrier(0);
   A2D_LDK(0) A2D_LDK(1) A2D_LDK(2) A2D_LDK(3)

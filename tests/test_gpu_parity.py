@@ -318,3 +318,16 @@ def test_long_context_tiles_sampled(a2d, name):
                                    np64(lse[:1]), 0, 0, False, scale)
     assert_close(np64(dK[:1, ksub]), rK, torch.bfloat16, name + " dK sampled keys")
     assert_close(np64(dV[:1, ksub]), rV, torch.bfloat16, name + " dV sampled keys")
+
+
+@pytest.mark.gpu
+def test_mfma_ceiling_probe_runs(a2d):
+    """The diagnostic MFMA-only probe returns a plausible rate and clock, and rejects a short scratch."""
+    tf, mhz = a2d.mfma_ceiling(2000, True)
+    assert 100.0 < tf < 20000.0 and 300.0 < mhz < 4000.0
+    import ctypes
+    scratch = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    t, m = ctypes.c_double(), ctypes.c_double()
+    rc = a2d.lib().a2d_mfma_ceiling(10, 0, ctypes.c_void_p(scratch.data_ptr()), scratch.numel(),
+                                    ctypes.byref(t), ctypes.byref(m))
+    assert rc == -4

@@ -100,3 +100,15 @@ def test_binding_rejects_cpu_tensors(binding):
     x = torch.zeros(1, 4, 128, dtype=torch.bfloat16)
     with pytest.raises(binding.A2DError):
         binding.partial_fwd(x, x, x)
+
+
+def test_mfma_ceiling_argument_errors(binding):
+    """The diagnostic probe validates before it touches the device."""
+    L = binding.lib()
+    P = ctypes.c_void_p(0x10000)
+    tf, mhz = ctypes.c_double(), ctypes.c_double()
+    assert L.a2d_mfma_ceiling(0, 1, P, 1 << 20, ctypes.byref(tf), ctypes.byref(mhz)) == -1
+    assert L.a2d_mfma_ceiling(1 << 23, 1, P, 1 << 20, ctypes.byref(tf), ctypes.byref(mhz)) == -1
+    assert L.a2d_mfma_ceiling(10, 1, P, 1 << 20, None, ctypes.byref(mhz)) == -1
+    assert L.a2d_mfma_ceiling(10, 1, None, 1 << 20, ctypes.byref(tf), ctypes.byref(mhz)) == -1
+    assert L.a2d_mfma_ceiling(10, 1, ctypes.c_void_p(0x10004), 1 << 20, ctypes.byref(tf), ctypes.byref(mhz)) == -3
