@@ -18,9 +18,9 @@
 //                    one barrier per step is the only synchronisation.  S and dP leave a lane
 //                    holding ONE key column, so P and dS feed the second contractions directly
 //                    as B operands; dO^T / Q^T come from the LDS transpose read.
-//   bwd_dq_kernel    owns query rows.  Workgroup = 4 wavefronts = 128 queries (32 per
-//                    wavefront, Q and dO fragments in registers), two workgroups per
-//                    compute unit; walks the key blocks, 64 keys per step.  S^T = K Q^T
+//   bwd_dq_kernel    owns query rows.  Workgroup = 8 wavefronts = 256 queries (32 per
+//                    wavefront, Q and dO fragments in registers), two wavefronts per
+//                    SIMD; walks the key blocks, 64 keys per step.  S^T = K Q^T
 //                    and dP^T = V dO^T leave a lane holding ONE query column;
 //                    dQ^T += K^T dS^T with K^T from the LDS transpose read.
 // Tiles that are read both ways (natural and transposed fragments) live in the "dual" LDS
@@ -394,8 +394,8 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
 }
 
 // ---------------------------------------------------------------------- dQ
-constexpr int DQ_THREADS = 256;
-constexpr int DQ_ROWS = 128;      // query rows per workgroup
+constexpr int DQ_THREADS = 512;
+constexpr int DQ_ROWS = 256;      // query rows per workgroup
 constexpr int BKS = 64;           // keys per step
 constexpr int VT_LD = 272;        // V tile row stride (natural reads only)
 // LDS: [buf]{ K tile (dual layout), V tile (272-byte rows) }
@@ -466,7 +466,7 @@ __device__ __forceinline__ void dq_piece(DqCtx& cx, int key0) {
 #undef A2D_LD2
 }
 
-__global__ __launch_bounds__(DQ_THREADS, 2) void bwd_dq_kernel(
+__global__ __launch_bounds__(DQ_THREADS) void bwd_dq_kernel(
     a2d_tile_desc d, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ delta, float* __restrict__ dQ) {
@@ -522,30 +522,23 @@ __global__ __launch_bounds__(DQ_THREADS, 2) void bwd_dq_kernel(
   cx.ka.init(lane, lds_base);
   cx.vnat = lds_base + DQ_VT + l32 * VT_LD + 16 * cx.half;
 
-  // ---- staging, in two halves of 32 key rows so that only 16 registers are in flight: thread
-  // moves chunk (tid & 15) of rows (tid >> 4) + 16 p of a half.  Rows beyond nkv re-read the last
-  // row (finite values, masked out).
+  // ---- staging, in two halves of 32 key rows: thread moves chunk (tid & 15) of row (tid >> 4) of
+  // a half.  Rows beyond nkv re-read the last row (finite values, masked out).
+  static_assert(DQ_THREADS == 32 * 16, "staging map: one 16-byte chunk of each tile per thread and half");
   const int st_row = tid >> 4, st_ch = tid & 15;
-  u32x4 kreg[2], vreg[2];
+  u32x4 kreg, vreg;
   auto load_half = [&](int k0, int hf) {
     const gptr_t kb = uniform_gptr(K + (int64_t)k0 * H);
     const gptr_t vb = uniform_gptr(V + (int64_t)k0 * H);
-    const int last = d.nkv - 1 - k0;
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const unsigned off = (unsigned)(min(32 * hf + st_row + 16 * p, last) * (H * 2) + st_ch * 16);
-      kreg[p] = gload_b128(kb, off);
-      vreg[p] = gload_b128(vb, off);
-    }
+    const unsigned off = (unsigned)(min(32 * hf + st_row, d.nkv - 1 - k0) * (H * 2) + st_ch * 16);
+    kreg = gload_b128(kb, off);
+    vreg = gload_b128(vb, off);
   };
   auto store_half = [&](int buf, int hf) {
     char* b = lds + buf * DQ_BUF;
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const int row = 32 * hf + st_row + 16 * p;
-      *reinterpret_cast<u32x4*>(b + dual_store_off(row, st_ch)) = kreg[p];
-      *reinterpret_cast<u32x4*>(b + DQ_VT + row * VT_LD + st_ch * 16) = vreg[p];
-    }
+    const int row = 32 * hf + st_row;
+    *reinterpret_cast<u32x4*>(b + dual_store_off(row, st_ch)) = kreg;
+    *reinterpret_cast<u32x4*>(b + DQ_VT + row * VT_LD + st_ch * 16) = vreg;
   };
 
   if (nblk > 0) {
