@@ -66,6 +66,9 @@ FWD_CASES = [
     (1, 96, 64, 64, True, 0, 1),             # the cyclic layout's r < c tile
     (1, 64, 64, 128, True, 0, 1000),         # wholly above the diagonal
     (2, 384, 512, 128, True, 256, 128),      # several blocks, offset diagonal
+    (1, 513, 257, 128, False, 0, 0),         # ragged tails past whole 256-row / 128-key workgroups
+    (2, 600, 333, 128, True, 40, 0),         # diagonal crossing several workgroups, ragged
+    (1, 700, 900, 128, True, 300, 100),      # more keys than queries, offset diagonal
 ]
 
 
@@ -133,6 +136,9 @@ BWD_CASES = [
     (1, 200, 131, 128, True, 0, 5),
     (1, 64, 64, 128, True, 0, 1000),
     (1, 384, 512, 128, True, 256, 128),
+    (1, 513, 257, 128, False, 0, 0),
+    (2, 600, 333, 128, True, 40, 0),
+    (1, 700, 900, 128, True, 300, 100),
 ]
 
 
