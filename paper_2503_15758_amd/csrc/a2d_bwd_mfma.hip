@@ -394,8 +394,6 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
 }
 
 // ---------------------------------------------------------------------- dQ
-constexpr int DQ_THREADS = 512;
-constexpr int DQ_ROWS = 256;      // query rows per workgroup
 constexpr int BKS = 64;           // keys per step
 constexpr int VT_LD = 272;        // V tile row stride (natural reads only)
 // LDS: [buf]{ K tile (dual layout), V tile (272-byte rows) }
@@ -466,12 +464,18 @@ __device__ __forceinline__ void dq_piece(DqCtx& cx, int key0) {
 #undef A2D_LD2
 }
 
-__global__ __launch_bounds__(DQ_THREADS) void bwd_dq_kernel(
+// WAVES wavefronts (32 query rows each) per workgroup: 8 fill a compute unit with one workgroup;
+// 4 (two workgroups per compute unit) are used when there are too few 256-row blocks to give
+// every compute unit one.
+template <int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
     a2d_tile_desc d, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ delta, float* __restrict__ dQ) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+  constexpr int DQ_ROWS = 32 * WAVES;      // query rows per workgroup
+  constexpr int DQ_THREADS = 64 * WAVES;
   const int nqb = (d.nq + DQ_ROWS - 1) / DQ_ROWS;
   int head, blk;
   if (!xcd_map(d.heads, nqb, head, blk)) return;
@@ -522,23 +526,31 @@ __global__ __launch_bounds__(DQ_THREADS) void bwd_dq_kernel(
   cx.ka.init(lane, lds_base);
   cx.vnat = lds_base + DQ_VT + l32 * VT_LD + 16 * cx.half;
 
-  // ---- staging, in two halves of 32 key rows: thread moves chunk (tid & 15) of row (tid >> 4) of
-  // a half.  Rows beyond nkv re-read the last row (finite values, masked out).
-  static_assert(DQ_THREADS == 32 * 16, "staging map: one 16-byte chunk of each tile per thread and half");
+  // ---- staging, in two halves of 32 key rows: thread moves chunk (tid & 15) of rows
+  // (tid >> 4) + ST_ROWS p of a half.  Rows beyond nkv re-read the last row (finite values,
+  // masked out).
+  constexpr int ST_ROWS = DQ_THREADS / 16, ST_N = 32 / ST_ROWS;
   const int st_row = tid >> 4, st_ch = tid & 15;
-  u32x4 kreg, vreg;
+  u32x4 kreg[ST_N], vreg[ST_N];
   auto load_half = [&](int k0, int hf) {
     const gptr_t kb = uniform_gptr(K + (int64_t)k0 * H);
     const gptr_t vb = uniform_gptr(V + (int64_t)k0 * H);
-    const unsigned off = (unsigned)(min(32 * hf + st_row, d.nkv - 1 - k0) * (H * 2) + st_ch * 16);
-    kreg = gload_b128(kb, off);
-    vreg = gload_b128(vb, off);
+    const int last = d.nkv - 1 - k0;
+#pragma unroll
+    for (int p = 0; p < ST_N; ++p) {
+      const unsigned off = (unsigned)(min(32 * hf + st_row + ST_ROWS * p, last) * (H * 2) + st_ch * 16);
+      kreg[p] = gload_b128(kb, off);
+      vreg[p] = gload_b128(vb, off);
+    }
   };
   auto store_half = [&](int buf, int hf) {
     char* b = lds + buf * DQ_BUF;
-    const int row = 32 * hf + st_row;
-    *reinterpret_cast<u32x4*>(b + dual_store_off(row, st_ch)) = kreg;
-    *reinterpret_cast<u32x4*>(b + DQ_VT + row * VT_LD + st_ch * 16) = vreg;
+#pragma unroll
+    for (int p = 0; p < ST_N; ++p) {
+      const int row = 32 * hf + st_row + ST_ROWS * p;
+      *reinterpret_cast<u32x4*>(b + dual_store_off(row, st_ch)) = kreg[p];
+      *reinterpret_cast<u32x4*>(b + DQ_VT + row * VT_LD + st_ch * 16) = vreg[p];
+    }
   };
 
   if (nblk > 0) {
@@ -579,17 +591,29 @@ hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K,
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, DK_LDS);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_kernel),
+  // dQ kernel: eight wavefronts per workgroup unless that leaves compute units without a workgroup
+  int dev = 0, cus = 0;
+  e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return e;
+  const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
+  e = hipFuncSetAttribute(big ? reinterpret_cast<const void*>(bwd_dq_kernel<8>)
+                              : reinterpret_cast<const void*>(bwd_dq_kernel<4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
   if (e != hipSuccess) return e;
   dim3 grid_kv(xcd_grid(d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS));
-  dim3 grid_q(xcd_grid(d.heads, (d.nq + DQ_ROWS - 1) / DQ_ROWS));
+  const int dq_rows = big ? 256 : 128;
+  dim3 grid_q(xcd_grid(d.heads, (d.nq + dq_rows - 1) / dq_rows));
   hipLaunchKernelGGL(bwd_dkdv_kernel, grid_kv, dim3(DK_THREADS), DK_LDS, s, d, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bwd_dq_kernel, grid_q, dim3(DQ_THREADS), DQ_LDS, s, d, (const bf16_t*)Q,
-                     (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
+  if (big)
+    hipLaunchKernelGGL(bwd_dq_kernel<8>, grid_q, dim3(512), DQ_LDS, s, d, (const bf16_t*)Q,
+                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
+  else
+    hipLaunchKernelGGL(bwd_dq_kernel<4>, grid_q, dim3(256), DQ_LDS, s, d, (const bf16_t*)Q,
+                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
   return hipGetLastError();
 }
 

@@ -35,9 +35,7 @@ namespace {
 
 using namespace mfma;
 
-constexpr int BM = 256;            // query rows per workgroup
 constexpr int BN = 64;             // keys per step
-constexpr int kThreads = 512;
 constexpr int KLD = 272;           // K tile row stride, bytes
 constexpr int VLD = 320;           // V tile row stride, bytes
 constexpr int K_BYTES = BN * KLD;
@@ -139,10 +137,16 @@ __device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], u
 #undef A2D_LDV
 }
 
-__global__ __launch_bounds__(kThreads) void fwd_mfma_kernel(
+// WAVES wavefronts (32 query rows each) per workgroup: 8 fill a compute unit with one workgroup;
+// 4 (two workgroups per compute unit) are used when there are too few 256-row blocks to give
+// every compute unit one.
+template <int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
     a2d_tile_desc d, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, float* __restrict__ O_part, float* __restrict__ m_out,
     float* __restrict__ l_out) {
+  constexpr int BM = 32 * WAVES;          // query rows per workgroup
+  constexpr int kThreads = 64 * WAVES;
   extern __shared__ __attribute__((aligned(16))) char lds[];
   // [buf]{ K tile (BN x KLD), V tile (BN x VLD) }
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
@@ -273,12 +277,24 @@ bool fwd_mfma_supported(const a2d_tile_desc& d) {
 
 hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
                            float* O_part, float* m, float* l, hipStream_t s) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_mfma_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  // eight wavefronts per workgroup unless that leaves compute units without a workgroup
+  int dev = 0, cus = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) return e;
-  dim3 grid(xcd_grid(d.heads, (d.nq + BM - 1) / BM)), block(kThreads);
-  hipLaunchKernelGGL(fwd_mfma_kernel, grid, block, kLdsBytes, s, d, (const bf16_t*)Q, (const bf16_t*)K,
-                     (const bf16_t*)V, O_part, m, l);
+  const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
+  const void* fn = big ? reinterpret_cast<const void*>(fwd_mfma_kernel<8>)
+                       : reinterpret_cast<const void*>(fwd_mfma_kernel<4>);
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  if (e != hipSuccess) return e;
+  const int bm = big ? 256 : 128;
+  dim3 grid(xcd_grid(d.heads, (d.nq + bm - 1) / bm)), block(big ? 512 : 256);
+  if (big)
+    hipLaunchKernelGGL(fwd_mfma_kernel<8>, grid, block, kLdsBytes, s, d, (const bf16_t*)Q, (const bf16_t*)K,
+                       (const bf16_t*)V, O_part, m, l);
+  else
+    hipLaunchKernelGGL(fwd_mfma_kernel<4>, grid, block, kLdsBytes, s, d, (const bf16_t*)Q, (const bf16_t*)K,
+                       (const bf16_t*)V, O_part, m, l);
   return hipGetLastError();
 }
 
