@@ -111,6 +111,48 @@ def partial_fwd(Q, K, V, q_off, kv_off, causal, scale):
     return N, m, d
 
 
+def segment_positions(segments):
+    """Global key indices of a gathered KV tile: the concatenation of sub-blocks, sub-block s
+    being `rows` consecutive tokens starting at token `kv_off` (list of (kv_off, rows))."""
+    pos = [np.arange(off, off + rows, dtype=np.int64) for off, rows in segments]
+    return np.ascontiguousarray(np.concatenate(pos) if pos else np.zeros(0, dtype=np.int64))
+
+
+def partial_fwd_pos(Q, K, V, q_off, kpos, causal, scale):
+    """Eq. (3) on one tile whose key r is token kpos[r]. Returns (N, m, d)."""
+    Q, K, V = _c(Q), _c(K), _c(V)
+    kpos = np.ascontiguousarray(kpos, dtype=np.int64)
+    heads, nq, H = Q.shape
+    nkv = K.shape[1]
+    assert K.shape == (heads, nkv, H) and V.shape == K.shape and kpos.shape == (nkv,)
+    N = np.empty((heads, nq, H))
+    m = np.empty((heads, nq))
+    d = np.empty((heads, nq))
+    _load().a2d_oracle_partial_fwd_pos(
+        ctypes.c_int(heads), ctypes.c_int(nq), ctypes.c_int(nkv), ctypes.c_int(H),
+        _p(Q), _p(K), _p(V), ctypes.c_int64(q_off), kpos.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+        ctypes.c_int(int(causal)), ctypes.c_double(scale), _p(N), _p(m), _p(d))
+    return N, m, d
+
+
+def partial_bwd_pos(Q, K, V, O, dO, lse, q_off, kpos, causal, scale):
+    """Per-tile gradients for a tile whose key r is token kpos[r]. Returns (dQ, dK, dV) partials."""
+    Q, K, V, O, dO, lse = map(_c, (Q, K, V, O, dO, lse))
+    kpos = np.ascontiguousarray(kpos, dtype=np.int64)
+    heads, nq, H = Q.shape
+    nkv = K.shape[1]
+    assert O.shape == Q.shape and dO.shape == Q.shape and lse.shape == (heads, nq) and kpos.shape == (nkv,)
+    dQ = np.empty((heads, nq, H))
+    dK = np.empty((heads, nkv, H))
+    dV = np.empty((heads, nkv, H))
+    _load().a2d_oracle_partial_bwd_pos(
+        ctypes.c_int(heads), ctypes.c_int(nq), ctypes.c_int(nkv), ctypes.c_int(H),
+        _p(Q), _p(K), _p(V), _p(O), _p(dO), _p(lse), ctypes.c_int64(q_off),
+        kpos.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), ctypes.c_int(int(causal)),
+        ctypes.c_double(scale), _p(dQ), _p(dK), _p(dV))
+    return dQ, dK, dV
+
+
 def attnfix_pair(M1, N1, D1, M2, N2, D2):
     """Alg. 2 on two partial triples. Returns (M, N, D)."""
     M1, N1, D1, M2, N2, D2 = map(_c, (M1, N1, D1, M2, N2, D2))

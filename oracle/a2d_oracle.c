@@ -11,6 +11,11 @@
  *     scale the paper's footnote in Sec. 2.1 leaves out, passed explicitly) and
  *     the textbook gradient of that expression,
  *   - partial_fwd                   : Sec. 3.1, Eq. (3),
+ *   - partial_fwd_pos / _bwd_pos    : the same tile computations when the keys of the tile
+ *                                     carry arbitrary global positions (the gathered K_g, V_g
+ *                                     of Alg. GatherComputeScatter line "Compute", whose
+ *                                     sub-blocks come from different devices; Sec. 5 names the
+ *                                     resulting step-like mask),
  *   - attnfix_pair                  : Alg. 2 (AttnFix),
  *   - fix                           : Alg. 2 folded over k partials followed by
  *                                     O = Diag(D^-1) N (Alg. 1, line 6) and
@@ -178,10 +183,12 @@ void a2d_oracle_attention_bwd(int heads, int n, int H, const double* Q,
 /* ------------------------------------------------------------------------- */
 /* Sec. 3.1, Eq. (3): attention of a block of queries restricted to the keys   */
 /* R_x of one tile.  N [heads][nq][H] unnormalised, m, d [heads][nq].          */
-void a2d_oracle_partial_fwd(int heads, int nq, int nkv, int H, const double* Q,
-                            const double* K, const double* V, int64_t q_off,
-                            int64_t kv_off, int causal, double scale,
-                            double* N, double* m_out, double* d_out) {
+/* kpos[r] is the global index of key r of the tile: key r is hidden from      */
+/* query i iff causal and q_off + i < kpos[r] (Sec. 2.1).                      */
+void a2d_oracle_partial_fwd_pos(int heads, int nq, int nkv, int H, const double* Q,
+                                const double* K, const double* V, int64_t q_off,
+                                const int64_t* kpos, int causal, double scale,
+                                double* N, double* m_out, double* d_out) {
 #pragma omp parallel for collapse(2) schedule(dynamic, 8)
   for (int b = 0; b < heads; ++b) {
     for (int i = 0; i < nq; ++i) {
@@ -191,7 +198,7 @@ void a2d_oracle_partial_fwd(int heads, int nq, int nkv, int H, const double* Q,
       double m = -INFINITY;
       for (int r = 0; r < nkv; ++r) {
         s[r] = score(q, K + ((size_t)b * nkv + r) * H, H, scale, causal,
-                     q_off + i, kv_off + r);
+                     q_off + i, kpos[r]);
         if (s[r] > m) m = s[r];
       }
       double* nrow = N + row * H;
@@ -211,6 +218,23 @@ void a2d_oracle_partial_fwd(int heads, int nq, int nkv, int H, const double* Q,
       free(s);
     }
   }
+}
+
+/* global key indices of a tile whose keys are consecutive tokens from kv_off */
+static int64_t* consecutive_positions(int nkv, int64_t kv_off) {
+  int64_t* kpos = (int64_t*)malloc(sizeof(int64_t) * (size_t)(nkv > 0 ? nkv : 1));
+  for (int r = 0; r < nkv; ++r) kpos[r] = kv_off + r;
+  return kpos;
+}
+
+/* The tile of consecutive tokens: key r is token kv_off + r. */
+void a2d_oracle_partial_fwd(int heads, int nq, int nkv, int H, const double* Q,
+                            const double* K, const double* V, int64_t q_off,
+                            int64_t kv_off, int causal, double scale,
+                            double* N, double* m_out, double* d_out) {
+  int64_t* kpos = consecutive_positions(nkv, kv_off);
+  a2d_oracle_partial_fwd_pos(heads, nq, nkv, H, Q, K, V, q_off, kpos, causal, scale, N, m_out, d_out);
+  free(kpos);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -266,11 +290,12 @@ void a2d_oracle_fix(int k, int64_t rows, int H, const double* const* Nparts,
 /* Alg. 1 line 7):  P_{i,r} = exp(s_{i,r} - lse_i),  delta_i = sum_j dO O,     */
 /* dV = P^T dO, dP = dO V^T, dS = P o (dP - delta), dQ = scale dS K,           */
 /* dK = scale dS^T Q.                                                           */
-void a2d_oracle_partial_bwd(int heads, int nq, int nkv, int H, const double* Q,
-                            const double* K, const double* V, const double* O,
-                            const double* dO, const double* lse, int64_t q_off,
-                            int64_t kv_off, int causal, double scale,
-                            double* dQ, double* dK, double* dV) {
+/* kpos[r]: global index of key r, as in partial_fwd_pos.                       */
+void a2d_oracle_partial_bwd_pos(int heads, int nq, int nkv, int H, const double* Q,
+                                const double* K, const double* V, const double* O,
+                                const double* dO, const double* lse, int64_t q_off,
+                                const int64_t* kpos, int causal, double scale,
+                                double* dQ, double* dK, double* dV) {
   size_t rows = (size_t)heads * nq;
   double* delta = (double*)malloc(sizeof(double) * (rows ? rows : 1));
 #pragma omp parallel for schedule(static)
@@ -291,7 +316,7 @@ void a2d_oracle_partial_bwd(int heads, int nq, int nkv, int H, const double* Q,
       for (int r = 0; r < nkv; ++r) {
         const double* k = K + ((size_t)b * nkv + r) * H;
         const double* v = V + ((size_t)b * nkv + r) * H;
-        double s = score(q, k, H, scale, causal, q_off + i, kv_off + r);
+        double s = score(q, k, H, scale, causal, q_off + i, kpos[r]);
         if (s == -INFINITY) continue;
         double p = exp(s - lse[row]);
         double dp = 0.0;
@@ -315,7 +340,7 @@ void a2d_oracle_partial_bwd(int heads, int nq, int nkv, int H, const double* Q,
         if (lse[row] == -INFINITY) continue;
         const double* q = Q + row * H;
         const double* go = dO + row * H;
-        double s = score(q, k, H, scale, causal, q_off + i, kv_off + r);
+        double s = score(q, k, H, scale, causal, q_off + i, kpos[r]);
         if (s == -INFINITY) continue;
         double p = exp(s - lse[row]);
         double dp = 0.0;
@@ -329,6 +354,18 @@ void a2d_oracle_partial_bwd(int heads, int nq, int nkv, int H, const double* Q,
     }
   }
   free(delta);
+}
+
+/* The tile of consecutive tokens: key r is token kv_off + r. */
+void a2d_oracle_partial_bwd(int heads, int nq, int nkv, int H, const double* Q,
+                            const double* K, const double* V, const double* O,
+                            const double* dO, const double* lse, int64_t q_off,
+                            int64_t kv_off, int causal, double scale,
+                            double* dQ, double* dK, double* dV) {
+  int64_t* kpos = consecutive_positions(nkv, kv_off);
+  a2d_oracle_partial_bwd_pos(heads, nq, nkv, H, Q, K, V, O, dO, lse, q_off, kpos, causal, scale,
+                             dQ, dK, dV);
+  free(kpos);
 }
 
 /* Alg. 3 lines 4-5: the gradient partials of a grid row / column are summed.  */

@@ -468,3 +468,124 @@ def test_fig2_index_sets_and_coverage():
             for i, gi in enumerate(gold[f"Qg({r})"]):
                 for j, gj in enumerate(gold[f"Kg({c})"]):
                     assert (gi >= gj) == (i >= j + (0 if r >= c else 1))
+
+
+# ----------------------------------------------------------------------------
+# gathered key/value tiles: sub-blocks with their own global offsets (the Compute line of
+# Alg. GatherComputeScatter; Sec. 5 calls the resulting mask step-like)
+# ----------------------------------------------------------------------------
+def brute_positions(Q, K, V, scale, q_off, kpos):
+    """Pure Python: attention of each query over the keys whose position does not exceed its own."""
+    out = []
+    for i in range(len(Q)):
+        vis = [r for r in range(len(K)) if kpos[r] <= q_off + i]
+        if not vis:
+            out.append(None)
+            continue
+        s = [scale * math.fsum(Q[i][h] * K[r][h] for h in range(len(Q[0]))) for r in vis]
+        m = max(s)
+        d = math.fsum(math.exp(x - m) for x in s)
+        o = [math.fsum(math.exp(s[t] - m) / d * V[r][j] for t, r in enumerate(vis)) for j in range(len(V[0]))]
+        out.append((o, m + math.log(d), m))
+    return out
+
+
+def test_segment_positions():
+    pos = oracle.segment_positions([(10, 3), (0, 2), (7, 1)])
+    assert pos.tolist() == [10, 11, 12, 0, 1, 7]
+
+
+def test_gathered_tile_brute_force():
+    g = rng(40)
+    nq, H = 6, 3
+    segs = [(4, 3), (0, 4), (9, 2), (2, 1)]          # unordered, overlapping, different lengths
+    kpos = oracle.segment_positions(segs)
+    nkv = len(kpos)
+    Q = g.standard_normal((1, nq, H)); K = g.standard_normal((1, nkv, H)); V = g.standard_normal((1, nkv, H))
+    scale, q_off = 0.6, 3
+    N, m, d = oracle.partial_fwd_pos(Q, K, V, q_off, kpos, True, scale)
+    ref = brute_positions(Q[0].tolist(), K[0].tolist(), V[0].tolist(), scale, q_off, kpos.tolist())
+    for i, r in enumerate(ref):
+        if r is None:
+            assert m[0, i] == -np.inf and d[0, i] == 0.0 and np.all(N[0, i] == 0.0)
+            continue
+        np.testing.assert_allclose(N[0, i] / d[0, i], r[0], atol=1e-14)
+        assert abs(m[0, i] + math.log(d[0, i]) - r[1]) < 1e-14 and abs(m[0, i] - r[2]) < 1e-14
+    # without the mask the positions do not matter
+    a = oracle.partial_fwd_pos(Q, K, V, q_off, kpos, False, scale)
+    b = oracle.partial_fwd(Q, K, V, 0, 0, False, scale)
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x, y)
+
+
+def test_gathered_tile_equals_merge_of_its_segments():
+    """One call on the gathered tile = AttnFix over one call per sub-block (the identity of Sec. 3.1);
+    its gradients: dQ is the sum over the sub-blocks, dK / dV their concatenation (Alg. 3 lines 4-5)."""
+    g = rng(41)
+    heads, nq, H = 2, 9, 4
+    segs = [(0, 5), (12, 4), (6, 7), (30, 3)]        # the last one is wholly invisible
+    kpos = oracle.segment_positions(segs)
+    nkv = len(kpos)
+    Q = g.standard_normal((heads, nq, H)); K = g.standard_normal((heads, nkv, H))
+    V = g.standard_normal((heads, nkv, H)); dO = g.standard_normal((heads, nq, H))
+    scale, q_off = 0.5, 8
+    N, m, d = oracle.partial_fwd_pos(Q, K, V, q_off, kpos, True, scale)
+    trip, start = [], 0
+    for off, rows in segs:
+        trip.append(oracle.partial_fwd(Q, K[:, start:start + rows], V[:, start:start + rows], q_off, off, True, scale))
+        start += rows
+    O1, l1 = oracle.fix([N], [m], [d])
+    O2, l2 = oracle.fix([t[0] for t in trip], [t[1] for t in trip], [t[2] for t in trip])
+    np.testing.assert_allclose(O1, O2, atol=1e-14)
+    np.testing.assert_allclose(l1, l2, atol=1e-14)
+    assert np.array_equal(m, np.max(np.stack([t[1] for t in trip]), axis=0))
+    dQ, dK, dV = oracle.partial_bwd_pos(Q, K, V, O1, dO, l1, q_off, kpos, True, scale)
+    dq_sum, start = np.zeros_like(dQ), 0
+    for off, rows in segs:
+        a, b, c = oracle.partial_bwd(Q, K[:, start:start + rows], V[:, start:start + rows], O1, dO, l1,
+                                     q_off, off, True, scale)
+        dq_sum += a
+        np.testing.assert_allclose(dK[:, start:start + rows], b, atol=1e-14)
+        np.testing.assert_allclose(dV[:, start:start + rows], c, atol=1e-14)
+        start += rows
+    np.testing.assert_allclose(dQ, dq_sum, atol=1e-13)
+    assert np.all(dK[:, -3:] == 0.0) and np.all(dV[:, -3:] == 0.0)
+
+
+@pytest.mark.parametrize("grid", [2, 3])
+def test_gathered_tile_cyclic_layout_reproduces_full_attention(grid):
+    """Overlapped algorithm, cyclic 1D layout: device (r, c) holds query block Q_n = tokens
+    {r' + sqrtP c' + i P} and the gathered K_g = tokens {c + j sqrtP}, made of sqrtP sub-blocks
+    {c + sqrtP s + j P}.  Against sub-block s the mask is i >= j when the block's first token does
+    not exceed the query block's, else i >= j + 1: segments (0 | 1, N / P).  Merging the sqrtP
+    gathered-tile results of a query block over the grid columns gives rows of full attention."""
+    g = rng(42)
+    heads, t, H = 1, 3, 3                      # t = N / P tokens per block
+    P = grid * grid
+    n = P * t
+    Q, K, V, dO = (g.standard_normal((heads, n, H)) for _ in range(4))
+    scale = 0.8
+    O, lse = oracle.attention_fwd(Q, K, V, scale, True)
+    dQf, dKf, dVf = oracle.attention_bwd(Q, K, V, dO, scale, True)
+    dK_acc, dV_acc = np.zeros_like(K), np.zeros_like(V)
+    for qa in range(P):                        # query block: tokens qa + i P
+        qi = np.arange(qa, n, P)
+        trip, keysets, segsets = [], [], []
+        for c in range(grid):                  # gathered keys of grid column c
+            ki = np.concatenate([np.arange(c + grid * s, n, P) for s in range(grid)])
+            segs = [(0 if c + grid * s <= qa else 1, t) for s in range(grid)]
+            trip.append(oracle.partial_fwd_pos(Q[:, qi], K[:, ki], V[:, ki], 0, oracle.segment_positions(segs), True, scale))
+            keysets.append(ki); segsets.append(segs)
+        Of, lf = oracle.fix([x[0] for x in trip], [x[1] for x in trip], [x[2] for x in trip])
+        np.testing.assert_allclose(Of, O[:, qi], atol=1e-13)
+        np.testing.assert_allclose(lf, lse[:, qi], atol=1e-13)
+        dq = np.zeros_like(Of)
+        for ki, segs in zip(keysets, segsets):
+            a, b, cc = oracle.partial_bwd_pos(Q[:, qi], K[:, ki], V[:, ki], Of, dO[:, qi], lf, 0,
+                                              oracle.segment_positions(segs), True, scale)
+            dq += a
+            dK_acc[:, ki] += b
+            dV_acc[:, ki] += cc
+        np.testing.assert_allclose(dq, dQf[:, qi], atol=1e-13)
+    np.testing.assert_allclose(dK_acc, dKf, atol=1e-13)
+    np.testing.assert_allclose(dV_acc, dVf, atol=1e-13)
