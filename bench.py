@@ -58,6 +58,7 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma-probe", action="store_true")
+    ap.add_argument("--no-gathered", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed steps run one plain 1 GiB device copy (torch copy_), so that a "
                          "rocprofv3 --pmc run of this command also holds the counter reading of a copy of "
@@ -208,6 +209,8 @@ def main():
         "attnfix_gbs": kernels["fix"]["achieved"], "attnfix_frac_hbm": kernels["fix"]["frac"],
         "roofline": roofline, "kernels": kernels,
     }
+    if not args.no_gathered and w.causal and w.name == "c3":
+        result["gathered"] = gathered_tile(a2d, synth, w, scale, kernels)
     if not args.no_mfma_probe:
         tf_r, mhz_r = a2d.mfma_ceiling(20000, True)
         tf_c, mhz_c = a2d.mfma_ceiling(20000, False)
@@ -217,6 +220,51 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, scale)
     print(json.dumps(result))
+
+
+def gathered_tile(a2d, synth, w, scale, kernels):
+    """The last query block against ALL sqrt(P) key/value blocks in ONE launch (a2d_partial_fwd_seg /
+    a2d_partial_bwd_seg: the step-like causal mask of a gathered K_g, V_g), timed beside what the same
+    work costs as one launch per key block (sqrt(P) - 1 unmasked tiles + the diagonal one, from the
+    per-call times above) plus, forward, the merge of their partials."""
+    import torch
+    T, G, H = w.tile, w.grid, w.hdim
+    r = G - 1
+    dev = lambda t: t.to("cuda")
+    Q = dev(synth.q_block(w, r))
+    dO = dev(synth.do_block(w, r))
+    K = torch.cat([dev(synth.k_block(w, c)) for c in range(G)], dim=1)
+    V = torch.cat([dev(synth.v_block(w, c)) for c in range(G)], dim=1)
+    segs = [(c * T, T) for c in range(G)]
+    out = a2d.partial_fwd(Q, K, V, r * T, 0, True, scale, segments=segs)
+    O, lse = a2d.fix([out[0]], [out[1]], [out[2]])
+    o3 = a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, segments=segs)
+    ws = torch.empty(w.heads * T * 4 + 256, dtype=torch.uint8, device="cuda")
+
+    def timeit(fn, n=5):
+        fn(); fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    t_f = timeit(lambda: a2d.partial_fwd(Q, K, V, r * T, 0, True, scale, out=out, segments=segs))
+    t_b = timeit(lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, out=o3, workspace=ws,
+                                         segments=segs))
+    frac = (G - 1) + (T + 1) / (2.0 * T)                      # visible tiles of the row
+    base = w.heads * T * T * H * frac
+    sep_f = (G - 1) * kernels["partial_fwd_full"]["avg_ms"] + kernels["partial_fwd_diag"]["avg_ms"] + \
+        kernels["fix"]["avg_ms"]
+    sep_b = (G - 1) * kernels["partial_bwd_full"]["avg_ms"] + kernels["partial_bwd_diag"]["avg_ms"]
+    return {"what": "query block %d against all %d key/value blocks in one launch" % (r, G),
+            "fwd_ms": round(t_f, 4), "fwd_tflops": round(4 * base / t_f / 1e9, 1),
+            "bwd_ms": round(t_b, 4), "bwd_tflops": round(10 * base / t_b / 1e9, 1),
+            "fwd_ms_one_launch_per_block_plus_fix": round(sep_f, 4),
+            "bwd_ms_one_launch_per_block": round(sep_b, 4)}
 
 
 def cpu_baseline(w, scale):

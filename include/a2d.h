@@ -65,6 +65,9 @@ typedef enum {
 /* Most partials one a2d_fix / a2d_fix_bwd call can merge (sqrt(P) in the paper). */
 #define A2D_MAX_PARTS 32
 
+/* Most key/value sub-blocks of one gathered tile (a2d_partial_fwd_seg / a2d_partial_bwd_seg). */
+#define A2D_MAX_SEGMENTS 32
+
 /* One tile problem: a block of nq queries against a block of nkv keys/values. */
 typedef struct {
   int32_t heads;   /* B * M, >= 1                                                     */
@@ -130,6 +133,42 @@ a2d_status a2d_partial_bwd(const a2d_tile_desc* desc, const void* Q, const void*
                            const float* lse, float* dQ_part, float* dK_part,
                            float* dV_part, void* workspace, size_t workspace_bytes,
                            void* stream);
+
+/*
+ * One sub-block of a GATHERED key/value tile: `rows` consecutive tokens starting at global
+ * token index kv_off.
+ */
+typedef struct {
+  int64_t kv_off; /* global index of the sub-block's first key                     */
+  int32_t rows;   /* its number of keys, >= 1                                      */
+  int32_t pad;    /* must be 0                                                     */
+} a2d_kv_segment;
+
+/*
+ * The tile calls for a gathered key/value tile: one query block against the concatenation
+ * of nseg sub-blocks that come from different places of the sequence - the Compute line of
+ * the paper's GatherComputeScatter algorithm (Sec. 4), which runs FlashAttn on one query
+ * block and the gathered K_g, V_g in one go.  Under the causal mask this is the step-like
+ * pattern Sec. 5 says the paper's own kernel could not express (it ran one call per
+ * sub-block instead).  K, V, dK_part, dV_part are [heads][nkv][H] with
+ * nkv = desc->nkv = sum of segs[s].rows, sub-blocks stored in the order of `segs`
+ * (a HOST array, read before the call returns); desc->kv_off is ignored; key kk of
+ * sub-block s is hidden from query i iff desc->causal and q_off + i < segs[s].kv_off + kk.
+ * The paper's cyclic layout maps to kv_off = 0 for a sub-block whose first token does not
+ * come after the query block's first token and 1 otherwise (with q_off = 0).
+ * Results equal AttnFix over / sums and concatenation of the per-sub-block calls; sub-blocks
+ * no query row can see cost nothing.  Everything else is as for a2d_partial_fwd /
+ * a2d_partial_bwd.  1 <= nseg <= A2D_MAX_SEGMENTS.
+ */
+a2d_status a2d_partial_fwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
+                               const void* Q, const void* K, const void* V, float* O_part,
+                               float* m, float* l, void* workspace, size_t workspace_bytes,
+                               void* stream);
+a2d_status a2d_partial_bwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
+                               const void* Q, const void* K, const void* V, const void* O,
+                               const void* dO, const float* lse, float* dQ_part,
+                               float* dK_part, float* dV_part, void* workspace,
+                               size_t workspace_bytes, void* stream);
 
 /*
  * Sum of k gradient partials (the reduce-scatters of Alg. 3 lines 4-5 use plain

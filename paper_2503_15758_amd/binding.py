@@ -18,6 +18,7 @@ OP_PARTIAL_FWD, OP_FIX, OP_PARTIAL_BWD, OP_FIX_BWD = 0, 1, 2, 3
 MAX_PARTS = 32
 
 EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
+           "a2d_partial_fwd_seg", "a2d_partial_bwd_seg",
            "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling",
            "a2d_status_str", "a2d_last_error", "a2d_version")
 
@@ -26,6 +27,13 @@ class TileDesc(ctypes.Structure):
     _fields_ = [("heads", ctypes.c_int32), ("nq", ctypes.c_int32), ("nkv", ctypes.c_int32),
                 ("hdim", ctypes.c_int32), ("q_off", ctypes.c_int64), ("kv_off", ctypes.c_int64),
                 ("causal", ctypes.c_int32), ("scale", ctypes.c_float), ("dtype", ctypes.c_int32)]
+
+
+class KvSegment(ctypes.Structure):
+    _fields_ = [("kv_off", ctypes.c_int64), ("rows", ctypes.c_int32), ("pad", ctypes.c_int32)]
+
+
+MAX_SEGMENTS = 32
 
 
 class A2DError(RuntimeError):
@@ -51,6 +59,12 @@ def lib():
         L.a2d_partial_fwd.restype = ctypes.c_int
         L.a2d_partial_fwd.argtypes = [ctypes.POINTER(TileDesc), vp, vp, vp, fp, fp, fp, vp,
                                       ctypes.c_size_t, vp]
+        L.a2d_partial_fwd_seg.restype = ctypes.c_int
+        L.a2d_partial_fwd_seg.argtypes = [ctypes.POINTER(TileDesc), ctypes.c_int, ctypes.POINTER(KvSegment),
+                                          vp, vp, vp, fp, fp, fp, vp, ctypes.c_size_t, vp]
+        L.a2d_partial_bwd_seg.restype = ctypes.c_int
+        L.a2d_partial_bwd_seg.argtypes = [ctypes.POINTER(TileDesc), ctypes.c_int, ctypes.POINTER(KvSegment),
+                                          vp, vp, vp, vp, vp, fp, fp, fp, fp, vp, ctypes.c_size_t, vp]
         L.a2d_fix.restype = ctypes.c_int
         L.a2d_fix.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                               ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, fp, vp]
@@ -113,7 +127,14 @@ def workspace_bytes(desc, op, k=0):
     return int(lib().a2d_workspace_bytes(ctypes.byref(desc), op, k))
 
 
-def partial_fwd(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None):
+def _segments(segments):
+    arr = (KvSegment * len(segments))()
+    for i, (off, rows) in enumerate(segments):
+        arr[i].kv_off, arr[i].rows, arr[i].pad = int(off), int(rows), 0
+    return arr
+
+
+def partial_fwd(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None, segments=None):
     """a2d_partial_fwd. Returns (O_part fp32 [heads][nq][H], m, l fp32 [heads][nq])."""
     for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
         _dev3(t, n)
@@ -127,6 +148,11 @@ def partial_fwd(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None):
         l = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
     else:
         O_part, m, l = out
+    if segments is not None:       # gathered tile: list of (kv_off, rows) sub-blocks, kv_off unused
+        _check(lib().a2d_partial_fwd_seg(ctypes.byref(d), len(segments), _segments(segments), _ptr(Q),
+                                         _ptr(K), _ptr(V), _ptr(O_part), _ptr(m), _ptr(l), None, 0,
+                                         _stream()))
+        return O_part, m, l
     _check(lib().a2d_partial_fwd(ctypes.byref(d), _ptr(Q), _ptr(K), _ptr(V), _ptr(O_part), _ptr(m),
                                  _ptr(l), None, 0, _stream()))
     return O_part, m, l
@@ -152,7 +178,7 @@ def fix(O_parts, ms, ls, out_dtype=torch.bfloat16, out=None):
 
 
 def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None, out=None,
-                workspace=None):
+                workspace=None, segments=None):
     """a2d_partial_bwd. Returns (dQ_part, dK_part, dV_part), all fp32."""
     for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
         _dev3(t, n)
@@ -169,6 +195,12 @@ def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None
         dV = torch.empty(K.shape, dtype=torch.float32, device=Q.device)
     else:
         dQ, dK, dV = out
+    if segments is not None:
+        _check(lib().a2d_partial_bwd_seg(ctypes.byref(d), len(segments), _segments(segments), _ptr(Q),
+                                         _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse), _ptr(dQ),
+                                         _ptr(dK), _ptr(dV), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream()))
+        return dQ, dK, dV
     _check(lib().a2d_partial_bwd(ctypes.byref(d), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO),
                                  _ptr(lse), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream()))

@@ -68,6 +68,86 @@ a2d_status hip_result(hipError_t e, const char* who) {
   return fail(A2D_ERR_HIP, "%s: HIP error %d (%s)", who, (int)e, hipGetErrorString(e));
 }
 
+// the plain tile as one sub-block
+a2d::SegList one_segment(const a2d_tile_desc* d) {
+  a2d::SegList g;
+  memset(&g, 0, sizeof(g));
+  g.n = 1;
+  g.start[0] = 0;
+  g.rows[0] = d->nkv;
+  g.rel[0] = d->q_off - d->kv_off;
+  return g;
+}
+
+a2d_status make_segments(const a2d_tile_desc* d, int nseg, const a2d_kv_segment* segs, const char* who,
+                         a2d::SegList* g) {
+  if (nseg < 1 || nseg > A2D_MAX_SEGMENTS)
+    return fail(A2D_ERR_INVALID_ARG, "%s: nseg=%d outside 1..%d", who, nseg, A2D_MAX_SEGMENTS);
+  if (!segs) return fail(A2D_ERR_INVALID_ARG, "%s: segs is NULL", who);
+  memset(g, 0, sizeof(*g));
+  g->n = nseg;
+  int64_t total = 0;
+  for (int s = 0; s < nseg; ++s) {
+    if (segs[s].rows < 1 || segs[s].pad != 0)
+      return fail(A2D_ERR_INVALID_ARG, "%s: segs[%d]: rows=%d must be >= 1 and pad 0", who, s, segs[s].rows);
+    if (segs[s].kv_off < -((int64_t)1 << 60) || segs[s].kv_off > ((int64_t)1 << 60))
+      return fail(A2D_ERR_INVALID_ARG, "%s: segs[%d].kv_off out of range", who, s);
+    g->start[s] = (int)total;
+    g->rows[s] = segs[s].rows;
+    g->rel[s] = d->q_off - segs[s].kv_off;
+    total += segs[s].rows;
+    if (total > d->nkv) break;
+  }
+  if (total != d->nkv)
+    return fail(A2D_ERR_INVALID_ARG, "%s: the sub-blocks hold %lld keys, desc->nkv is %d", who,
+                (long long)total, d->nkv);
+  return A2D_OK;
+}
+
+a2d_status partial_fwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, const void* Q, const void* K,
+                            const void* V, float* O_part, float* m, float* l, void* stream,
+                            const char* who) {
+  A2D_TRY(check_ptr(Q, who, "Q"));
+  A2D_TRY(check_ptr(K, who, "K"));
+  A2D_TRY(check_ptr(V, who, "V"));
+  A2D_TRY(check_ptr(O_part, who, "O_part"));
+  A2D_TRY(check_ptr(m, who, "m"));
+  A2D_TRY(check_ptr(l, who, "l"));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!force_generic() && a2d::fwd_mfma_supported(*desc))
+    return hip_result(a2d::launch_fwd_mfma(*desc, g, Q, K, V, O_part, m, l, s), who);
+  return hip_result(a2d::launch_fwd_generic(*desc, g, Q, K, V, O_part, m, l, s), who);
+}
+
+a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, const void* Q, const void* K,
+                            const void* V, const void* O, const void* dO, const float* lse,
+                            float* dQ_part, float* dK_part, float* dV_part, void* workspace,
+                            size_t workspace_bytes, void* stream, const char* who) {
+  A2D_TRY(check_ptr(Q, who, "Q"));
+  A2D_TRY(check_ptr(K, who, "K"));
+  A2D_TRY(check_ptr(V, who, "V"));
+  A2D_TRY(check_ptr(O, who, "O"));
+  A2D_TRY(check_ptr(dO, who, "dO"));
+  A2D_TRY(check_ptr(lse, who, "lse"));
+  A2D_TRY(check_ptr(dQ_part, who, "dQ_part"));
+  A2D_TRY(check_ptr(dK_part, who, "dK_part"));
+  A2D_TRY(check_ptr(dV_part, who, "dV_part"));
+  const size_t need = a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD, 0);
+  if (!workspace || workspace_bytes < need)
+    return fail(A2D_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need,
+                workspace ? workspace_bytes : (size_t)0);
+  if (!aligned16(workspace)) return fail(A2D_ERR_MISALIGNED, "%s: workspace is not 16-byte aligned", who);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* delta = static_cast<float*>(workspace);
+  A2D_TRY(hip_result(a2d::launch_delta(desc->dtype, (int64_t)desc->heads * desc->nq, desc->hdim, O,
+                                       dO, delta, s), who));
+  if (!force_generic() && a2d::bwd_mfma_supported(*desc))
+    return hip_result(a2d::launch_bwd_mfma(*desc, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
+                                           dV_part, s), who);
+  return hip_result(a2d::launch_bwd_generic(*desc, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
+                                            dV_part, s), who);
+}
+
 }  // namespace
 
 extern "C" {
@@ -79,21 +159,23 @@ size_t a2d_workspace_bytes(const a2d_tile_desc* desc, int op, int /*k*/) {
   return ((rows * sizeof(float) + 255) / 256) * 256;
 }
 
+a2d_status a2d_partial_fwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
+                               const void* Q, const void* K, const void* V, float* O_part,
+                               float* m, float* l, void* /*workspace*/, size_t /*workspace_bytes*/,
+                               void* stream) {
+  const char* who = "a2d_partial_fwd_seg";
+  A2D_TRY(check_desc(desc, who));
+  a2d::SegList g;
+  A2D_TRY(make_segments(desc, nseg, segs, who, &g));
+  return partial_fwd_impl(desc, g, Q, K, V, O_part, m, l, stream, who);
+}
+
 a2d_status a2d_partial_fwd(const a2d_tile_desc* desc, const void* Q, const void* K, const void* V,
                            float* O_part, float* m, float* l, void* /*workspace*/,
                            size_t /*workspace_bytes*/, void* stream) {
   const char* who = "a2d_partial_fwd";
   A2D_TRY(check_desc(desc, who));
-  A2D_TRY(check_ptr(Q, who, "Q"));
-  A2D_TRY(check_ptr(K, who, "K"));
-  A2D_TRY(check_ptr(V, who, "V"));
-  A2D_TRY(check_ptr(O_part, who, "O_part"));
-  A2D_TRY(check_ptr(m, who, "m"));
-  A2D_TRY(check_ptr(l, who, "l"));
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (!force_generic() && a2d::fwd_mfma_supported(*desc))
-    return hip_result(a2d::launch_fwd_mfma(*desc, Q, K, V, O_part, m, l, s), who);
-  return hip_result(a2d::launch_fwd_generic(*desc, Q, K, V, O_part, m, l, s), who);
+  return partial_fwd_impl(desc, one_segment(desc), Q, K, V, O_part, m, l, stream, who);
 }
 
 a2d_status a2d_fix(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
@@ -124,35 +206,27 @@ a2d_status a2d_fix(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
                                     static_cast<hipStream_t>(stream)), who);
 }
 
+a2d_status a2d_partial_bwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
+                               const void* Q, const void* K, const void* V, const void* O,
+                               const void* dO, const float* lse, float* dQ_part, float* dK_part,
+                               float* dV_part, void* workspace, size_t workspace_bytes,
+                               void* stream) {
+  const char* who = "a2d_partial_bwd_seg";
+  A2D_TRY(check_desc(desc, who));
+  a2d::SegList g;
+  A2D_TRY(make_segments(desc, nseg, segs, who, &g));
+  return partial_bwd_impl(desc, g, Q, K, V, O, dO, lse, dQ_part, dK_part, dV_part, workspace,
+                          workspace_bytes, stream, who);
+}
+
 a2d_status a2d_partial_bwd(const a2d_tile_desc* desc, const void* Q, const void* K, const void* V,
                            const void* O, const void* dO, const float* lse, float* dQ_part,
                            float* dK_part, float* dV_part, void* workspace, size_t workspace_bytes,
                            void* stream) {
   const char* who = "a2d_partial_bwd";
   A2D_TRY(check_desc(desc, who));
-  A2D_TRY(check_ptr(Q, who, "Q"));
-  A2D_TRY(check_ptr(K, who, "K"));
-  A2D_TRY(check_ptr(V, who, "V"));
-  A2D_TRY(check_ptr(O, who, "O"));
-  A2D_TRY(check_ptr(dO, who, "dO"));
-  A2D_TRY(check_ptr(lse, who, "lse"));
-  A2D_TRY(check_ptr(dQ_part, who, "dQ_part"));
-  A2D_TRY(check_ptr(dK_part, who, "dK_part"));
-  A2D_TRY(check_ptr(dV_part, who, "dV_part"));
-  const size_t need = a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD, 0);
-  if (!workspace || workspace_bytes < need)
-    return fail(A2D_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need,
-                workspace ? workspace_bytes : (size_t)0);
-  if (!aligned16(workspace)) return fail(A2D_ERR_MISALIGNED, "%s: workspace is not 16-byte aligned", who);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  float* delta = static_cast<float*>(workspace);
-  A2D_TRY(hip_result(a2d::launch_delta(desc->dtype, (int64_t)desc->heads * desc->nq, desc->hdim, O,
-                                       dO, delta, s), who));
-  if (!force_generic() && a2d::bwd_mfma_supported(*desc))
-    return hip_result(a2d::launch_bwd_mfma(*desc, Q, K, V, dO, lse, delta, dQ_part, dK_part,
-                                           dV_part, s), who);
-  return hip_result(a2d::launch_bwd_generic(*desc, Q, K, V, dO, lse, delta, dQ_part, dK_part,
-                                            dV_part, s), who);
+  return partial_bwd_impl(desc, one_segment(desc), Q, K, V, O, dO, lse, dQ_part, dK_part, dV_part,
+                          workspace, workspace_bytes, stream, who);
 }
 
 a2d_status a2d_fix_bwd(int k, int64_t n, int32_t out_dtype, const float* const* parts, void* out,
@@ -224,8 +298,8 @@ a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t sc
   unsigned long long clocks[2] = {0, 0};
   if (e == hipSuccess)
     e = hipMemcpy(clocks, sc + (size_t)blocks * a2d::mfma_probe_threads(), sizeof(clocks), hipMemcpyDeviceToHost);
-  hipEventDestroy(e0);
-  hipEventDestroy(e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
   if (e != hipSuccess) return hip_result(e, who);
   // every wavefront issues iters * 16 MFMAs of 2 * 32 * 32 * 16 flop; 8 wavefronts per workgroup
   const double flop = (double)blocks * (a2d::mfma_probe_threads() / 64) * iters *

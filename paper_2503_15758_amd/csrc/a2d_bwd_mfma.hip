@@ -189,7 +189,7 @@ __device__ __forceinline__ void dk_second(DkCtx& cx, bf16x8 (&t)[4], const bf16x
 #undef A2D_NAT
 
 __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
-    a2d_tile_desc d, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+    a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ delta, float* __restrict__ dK, float* __restrict__ dV) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -224,19 +224,43 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
 #pragma unroll
   for (int t = 0; t < 4; ++t) cx.acc[t] = zero16();
 
-  // query i sees key r iff i >= r - rel  (local indices), rel = q_off - kv_off
-  const int64_t rel = d.q_off - d.kv_off;
-  auto first_row = [&](int r) -> int {          // first local query row that sees local key r
-    if (!d.causal) return 0;
-    const int64_t f = (int64_t)r - rel;
+  // Query i sees key kk of key/value sub-block s iff i >= kk - rel[s].  seg_first_row(sb, r): first
+  // local query row that sees local key r of sub-block sb (nq if none does).
+  auto seg_first_row = [&](int sb, int r) -> int {
+    const int64_t f = (int64_t)(r - g.start[sb]) - g.rel[sb];
     return f <= 0 ? 0 : (f >= d.nq ? d.nq : (int)f);
   };
-  const int i_start = (first_row(k0) / BQ) * BQ;
+  // smallest / largest such row over the local keys a .. b - 1 (inside a sub-block it grows with
+  // the key, so only the ends of the covered part of each sub-block matter).  Each sub-block's
+  // table entries are read once, with no load depending on another.
+  auto first_row_range = [&](int a, int b, int& lo, int& hi) {
+    lo = d.nq; hi = 0;
+    if (!d.causal) { lo = 0; return; }
+    for (int sb = 0; sb < g.n; ++sb) {
+      const int x = max(a, g.start[sb]), y = min(b, g.start[sb] + g.rows[sb]);
+      if (x >= y) continue;
+      lo = min(lo, seg_first_row(sb, x));
+      hi = max(hi, seg_first_row(sb, y - 1));
+    }
+  };
+  int wg_lo, wg_hi;
+  first_row_range(k0, min(k0 + DK_KEYS, d.nkv), wg_lo, wg_hi);
+  const int i_start = (wg_lo / BQ) * BQ;
   const int nsteps = (d.nq - i_start + BQ - 1) / BQ;
-  const int wk_first = k0 + pair * 32, wk_last = wk_first + 31;
-  cx.my_first = (key < d.nkv) ? first_row(key) : d.nq;       // padding keys see nothing
-  const int w_any = first_row(wk_first);                      // rows below see none of the pair's keys
-  const int w_all = (wk_last < d.nkv) ? first_row(wk_last) : d.nq;   // rows from here see all of them
+  const int wk_first = k0 + pair * 32, wk_end = min(wk_first + 32, d.nkv);
+  cx.my_first = d.nq;                                         // padding keys see nothing
+  if (key < d.nkv) {
+    cx.my_first = 0;
+    if (d.causal) {
+      for (int sb = 0; sb < g.n; ++sb)                        // uniform loop, per-lane select
+        if (key >= g.start[sb] && key < g.start[sb] + g.rows[sb]) cx.my_first = seg_first_row(sb, key);
+    }
+  }
+  int w_any = d.nq, w_all = d.nq;   // rows below w_any see none of the pair's keys, rows from w_all on all
+  if (wk_first < wk_end) {
+    first_row_range(wk_first, wk_end, w_any, w_all);
+    if (wk_end < wk_first + 32) w_all = d.nq;                 // padding keys in the pair: always masked
+  }
 
   // ---- The gradient waves run ONE STEP BEHIND the score waves: in iteration j the score wave
   // computes S, P, dV of step j and leaves P in mailbox slot j & 1, while the gradient wave of
@@ -469,7 +493,7 @@ __device__ __forceinline__ void dq_piece(DqCtx& cx, int key0) {
 // every compute unit one.
 template <int WAVES>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
-    a2d_tile_desc d, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+    a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ delta, float* __restrict__ dQ) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -507,19 +531,23 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   }
   wait_vmem_all();
 
-  const int64_t rel = d.q_off - d.kv_off;
-  auto vis_count = [&](int i) -> int {
-    if (!d.causal) return d.nkv;
-    const int64_t v = (int64_t)i + rel + 1;
-    return v <= 0 ? 0 : (v < d.nkv ? (int)v : d.nkv);
+  // visibility per key/value sub-block s: query i sees the first vis_count(i, s) keys of it
+  auto vis_count = [&](int i, int s) -> int {
+    if (!d.causal) return g.rows[s];
+    const int64_t v = (int64_t)i + g.rel[s] + 1;
+    return v <= 0 ? 0 : (v < g.rows[s] ? (int)v : g.rows[s]);
   };
   const int blk_last = min(q0 + DQ_ROWS, d.nq) - 1;
-  const int nblk = (vis_count(blk_last) + BKS - 1) / BKS;
   const int w_first = min(q0 + wave * 32, d.nq - 1);
   const int w_last = min(q0 + wave * 32 + 31, d.nq - 1);
-  const int nvis_wave = vis_count(w_last);
-  const int nfull_wave = vis_count(w_first);
-  cx.my_vis = vis_count(q_ld);
+  // key blocks of sub-block s that some row of the workgroup sees; the walk over (sub-block, block)
+  auto seg_blocks = [&](int s) { return (vis_count(blk_last, s) + BKS - 1) / BKS; };
+  int nvis_wave = 0, nfull_wave = 0;               // of the current sub-block
+  auto enter_segment = [&](int s) {
+    nvis_wave = vis_count(w_last, s);
+    nfull_wave = vis_count(w_first, s);
+    cx.my_vis = vis_count(q_ld, s);
+  };
 #pragma unroll
   for (int t = 0; t < 4; ++t) cx.dq[t] = zero16();
 
@@ -532,10 +560,12 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   constexpr int ST_ROWS = DQ_THREADS / 16, ST_N = 32 / ST_ROWS;
   const int st_row = tid >> 4, st_ch = tid & 15;
   u32x4 kreg[ST_N], vreg[ST_N];
-  auto load_half = [&](int k0, int hf) {
+  // half hf of block j of the sub-block of seg_rows keys that starts at local key seg_start
+  auto load_half = [&](int seg_start, int seg_rows, int j, int hf) {
+    const int k0 = seg_start + j * BKS;
     const gptr_t kb = uniform_gptr(K + (int64_t)k0 * H);
     const gptr_t vb = uniform_gptr(V + (int64_t)k0 * H);
-    const int last = d.nkv - 1 - k0;
+    const int last = seg_rows - 1 - j * BKS;       // rows beyond the sub-block re-read its last row
 #pragma unroll
     for (int p = 0; p < ST_N; ++p) {
       const unsigned off = (unsigned)(min(32 * hf + st_row + ST_ROWS * p, last) * (H * 2) + st_ch * 16);
@@ -553,28 +583,46 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
     }
   };
 
-  if (nblk > 0) {
-    load_half(0, 0); store_half(0, 0);
-    load_half(0, 1); store_half(0, 1);
+  // Walk over (sub-block, key block).  The sub-block table lives in kernel-argument memory, and
+  // scalar loads share a wait counter with the LDS reads in flight, so it is only touched when
+  // the walk moves to another sub-block; in between its values sit in registers.
+  int sb = 0, j = 0;                               // current sub-block and key block within it
+  while (sb < g.n && seg_blocks(sb) == 0) ++sb;
+  int nblk = 0, nx_start = 0, nx_rows = 0, nx_nblk = 0;   // blocks of sb; start / rows / blocks of the next block's sub-block
+  if (sb < g.n) {
+    enter_segment(sb);
+    nblk = nx_nblk = seg_blocks(sb); nx_start = g.start[sb]; nx_rows = g.rows[sb];
+    load_half(nx_start, nx_rows, 0, 0); store_half(0, 0);
+    load_half(nx_start, nx_rows, 0, 1); store_half(0, 1);
   }
   __syncthreads();
 
-  for (int j = 0; j < nblk; ++j) {
-    const int k0 = j * BKS;
-    const bool more = j + 1 < nblk;
-    if (more) load_half(k0 + BKS, 0);
+  int buf = 0;
+  while (sb < g.n) {
+    int nsb = sb, nj = j + 1;
+    if (nj >= nblk) {                              // the next block opens another sub-block
+      nj = 0;
+      do { ++nsb; } while (nsb < g.n && seg_blocks(nsb) == 0);
+      if (nsb < g.n) { nx_start = g.start[nsb]; nx_rows = g.rows[nsb]; nx_nblk = seg_blocks(nsb); }
+    }
+    const bool more = nsb < g.n;
+    const int k0 = j * BKS;                        // local to the sub-block
+    if (more) load_half(nx_start, nx_rows, nj, 0);
     if (k0 < nvis_wave) {
       if (k0 + 32 > nfull_wave) dq_piece<0, true>(cx, k0); else dq_piece<0, false>(cx, k0);
     }
-    if (more) { store_half((j + 1) & 1, 0); load_half(k0 + BKS, 1); }
+    if (more) { store_half(buf ^ 1, 0); load_half(nx_start, nx_rows, nj, 1); }
     if (k0 + 32 < nvis_wave) {
       if (k0 + 64 > nfull_wave) dq_piece<1, true>(cx, k0 + 32); else dq_piece<1, false>(cx, k0 + 32);
     }
-    if (more) store_half((j + 1) & 1, 1);
-    const int tog = (j & 1) ? -DQ_BUF : DQ_BUF;
+    if (more) store_half(buf ^ 1, 1);
+    const int tog = buf ? -DQ_BUF : DQ_BUF;
     cx.ka.shift(tog);
     cx.vnat += tog;
     __syncthreads();
+    if (more && nsb != sb) { enter_segment(nsb); nblk = nx_nblk; }
+    sb = nsb; j = nj;
+    buf ^= 1;
   }
   if (q_ok) store_acc_t(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, d.scale);
 }
@@ -585,7 +633,7 @@ bool bwd_mfma_supported(const a2d_tile_desc& d) {
   return d.dtype == A2D_BF16 && d.hdim == mfma::H;
 }
 
-hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                            const void* dO, const float* lse, const float* delta, float* dQ,
                            float* dK, float* dV, hipStream_t s) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_kernel),
@@ -604,15 +652,15 @@ hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K,
   dim3 grid_kv(xcd_grid(d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS));
   const int dq_rows = big ? 256 : 128;
   dim3 grid_q(xcd_grid(d.heads, (d.nq + dq_rows - 1) / dq_rows));
-  hipLaunchKernelGGL(bwd_dkdv_kernel, grid_kv, dim3(DK_THREADS), DK_LDS, s, d, (const bf16_t*)Q,
+  hipLaunchKernelGGL(bwd_dkdv_kernel, grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (big)
-    hipLaunchKernelGGL(bwd_dq_kernel<8>, grid_q, dim3(512), DQ_LDS, s, d, (const bf16_t*)Q,
+    hipLaunchKernelGGL(bwd_dq_kernel<8>, grid_q, dim3(512), DQ_LDS, s, d, g, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
   else
-    hipLaunchKernelGGL(bwd_dq_kernel<4>, grid_q, dim3(256), DQ_LDS, s, d, (const bf16_t*)Q,
+    hipLaunchKernelGGL(bwd_dq_kernel<4>, grid_q, dim3(256), DQ_LDS, s, d, g, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
   return hipGetLastError();
 }

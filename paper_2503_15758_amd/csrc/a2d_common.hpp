@@ -33,13 +33,36 @@ template <typename T> struct dtype_of;
 template <> struct dtype_of<float> { static constexpr int value = A2D_F32; };
 template <> struct dtype_of<bf16_t> { static constexpr int value = A2D_BF16; };
 
+// Key/value sub-blocks of a tile for the causal mask.  Sub-block s covers the local keys
+// start[s] .. start[s] + rows[s] - 1 (the sub-blocks tile 0 .. nkv - 1 in order) and its keys are
+// consecutive tokens; rel[s] = q_off - (global index of its first key).  Query row i (local) sees
+// key start[s] + kk of sub-block s iff kk <= i + rel[s].  A plain tile is one sub-block.
+struct SegList {
+  int n;
+  int start[A2D_MAX_SEGMENTS];
+  int rows[A2D_MAX_SEGMENTS];
+  int64_t rel[A2D_MAX_SEGMENTS];
+};
+
+// sub-block that holds local key c (c < nkv)
+__device__ __forceinline__ int seg_of_key(const SegList& g, int c) {
+  int s = 0;
+  while (s + 1 < g.n && c >= g.start[s + 1]) ++s;
+  return s;
+}
+// does query row i see local key c (causal mask)?
+__device__ __forceinline__ bool seg_visible(const SegList& g, int i, int c) {
+  const int s = seg_of_key(g, c);
+  return (int64_t)(c - g.start[s]) <= (int64_t)i + g.rel[s];
+}
+
 // ---- launchers (each returns the launch's hipError_t; none synchronises) ----
 
 // Generic tile kernels: fp32 arithmetic on the vector ALUs for fp32 or bf16
 // inputs, any nq / nkv, H in {64, 128}.
-hipError_t launch_fwd_generic(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+hipError_t launch_fwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                               float* O_part, float* m, float* l, hipStream_t s);
-hipError_t launch_bwd_generic(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+hipError_t launch_bwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                               const void* dO, const float* lse, const float* delta, float* dQ,
                               float* dK, float* dV, hipStream_t s);
 
@@ -49,10 +72,10 @@ hipError_t launch_delta(int dtype, int64_t rows, int hdim, const void* O, const 
 
 // bf16 MFMA tile kernels (H = 128).  `supported` tells whether the shape is covered.
 bool fwd_mfma_supported(const a2d_tile_desc& d);
-hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                            float* O_part, float* m, float* l, hipStream_t s);
 bool bwd_mfma_supported(const a2d_tile_desc& d);
-hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                            const void* dO, const float* lse, const float* delta, float* dQ,
                            float* dK, float* dV, hipStream_t s);
 

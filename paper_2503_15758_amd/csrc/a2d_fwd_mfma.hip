@@ -142,7 +142,7 @@ __device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], u
 // every compute unit one.
 template <int WAVES>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
-    a2d_tile_desc d, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+    a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, float* __restrict__ O_part, float* __restrict__ m_out,
     float* __restrict__ l_out) {
   constexpr int BM = 32 * WAVES;          // query rows per workgroup
@@ -174,20 +174,24 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   }
   wait_vmem_all();
 
-  // ---- visibility bounds in local key indices: query i sees key r iff r <= i + rel
-  const int64_t rel = d.q_off - d.kv_off;
-  auto vis_count = [&](int i) -> int {      // number of leading keys query row i can see
-    if (!d.causal) return d.nkv;
-    const int64_t v = (int64_t)i + rel + 1;
-    return v <= 0 ? 0 : (v < d.nkv ? (int)v : d.nkv);
+  // ---- visibility, per key/value sub-block s: query i sees the first vis_count(i, s) keys of it
+  // (key kk of the sub-block iff kk <= i + rel[s])
+  auto vis_count = [&](int i, int s) -> int {
+    if (!d.causal) return g.rows[s];
+    const int64_t v = (int64_t)i + g.rel[s] + 1;
+    return v <= 0 ? 0 : (v < g.rows[s] ? (int)v : g.rows[s]);
   };
   const int blk_last = min(q0 + BM, d.nq) - 1;
-  const int nblk = (vis_count(blk_last) + BN - 1) / BN;
   const int w_first = min(q0 + wave * 32, d.nq - 1);
   const int w_last = min(q0 + wave * 32 + 31, d.nq - 1);
-  const int nvis_wave = vis_count(w_last);      // keys any row of the wave sees
-  const int nfull_wave = vis_count(w_first);    // keys every row of the wave sees
-  const int my_vis = vis_count(min(q_row, d.nq - 1));
+  // key blocks of sub-block s that some row of the workgroup sees; the walk over (sub-block, block)
+  auto seg_blocks = [&](int s) { return (vis_count(blk_last, s) + BN - 1) / BN; };
+  int nvis_wave = 0, nfull_wave = 0, my_vis = 0;   // of the current sub-block
+  auto enter_segment = [&](int s) {
+    nvis_wave = vis_count(w_last, s);        // keys any row of the wave sees
+    nfull_wave = vis_count(w_first, s);      // keys every row of the wave sees
+    my_vis = vis_count(min(q_row, d.nq - 1), s);
+  };
 
   FwdState st;
 #pragma unroll
@@ -204,10 +208,13 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   const int v_wr = K_BYTES + ld_row * VLD + ld_chunk * 16;
   constexpr int ST_ROWS = kThreads / 16, ST_N = BN / ST_ROWS;   // rows per pass, passes per tile
   u32x4 kreg[ST_N], vreg[ST_N];
-  auto load_tile = [&](int k0) {
+  // block j of the sub-block of seg_rows keys that starts at local key seg_start; rows beyond its
+  // end re-read its last row
+  auto load_tile = [&](int seg_start, int seg_rows, int j) {
+    const int k0 = seg_start + j * BN;
     const gptr_t kb = uniform_gptr(K + (int64_t)k0 * H);   // scalar bases
     const gptr_t vb = uniform_gptr(V + (int64_t)k0 * H);
-    const int last = d.nkv - 1 - k0;
+    const int last = seg_rows - 1 - j * BN;
 #pragma unroll
     for (int p = 0; p < ST_N; ++p) {
       const unsigned off = (unsigned)(min(ld_row + ST_ROWS * p, last) * (H * 2) + ld_chunk * 16);
@@ -228,23 +235,40 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   const unsigned v_rd0 =
       lds_base + K_BYTES + (4 * (g16 >> 1) + (j16 >> 2)) * VLD + (16 * (g16 & 1) + 4 * (j16 & 3)) * 2;
 
-  if (nblk > 0) {
-    load_tile(0);
+  // Walk over (sub-block, key block).  The sub-block table lives in kernel-argument memory, and
+  // scalar loads share a wait counter with the LDS reads in flight, so it is only touched when
+  // the walk moves to another sub-block; in between its values sit in registers.
+  int sb = 0, j = 0;                               // current sub-block and key block within it
+  while (sb < g.n && seg_blocks(sb) == 0) ++sb;    // first sub-block with visible keys
+  int nblk = 0, nx_start = 0, nx_rows = 0, nx_nblk = 0;   // blocks of sb; start / rows / blocks of the next block's sub-block
+  if (sb < g.n) {
+    enter_segment(sb);
+    nblk = nx_nblk = seg_blocks(sb); nx_start = g.start[sb]; nx_rows = g.rows[sb];
+    load_tile(nx_start, nx_rows, 0);
     store_tile(0);
   }
   __syncthreads();
 
-  for (int j = 0; j < nblk; ++j) {
-    const int k0 = j * BN;
-    const int boff = (j & 1) * BUF_BYTES;
-    const bool more = j + 1 < nblk;
-    if (more) load_tile(k0 + BN);
+  int boff = 0;
+  while (sb < g.n) {
+    int nsb = sb, nj = j + 1;
+    if (nj >= nblk) {                              // the next block opens another sub-block
+      nj = 0;
+      do { ++nsb; } while (nsb < g.n && seg_blocks(nsb) == 0);
+      if (nsb < g.n) { nx_start = g.start[nsb]; nx_rows = g.rows[nsb]; nx_nblk = seg_blocks(nsb); }
+    }
+    const bool more = nsb < g.n;
+    if (more) load_tile(nx_start, nx_rows, nj);
+    const int k0 = j * BN;                         // local to the sub-block
     if (k0 < nvis_wave) {
       if (k0 + BN > nfull_wave) fwd_block<true>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
       else fwd_block<false>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
     }
     if (more) store_tile(BUF_BYTES - boff);
     __syncthreads();
+    if (more && nsb != sb) { enter_segment(nsb); nblk = nx_nblk; }
+    sb = nsb; j = nj;
+    boff = BUF_BYTES - boff;
   }
 
   // ---- epilogue: bring N and l to the true row maximum, store N, m (scaled units), l
@@ -275,7 +299,7 @@ bool fwd_mfma_supported(const a2d_tile_desc& d) {
   return d.dtype == A2D_BF16 && d.hdim == mfma::H;
 }
 
-hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                            float* O_part, float* m, float* l, hipStream_t s) {
   // eight wavefronts per workgroup unless that leaves compute units without a workgroup
   int dev = 0, cus = 0;
@@ -290,10 +314,10 @@ hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const void* Q, const void* K,
   const int bm = big ? 256 : 128;
   dim3 grid(xcd_grid(d.heads, (d.nq + bm - 1) / bm)), block(big ? 512 : 256);
   if (big)
-    hipLaunchKernelGGL(fwd_mfma_kernel<8>, grid, block, kLdsBytes, s, d, (const bf16_t*)Q, (const bf16_t*)K,
+    hipLaunchKernelGGL(fwd_mfma_kernel<8>, grid, block, kLdsBytes, s, d, g, (const bf16_t*)Q, (const bf16_t*)K,
                        (const bf16_t*)V, O_part, m, l);
   else
-    hipLaunchKernelGGL(fwd_mfma_kernel<4>, grid, block, kLdsBytes, s, d, (const bf16_t*)Q, (const bf16_t*)K,
+    hipLaunchKernelGGL(fwd_mfma_kernel<4>, grid, block, kLdsBytes, s, d, g, (const bf16_t*)Q, (const bf16_t*)K,
                        (const bf16_t*)V, O_part, m, l);
   return hipGetLastError();
 }

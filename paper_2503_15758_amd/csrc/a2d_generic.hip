@@ -45,16 +45,22 @@ __device__ __forceinline__ float group16_sum(float v) {
 
 // number of leading keys of the tile that at least one of the query rows
 // [.., q_last] can see under the causal mask (all nkv without a mask)
-__device__ __forceinline__ int visible_keys(const a2d_tile_desc& d, int q_last) {
+// (with several sub-blocks: one past the last key that any of them shows to row q_last)
+__device__ __forceinline__ int visible_keys(const a2d_tile_desc& d, const SegList& g, int q_last) {
   if (!d.causal) return d.nkv;
-  const int64_t v = d.q_off + q_last - d.kv_off + 1;
-  return v <= 0 ? 0 : (v < d.nkv ? (int)v : d.nkv);
+  int nvis = 0;
+  for (int s = 0; s < g.n; ++s) {
+    const int64_t v = (int64_t)q_last + g.rel[s] + 1;          // visible keys of sub-block s
+    const int vs = v <= 0 ? 0 : (v < g.rows[s] ? (int)v : g.rows[s]);
+    if (vs > 0) nvis = g.start[s] + vs;
+  }
+  return nvis;
 }
 
 // ------------------------------------------------------------------ forward
 template <typename T, int H>
 __global__ __launch_bounds__(kThreads) void fwd_generic_kernel(
-    a2d_tile_desc d, const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    a2d_tile_desc d, SegList g, const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     float* __restrict__ O_part, float* __restrict__ m_out, float* __restrict__ l_out) {
   constexpr int BM = 64, BN = 64, LD = H + 1, HB = H / 16;
   extern __shared__ float smem[];
@@ -80,7 +86,7 @@ __global__ __launch_bounds__(kThreads) void fwd_generic_kernel(
     for (int b = 0; b < HB; ++b) o[a][b] = 0.f;
   }
   const int q_last = min(q0 + BM, d.nq) - 1;
-  const int nvis = visible_keys(d, q_last);
+  const int nvis = visible_keys(d, g, q_last);
 
   for (int k0 = 0; k0 < nvis; k0 += BN) {
     __syncthreads();
@@ -105,12 +111,12 @@ __global__ __launch_bounds__(kThreads) void fwd_generic_kernel(
     }
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
-      const int64_t gi = d.q_off + q0 + ty * 4 + a;
+      const int gi = q0 + ty * 4 + a;
       float rmax = -INFINITY;
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
         const int c = k0 + tx + 16 * b;
-        const bool vis = (c < d.nkv) && (!d.causal || gi >= d.kv_off + c);
+        const bool vis = (c < d.nkv) && (!d.causal || seg_visible(g, gi, c));
         s[a][b] = vis ? s[a][b] * d.scale : -INFINITY;
         rmax = fmaxf(rmax, s[a][b]);
       }
@@ -159,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void fwd_generic_kernel(
 // ------------------------------------------------------------- backward: dK, dV
 template <typename T, int H>
 __global__ __launch_bounds__(kThreads) void bwd_dkdv_generic_kernel(
-    a2d_tile_desc d, const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    a2d_tile_desc d, SegList g, const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ delta,
     float* __restrict__ dK, float* __restrict__ dV) {
   constexpr int BK = 64, BQ = 32, LD = H + 1, HB = H / 16, LP = BK + 1;
@@ -190,10 +196,18 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_generic_kernel(
     for (int b = 0; b < HB; ++b) { dk[a][b] = 0.f; dv[a][b] = 0.f; }
 
   // first query row that can see key k0 (rows before it see none of this block's keys)
+  // (with several sub-blocks: the earliest such row over the sub-blocks this key block touches)
   int i_first = 0;
   if (d.causal) {
-    const int64_t f = d.kv_off + k0 - d.q_off;
-    i_first = f <= 0 ? 0 : (f >= d.nq ? d.nq : (int)f);
+    i_first = d.nq;
+    const int k_end = min(k0 + BK, d.nkv);
+    for (int sb = 0; sb < g.n; ++sb) {
+      const int a = max(k0, g.start[sb]), b = min(k_end, g.start[sb] + g.rows[sb]);
+      if (a >= b) continue;
+      const int64_t f = (int64_t)(a - g.start[sb]) - g.rel[sb];      // first row that sees key a
+      const int fr = f <= 0 ? 0 : (f >= d.nq ? d.nq : (int)f);
+      i_first = min(i_first, fr);
+    }
   }
   for (int i0 = (i_first / BQ) * BQ; i0 < d.nq; i0 += BQ) {
     __syncthreads();
@@ -225,12 +239,11 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_generic_kernel(
       const bool row_ok = i < d.nq;
       const float lse_i = row_ok ? lse[i] : -INFINITY;
       const float del_i = row_ok ? delta[i] : 0.f;
-      const int64_t gi = d.q_off + i;
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
         const int c = k0 + tx + 16 * b;
         const bool vis = row_ok && (lse_i != -INFINITY) && (c < d.nkv) &&
-                         (!d.causal || gi >= d.kv_off + c);
+                         (!d.causal || seg_visible(g, i, c));
         const float p = vis ? fast_exp2((s[a][b] * d.scale - lse_i) * kLog2e) : 0.f;
         Ps[(ty * 2 + a) * LP + tx + 16 * b] = p;
         dSs[(ty * 2 + a) * LP + tx + 16 * b] = p * (dp[a][b] - del_i);
@@ -269,7 +282,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_generic_kernel(
 // ---------------------------------------------------------------- backward: dQ
 template <typename T, int H>
 __global__ __launch_bounds__(kThreads) void bwd_dq_generic_kernel(
-    a2d_tile_desc d, const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    a2d_tile_desc d, SegList g, const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ delta,
     float* __restrict__ dQ) {
   constexpr int BQ = 64, BK = 32, LD = H + 1, HB = H / 16, LP = BK + 1;
@@ -303,7 +316,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_generic_kernel(
     for (int b = 0; b < HB; ++b) dq[a][b] = 0.f;
   }
   const int q_last = min(q0 + BQ, d.nq) - 1;
-  const int nvis = visible_keys(d, q_last);
+  const int nvis = visible_keys(d, g, q_last);
 
   for (int k0 = 0; k0 < nvis; k0 += BK) {
     __syncthreads();
@@ -331,11 +344,11 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_generic_kernel(
     }
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
-      const int64_t gi = d.q_off + q0 + ty * 4 + a;
+      const int gi = q0 + ty * 4 + a;
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
         const int c = k0 + tx + 16 * b;
-        const bool vis = (lse_i[a] != -INFINITY) && (c < d.nkv) && (!d.causal || gi >= d.kv_off + c);
+        const bool vis = (lse_i[a] != -INFINITY) && (c < d.nkv) && (!d.causal || seg_visible(g, gi, c));
         const float p = vis ? fast_exp2((s[a][b] * d.scale - lse_i[a]) * kLog2e) : 0.f;
         dSs[(ty * 4 + a) * LP + tx + 16 * b] = p * (dp[a][b] - del_i[a]);
       }
@@ -397,19 +410,19 @@ hipError_t set_lds(K kernel, size_t bytes) {
 }
 
 template <typename T, int H>
-hipError_t fwd_launch(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+hipError_t fwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                       float* O_part, float* m, float* l, hipStream_t s) {
   constexpr size_t lds = sizeof(float) * (64 * (H + 1) * 2 + 64 * H + 64 * 65);
   hipError_t e = set_lds(fwd_generic_kernel<T, H>, lds);
   if (e != hipSuccess) return e;
   dim3 grid((d.nq + 63) / 64, d.heads), block(kThreads);
-  hipLaunchKernelGGL((fwd_generic_kernel<T, H>), grid, block, lds, s, d, (const T*)Q, (const T*)K,
+  hipLaunchKernelGGL((fwd_generic_kernel<T, H>), grid, block, lds, s, d, g, (const T*)Q, (const T*)K,
                      (const T*)V, O_part, m, l);
   return hipGetLastError();
 }
 
 template <typename T, int H>
-hipError_t bwd_launch(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+hipError_t bwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                       const void* dO, const float* lse, const float* delta, float* dQ, float* dK,
                       float* dV, hipStream_t s) {
   constexpr size_t lds_kv = sizeof(float) * (2 * 64 * (H + 1) + 2 * 32 * (H + 1) + 2 * 32 * 65);
@@ -420,36 +433,36 @@ hipError_t bwd_launch(const a2d_tile_desc& d, const void* Q, const void* K, cons
   if (e != hipSuccess) return e;
   dim3 block(kThreads);
   dim3 grid_kv((d.nkv + 63) / 64, d.heads), grid_q((d.nq + 63) / 64, d.heads);
-  hipLaunchKernelGGL((bwd_dkdv_generic_kernel<T, H>), grid_kv, block, lds_kv, s, d, (const T*)Q,
+  hipLaunchKernelGGL((bwd_dkdv_generic_kernel<T, H>), grid_kv, block, lds_kv, s, d, g, (const T*)Q,
                      (const T*)K, (const T*)V, (const T*)dO, lse, delta, dK, dV);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((bwd_dq_generic_kernel<T, H>), grid_q, block, lds_q, s, d, (const T*)Q,
+  hipLaunchKernelGGL((bwd_dq_generic_kernel<T, H>), grid_q, block, lds_q, s, d, g, (const T*)Q,
                      (const T*)K, (const T*)V, (const T*)dO, lse, delta, dQ);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_fwd_generic(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+hipError_t launch_fwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                               float* O_part, float* m, float* l, hipStream_t s) {
   if (d.dtype == A2D_BF16) {
-    return d.hdim == 128 ? fwd_launch<bf16_t, 128>(d, Q, K, V, O_part, m, l, s)
-                         : fwd_launch<bf16_t, 64>(d, Q, K, V, O_part, m, l, s);
+    return d.hdim == 128 ? fwd_launch<bf16_t, 128>(d, g, Q, K, V, O_part, m, l, s)
+                         : fwd_launch<bf16_t, 64>(d, g, Q, K, V, O_part, m, l, s);
   }
-  return d.hdim == 128 ? fwd_launch<float, 128>(d, Q, K, V, O_part, m, l, s)
-                       : fwd_launch<float, 64>(d, Q, K, V, O_part, m, l, s);
+  return d.hdim == 128 ? fwd_launch<float, 128>(d, g, Q, K, V, O_part, m, l, s)
+                       : fwd_launch<float, 64>(d, g, Q, K, V, O_part, m, l, s);
 }
 
-hipError_t launch_bwd_generic(const a2d_tile_desc& d, const void* Q, const void* K, const void* V,
+hipError_t launch_bwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                               const void* dO, const float* lse, const float* delta, float* dQ,
                               float* dK, float* dV, hipStream_t s) {
   if (d.dtype == A2D_BF16) {
-    return d.hdim == 128 ? bwd_launch<bf16_t, 128>(d, Q, K, V, dO, lse, delta, dQ, dK, dV, s)
-                         : bwd_launch<bf16_t, 64>(d, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
+    return d.hdim == 128 ? bwd_launch<bf16_t, 128>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s)
+                         : bwd_launch<bf16_t, 64>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
   }
-  return d.hdim == 128 ? bwd_launch<float, 128>(d, Q, K, V, dO, lse, delta, dQ, dK, dV, s)
-                       : bwd_launch<float, 64>(d, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
+  return d.hdim == 128 ? bwd_launch<float, 128>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s)
+                       : bwd_launch<float, 64>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
 }
 
 hipError_t launch_delta(int dtype, int64_t rows, int hdim, const void* O, const void* dO,

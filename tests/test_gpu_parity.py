@@ -337,3 +337,66 @@ def test_mfma_ceiling_probe_runs(a2d):
     rc = a2d.lib().a2d_mfma_ceiling(10, 0, ctypes.c_void_p(scratch.data_ptr()), scratch.numel(),
                                     ctypes.byref(t), ctypes.byref(m))
     assert rc == -4
+
+
+# ----------------------------------------------------------------------------- gathered tiles
+SEG_CASES = [
+    # heads, nq, H, q_off, causal, [(kv_off, rows), ...]
+    (2, 128, 128, 0, True, [(0, 128), (1, 128)]),                          # cyclic layout: i >= j and i >= j + 1
+    (1, 200, 128, 300, True, [(0, 100), (700, 64), (250, 131), (100, 77)]),  # ragged, unordered, one invisible
+    (2, 256, 128, 512, True, [(0, 256), (256, 256), (512, 256), (768, 256)]),  # contiguous blocks, last above the diagonal
+    (1, 300, 128, 64, True, [(1000, 64), (0, 192), (3000, 200), (64, 300)]),  # invisible sub-blocks first and in between
+    (2, 130, 128, 0, False, [(5, 70), (0, 190)]),                          # no mask: offsets are irrelevant
+    (1, 96, 64, 40, True, [(0, 50), (30, 70)]),                            # generic (H = 64) kernels
+    (1, 8, 128, 0, True, [(100, 16), (200, 16)]),                          # nothing visible at all
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("case", SEG_CASES, ids=lambda c: "%dx%dxH%d_q%d_%s_%dseg" % (c[0], c[1], c[2], c[3], c[4], len(c[5])))
+def test_gathered_tile_fwd_bwd(a2d, dt, case):
+    """a2d_partial_fwd_seg / a2d_partial_bwd_seg against the oracle's key-position functions."""
+    heads, nq, H, q_off, causal, segs = case
+    nkv = sum(r for _, r in segs)
+    scale = 1.0 / math.sqrt(H)
+    Q = synth.normal((heads, nq, H), 31, 0, 1.0, dt)
+    K = synth.normal((heads, nkv, H), 31, 1, 1.0, dt)
+    V = synth.normal((heads, nkv, H), 31, 2, 1.0, dt)
+    dO = synth.normal((heads, nq, H), 31, 3, 1.0, dt)
+    kpos = oracle.segment_positions(segs)
+    what = "seg %s %s" % (dt, case[:5])
+    Np, m, l = a2d.partial_fwd(dev(Q), dev(K), dev(V), q_off, 0, causal, scale, segments=segs)
+    torch.cuda.synchronize()
+    Nr, mr, lr = oracle.partial_fwd_pos(np64(Q), np64(K), np64(V), q_off, kpos, causal, scale)
+    Ng, mg, lg = np64(Np), np64(m), np64(l)
+    empty = np.isinf(mr)
+    assert np.array_equal(np.isinf(mg) & (mg < 0), empty), what + ": set of empty rows differs"
+    assert np.all(lg[empty] == 0.0) and np.all(Ng[empty] == 0.0)
+    ok = ~empty
+    if ok.any():
+        assert_close(mg[ok], mr[ok], DT[dt], what + " m", rel=False)
+        assert_close(Ng[ok] / lg[ok][:, None], Nr[ok] / lr[ok][:, None], DT[dt], what + " N/l")
+        assert_close(mg[ok] + np.log(lg[ok]), mr[ok] + np.log(lr[ok]), DT[dt], what + " m+ln l", rel=False)
+    # backward from the oracle's final O / lse of this (single) gathered tile
+    Or, lser = oracle.fix([Nr], [mr], [lr])
+    O_in = torch.from_numpy(Or).to(DT[dt])
+    lse_in = torch.from_numpy(lser).to(torch.float32)
+    dQ, dK, dV = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, 0, causal,
+                                 scale, segments=segs)
+    torch.cuda.synchronize()
+    with np.errstate(invalid="ignore"):
+        rq, rk, rv = oracle.partial_bwd_pos(np64(Q), np64(K), np64(V), np64(O_in), np64(dO), np64(lse_in),
+                                            q_off, kpos, causal, scale)
+    assert_close(dQ, rq, DT[dt], what + " dQ")
+    assert_close(dK, rk, DT[dt], what + " dK")
+    assert_close(dV, rv, DT[dt], what + " dV")
+    # one sub-block = the plain call, bit for bit
+    if len(segs) >= 1:
+        off0, rows0 = segs[0]
+        a = a2d.partial_fwd(dev(Q), dev(K[:, :rows0].contiguous()), dev(V[:, :rows0].contiguous()), q_off, off0, causal, scale)
+        b = a2d.partial_fwd(dev(Q), dev(K[:, :rows0].contiguous()), dev(V[:, :rows0].contiguous()), q_off, 0, causal, scale,
+                            segments=[(off0, rows0)])
+        torch.cuda.synchronize()
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)

@@ -112,3 +112,23 @@ def test_mfma_ceiling_argument_errors(binding):
     assert L.a2d_mfma_ceiling(10, 1, P, 1 << 20, None, ctypes.byref(mhz)) == -1
     assert L.a2d_mfma_ceiling(10, 1, None, 1 << 20, ctypes.byref(tf), ctypes.byref(mhz)) == -1
     assert L.a2d_mfma_ceiling(10, 1, ctypes.c_void_p(0x10004), 1 << 20, ctypes.byref(tf), ctypes.byref(mhz)) == -3
+
+
+def test_gathered_tile_argument_errors(binding):
+    b, L = binding, binding.lib()
+    P = ctypes.c_void_p(0x10000)
+    d = _desc(b, nkv=128)
+    def fwd(segs, n=None):
+        arr = (b.KvSegment * max(len(segs), 1))()
+        for i, (o, r, pad) in enumerate(segs):
+            arr[i].kv_off, arr[i].rows, arr[i].pad = o, r, pad
+        return L.a2d_partial_fwd_seg(ctypes.byref(d), len(segs) if n is None else n, arr, P, P, P, P, P, P, None, 0, None)
+    assert fwd([(0, 64, 0), (5, 63, 0)]) == -1 and b"128" in L.a2d_last_error()     # rows do not add up
+    assert fwd([(0, 128, 0), (5, 1, 0)]) == -1
+    assert fwd([(0, 0, 0), (5, 128, 0)]) == -1
+    assert fwd([(0, 128, 1)]) == -1
+    assert fwd([(0, 128, 0)], n=0) == -1
+    assert fwd([(0, 128, 0)], n=33) == -1
+    assert L.a2d_partial_fwd_seg(ctypes.byref(d), 1, None, P, P, P, P, P, P, None, 0, None) == -1
+    arr = (b.KvSegment * 1)(); arr[0].kv_off, arr[0].rows = 0, 128
+    assert L.a2d_partial_bwd_seg(ctypes.byref(d), 1, arr, P, P, P, P, P, P, P, P, P, None, 0, None) == -4
