@@ -255,6 +255,10 @@ def gathered_tile(a2d, synth, w, scale, kernels):
     t_f = timeit(lambda: a2d.partial_fwd(Q, K, V, r * T, 0, True, scale, out=out, segments=segs))
     t_b = timeit(lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, out=o3, workspace=ws,
                                          segments=segs))
+    # accumulating form on one unmasked tile: starts from the triple in `acc` and merges in place
+    K0, V0 = dev(synth.k_block(w, 0)), dev(synth.v_block(w, 0))
+    acc = a2d.partial_fwd(Q, dev(synth.k_block(w, 1)), dev(synth.v_block(w, 1)), r * T, T, True, scale)
+    t_acc = timeit(lambda: a2d.partial_fwd(Q, K0, V0, r * T, 0, True, scale, out=acc, accumulate=True), n=10)
     frac = (G - 1) + (T + 1) / (2.0 * T)                      # visible tiles of the row
     base = w.heads * T * T * H * frac
     sep_f = (G - 1) * kernels["partial_fwd_full"]["avg_ms"] + kernels["partial_fwd_diag"]["avg_ms"] + \
@@ -264,7 +268,10 @@ def gathered_tile(a2d, synth, w, scale, kernels):
             "fwd_ms": round(t_f, 4), "fwd_tflops": round(4 * base / t_f / 1e9, 1),
             "bwd_ms": round(t_b, 4), "bwd_tflops": round(10 * base / t_b / 1e9, 1),
             "fwd_ms_one_launch_per_block_plus_fix": round(sep_f, 4),
-            "bwd_ms_one_launch_per_block": round(sep_b, 4)}
+            "bwd_ms_one_launch_per_block": round(sep_b, 4),
+            "fwd_acc_unmasked_tile_ms": round(t_acc, 4),
+            "fwd_acc_note": "a2d_partial_fwd_acc on one unmasked tile (merges into an existing triple); "
+                            "compare kernels.partial_fwd_full.avg_ms"}
 
 
 def cpu_baseline(w, scale):

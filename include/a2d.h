@@ -171,6 +171,30 @@ a2d_status a2d_partial_bwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv
                                size_t workspace_bytes, void* stream);
 
 /*
+ * Accumulating forms of the tile calls: the compute-then-reduce pair of the paper's overlapped
+ * algorithms (FlashAttn followed by AttnFix in GatherCompute and GatherComputeScatter, Sec. 4;
+ * "dQ += ..." in their backward counterparts) fused into the tile kernel.
+ *   a2d_partial_fwd_acc: O_part, m, l are IN/OUT.  On entry they hold a partial triple of the same
+ *     query block (e.g. written by an earlier tile call; m = -inf, l = 0, N = 0 is the empty
+ *     one); on exit they hold AttnFix(that triple, the partial of this tile): m the larger
+ *     maximum, N and l both rescaled to it and added.  Equal to a2d_partial_fwd into a second
+ *     buffer followed by a pairwise merge, up to fp32 rounding.
+ *   a2d_partial_bwd_acc: dQ_part is IN/OUT (this tile's dQ share is added to it); dK_part and
+ *     dV_part are written as by a2d_partial_bwd.
+ * nseg = 0 (segs ignored) means the plain tile of desc->kv_off; nseg >= 1 a gathered tile as for
+ * the _seg calls.  Calls that accumulate into the same buffers must be ordered on one stream.
+ */
+a2d_status a2d_partial_fwd_acc(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
+                               const void* Q, const void* K, const void* V, float* O_part,
+                               float* m, float* l, void* workspace, size_t workspace_bytes,
+                               void* stream);
+a2d_status a2d_partial_bwd_acc(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
+                               const void* Q, const void* K, const void* V, const void* O,
+                               const void* dO, const float* lse, float* dQ_part,
+                               float* dK_part, float* dV_part, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+/*
  * Sum of k gradient partials (the reduce-scatters of Alg. 3 lines 4-5 use plain
  * summation): out[i] = sum_k parts[k][i], added in index order in fp32, rounded
  * once to out_dtype.  parts: HOST array of k device pointers to n fp32 values;

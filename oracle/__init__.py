@@ -165,6 +165,15 @@ def attnfix_pair(M1, N1, D1, M2, N2, D2):
     return M, N, D
 
 
+def partial_fwd_acc(N_in, m_in, d_in, Q, K, V, q_off, kpos, causal, scale):
+    """The compute-then-reduce pair of the overlapped algorithms (Alg. GatherCompute /
+    GatherComputeScatter, lines Compute and Reduce): the tile's partial (Eq. (3)) merged by
+    AttnFix (Alg. 2) into an existing partial triple of the same query block.  Returns (N, m, d)."""
+    N, m, d = partial_fwd_pos(Q, K, V, q_off, kpos, causal, scale)
+    M, Nn, D = attnfix_pair(m_in, N_in, d_in, m, N, d)
+    return Nn, M, D
+
+
 def fix(Nparts, Mparts, Dparts):
     """k-way AttnFix + normalisation. Returns (O, lse)."""
     Nparts = [_c(a) for a in Nparts]

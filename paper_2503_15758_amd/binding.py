@@ -18,7 +18,7 @@ OP_PARTIAL_FWD, OP_FIX, OP_PARTIAL_BWD, OP_FIX_BWD = 0, 1, 2, 3
 MAX_PARTS = 32
 
 EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
-           "a2d_partial_fwd_seg", "a2d_partial_bwd_seg",
+           "a2d_partial_fwd_seg", "a2d_partial_bwd_seg", "a2d_partial_fwd_acc", "a2d_partial_bwd_acc",
            "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling",
            "a2d_status_str", "a2d_last_error", "a2d_version")
 
@@ -65,6 +65,10 @@ def lib():
         L.a2d_partial_bwd_seg.restype = ctypes.c_int
         L.a2d_partial_bwd_seg.argtypes = [ctypes.POINTER(TileDesc), ctypes.c_int, ctypes.POINTER(KvSegment),
                                           vp, vp, vp, vp, vp, fp, fp, fp, fp, vp, ctypes.c_size_t, vp]
+        L.a2d_partial_fwd_acc.restype = ctypes.c_int
+        L.a2d_partial_fwd_acc.argtypes = L.a2d_partial_fwd_seg.argtypes
+        L.a2d_partial_bwd_acc.restype = ctypes.c_int
+        L.a2d_partial_bwd_acc.argtypes = L.a2d_partial_bwd_seg.argtypes
         L.a2d_fix.restype = ctypes.c_int
         L.a2d_fix.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                               ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, fp, vp]
@@ -134,7 +138,8 @@ def _segments(segments):
     return arr
 
 
-def partial_fwd(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None, segments=None):
+def partial_fwd(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None, segments=None,
+                accumulate=False):
     """a2d_partial_fwd. Returns (O_part fp32 [heads][nq][H], m, l fp32 [heads][nq])."""
     for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
         _dev3(t, n)
@@ -148,6 +153,14 @@ def partial_fwd(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None, 
         l = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
     else:
         O_part, m, l = out
+    if accumulate:                 # out holds a partial triple of the same query block: merged in place
+        if out is None:
+            raise A2DError(-1, "accumulate needs out=(O_part, m, l)")
+        n = len(segments) if segments is not None else 0
+        _check(lib().a2d_partial_fwd_acc(ctypes.byref(d), n, _segments(segments) if n else None, _ptr(Q),
+                                         _ptr(K), _ptr(V), _ptr(O_part), _ptr(m), _ptr(l), None, 0,
+                                         _stream()))
+        return O_part, m, l
     if segments is not None:       # gathered tile: list of (kv_off, rows) sub-blocks, kv_off unused
         _check(lib().a2d_partial_fwd_seg(ctypes.byref(d), len(segments), _segments(segments), _ptr(Q),
                                          _ptr(K), _ptr(V), _ptr(O_part), _ptr(m), _ptr(l), None, 0,
@@ -178,7 +191,7 @@ def fix(O_parts, ms, ls, out_dtype=torch.bfloat16, out=None):
 
 
 def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None, out=None,
-                workspace=None, segments=None):
+                workspace=None, segments=None, accumulate=False):
     """a2d_partial_bwd. Returns (dQ_part, dK_part, dV_part), all fp32."""
     for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
         _dev3(t, n)
@@ -195,6 +208,15 @@ def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None
         dV = torch.empty(K.shape, dtype=torch.float32, device=Q.device)
     else:
         dQ, dK, dV = out
+    if accumulate:                 # out[0] (dQ_part) is added to
+        if out is None:
+            raise A2DError(-1, "accumulate needs out=(dQ_part, dK_part, dV_part)")
+        n = len(segments) if segments is not None else 0
+        _check(lib().a2d_partial_bwd_acc(ctypes.byref(d), n, _segments(segments) if n else None, _ptr(Q),
+                                         _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse), _ptr(dQ),
+                                         _ptr(dK), _ptr(dV), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream()))
+        return dQ, dK, dV
     if segments is not None:
         _check(lib().a2d_partial_bwd_seg(ctypes.byref(d), len(segments), _segments(segments), _ptr(Q),
                                          _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse), _ptr(dQ),

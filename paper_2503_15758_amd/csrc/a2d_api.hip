@@ -170,6 +170,18 @@ a2d_status a2d_partial_fwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv
   return partial_fwd_impl(desc, g, Q, K, V, O_part, m, l, stream, who);
 }
 
+a2d_status a2d_partial_fwd_acc(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
+                               const void* Q, const void* K, const void* V, float* O_part,
+                               float* m, float* l, void* /*workspace*/, size_t /*workspace_bytes*/,
+                               void* stream) {
+  const char* who = "a2d_partial_fwd_acc";
+  A2D_TRY(check_desc(desc, who));
+  a2d::SegList g = one_segment(desc);
+  if (nseg != 0) A2D_TRY(make_segments(desc, nseg, segs, who, &g));
+  g.acc = 1;
+  return partial_fwd_impl(desc, g, Q, K, V, O_part, m, l, stream, who);
+}
+
 a2d_status a2d_partial_fwd(const a2d_tile_desc* desc, const void* Q, const void* K, const void* V,
                            float* O_part, float* m, float* l, void* /*workspace*/,
                            size_t /*workspace_bytes*/, void* stream) {
@@ -215,6 +227,20 @@ a2d_status a2d_partial_bwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv
   A2D_TRY(check_desc(desc, who));
   a2d::SegList g;
   A2D_TRY(make_segments(desc, nseg, segs, who, &g));
+  return partial_bwd_impl(desc, g, Q, K, V, O, dO, lse, dQ_part, dK_part, dV_part, workspace,
+                          workspace_bytes, stream, who);
+}
+
+a2d_status a2d_partial_bwd_acc(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
+                               const void* Q, const void* K, const void* V, const void* O,
+                               const void* dO, const float* lse, float* dQ_part, float* dK_part,
+                               float* dV_part, void* workspace, size_t workspace_bytes,
+                               void* stream) {
+  const char* who = "a2d_partial_bwd_acc";
+  A2D_TRY(check_desc(desc, who));
+  a2d::SegList g = one_segment(desc);
+  if (nseg != 0) A2D_TRY(make_segments(desc, nseg, segs, who, &g));
+  g.acc = 1;
   return partial_bwd_impl(desc, g, Q, K, V, O, dO, lse, dQ_part, dK_part, dV_part, workspace,
                           workspace_bytes, stream, who);
 }

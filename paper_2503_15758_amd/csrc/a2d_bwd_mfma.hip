@@ -36,15 +36,21 @@ namespace {
 using namespace mfma;
 
 // stores a transposed accumulator (lane = one output row, registers = 4-column groups)
+// (add: onto what the row already holds)
 __device__ __forceinline__ void store_acc_t(float* __restrict__ out_row, const f32x16 (&acc)[4],
-                                            int half, float mul) {
+                                            int half, float mul, bool add = false) {
 #pragma unroll
   for (int ht = 0; ht < 4; ++ht)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       f32x4 v = {acc[ht][4 * g] * mul, acc[ht][4 * g + 1] * mul, acc[ht][4 * g + 2] * mul,
                  acc[ht][4 * g + 3] * mul};
-      *reinterpret_cast<f32x4*>(out_row + 32 * ht + 8 * g + 4 * half) = v;
+      f32x4* p = reinterpret_cast<f32x4*>(out_row + 32 * ht + 8 * g + 4 * half);
+      if (add) {
+        const f32x4 o = *p;
+        v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
+      }
+      *p = v;
     }
 }
 
@@ -624,7 +630,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
     sb = nsb; j = nj;
     buf ^= 1;
   }
-  if (q_ok) store_acc_t(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, d.scale);
+  if (q_ok) store_acc_t(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, d.scale, g.acc != 0);
 }
 
 }  // namespace

@@ -37,8 +37,11 @@ template <> struct dtype_of<bf16_t> { static constexpr int value = A2D_BF16; };
 // start[s] .. start[s] + rows[s] - 1 (the sub-blocks tile 0 .. nkv - 1 in order) and its keys are
 // consecutive tokens; rel[s] = q_off - (global index of its first key).  Query row i (local) sees
 // key start[s] + kk of sub-block s iff kk <= i + rel[s].  A plain tile is one sub-block.
+// `acc` rides along: != 0 makes the forward start from the (N, m, l) already in its output
+// buffers and the backward add to the dQ partial already in its output buffer.
 struct SegList {
   int n;
+  int acc;
   int start[A2D_MAX_SEGMENTS];
   int rows[A2D_MAX_SEGMENTS];
   int64_t rel[A2D_MAX_SEGMENTS];

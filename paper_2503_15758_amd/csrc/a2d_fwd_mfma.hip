@@ -200,6 +200,23 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   st.m_ref = -INFINITY;
   st.l_run = 0.f;
   const float c = d.scale * kLog2e;
+  if (g.acc && q_row < d.nq) {
+    // continue from the (N, m, l) already in the output buffers (same element mapping as the
+    // epilogue's stores): m becomes the exponent reference in raw units, l goes to one of the two
+    // lanes of the row
+    const int64_t row = (int64_t)head * d.nq + q_row;
+    const float* op = O_part + row * H + 4 * half;
+#pragma unroll
+    for (int ht = 0; ht < 4; ++ht)
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(op + 32 * ht + 8 * gq);
+        st.o[ht][4 * gq] = v[0]; st.o[ht][4 * gq + 1] = v[1]; st.o[ht][4 * gq + 2] = v[2]; st.o[ht][4 * gq + 3] = v[3];
+      }
+    st.m_lane = st.m_ref = m_out[row] / d.scale;       // -inf stays -inf
+    st.l_run = half == 0 ? l_out[row] : 0.f;
+    wait_vmem_all();
+  }
 
   // ---- staging: thread moves the 16-byte chunk (tid & 15) of rows (tid >> 4) + 32 p.
   // Rows beyond nkv re-read the last row: finite values, masked out of the scores.

@@ -84,6 +84,14 @@ __global__ __launch_bounds__(kThreads) void fwd_generic_kernel(
     mi[a] = -INFINITY; li[a] = 0.f;
 #pragma unroll
     for (int b = 0; b < HB; ++b) o[a][b] = 0.f;
+    const int gi = q0 + ty * 4 + a;
+    if (g.acc && gi < d.nq) {          // continue from the triple already in the output buffers
+      const int64_t row = (int64_t)head * d.nq + gi;
+      mi[a] = m_out[row];
+      li[a] = (tx == 0) ? l_out[row] : 0.f;     // the lanes' shares are summed at the end
+#pragma unroll
+      for (int b = 0; b < HB; ++b) o[a][b] = O_part[row * H + tx + 16 * b];
+    }
   }
   const int q_last = min(q0 + BM, d.nq) - 1;
   const int nvis = visible_keys(d, g, q_last);
@@ -372,7 +380,10 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_generic_kernel(
     if (i < d.nq) {
       const int64_t row = (int64_t)head * d.nq + i;
 #pragma unroll
-      for (int b = 0; b < HB; ++b) dQ[row * H + tx + 16 * b] = dq[a][b] * d.scale;
+      for (int b = 0; b < HB; ++b) {
+        const float v = dq[a][b] * d.scale;
+        dQ[row * H + tx + 16 * b] = g.acc ? dQ[row * H + tx + 16 * b] + v : v;
+      }
     }
   }
 }

@@ -400,3 +400,61 @@ def test_gathered_tile_fwd_bwd(a2d, dt, case):
         torch.cuda.synchronize()
         for x, y in zip(a, b):
             assert torch.equal(x, y)
+
+
+# ----------------------------------------------------------------------------- accumulating calls
+@pytest.mark.gpu
+@pytest.mark.parametrize("dt,H", [("bf16", 128), ("f32", 64)])
+def test_accumulating_tile_calls(a2d, dt, H):
+    """a2d_partial_fwd_acc walks a query block over its key blocks into ONE triple (plain tiles and
+    a gathered one); a2d_partial_bwd_acc adds the dQ shares into one buffer."""
+    heads, T, grid = 2, 192, 3
+    n = T * grid
+    scale = 1.0 / math.sqrt(H)
+    Q = synth.normal((heads, n, H), 41, 0, 1.0, dt)
+    K = synth.normal((heads, n, H), 41, 1, 1.0, dt)
+    V = synth.normal((heads, n, H), 41, 2, 1.0, dt)
+    dO = synth.normal((heads, n, H), 41, 3, 1.0, dt)
+    Of, lsef = oracle.attention_fwd(np64(Q), np64(K), np64(V), scale, True)
+    dQf, _, _ = oracle.attention_bwd(np64(Q), np64(K), np64(V), np64(dO), scale, True)
+    r = grid - 1
+    qs = slice(r * T, n)
+    Qb, dOb = dev(Q[:, qs].contiguous()), dev(dO[:, qs].contiguous())
+    blk = lambda X, c: dev(X[:, c * T:(c + 1) * T].contiguous())
+    f32 = dict(dtype=torch.float32, device="cuda")
+    trip = (torch.zeros(heads, T, H, **f32), torch.full((heads, T), -float("inf"), **f32), torch.zeros(heads, T, **f32))
+    # oracle chain beside it
+    No = np.zeros((heads, T, H)); mo = np.full((heads, T), -np.inf); do_ = np.zeros((heads, T))
+    # key block 1 alone, then blocks 2 and 0 as one gathered tile
+    a2d.partial_fwd(Qb, blk(K, 1), blk(V, 1), r * T, 1 * T, True, scale, out=trip, accumulate=True)
+    No, mo, do_ = oracle.partial_fwd_acc(No, mo, do_, np64(Q[:, qs]), np64(K[:, T:2 * T]), np64(V[:, T:2 * T]),
+                                         r * T, oracle.segment_positions([(T, T)]), True, scale)
+    torch.cuda.synchronize()
+    assert_close(np64(trip[1]), mo, DT[dt], "acc m after one tile", rel=False)
+    assert_close(np64(trip[0]) / np64(trip[2])[..., None], No / do_[..., None], DT[dt], "acc N/l after one tile")
+    Kg = torch.cat([blk(K, 2), blk(K, 0)], dim=1)
+    Vg = torch.cat([blk(V, 2), blk(V, 0)], dim=1)
+    segs = [(2 * T, T), (0, T)]
+    a2d.partial_fwd(Qb, Kg, Vg, r * T, 0, True, scale, out=trip, accumulate=True, segments=segs)
+    O, lse = a2d.fix([trip[0]], [trip[1]], [trip[2]], DT[dt])
+    torch.cuda.synchronize()
+    assert_close(O, Of[:, qs], DT[dt], "acc walk O")
+    assert_close(lse, lsef[:, qs], DT[dt], "acc walk lse", rel=False)
+    # backward: dQ of the block accumulated over the same two calls
+    O_in = torch.from_numpy(Of[:, qs]).to(DT[dt]).contiguous()
+    lse_in = torch.from_numpy(lsef[:, qs]).to(torch.float32).contiguous()
+    dq = torch.zeros(heads, T, H, **f32)
+    o1 = (dq, torch.empty(heads, T, H, **f32), torch.empty(heads, T, H, **f32))
+    a2d.partial_bwd(Qb, blk(K, 1), blk(V, 1), dev(O_in), dOb, dev(lse_in), r * T, T, True, scale, out=o1, accumulate=True)
+    o2 = (dq, torch.empty(heads, 2 * T, H, **f32), torch.empty(heads, 2 * T, H, **f32))
+    a2d.partial_bwd(Qb, Kg, Vg, dev(O_in), dOb, dev(lse_in), r * T, 0, True, scale, out=o2, accumulate=True, segments=segs)
+    torch.cuda.synchronize()
+    # reference: the oracle's gradient shares from the SAME rounded O / lse the kernels were given
+    ref = np.zeros((heads, T, H))
+    for c in range(grid):
+        a, _, _ = oracle.partial_bwd(np64(Q[:, qs]), np64(K[:, c * T:(c + 1) * T]), np64(V[:, c * T:(c + 1) * T]),
+                                     np64(O_in), np64(dO[:, qs]), np64(lse_in), r * T, c * T, True, scale)
+        ref += a
+    assert_close(dq, ref, DT[dt], "acc dQ")
+    if dt == "f32":
+        assert_close(dq, dQf[:, qs], DT[dt], "acc dQ vs full gradient")

@@ -132,3 +132,15 @@ def test_gathered_tile_argument_errors(binding):
     assert L.a2d_partial_fwd_seg(ctypes.byref(d), 1, None, P, P, P, P, P, P, None, 0, None) == -1
     arr = (b.KvSegment * 1)(); arr[0].kv_off, arr[0].rows = 0, 128
     assert L.a2d_partial_bwd_seg(ctypes.byref(d), 1, arr, P, P, P, P, P, P, P, P, P, None, 0, None) == -4
+
+
+def test_accumulating_calls_argument_errors(binding):
+    b, L = binding, binding.lib()
+    P = ctypes.c_void_p(0x10000)
+    d = _desc(b, nkv=128)
+    arr = (b.KvSegment * 1)(); arr[0].kv_off, arr[0].rows = 0, 100
+    # nseg = 0: plain tile, segs ignored; the first failing check is then the NULL output pointer
+    assert L.a2d_partial_fwd_acc(ctypes.byref(d), 0, None, P, P, P, None, P, P, None, 0, None) == -1
+    assert L.a2d_partial_fwd_acc(ctypes.byref(d), 1, arr, P, P, P, P, P, P, None, 0, None) == -1      # 100 != 128 keys
+    assert L.a2d_partial_fwd_acc(ctypes.byref(d), -1, arr, P, P, P, P, P, P, None, 0, None) == -1
+    assert L.a2d_partial_bwd_acc(ctypes.byref(d), 0, None, P, P, P, P, P, P, P, P, P, None, 0, None) == -4

@@ -589,3 +589,32 @@ def test_gathered_tile_cyclic_layout_reproduces_full_attention(grid):
         np.testing.assert_allclose(dq, dQf[:, qi], atol=1e-13)
     np.testing.assert_allclose(dK_acc, dKf, atol=1e-13)
     np.testing.assert_allclose(dV_acc, dVf, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------
+# accumulating tile call = FlashAttn followed by AttnFix (Compute and Reduce lines of the
+# overlapped algorithms, Sec. 4)
+# ----------------------------------------------------------------------------
+def test_accumulating_partial_walks_to_full_attention():
+    g = rng(50)
+    heads, grid, T, H = 2, 3, 5, 4
+    n = grid * T
+    Q, K, V = (g.standard_normal((heads, n, H)) for _ in range(3))
+    scale = 0.6
+    O, lse = oracle.attention_fwd(Q, K, V, scale, True)
+    for r in range(grid):
+        qs = slice(r * T, (r + 1) * T)
+        N = np.zeros((heads, T, H)); m = np.full((heads, T), -np.inf); d = np.zeros((heads, T))
+        for c in (2, 0, 1):                                 # any order, including the empty tile above the diagonal
+            ks = slice(c * T, (c + 1) * T)
+            prev = (N.copy(), m.copy(), d.copy())
+            N, m, d = oracle.partial_fwd_acc(N, m, d, Q[:, qs], K[:, ks], V[:, ks], r * T,
+                                             oracle.segment_positions([(c * T, T)]), True, scale)
+            assert np.all(m >= prev[1])                     # the maximum only grows
+            if np.all(np.isinf(prev[1])):                   # from the empty triple: the tile's own partial, exactly
+                P = oracle.partial_fwd(Q[:, qs], K[:, ks], V[:, ks], r * T, c * T, True, scale)
+                for x, y in zip((N, m, d), P):
+                    np.testing.assert_array_equal(x, y)
+        Of, lf = oracle.fix([N], [m], [d])
+        np.testing.assert_allclose(Of, O[:, qs], atol=1e-13)
+        np.testing.assert_allclose(lf, lse[:, qs], atol=1e-13)
