@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma-probe", action="store_true")
     ap.add_argument("--no-gathered", action="store_true")
+    ap.add_argument("--grid-emulation", action="store_true",
+                    help="also time Alg. 1 + Alg. 3 over all P tiles of the c2 sequence (8192 tokens, 4 x 4 grid)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed steps run one plain 1 GiB device copy (torch copy_), so that a "
                          "rocprofv3 --pmc run of this command also holds the counter reading of a copy of "
@@ -211,6 +213,8 @@ def main():
     }
     if not args.no_gathered and w.causal and w.name == "c3":
         result["gathered"] = gathered_tile(a2d, synth, w, scale, kernels)
+    if args.grid_emulation:
+        result["grid_emulation"] = grid_emulation(synth)
     if not args.no_mfma_probe:
         tf_r, mhz_r = a2d.mfma_ceiling(20000, True)
         tf_c, mhz_c = a2d.mfma_ceiling(20000, False)
@@ -258,6 +262,8 @@ def gathered_tile(a2d, synth, w, scale, kernels):
     # accumulating form on one unmasked tile: starts from the triple in `acc` and merges in place
     K0, V0 = dev(synth.k_block(w, 0)), dev(synth.v_block(w, 0))
     acc = a2d.partial_fwd(Q, dev(synth.k_block(w, 1)), dev(synth.v_block(w, 1)), r * T, T, True, scale)
+    plain = a2d.partial_fwd(Q, K0, V0, r * T, 0, True, scale)
+    t_plain = timeit(lambda: a2d.partial_fwd(Q, K0, V0, r * T, 0, True, scale, out=plain), n=10)
     t_acc = timeit(lambda: a2d.partial_fwd(Q, K0, V0, r * T, 0, True, scale, out=acc, accumulate=True), n=10)
     frac = (G - 1) + (T + 1) / (2.0 * T)                      # visible tiles of the row
     base = w.heads * T * T * H * frac
@@ -269,9 +275,38 @@ def gathered_tile(a2d, synth, w, scale, kernels):
             "bwd_ms": round(t_b, 4), "bwd_tflops": round(10 * base / t_b / 1e9, 1),
             "fwd_ms_one_launch_per_block_plus_fix": round(sep_f, 4),
             "bwd_ms_one_launch_per_block": round(sep_b, 4),
-            "fwd_acc_unmasked_tile_ms": round(t_acc, 4),
-            "fwd_acc_note": "a2d_partial_fwd_acc on one unmasked tile (merges into an existing triple); "
-                            "compare kernels.partial_fwd_full.avg_ms"}
+            "fwd_acc_unmasked_tile_ms": round(t_acc, 4), "fwd_plain_unmasked_tile_ms": round(t_plain, 4),
+            "fwd_acc_note": "a2d_partial_fwd_acc (merges into an existing triple) and a2d_partial_fwd on the same "
+                            "unmasked tile, timed back to back"}
+
+
+def grid_emulation(synth):
+    """Alg. 1 + Alg. 3 over the whole 4 x 4 grid of the c2 sequence (causal, both layouts) on one GPU:
+    all tile calls on several streams, merges, gathers and scatters included."""
+    import torch
+    from paper_2503_15758_amd import grid as g2d
+    w = synth.WORKLOADS["c2"]
+    n, G, H = w.tile * w.grid, w.grid, w.hdim
+    gen = torch.Generator(device="cuda"); gen.manual_seed(7)
+    mk = lambda: torch.randn(w.heads, n, H, device="cuda", generator=gen).to(torch.bfloat16)
+    Q, K, V, dO = mk(), mk(), mk(), mk()
+    out = {}
+    flops = 14.0 * w.heads * n * n * H * (n + 1) / (2.0 * n)          # causal fwd + bwd, algorithmic
+    for layout in ("cyclic", "contiguous"):
+        for streams in (1, 4):
+            def run():
+                O, lse = g2d.forward(Q, K, V, G, True, layout, None, streams)
+                return g2d.backward(Q, K, V, O, dO, lse, G, True, layout, None, streams)
+            run(); run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                run()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / 5
+            out["%s_%dstream" % (layout, streams)] = {"ms": round(ms, 3), "tflops": round(flops / ms / 1e9, 1)}
+    out["what"] = "causal fwd + bwd of %d tokens, %d heads, H%d over a %dx%d grid" % (n, w.heads, H, G, G)
+    return out
 
 
 def cpu_baseline(w, scale):

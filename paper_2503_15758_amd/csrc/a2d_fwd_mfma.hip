@@ -172,7 +172,58 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
 #pragma unroll
     for (int x = 0; x < 8; ++x) qf[x] = *reinterpret_cast<const bf16x8*>(qp + 16 * x);
   }
+  FwdState st;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) st.o[t] = zero16();
+  st.l_run = 0.f;
+  const float c = d.scale * kLog2e;
+  float m_in = -INFINITY;
+  if (g.acc) {
+    // Continue from the (N, m, l) already in the output buffers: N into the accumulators (same
+    // element mapping as the epilogue's stores), m as the exponent reference, l into one of the two
+    // lanes of the row.  A lane's share of N is 16 scattered 16-byte pieces of its row, so the
+    // rows come in through LDS: each wavefront reads 16 of its rows at a time with whole-row
+    // coalesced loads into a private, padded LDS area and the owning lanes pick their pieces.
+    constexpr int ALD = H * 4 + 16;                           // padded row stride, bytes
+    static_assert(16 * ALD * (kThreads / 64) <= kLdsBytes, "accumulator staging must fit the tile buffers");
+    char* area = lds + wave * 16 * ALD;
+    const int64_t wrow0 = (int64_t)head * d.nq + q0 + wave * 32;   // first row of the wavefront
+    const int64_t last_row = (int64_t)head * d.nq + d.nq - 1;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      u32x4 t[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {                          // two whole rows per load instruction
+        const int64_t r = wrow0 + 16 * pass + 2 * i + (lane >> 5);
+        t[i] = *reinterpret_cast<const u32x4*>(O_part + (r < last_row ? r : last_row) * H + 4 * (lane & 31));
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        *reinterpret_cast<u32x4*>(area + (2 * i + (lane >> 5)) * ALD + 16 * (lane & 31)) = t[i];
+      __syncthreads();
+      if ((l32 >> 4) == pass) {
+        const char* mine = area + (l32 & 15) * ALD + 16 * half;
+#pragma unroll
+        for (int ht = 0; ht < 4; ++ht)
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(mine + (32 * ht + 8 * gq) * 4);
+            st.o[ht][4 * gq] = v[0]; st.o[ht][4 * gq + 1] = v[1]; st.o[ht][4 * gq + 2] = v[2]; st.o[ht][4 * gq + 3] = v[3];
+          }
+      }
+      __syncthreads();
+    }
+    if (q_row < d.nq) {
+      const int64_t row = (int64_t)head * d.nq + q_row;
+      m_in = m_out[row];
+      st.l_run = half == 0 ? l_out[row] : 0.f;
+    } else {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) st.o[t] = zero16();        // rows beyond nq: nothing to continue
+    }
+  }
   wait_vmem_all();
+  st.m_lane = st.m_ref = m_in / d.scale;               // -inf stays -inf
 
   // ---- visibility, per key/value sub-block s: query i sees the first vis_count(i, s) keys of it
   // (key kk of the sub-block iff kk <= i + rel[s])
@@ -193,30 +244,6 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
     my_vis = vis_count(min(q_row, d.nq - 1), s);
   };
 
-  FwdState st;
-#pragma unroll
-  for (int t = 0; t < 4; ++t) st.o[t] = zero16();
-  st.m_lane = -INFINITY;
-  st.m_ref = -INFINITY;
-  st.l_run = 0.f;
-  const float c = d.scale * kLog2e;
-  if (g.acc && q_row < d.nq) {
-    // continue from the (N, m, l) already in the output buffers (same element mapping as the
-    // epilogue's stores): m becomes the exponent reference in raw units, l goes to one of the two
-    // lanes of the row
-    const int64_t row = (int64_t)head * d.nq + q_row;
-    const float* op = O_part + row * H + 4 * half;
-#pragma unroll
-    for (int ht = 0; ht < 4; ++ht)
-#pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        const f32x4 v = *reinterpret_cast<const f32x4*>(op + 32 * ht + 8 * gq);
-        st.o[ht][4 * gq] = v[0]; st.o[ht][4 * gq + 1] = v[1]; st.o[ht][4 * gq + 2] = v[2]; st.o[ht][4 * gq + 3] = v[3];
-      }
-    st.m_lane = st.m_ref = m_out[row] / d.scale;       // -inf stays -inf
-    st.l_run = half == 0 ? l_out[row] : 0.f;
-    wait_vmem_all();
-  }
 
   // ---- staging: thread moves the 16-byte chunk (tid & 15) of rows (tid >> 4) + 32 p.
   // Rows beyond nkv re-read the last row: finite values, masked out of the scores.
