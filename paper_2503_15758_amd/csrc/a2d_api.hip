@@ -38,8 +38,8 @@ a2d_status check_desc(const a2d_tile_desc* d, const char* who) {
                 d->nq, d->nkv);
   if (d->dtype != A2D_F32 && d->dtype != A2D_BF16)
     return fail(A2D_ERR_UNSUPPORTED, "%s: dtype %d is neither A2D_F32 nor A2D_BF16", who, d->dtype);
-  if (d->hdim != 64 && d->hdim != 128)
-    return fail(A2D_ERR_UNSUPPORTED, "%s: head size %d not supported (64 or 128)", who, d->hdim);
+  if (d->hdim != 64 && d->hdim != 80 && d->hdim != 96 && d->hdim != 128)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: head size %d not supported (64, 80, 96 or 128)", who, d->hdim);
   if (!(d->scale > 0.f) || !std::isfinite(d->scale))
     return fail(A2D_ERR_INVALID_ARG, "%s: scale must be finite and > 0", who);
   if (d->causal != 0 && d->causal != 1)

@@ -391,16 +391,19 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_generic_kernel(
 // --------------------------------------------------- delta = rowsum(dO o O)
 // LPR lanes share a row, each reading 16 bytes of O and of dO per step.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void delta_kernel(int64_t rows, int H, const T* __restrict__ O,
+__global__ __launch_bounds__(kThreads) void delta_kernel(int64_t rows, int H, int lpr,
+                                                         const T* __restrict__ O,
                                                          const T* __restrict__ dO,
                                                          float* __restrict__ delta) {
   constexpr int EPL = 16 / sizeof(T);          // elements per lane per load
-  const int lpr = H / EPL;                     // lanes per row: 8, 16 or 32
+  // lpr lanes per row: the power of two that covers H / EPL loads (8 .. 32); for head sizes that
+  // are not powers of two the surplus lanes of a row idle
+  const int nload = H / EPL;
   const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   const int64_t row = idx / lpr;
   const int c = (int)(idx - row * lpr);
   float acc = 0.f;
-  if (row < rows) {
+  if (row < rows && c < nload) {
     const T* o = O + row * H + c * EPL;
     const T* g = dO + row * H + c * EPL;
     const u32x4 ow = *reinterpret_cast<const u32x4*>(o);
@@ -455,37 +458,41 @@ hipError_t bwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, c
 
 }  // namespace
 
+// head sizes of the paper's models (Table 3): 128, 96, 80; and 64
+#define A2D_DISPATCH_H(FN, T, ...)                  \
+  switch (d.hdim) {                                 \
+    case 128: return FN<T, 128>(__VA_ARGS__);       \
+    case 96: return FN<T, 96>(__VA_ARGS__);         \
+    case 80: return FN<T, 80>(__VA_ARGS__);         \
+    default: return FN<T, 64>(__VA_ARGS__);         \
+  }
+
 hipError_t launch_fwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                               float* O_part, float* m, float* l, hipStream_t s) {
-  if (d.dtype == A2D_BF16) {
-    return d.hdim == 128 ? fwd_launch<bf16_t, 128>(d, g, Q, K, V, O_part, m, l, s)
-                         : fwd_launch<bf16_t, 64>(d, g, Q, K, V, O_part, m, l, s);
-  }
-  return d.hdim == 128 ? fwd_launch<float, 128>(d, g, Q, K, V, O_part, m, l, s)
-                       : fwd_launch<float, 64>(d, g, Q, K, V, O_part, m, l, s);
+  if (d.dtype == A2D_BF16) { A2D_DISPATCH_H(fwd_launch, bf16_t, d, g, Q, K, V, O_part, m, l, s) }
+  A2D_DISPATCH_H(fwd_launch, float, d, g, Q, K, V, O_part, m, l, s)
 }
 
 hipError_t launch_bwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                               const void* dO, const float* lse, const float* delta, float* dQ,
                               float* dK, float* dV, hipStream_t s) {
-  if (d.dtype == A2D_BF16) {
-    return d.hdim == 128 ? bwd_launch<bf16_t, 128>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s)
-                         : bwd_launch<bf16_t, 64>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
-  }
-  return d.hdim == 128 ? bwd_launch<float, 128>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s)
-                       : bwd_launch<float, 64>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
+  if (d.dtype == A2D_BF16) { A2D_DISPATCH_H(bwd_launch, bf16_t, d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s) }
+  A2D_DISPATCH_H(bwd_launch, float, d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s)
 }
+#undef A2D_DISPATCH_H
 
 hipError_t launch_delta(int dtype, int64_t rows, int hdim, const void* O, const void* dO,
                         float* delta, hipStream_t s) {
   const int epl = dtype == A2D_BF16 ? 8 : 4;
-  const int64_t threads = rows * (hdim / epl);
+  int lpr = 1;
+  while (lpr < hdim / epl) lpr <<= 1;
+  const int64_t threads = rows * lpr;
   dim3 grid((unsigned)((threads + kThreads - 1) / kThreads)), block(kThreads);
   if (dtype == A2D_BF16)
-    hipLaunchKernelGGL((delta_kernel<bf16_t>), grid, block, 0, s, rows, hdim, (const bf16_t*)O,
+    hipLaunchKernelGGL((delta_kernel<bf16_t>), grid, block, 0, s, rows, hdim, lpr, (const bf16_t*)O,
                        (const bf16_t*)dO, delta);
   else
-    hipLaunchKernelGGL((delta_kernel<float>), grid, block, 0, s, rows, hdim, (const float*)O,
+    hipLaunchKernelGGL((delta_kernel<float>), grid, block, 0, s, rows, hdim, lpr, (const float*)O,
                        (const float*)dO, delta);
   return hipGetLastError();
 }

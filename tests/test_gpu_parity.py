@@ -69,6 +69,8 @@ FWD_CASES = [
     (1, 513, 257, 128, False, 0, 0),         # ragged tails past whole 256-row / 128-key workgroups
     (2, 600, 333, 128, True, 40, 0),         # diagonal crossing several workgroups, ragged
     (1, 700, 900, 128, True, 300, 100),      # more keys than queries, offset diagonal
+    (2, 150, 200, 80, True, 60, 0),          # the head sizes of the paper's smaller models
+    (2, 130, 170, 96, False, 0, 0),
 ]
 
 
@@ -139,6 +141,8 @@ BWD_CASES = [
     (1, 513, 257, 128, False, 0, 0),
     (2, 600, 333, 128, True, 40, 0),
     (1, 700, 900, 128, True, 300, 100),
+    (2, 150, 200, 80, True, 60, 0),
+    (2, 130, 170, 96, False, 0, 0),
 ]
 
 

@@ -57,7 +57,7 @@ def test_argument_errors_enqueue_nothing(binding):
     odd = ctypes.c_void_p(0x10004)
     fwd = lambda d, q=P, o=P: L.a2d_partial_fwd(ctypes.byref(d) if d else None, q, P, P, o, P, P, None, 0, None)
     assert fwd(None) == -1 and b"NULL" in L.a2d_last_error()
-    assert fwd(_desc(b, hdim=80)) == -2
+    assert fwd(_desc(b, hdim=72)) == -2
     assert fwd(_desc(b, dtype=7)) == -2
     assert fwd(_desc(b, nq=0)) == -1
     assert fwd(_desc(b, scale=0.0)) == -1
