@@ -1,18 +1,15 @@
-// Building blocks shared by the bf16 MFMA tile kernels (H = 128): the swizzled LDS
-// tile, its global->LDS staging, and the two kinds of fragment reads.
+// Building blocks shared by the bf16 MFMA tile kernels (H = 128): the MFMA wrapper and its
+// fragment layouts, LDS fragment reads, the "dual" LDS tile layout, scalar-base global loads and
+// the XCD-aware work mapping.
 //
 // MFMA used everywhere: v_mfma_f32_32x32x16_bf16, D(32x32) += A(32x16) * B(16x32).
 //   A fragment: lane holds row (lane & 31), contraction indices 8*(lane>>5) + 0..7
 //   B fragment: lane holds column (lane & 31), contraction indices 8*(lane>>5) + 0..7
 //   D: lane holds column (lane & 31); register r is row 8*(r>>2) + 4*(lane>>5) + (r&3)
-//
-// LDS tile: R rows x 128 bf16, 256 B per row, no padding; the 16-byte chunk c of
-// row r is stored at chunk position c ^ f(r), f(r) = ((r&3)<<2) | ((r>>2)&3).
-// With this swizzle both access patterns used here touch every bank once per pass:
-//   - "natural" fragments (contraction along H): 128-bit reads, 16 consecutive rows
-//     at one logical chunk land on 16 different chunk positions;
-//   - "transposed" fragments (contraction along the row index): ds_read_b64_tr_b16,
-//     where a 32-lane pass reads 4 consecutive rows x 64 contiguous bytes.
+// Two kinds of fragment reads from a row-major LDS tile (rows x 128 bf16):
+//   - "natural" fragments (contraction along H): one 128-bit read per lane;
+//   - "transposed" fragments (contraction along the row index): two ds_read_b64_tr_b16, where a
+//     16-lane group reads 4 consecutive rows x 16 columns and every lane receives a column.
 #pragma once
 #include "a2d_common.hpp"
 
@@ -20,12 +17,9 @@ namespace a2d {
 namespace mfma {
 
 constexpr int H = 128;
-constexpr int ROW_BYTES = 256;
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef short s16x8 __attribute__((ext_vector_type(8)));
-
-__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 
 __device__ __forceinline__ f32x16 zero16() {
   f32x16 z;
@@ -77,64 +71,6 @@ __device__ __forceinline__ bf16x8 lds_load_tr(unsigned addr_lo, unsigned addr_hi
   const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
 }
-
-// Per-lane constants of the fragment reads; rows are relative to a row base that is a
-// multiple of 16 (so the swizzle term depends on the lane only).
-struct FragAddr {
-  int nat;    // byte offset of the natural fragment of contraction step 0: row (lane&31)
-  int tr_lo;  // byte offset of the transposing read, rows +0..7 of a 16-row group, column tile 0
-  int tr_hi;  // same for rows +8..15
-  __device__ __forceinline__ void init(int lane) {
-    const int l32 = lane & 31, half = lane >> 5;
-    nat = l32 * ROW_BYTES + (((half ^ swz(l32 & 15)) & 15) << 4);
-    const int g16 = lane >> 4, j16 = lane & 15;
-    const int row = 4 * (g16 >> 1) + (j16 >> 2);           // 0..7
-    const int cl = 2 * (g16 & 1) + ((j16 & 3) >> 1);       // logical chunk within a 32-column tile
-    const int sub = 8 * (j16 & 1);                         // byte within the chunk
-    tr_lo = row * ROW_BYTES + (((cl ^ swz(row)) & 15) << 4) + sub;
-    tr_hi = (row + 8) * ROW_BYTES + (((cl ^ swz(row + 8)) & 15) << 4) + sub;
-  }
-};
-
-// natural fragment: rows row_base + (lane&31), contraction indices 16*st + 8*(lane>>5) + 0..7 of H
-__device__ __forceinline__ bf16x8 read_nat(const char* tile, const FragAddr& fa, int row_base, int st) {
-  const int off = (row_base * ROW_BYTES + fa.nat) ^ (st << 5);
-  return *reinterpret_cast<const bf16x8*>(tile + off);
-}
-
-// transposed fragment: lane holds column 32*ct + (lane&31) of H; contraction indices are the rows
-// row_base + {4*(lane>>5) + 0..3, 8 + 4*(lane>>5) + 0..3} (row_base a multiple of 16) - the same
-// permutation in which eight consecutive D registers enumerate their rows.
-__device__ __forceinline__ bf16x8 read_tr(const char* tile, const FragAddr& fa, int row_base, int ct) {
-  const int base = row_base * ROW_BYTES;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + ((base + fa.tr_lo) ^ (ct << 6))));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + ((base + fa.tr_hi) ^ (ct << 6))));
-  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-// Staging of a 64-row tile by 256 threads: thread moves the 16-byte chunk (tid & 15) of rows
-// (tid >> 4) + 16 p, p = 0..3.  Rows at or beyond nrows are zero-filled.
-struct Stage64 {
-  u32x4 v[4];
-  __device__ __forceinline__ void load(const bf16_t* __restrict__ src, int row0, int nrows, int tid) {
-    const int r = tid >> 4, c = tid & 15;
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int g = row0 + r + 16 * p;
-      if (g < nrows) v[p] = *reinterpret_cast<const u32x4*>(src + (int64_t)g * H + c * 8);
-      else v[p] = u32x4{0, 0, 0, 0};
-    }
-  }
-  __device__ __forceinline__ void store(char* tile, int tid) const {
-    const int r = tid >> 4, c = tid & 15;
-    const int off = r * ROW_BYTES + (((c ^ swz(r)) & 15) << 4);
-#pragma unroll
-    for (int p = 0; p < 4; ++p) *reinterpret_cast<u32x4*>(tile + off + 16 * p * ROW_BYTES) = v[p];
-  }
-};
-
-constexpr int TILE64_BYTES = 64 * ROW_BYTES;
 
 // "Dual" LDS tile layout for tiles read BOTH ways (natural and transposed) with
 // immediate-only addressing: rows of 320 B (256 B data + 64 B pad), and within a row the
