@@ -213,6 +213,8 @@ def main():
     }
     if not args.no_gathered and w.causal and w.name == "c3":
         result["gathered"] = gathered_tile(a2d, synth, w, scale, kernels)
+    if not args.no_gathered and w.name == "c3":
+        result["normalised_partials"] = normalised_format(a2d, synth, w, scale, kernels)
     if args.grid_emulation:
         result["grid_emulation"] = grid_emulation(synth)
     if not args.no_mfma_probe:
@@ -278,6 +280,43 @@ def gathered_tile(a2d, synth, w, scale, kernels):
             "fwd_acc_unmasked_tile_ms": round(t_acc, 4), "fwd_plain_unmasked_tile_ms": round(t_plain, 4),
             "fwd_acc_note": "a2d_partial_fwd_acc (merges into an existing triple) and a2d_partial_fwd on the same "
                             "unmasked tile, timed back to back"}
+
+
+def normalised_format(a2d, synth, w, scale, kernels):
+    """The bf16 normalised partial format (a2d_partial_fwd_norm / a2d_fix_norm): the merge of the
+    sqrt(P) partials of a query block moves half the bytes of the fp32 unnormalised format."""
+    import torch
+    T, G, H = w.tile, w.grid, w.hdim
+    r = G - 1
+    dev = lambda t: t.to("cuda")
+    Q = dev(synth.q_block(w, r))
+    parts = []
+    for c in range(G):
+        parts.append(a2d.partial_fwd_norm(Q, dev(synth.k_block(w, c)), dev(synth.v_block(w, c)), r * T, c * T,
+                                          True, scale))
+    K0, V0 = dev(synth.k_block(w, 0)), dev(synth.v_block(w, 0))
+    O = torch.empty(w.heads, T, H, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(w.heads, T, dtype=torch.float32, device="cuda")
+
+    def timeit(fn, n=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    t_fix = timeit(lambda: a2d.fix_norm([p[0] for p in parts], [p[1] for p in parts], out=(O, lse)))
+    t_fwd = timeit(lambda: a2d.partial_fwd_norm(Q, K0, V0, r * T, 0, True, scale, out=parts[0]), n=10)
+    rows = w.heads * T
+    nbytes = rows * (G * (H * 2 + 4) + H * 2 + 4)
+    return {"fix_norm_ms": round(t_fix, 4), "fix_norm_gbs": round(nbytes / t_fix / 1e6, 1),
+            "fix_norm_frac_hbm": round(nbytes / t_fix / 1e6 / PEAK_HBM_GBS, 4), "fix_norm_bytes": nbytes,
+            "fix_fp32_ms": kernels["fix"]["avg_ms"], "partial_fwd_norm_unmasked_tile_ms": round(t_fwd, 4)}
 
 
 def grid_emulation(synth):

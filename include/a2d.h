@@ -195,6 +195,27 @@ a2d_status a2d_partial_bwd_acc(const a2d_tile_desc* desc, int nseg, const a2d_kv
                                size_t workspace_bytes, void* stream);
 
 /*
+ * Normalised partial format: a partial as (O' = N / l in the input dtype, lse' = m + ln l), the
+ * pair FlashAttention-style kernels return (footnote of Sec. 3.2), instead of the unnormalised
+ * fp32 triple.  Half the bytes per partial and a quarter for bf16 inputs, at the price of one
+ * rounding of every partial to the input dtype before the merge.
+ *   a2d_partial_fwd_norm: as a2d_partial_fwd (nseg = 0) or a2d_partial_fwd_seg (nseg >= 1), but
+ *     out: O_norm [heads][nq][H] in desc->dtype, lse_part [heads][nq] fp32 (a row that sees no
+ *     key: O' = 0, lse' = -inf).
+ *   a2d_fix_norm: merge of k such partials of one query block: L = log sum_k exp(lse_k),
+ *     O = sum_k exp(lse_k - L) O'_k, sums in index order; O_norm_parts, lse_parts: HOST arrays of
+ *     k device pointers; in_dtype: dtype of the partials; out: O [rows][hdim] in out_dtype,
+ *     lse [rows] fp32.  1 <= k <= A2D_MAX_PARTS; hdim a multiple of 4.
+ */
+a2d_status a2d_partial_fwd_norm(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
+                                const void* Q, const void* K, const void* V, void* O_norm,
+                                float* lse_part, void* workspace, size_t workspace_bytes,
+                                void* stream);
+a2d_status a2d_fix_norm(int k, int64_t rows, int32_t hdim, int32_t in_dtype, int32_t out_dtype,
+                        const void* const* O_norm_parts, const float* const* lse_parts, void* O,
+                        float* lse, void* stream);
+
+/*
  * Sum of k gradient partials (the reduce-scatters of Alg. 3 lines 4-5 use plain
  * summation): out[i] = sum_k parts[k][i], added in index order in fp32, rounded
  * once to out_dtype.  parts: HOST array of k device pointers to n fp32 values;

@@ -174,6 +174,37 @@ def partial_fwd_acc(N_in, m_in, d_in, Q, K, V, q_off, kpos, causal, scale):
     return Nn, M, D
 
 
+def normalised_partial(N, m, d):
+    """The FlashAttention-style form of a partial triple (footnote of Sec. 3.2): O' = Diag(d^-1) N,
+    lse' = m + log d; a row with no visible key gives O' = 0, lse' = -inf."""
+    N, m, d = _c(N), _c(m), _c(d)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        On = np.where(d[..., None] > 0, N / d[..., None], 0.0)
+        lse = np.where(d > 0, m + np.log(d), -np.inf)
+    return np.ascontiguousarray(On), np.ascontiguousarray(lse)
+
+
+def fix_norm(Onorms, lses):
+    """Merge of k normalised partials of one query block: with L = log sum_k exp(lse_k),
+    O = sum_k exp(lse_k - L) O'_k (AttnFix, Alg. 2, and the final division of Alg. 1 line 6 written
+    for the normalised form; sums in index order).  Returns (O, L)."""
+    Onorms = [_c(a) for a in Onorms]
+    lses = [_c(a) for a in lses]
+    M = np.max(np.stack(lses), axis=0)
+    Ms = np.where(np.isinf(M), 0.0, M)
+    D = np.zeros_like(M)
+    acc = np.zeros_like(Onorms[0])
+    for On, l in zip(Onorms, lses):
+        with np.errstate(invalid="ignore"):
+            w = np.where(np.isinf(l), 0.0, np.exp(l - Ms))
+        D += w
+        acc += w[..., None] * On
+    with np.errstate(divide="ignore", invalid="ignore"):
+        O = np.where(D[..., None] > 0, acc / D[..., None], 0.0)
+        L = np.where(D > 0, Ms + np.log(D), -np.inf)
+    return O, L
+
+
 def fix(Nparts, Mparts, Dparts):
     """k-way AttnFix + normalisation. Returns (O, lse)."""
     Nparts = [_c(a) for a in Nparts]

@@ -19,6 +19,7 @@ MAX_PARTS = 32
 
 EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
            "a2d_partial_fwd_seg", "a2d_partial_bwd_seg", "a2d_partial_fwd_acc", "a2d_partial_bwd_acc",
+           "a2d_partial_fwd_norm", "a2d_fix_norm",
            "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling",
            "a2d_status_str", "a2d_last_error", "a2d_version")
 
@@ -69,6 +70,12 @@ def lib():
         L.a2d_partial_fwd_acc.argtypes = L.a2d_partial_fwd_seg.argtypes
         L.a2d_partial_bwd_acc.restype = ctypes.c_int
         L.a2d_partial_bwd_acc.argtypes = L.a2d_partial_bwd_seg.argtypes
+        L.a2d_partial_fwd_norm.restype = ctypes.c_int
+        L.a2d_partial_fwd_norm.argtypes = [ctypes.POINTER(TileDesc), ctypes.c_int, ctypes.POINTER(KvSegment),
+                                           vp, vp, vp, vp, fp, vp, ctypes.c_size_t, vp]
+        L.a2d_fix_norm.restype = ctypes.c_int
+        L.a2d_fix_norm.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                   ctypes.POINTER(vp), ctypes.POINTER(vp), vp, fp, vp]
         L.a2d_fix.restype = ctypes.c_int
         L.a2d_fix.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                               ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, fp, vp]
@@ -169,6 +176,44 @@ def partial_fwd(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None, 
     _check(lib().a2d_partial_fwd(ctypes.byref(d), _ptr(Q), _ptr(K), _ptr(V), _ptr(O_part), _ptr(m),
                                  _ptr(l), None, 0, _stream()))
     return O_part, m, l
+
+
+def partial_fwd_norm(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None, segments=None):
+    """a2d_partial_fwd_norm: the normalised partial (O' in Q's dtype, lse' fp32) of a plain or gathered tile."""
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
+        _dev3(t, n)
+    if K.shape != V.shape or K.shape[0] != Q.shape[0] or K.shape[2] != Q.shape[2] or \
+            K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise A2DError(-1, "Q, K, V shapes / dtypes do not match")
+    d = tile_desc(Q, K, q_off, kv_off, causal, scale)
+    if out is None:
+        O_norm = torch.empty(Q.shape, dtype=Q.dtype, device=Q.device)
+        lse = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
+    else:
+        O_norm, lse = out
+    n = len(segments) if segments is not None else 0
+    _check(lib().a2d_partial_fwd_norm(ctypes.byref(d), n, _segments(segments) if n else None, _ptr(Q),
+                                      _ptr(K), _ptr(V), _ptr(O_norm), _ptr(lse), None, 0, _stream()))
+    return O_norm, lse
+
+
+def fix_norm(O_norms, lses, out_dtype=torch.bfloat16, out=None):
+    """a2d_fix_norm over k normalised partials. Returns (O in out_dtype, lse fp32)."""
+    k = len(O_norms)
+    if k < 1 or len(lses) != k:
+        raise A2DError(-1, "need k >= 1 normalised partials")
+    shape = O_norms[0].shape
+    rows = 1
+    for s in shape[:-1]:
+        rows *= s
+    if out is None:
+        O = torch.empty(shape, dtype=out_dtype, device=O_norms[0].device)
+        lse = torch.empty(shape[:-1], dtype=torch.float32, device=O_norms[0].device)
+    else:
+        O, lse = out
+    _check(lib().a2d_fix_norm(k, rows, shape[-1], _dtype_code(O_norms[0].dtype), _dtype_code(O.dtype),
+                              _ptr_array(O_norms), _ptr_array(lses), _ptr(O), _ptr(lse), _stream()))
+    return O, lse
 
 
 def fix(O_parts, ms, ls, out_dtype=torch.bfloat16, out=None):

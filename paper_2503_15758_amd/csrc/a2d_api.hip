@@ -170,6 +170,46 @@ a2d_status a2d_partial_fwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv
   return partial_fwd_impl(desc, g, Q, K, V, O_part, m, l, stream, who);
 }
 
+a2d_status a2d_partial_fwd_norm(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
+                                const void* Q, const void* K, const void* V, void* O_norm,
+                                float* lse_part, void* /*workspace*/, size_t /*workspace_bytes*/,
+                                void* stream) {
+  const char* who = "a2d_partial_fwd_norm";
+  A2D_TRY(check_desc(desc, who));
+  a2d::SegList g = one_segment(desc);
+  if (nseg != 0) A2D_TRY(make_segments(desc, nseg, segs, who, &g));
+  g.norm = 1;
+  // the kernels take the normalised output through the O_part argument and lse' through m; l is unused
+  return partial_fwd_impl(desc, g, Q, K, V, static_cast<float*>(O_norm), lse_part, lse_part, stream, who);
+}
+
+a2d_status a2d_fix_norm(int k, int64_t rows, int32_t hdim, int32_t in_dtype, int32_t out_dtype,
+                        const void* const* O_norm_parts, const float* const* lse_parts, void* O,
+                        float* lse, void* stream) {
+  const char* who = "a2d_fix_norm";
+  if (k < 1 || k > A2D_MAX_PARTS)
+    return fail(A2D_ERR_INVALID_ARG, "%s: k=%d outside 1..%d", who, k, A2D_MAX_PARTS);
+  if (rows < 1) return fail(A2D_ERR_INVALID_ARG, "%s: rows=%lld must be >= 1", who, (long long)rows);
+  if (hdim < 4 || hdim % 4 != 0 || hdim > 1024)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: hdim=%d must be a multiple of 4 in 4..1024", who, hdim);
+  if ((in_dtype != A2D_F32 && in_dtype != A2D_BF16) || (out_dtype != A2D_F32 && out_dtype != A2D_BF16))
+    return fail(A2D_ERR_UNSUPPORTED, "%s: dtype %d / %d not supported", who, in_dtype, out_dtype);
+  if (rows * (int64_t)(hdim / 4) > ((int64_t)1 << 39))
+    return fail(A2D_ERR_INVALID_ARG, "%s: rows * hdim too large", who);
+  if (!O_norm_parts || !lse_parts) return fail(A2D_ERR_INVALID_ARG, "%s: pointer array is NULL", who);
+  A2D_TRY(check_ptr(O, who, "O"));
+  A2D_TRY(check_ptr(lse, who, "lse"));
+  a2d::NormPtrs p;
+  memset(&p, 0, sizeof(p));
+  for (int x = 0; x < k; ++x) {
+    A2D_TRY(check_ptr(O_norm_parts[x], who, "O_norm_parts[x]"));
+    A2D_TRY(check_ptr(lse_parts[x], who, "lse_parts[x]"));
+    p.o[x] = O_norm_parts[x]; p.lse[x] = lse_parts[x];
+  }
+  return hip_result(a2d::launch_fix_norm(k, rows, hdim, in_dtype, out_dtype, p, O, lse,
+                                         static_cast<hipStream_t>(stream)), who);
+}
+
 a2d_status a2d_partial_fwd_acc(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
                                const void* Q, const void* K, const void* V, float* O_part,
                                float* m, float* l, void* /*workspace*/, size_t /*workspace_bytes*/,

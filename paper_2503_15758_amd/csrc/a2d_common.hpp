@@ -39,9 +39,12 @@ template <> struct dtype_of<bf16_t> { static constexpr int value = A2D_BF16; };
 // key start[s] + kk of sub-block s iff kk <= i + rel[s].  A plain tile is one sub-block.
 // `acc` rides along: != 0 makes the forward start from the (N, m, l) already in its output
 // buffers and the backward add to the dQ partial already in its output buffer.
+// `norm` != 0: the forward writes the NORMALISED partial O' = N / l in the input dtype (into the
+// buffer passed as O_part) and lse' = m + ln l (into the buffer passed as m) instead of (N, m, l).
 struct SegList {
   int n;
   int acc;
+  int norm;
   int start[A2D_MAX_SEGMENTS];
   int rows[A2D_MAX_SEGMENTS];
   int64_t rel[A2D_MAX_SEGMENTS];
@@ -94,6 +97,13 @@ hipError_t launch_fix(int k, int64_t rows, int hdim, int out_dtype, const FixPtr
                       float* lse, hipStream_t s);
 hipError_t launch_fix_bwd(int k, int64_t n, int out_dtype, const SumPtrs& p, void* out,
                           hipStream_t s);
+// merge of k NORMALISED partials (O'_k in in_dtype, lse_k)
+struct NormPtrs {
+  const void* o[A2D_MAX_PARTS];
+  const float* lse[A2D_MAX_PARTS];
+};
+hipError_t launch_fix_norm(int k, int64_t rows, int hdim, int in_dtype, int out_dtype, const NormPtrs& p,
+                           void* O, float* lse, hipStream_t s);
 
 // MFMA-only ceiling probe (diagnostic)
 hipError_t launch_mfma_probe(int blocks, int iters, int random_data, float* scratch, hipStream_t s);

@@ -319,16 +319,31 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   const float m_row = fmaxf(st.m_lane, __shfl_xor(st.m_lane, 32, 64));
   const float f = (m_row == -INFINITY) ? 0.f : fast_exp2((st.m_ref - m_row) * c);
   const float l_tot = (st.l_run + __shfl_xor(st.l_run, 32, 64)) * f;
-  if (q_row < d.nq) {
+  if (q_row < d.nq && g.norm) {
+    // normalised partial: O' = N / l rounded to bf16, lse' = m + ln l (Sec. 3.2, footnote)
+    const int64_t row = (int64_t)head * d.nq + q_row;
+    const float fn = l_tot > 0.f ? f / l_tot : 0.f;
+    bf16_t* op = reinterpret_cast<bf16_t*>(O_part) + row * H + 4 * half;
+#pragma unroll
+    for (int ht = 0; ht < 4; ++ht)
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        bf16x4 v;
+        v[0] = (bf16_t)(st.o[ht][4 * gq] * fn); v[1] = (bf16_t)(st.o[ht][4 * gq + 1] * fn);
+        v[2] = (bf16_t)(st.o[ht][4 * gq + 2] * fn); v[3] = (bf16_t)(st.o[ht][4 * gq + 3] * fn);
+        *reinterpret_cast<bf16x4*>(op + 32 * ht + 8 * gq) = v;
+      }
+    if (half == 0) m_out[row] = l_tot > 0.f ? m_row * d.scale + logf(l_tot) : -INFINITY;
+  } else if (q_row < d.nq) {
     const int64_t row = (int64_t)head * d.nq + q_row;
     float* op = O_part + row * H + 4 * half;
 #pragma unroll
     for (int ht = 0; ht < 4; ++ht)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f32x4 v = {st.o[ht][4 * g] * f, st.o[ht][4 * g + 1] * f, st.o[ht][4 * g + 2] * f,
-                   st.o[ht][4 * g + 3] * f};
-        *reinterpret_cast<f32x4*>(op + 32 * ht + 8 * g) = v;
+      for (int gq = 0; gq < 4; ++gq) {
+        f32x4 v = {st.o[ht][4 * gq] * f, st.o[ht][4 * gq + 1] * f, st.o[ht][4 * gq + 2] * f,
+                   st.o[ht][4 * gq + 3] * f};
+        *reinterpret_cast<f32x4*>(op + 32 * ht + 8 * gq) = v;
       }
     if (half == 0) {
       m_out[row] = m_row * d.scale;      // -inf stays -inf (scale > 0)

@@ -161,7 +161,15 @@ __global__ __launch_bounds__(kThreads) void fwd_generic_kernel(
   for (int a = 0; a < 4; ++a) {
     const int gi = q0 + ty * 4 + a;
     const float lsum = group16_sum(li[a]);
-    if (gi < d.nq) {
+    if (gi < d.nq && g.norm) {
+      // normalised partial in the input dtype and lse' = m + ln l
+      const int64_t row = (int64_t)head * d.nq + gi;
+      const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+      T* on = reinterpret_cast<T*>(O_part);
+#pragma unroll
+      for (int b = 0; b < HB; ++b) on[row * H + tx + 16 * b] = (T)(o[a][b] * inv);
+      if (tx == 0) m_out[row] = lsum > 0.f ? mi[a] + logf(lsum) : -INFINITY;
+    } else if (gi < d.nq) {
       const int64_t row = (int64_t)head * d.nq + gi;
 #pragma unroll
       for (int b = 0; b < HB; ++b) O_part[row * H + tx + 16 * b] = o[a][b];

@@ -493,3 +493,48 @@ def test_grid_emulation_matches_full_attention(a2d, layout, dt, H, grid):
     O1, lse1 = g2d.forward(dev(Q), dev(K), dev(V), grid, True, layout, scale, streams=1)
     torch.cuda.synchronize()
     assert torch.equal(O, O1) and torch.equal(lse, lse1)
+
+
+# ----------------------------------------------------------------------------- normalised partials
+@pytest.mark.gpu
+@pytest.mark.parametrize("dt,H", [("bf16", 128), ("f32", 64), ("bf16", 96)])
+def test_normalised_partial_format(a2d, dt, H):
+    """a2d_partial_fwd_norm + a2d_fix_norm over a causal grid row (plain tiles and a gathered one,
+    one tile above the diagonal) against the oracle's normalised forms and full attention."""
+    heads, T, grid = 2, 160, 4
+    n = T * grid
+    scale = 1.0 / math.sqrt(H)
+    Q, K, V = (synth.normal((heads, n, H), 61, s, 1.0, dt) for s in range(3))
+    Of, lsef = oracle.attention_fwd(np64(Q), np64(K), np64(V), scale, True)
+    r = 2
+    qs = slice(r * T, (r + 1) * T)
+    Qb = dev(Q[:, qs].contiguous())
+    blk = lambda X, c: dev(X[:, c * T:(c + 1) * T].contiguous())
+    parts = [a2d.partial_fwd_norm(Qb, blk(K, c), blk(V, c), r * T, c * T, True, scale) for c in (2, 3)]
+    Kg = torch.cat([blk(K, 1), blk(K, 0)], dim=1)
+    Vg = torch.cat([blk(V, 1), blk(V, 0)], dim=1)
+    parts.append(a2d.partial_fwd_norm(Qb, Kg, Vg, r * T, 0, True, scale, segments=[(T, T), (0, T)]))
+    torch.cuda.synchronize()
+    # each partial against the oracle's normalised partial
+    for (On, ln), c in zip(parts[:2], (2, 3)):
+        ref = oracle.normalised_partial(*oracle.partial_fwd(np64(Q[:, qs]), np64(K[:, c * T:(c + 1) * T]),
+                                                            np64(V[:, c * T:(c + 1) * T]), r * T, c * T, True, scale))
+        assert On.dtype == DT[dt]
+        assert_close(On, ref[0], DT[dt], "norm partial O' c=%d" % c)
+        assert_close(ln, ref[1], DT[dt], "norm partial lse c=%d" % c, rel=False)
+    assert torch.all(torch.isinf(parts[1][1])) and torch.all(parts[1][0] == 0)        # the tile above the diagonal
+    O, lse = a2d.fix_norm([p[0] for p in parts], [p[1] for p in parts], DT[dt])
+    torch.cuda.synchronize()
+    assert_close(O, Of[:, qs], DT[dt], "norm merge O")
+    assert_close(lse, lsef[:, qs], DT[dt], "norm merge lse", rel=False)
+    # the merge alone, from the oracle's partials rounded to the partial dtype
+    ref_parts = [oracle.normalised_partial(*oracle.partial_fwd(np64(Q[:, qs]), np64(K[:, c * T:(c + 1) * T]),
+                                                               np64(V[:, c * T:(c + 1) * T]), r * T, c * T, True, scale))
+                 for c in range(grid)]
+    Oin = [torch.from_numpy(p[0]).to(DT[dt]) for p in ref_parts]
+    lin = [torch.from_numpy(p[1]).to(torch.float32) for p in ref_parts]
+    O2, l2 = a2d.fix_norm([dev(x) for x in Oin], [dev(x) for x in lin], torch.float32)
+    torch.cuda.synchronize()
+    Or, lr = oracle.fix_norm([np64(x) for x in Oin], [np64(x) for x in lin])
+    assert_close(O2, Or, torch.float32, "fix_norm alone O")
+    assert_close(l2, lr, torch.float32, "fix_norm alone lse", rel=False)

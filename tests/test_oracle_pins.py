@@ -618,3 +618,37 @@ def test_accumulating_partial_walks_to_full_attention():
         Of, lf = oracle.fix([N], [m], [d])
         np.testing.assert_allclose(Of, O[:, qs], atol=1e-13)
         np.testing.assert_allclose(lf, lse[:, qs], atol=1e-13)
+
+
+# ----------------------------------------------------------------------------
+# normalised partial format (O' = N / d, lse' = m + log d)
+# ----------------------------------------------------------------------------
+def test_normalised_partials_merge_like_the_triples():
+    g = rng(60)
+    heads, T, H, grid = 2, 5, 3, 4
+    n = grid * T
+    Q, K, V = (g.standard_normal((heads, n, H)) for _ in range(3))
+    scale = 0.9
+    O, lse = oracle.attention_fwd(Q, K, V, scale, True)
+    for r in (0, 2, 3):
+        qs = slice(r * T, (r + 1) * T)
+        trip = [oracle.partial_fwd(Q[:, qs], K[:, c * T:(c + 1) * T], V[:, c * T:(c + 1) * T], r * T, c * T, True, scale)
+                for c in range(grid)]                       # includes empty tiles above the diagonal
+        norm = [oracle.normalised_partial(*t) for t in trip]
+        for (On, ln), (N, m, d) in zip(norm, trip):
+            empty = d == 0
+            assert np.all(np.isinf(ln[empty])) and np.all(On[empty] == 0)
+            # a normalised partial alone is attention over the tile's visible keys: rows are convex combinations of V
+            assert np.all(np.abs(On) <= np.abs(V).max() + 1e-12)
+        O1, l1 = oracle.fix_norm([x[0] for x in norm], [x[1] for x in norm])
+        O2, l2 = oracle.fix([t[0] for t in trip], [t[1] for t in trip], [t[2] for t in trip])
+        np.testing.assert_allclose(O1, O2, atol=1e-14)
+        np.testing.assert_allclose(l1, l2, atol=1e-14)
+        np.testing.assert_allclose(O1, O[:, qs], atol=1e-13)
+        np.testing.assert_allclose(l1, lse[:, qs], atol=1e-13)
+    # closed form: two partials with equal lse average their outputs; an empty one is ignored
+    a, b = g.standard_normal((1, 2, 3)), g.standard_normal((1, 2, 3))
+    l = np.array([[0.3, -1.0]])
+    Om, Lm = oracle.fix_norm([a, b, np.zeros_like(a)], [l, l, np.full_like(l, -np.inf)])
+    np.testing.assert_allclose(Om, (a + b) / 2, atol=1e-15)
+    np.testing.assert_allclose(Lm, l + math.log(2.0), atol=1e-15)
