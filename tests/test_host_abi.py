@@ -144,3 +144,20 @@ def test_accumulating_calls_argument_errors(binding):
     assert L.a2d_partial_fwd_acc(ctypes.byref(d), 1, arr, P, P, P, P, P, P, None, 0, None) == -1      # 100 != 128 keys
     assert L.a2d_partial_fwd_acc(ctypes.byref(d), -1, arr, P, P, P, P, P, P, None, 0, None) == -1
     assert L.a2d_partial_bwd_acc(ctypes.byref(d), 0, None, P, P, P, P, P, P, P, P, P, None, 0, None) == -4
+
+
+def test_normalised_format_argument_errors(binding):
+    b, L = binding, binding.lib()
+    P = ctypes.c_void_p(0x10000)
+    d = _desc(b)
+    assert L.a2d_partial_fwd_norm(ctypes.byref(d), 0, None, P, P, P, None, P, None, 0, None) == -1
+    assert L.a2d_partial_fwd_norm(ctypes.byref(d), 0, None, P, P, P, ctypes.c_void_p(0x10002), P, None, 0, None) == -3
+    arr = (ctypes.c_void_p * 2)(0x10000, 0x20000)
+    fix = lambda k, rows, h, i, o, a=arr: L.a2d_fix_norm(k, rows, h, i, o, a, arr, P, P, None)
+    assert fix(0, 10, 128, b.A2D_BF16, b.A2D_BF16) == -1
+    assert fix(33, 10, 128, b.A2D_BF16, b.A2D_BF16) == -1
+    assert fix(2, 0, 128, b.A2D_BF16, b.A2D_BF16) == -1
+    assert fix(2, 10, 126, b.A2D_BF16, b.A2D_BF16) == -2
+    assert fix(2, 10, 128, 5, b.A2D_BF16) == -2
+    assert fix(2, 10, 128, b.A2D_BF16, 5) == -2
+    assert fix(2, 10, 128, b.A2D_BF16, b.A2D_BF16, None) == -1
