@@ -1,4 +1,4 @@
-// bf16 MFMA forward tile kernel for H = 128 (Sec. 3.1, Eq. (3), evaluated block by
+// bf16 MFMA forward tile kernel for H = 128, 96 and 80 (Sec. 3.1, Eq. (3), evaluated block by
 // block with the recurrence of Sec. 2.2).
 //
 // Work split: one workgroup = 8 wavefronts = 256 query rows of one head; each
@@ -36,16 +36,16 @@ namespace {
 using namespace mfma;
 
 constexpr int BN = 64;             // keys per step
-constexpr int KLD = 272;           // K tile row stride, bytes
-constexpr int VLD = 320;           // V tile row stride, bytes
-constexpr int K_BYTES = BN * KLD;
-constexpr int V_BYTES = BN * VLD;
-constexpr int BUF_BYTES = K_BYTES + V_BYTES;
-constexpr int kLdsBytes = 2 * BUF_BYTES;
+constexpr int VLD = 320;           // V tile row stride, bytes (256 of data at most + a pad that shifts rows by 16 banks)
+// K tile row stride: the row's bytes + 16, which shifts consecutive rows by one 128-bit bank group
+__host__ __device__ constexpr int kld(int hd) { return hd * 2 + 16; }
+__host__ __device__ constexpr int buf_bytes(int hd) { return BN * kld(hd) + BN * VLD; }
+__host__ __device__ constexpr int lds_bytes(int hd) { return 2 * buf_bytes(hd); }
 constexpr float kRescaleThreshold = 8.0f;   // log2 units
 
+template <int HD>
 struct FwdState {
-  f32x16 o[4];
+  f32x16 o[HD / 32];
   float m_lane;   // true running max of this lane's raw dot products
   float m_ref;    // reference the exponentials are taken against (raw units, same in both lanes of a row)
   float l_run;    // this lane's share of the row sum, relative to m_ref
@@ -53,9 +53,11 @@ struct FwdState {
 
 // One 64-key block for one wavefront.  k_rd / v_rd: per-lane LDS byte addresses of the
 // natural K fragment (t = 0, st = 0) and of the transposing V read (u = 0, ht = 0, low rows).
-template <bool MASK>
-__device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], unsigned k_rd, unsigned v_rd,
+// HD / 16 slices of H in the score contraction, HD / 32 column tiles in the output contraction.
+template <int HD, bool MASK>
+__device__ __forceinline__ void fwd_block(FwdState<HD>& st, const bf16x8 (&qf)[HD / 16], unsigned k_rd, unsigned v_rd,
                                           int k0, int my_vis, int half, float c) {
+  constexpr int KS = HD / 16, CT = HD / 32, KLD = kld(HD);
   // K fragments go through a ring four deep: each is requested four MFMAs before its use (the
   // scheduling fences keep the compiler from sinking the requests back to their uses)
   f32x16 s[2];
@@ -64,17 +66,18 @@ __device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], u
   bf16x8 kr[4];
   // step I works on key tile I & 1, slice I >> 1 of H: the two accumulators alternate, so that no
   // MFMA accumulates onto the result of the one issued just before it
-#define A2D_LDK(I) kr[(I) & 3] = lds_load_b128(k_rd + ((I) & 1) * 32 * KLD + ((I) >> 1) * 32);
-#define A2D_S(I)                                              \
-  s[(I) & 1] = mma(kr[(I) & 3], qf[(I) >> 1], s[(I) & 1]);    \
-  if ((I) + 4 < 16) { A2D_LDK(((I) + 4) & 15) }               \
+  auto ldk = [&](auto I) {
+    constexpr int i = decltype(I)::value;
+    kr[i & 3] = lds_load_b128(k_rd + (i & 1) * 32 * KLD + (i >> 1) * 32);
+  };
+  static_for<0, 4>(ldk);
   __builtin_amdgcn_sched_barrier(0);
-  A2D_LDK(0) A2D_LDK(1) A2D_LDK(2) A2D_LDK(3)
-  __builtin_amdgcn_sched_barrier(0);
-  A2D_S(0) A2D_S(1) A2D_S(2) A2D_S(3) A2D_S(4) A2D_S(5) A2D_S(6) A2D_S(7)
-  A2D_S(8) A2D_S(9) A2D_S(10) A2D_S(11) A2D_S(12) A2D_S(13) A2D_S(14) A2D_S(15)
-#undef A2D_S
-#undef A2D_LDK
+  static_for<0, 2 * KS>([&](auto I) {
+    constexpr int i = decltype(I)::value;
+    s[i & 1] = mma(kr[i & 3], qf[i >> 1], s[i & 1]);
+    if constexpr (i + 4 < 2 * KS) ldk(std::integral_constant<int, i + 4>{});
+    __builtin_amdgcn_sched_barrier(0);
+  });
   if (MASK) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -100,20 +103,20 @@ __device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], u
     st.m_ref = m_row;
     st.l_run *= alpha;
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < CT; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) st.o[t][r] *= alpha;
   }
   const float mc = (st.m_ref == -INFINITY) ? 0.f : st.m_ref * c;
-  // V^T fragments (i = 4 u + ht) go through a ring four deep as well; the first four are
-  // requested before the exponentials
+  // V^T fragments (step I: 16-key group I / CT, column tile I % CT) go through a ring four deep
+  // as well; the first four are requested before the exponentials
   bf16x8 vr[4];
-#define A2D_LDV(I)                                                          \
-  {                                                                         \
-    const unsigned a = v_rd + ((I) >> 2) * 16 * VLD + ((I) & 3) * 64;       \
-    vr[(I) & 3] = lds_load_tr(a, a + 8 * VLD);                              \
-  }
-  A2D_LDV(0) A2D_LDV(1) A2D_LDV(2) A2D_LDV(3)
+  auto ldv = [&](auto I) {
+    constexpr int i = decltype(I)::value;
+    const unsigned a = v_rd + (i / CT) * 16 * VLD + (i % CT) * 64;
+    vr[i & 3] = lds_load_tr(a, a + 8 * VLD);
+  };
+  static_for<0, 4>(ldv);
   __builtin_amdgcn_sched_barrier(0);
   float psum = 0.f;
   bf16x8 pb[4];
@@ -127,26 +130,29 @@ __device__ __forceinline__ void fwd_block(FwdState& st, const bf16x8 (&qf)[8], u
     }
   st.l_run += psum;
   __builtin_amdgcn_sched_barrier(0);
-#define A2D_PV(I)                                                  \
-  st.o[(I) & 3] = mma(vr[(I) & 3], pb[(I) >> 2], st.o[(I) & 3]);   \
-  if ((I) + 4 < 16) A2D_LDV(((I) + 4) & 15)                        \
-  __builtin_amdgcn_sched_barrier(0);
-  A2D_PV(0) A2D_PV(1) A2D_PV(2) A2D_PV(3) A2D_PV(4) A2D_PV(5) A2D_PV(6) A2D_PV(7)
-  A2D_PV(8) A2D_PV(9) A2D_PV(10) A2D_PV(11) A2D_PV(12) A2D_PV(13) A2D_PV(14) A2D_PV(15)
-#undef A2D_PV
-#undef A2D_LDV
+  static_for<0, 4 * CT>([&](auto I) {
+    constexpr int i = decltype(I)::value;
+    st.o[i % CT] = mma(vr[i & 3], pb[i / CT], st.o[i % CT]);
+    if constexpr (i + 4 < 4 * CT) ldv(std::integral_constant<int, i + 4>{});
+    __builtin_amdgcn_sched_barrier(0);
+  });
 }
 
 // WAVES wavefronts (32 query rows each) per workgroup: 8 fill a compute unit with one workgroup;
 // 4 (two workgroups per compute unit) are used when there are too few 256-row blocks to give
 // every compute unit one.
-template <int WAVES>
+// HD: padded head size of the LDS tiles and fragments (96 or 128); the true head size d.hdim
+// (80, 96 or 128) is the row length in memory.
+template <int WAVES, int HD>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
     a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, float* __restrict__ O_part, float* __restrict__ m_out,
     float* __restrict__ l_out) {
   constexpr int BM = 32 * WAVES;          // query rows per workgroup
   constexpr int kThreads = 64 * WAVES;
+  constexpr int KS = HD / 16, CT = HD / 32, KLD = kld(HD), K_BYTES = BN * KLD, BUF_BYTES = buf_bytes(HD);
+  constexpr int kLdsBytes = lds_bytes(HD);
+  const int H = d.hdim;                   // row length in memory
   extern __shared__ __attribute__((aligned(16))) char lds[];
   // [buf]{ K tile (BN x KLD), V tile (BN x VLD) }
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
@@ -166,15 +172,18 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   // ---- Q^T fragments: lane holds query row (l32), h = 16*step + 8*half + 0..7.
   // Rows beyond nq re-read the last row (their results are never stored).
   const int q_row = q0 + wave * 32 + l32;
-  bf16x8 qf[8];
+  bf16x8 qf[KS];
   {
     const bf16_t* qp = Q + (int64_t)min(q_row, d.nq - 1) * H + 8 * half;
 #pragma unroll
-    for (int x = 0; x < 8; ++x) qf[x] = *reinterpret_cast<const bf16x8*>(qp + 16 * x);
+    for (int x = 0; x < KS; ++x) {
+      if (16 * x < H) qf[x] = *reinterpret_cast<const bf16x8*>(qp + 16 * x);
+      else qf[x] = bf16x8{};                                  // columns past the head size are zero
+    }
   }
-  FwdState st;
+  FwdState<HD> st;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) st.o[t] = zero16();
+  for (int t = 0; t < CT; ++t) st.o[t] = zero16();
   st.l_run = 0.f;
   const float c = d.scale * kLog2e;
   float m_in = -INFINITY;
@@ -184,27 +193,32 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
     // lanes of the row.  A lane's share of N is 16 scattered 16-byte pieces of its row, so the
     // rows come in through LDS: each wavefront reads 16 of its rows at a time with whole-row
     // coalesced loads into a private, padded LDS area and the owning lanes pick their pieces.
-    constexpr int ALD = H * 4 + 16;                           // padded row stride, bytes
+    constexpr int ALD = HD * 4 + 16;                          // padded row stride, bytes
     static_assert(16 * ALD * (kThreads / 64) <= kLdsBytes, "accumulator staging must fit the tile buffers");
     char* area = lds + wave * 16 * ALD;
     const int64_t wrow0 = (int64_t)head * d.nq + q0 + wave * 32;   // first row of the wavefront
     const int64_t last_row = (int64_t)head * d.nq + d.nq - 1;
+    const bool col_ok = 4 * (lane & 31) < H;                 // this lane's 16-byte piece exists in the row
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
       u32x4 t[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) {                          // two whole rows per load instruction
         const int64_t r = wrow0 + 16 * pass + 2 * i + (lane >> 5);
-        t[i] = *reinterpret_cast<const u32x4*>(O_part + (r < last_row ? r : last_row) * H + 4 * (lane & 31));
+        t[i] = u32x4{0, 0, 0, 0};
+        if (col_ok)
+          t[i] = *reinterpret_cast<const u32x4*>(O_part + (r < last_row ? r : last_row) * H + 4 * (lane & 31));
       }
+      if (4 * (lane & 31) < HD) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-        *reinterpret_cast<u32x4*>(area + (2 * i + (lane >> 5)) * ALD + 16 * (lane & 31)) = t[i];
+        for (int i = 0; i < 8; ++i)
+          *reinterpret_cast<u32x4*>(area + (2 * i + (lane >> 5)) * ALD + 16 * (lane & 31)) = t[i];
+      }
       __syncthreads();
       if ((l32 >> 4) == pass) {
         const char* mine = area + (l32 & 15) * ALD + 16 * half;
 #pragma unroll
-        for (int ht = 0; ht < 4; ++ht)
+        for (int ht = 0; ht < CT; ++ht)
 #pragma unroll
           for (int gq = 0; gq < 4; ++gq) {
             const f32x4 v = *reinterpret_cast<const f32x4*>(mine + (32 * ht + 8 * gq) * 4);
@@ -219,7 +233,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
       st.l_run = half == 0 ? l_out[row] : 0.f;
     } else {
 #pragma unroll
-      for (int t = 0; t < 4; ++t) st.o[t] = zero16();        // rows beyond nq: nothing to continue
+      for (int t = 0; t < CT; ++t) st.o[t] = zero16();       // rows beyond nq: nothing to continue
     }
   }
   wait_vmem_all();
@@ -248,10 +262,14 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   // ---- staging: thread moves the 16-byte chunk (tid & 15) of rows (tid >> 4) + 32 p.
   // Rows beyond nkv re-read the last row: finite values, masked out of the scores.
   const int ld_row = tid >> 4, ld_chunk = tid & 15;
+  const bool ld_ok = ld_chunk * 8 < H;          // the chunk exists in memory (else it is a zero pad column group)
+  const bool st_ok = ld_chunk * 8 < HD;         // the chunk exists in the LDS tile
   const int k_wr = ld_row * KLD + ld_chunk * 16;
   const int v_wr = K_BYTES + ld_row * VLD + ld_chunk * 16;
   constexpr int ST_ROWS = kThreads / 16, ST_N = BN / ST_ROWS;   // rows per pass, passes per tile
   u32x4 kreg[ST_N], vreg[ST_N];
+#pragma unroll
+  for (int p = 0; p < ST_N; ++p) { kreg[p] = u32x4{0, 0, 0, 0}; vreg[p] = u32x4{0, 0, 0, 0}; }
   // block j of the sub-block of seg_rows keys that starts at local key seg_start; rows beyond its
   // end re-read its last row
   auto load_tile = [&](int seg_start, int seg_rows, int j) {
@@ -259,18 +277,22 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
     const gptr_t kb = uniform_gptr(K + (int64_t)k0 * H);   // scalar bases
     const gptr_t vb = uniform_gptr(V + (int64_t)k0 * H);
     const int last = seg_rows - 1 - j * BN;
+    if (ld_ok) {
 #pragma unroll
-    for (int p = 0; p < ST_N; ++p) {
-      const unsigned off = (unsigned)(min(ld_row + ST_ROWS * p, last) * (H * 2) + ld_chunk * 16);
-      kreg[p] = gload_b128(kb, off);
-      vreg[p] = gload_b128(vb, off);
+      for (int p = 0; p < ST_N; ++p) {
+        const unsigned off = (unsigned)(min(ld_row + ST_ROWS * p, last) * (H * 2) + ld_chunk * 16);
+        kreg[p] = gload_b128(kb, off);
+        vreg[p] = gload_b128(vb, off);
+      }
     }
   };
   auto store_tile = [&](int boff) {
+    if (st_ok) {
 #pragma unroll
-    for (int p = 0; p < ST_N; ++p) {
-      *reinterpret_cast<u32x4*>(lds + boff + k_wr + p * ST_ROWS * KLD) = kreg[p];
-      *reinterpret_cast<u32x4*>(lds + boff + v_wr + p * ST_ROWS * VLD) = vreg[p];
+      for (int p = 0; p < ST_N; ++p) {
+        *reinterpret_cast<u32x4*>(lds + boff + k_wr + p * ST_ROWS * KLD) = kreg[p];
+        *reinterpret_cast<u32x4*>(lds + boff + v_wr + p * ST_ROWS * VLD) = vreg[p];
+      }
     }
   };
   // fragment read bases (buffer 0)
@@ -305,8 +327,8 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
     if (more) load_tile(nx_start, nx_rows, nj);
     const int k0 = j * BN;                         // local to the sub-block
     if (k0 < nvis_wave) {
-      if (k0 + BN > nfull_wave) fwd_block<true>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
-      else fwd_block<false>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
+      if (k0 + BN > nfull_wave) fwd_block<HD, true>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
+      else fwd_block<HD, false>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
     }
     if (more) store_tile(BUF_BYTES - boff);
     __syncthreads();
@@ -319,31 +341,32 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   const float m_row = fmaxf(st.m_lane, __shfl_xor(st.m_lane, 32, 64));
   const float f = (m_row == -INFINITY) ? 0.f : fast_exp2((st.m_ref - m_row) * c);
   const float l_tot = (st.l_run + __shfl_xor(st.l_run, 32, 64)) * f;
+  // a lane's piece (column tile ht, group gq) covers columns 32 ht + 8 gq + 4 half + 0..3
   if (q_row < d.nq && g.norm) {
     // normalised partial: O' = N / l rounded to bf16, lse' = m + ln l (Sec. 3.2, footnote)
     const int64_t row = (int64_t)head * d.nq + q_row;
     const float fn = l_tot > 0.f ? f / l_tot : 0.f;
     bf16_t* op = reinterpret_cast<bf16_t*>(O_part) + row * H + 4 * half;
 #pragma unroll
-    for (int ht = 0; ht < 4; ++ht)
+    for (int ht = 0; ht < CT; ++ht)
 #pragma unroll
       for (int gq = 0; gq < 4; ++gq) {
         bf16x4 v;
         v[0] = (bf16_t)(st.o[ht][4 * gq] * fn); v[1] = (bf16_t)(st.o[ht][4 * gq + 1] * fn);
         v[2] = (bf16_t)(st.o[ht][4 * gq + 2] * fn); v[3] = (bf16_t)(st.o[ht][4 * gq + 3] * fn);
-        *reinterpret_cast<bf16x4*>(op + 32 * ht + 8 * gq) = v;
+        if (32 * ht + 8 * gq + 4 * half < H) *reinterpret_cast<bf16x4*>(op + 32 * ht + 8 * gq) = v;
       }
     if (half == 0) m_out[row] = l_tot > 0.f ? m_row * d.scale + logf(l_tot) : -INFINITY;
   } else if (q_row < d.nq) {
     const int64_t row = (int64_t)head * d.nq + q_row;
     float* op = O_part + row * H + 4 * half;
 #pragma unroll
-    for (int ht = 0; ht < 4; ++ht)
+    for (int ht = 0; ht < CT; ++ht)
 #pragma unroll
       for (int gq = 0; gq < 4; ++gq) {
         f32x4 v = {st.o[ht][4 * gq] * f, st.o[ht][4 * gq + 1] * f, st.o[ht][4 * gq + 2] * f,
                    st.o[ht][4 * gq + 3] * f};
-        *reinterpret_cast<f32x4*>(op + 32 * ht + 8 * gq) = v;
+        if (32 * ht + 8 * gq + 4 * half < H) *reinterpret_cast<f32x4*>(op + 32 * ht + 8 * gq) = v;
       }
     if (half == 0) {
       m_out[row] = m_row * d.scale;      // -inf stays -inf (scale > 0)
@@ -355,8 +378,23 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
 }  // namespace
 
 bool fwd_mfma_supported(const a2d_tile_desc& d) {
-  return d.dtype == A2D_BF16 && d.hdim == mfma::H;
+  return d.dtype == A2D_BF16 && (d.hdim == 128 || d.hdim == 96 || d.hdim == 80);
 }
+
+namespace {
+template <int WAVES, int HD>
+hipError_t fwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
+                      float* O_part, float* m, float* l, hipStream_t s) {
+  constexpr int bytes = lds_bytes(HD);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_mfma_kernel<WAVES, HD>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess) return e;
+  dim3 grid(xcd_grid(d.heads, (d.nq + 32 * WAVES - 1) / (32 * WAVES))), block(64 * WAVES);
+  hipLaunchKernelGGL((fwd_mfma_kernel<WAVES, HD>), grid, block, bytes, s, d, g, (const bf16_t*)Q,
+                     (const bf16_t*)K, (const bf16_t*)V, O_part, m, l);
+  return hipGetLastError();
+}
+}  // namespace
 
 hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                            float* O_part, float* m, float* l, hipStream_t s) {
@@ -366,19 +404,9 @@ hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const SegList& g, const void*
   if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) return e;
   const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
-  const void* fn = big ? reinterpret_cast<const void*>(fwd_mfma_kernel<8>)
-                       : reinterpret_cast<const void*>(fwd_mfma_kernel<4>);
-  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-  if (e != hipSuccess) return e;
-  const int bm = big ? 256 : 128;
-  dim3 grid(xcd_grid(d.heads, (d.nq + bm - 1) / bm)), block(big ? 512 : 256);
-  if (big)
-    hipLaunchKernelGGL(fwd_mfma_kernel<8>, grid, block, kLdsBytes, s, d, g, (const bf16_t*)Q, (const bf16_t*)K,
-                       (const bf16_t*)V, O_part, m, l);
-  else
-    hipLaunchKernelGGL(fwd_mfma_kernel<4>, grid, block, kLdsBytes, s, d, g, (const bf16_t*)Q, (const bf16_t*)K,
-                       (const bf16_t*)V, O_part, m, l);
-  return hipGetLastError();
+  if (padded_head(d.hdim) == 128)
+    return big ? fwd_launch<8, 128>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 128>(d, g, Q, K, V, O_part, m, l, s);
+  return big ? fwd_launch<8, 96>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 96>(d, g, Q, K, V, O_part, m, l, s);
 }
 
 }  // namespace a2d

@@ -11,12 +11,27 @@
 //   - "transposed" fragments (contraction along the row index): two ds_read_b64_tr_b16, where a
 //     16-lane group reads 4 consecutive rows x 16 columns and every lane receives a column.
 #pragma once
+#include <type_traits>
+
 #include "a2d_common.hpp"
 
 namespace a2d {
 namespace mfma {
 
+// Head sizes of the MFMA kernels: the tiles are laid out for HD = 96 or 128 columns (multiples of
+// the 32-column accumulator tile); a head size of 80 runs as HD = 96 with its last 16 columns
+// zero in LDS and in the register fragments and left out of every store.
 constexpr int H = 128;
+__host__ __device__ constexpr int padded_head(int h) { return h > 96 ? 128 : 96; }
+
+// compile-time loop: f(std::integral_constant<int, B>{}), ..., f(std::integral_constant<int, E - 1>{})
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E>(f);
+  }
+}
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef short s16x8 __attribute__((ext_vector_type(8)));
