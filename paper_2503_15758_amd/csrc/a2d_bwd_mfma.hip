@@ -1,4 +1,4 @@
-// bf16 MFMA backward tile kernels for H = 128: the per-tile gradient call of Alg. 3
+// bf16 MFMA backward tile kernels for H = 128, 96 and 80: the per-tile gradient call of Alg. 3
 // line 3 with P = exp(S - lse) rebuilt from the FINAL log-sum-exp of the query block,
 //   dV = P^T dO,  dP = dO V^T,  dS = P o (dP - delta),  dQ = scale dS K,  dK = scale dS^T Q.
 //
@@ -37,12 +37,15 @@ using namespace mfma;
 
 // stores a transposed accumulator (lane = one output row, registers = 4-column groups)
 // (add: onto what the row already holds)
-__device__ __forceinline__ void store_acc_t(float* __restrict__ out_row, const f32x16 (&acc)[4],
-                                            int half, float mul, bool add = false) {
+// CT column tiles of 32; pieces whose columns lie past the head size h are skipped
+template <int CT>
+__device__ __forceinline__ void store_acc_t(float* __restrict__ out_row, const f32x16 (&acc)[CT],
+                                            int half, float mul, int h, bool add = false) {
 #pragma unroll
-  for (int ht = 0; ht < 4; ++ht)
+  for (int ht = 0; ht < CT; ++ht)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
+      if (32 * ht + 8 * g + 4 * half >= h) continue;
       f32x4 v = {acc[ht][4 * g] * mul, acc[ht][4 * g + 1] * mul, acc[ht][4 * g + 2] * mul,
                  acc[ht][4 * g + 3] * mul};
       f32x4* p = reinterpret_cast<f32x4*>(out_row + 32 * ht + 8 * g + 4 * half);
@@ -85,9 +88,10 @@ constexpr int DK_LDS = DK_MBOX + 2 * DK_MBOX_SLOT;
 //                           transposed reads from the dO tile, acc = dV^T
 //   gradient wave (role 1): frag = V^T fragments, natural reads from the dO tile,
 //                           transposed reads from the Q tile, acc = dK^T
+template <int HD>
 struct DkCtx {
-  f32x16 acc[4];
-  bf16x8 frag[8];
+  f32x16 acc[HD / 32];
+  bf16x8 frag[HD / 16];
   unsigned nat_e, nat_o, tr_lo, tr_hi;   // dual-layout bases in the tile buffer of this wave's step
   unsigned stat;        // lse (role 0) or delta (role 1) row of that buffer, + 16 * half
   unsigned mbox;        // this lane's place in the pair's mailbox, slot of this wave's step
@@ -102,26 +106,27 @@ struct DkCtx {
   lds_load_tr(cx.tr_lo + (U) * 16 * DUAL_LD + 64 * (HT), cx.tr_hi + (U) * 16 * DUAL_LD + 64 * (HT))
 #define A2D_FENCE __builtin_amdgcn_sched_barrier(0);
 
-// First contraction of a 32-query x 32-key step (S = Q K^T or dP = dO V^T): eight MFMAs over
+// First contraction of a 32-query x 32-key step (S = Q K^T or dP = dO V^T): HD / 16 MFMAs over
 // H.  The natural fragments travel through a ring of four: dk_first_pre requests fragments
-// 0..3, the body requests 4..7 while it consumes 0..3.  (The fences keep the compiler from
-// sinking the requests down to their uses.)
-__device__ __forceinline__ void dk_first_pre(const DkCtx& cx, bf16x8 (&n)[4]) {
+// 0..3, the body requests the others while it consumes those.  (The fences keep the compiler
+// from sinking the requests down to their uses.)
+template <int HD>
+__device__ __forceinline__ void dk_first_pre(const DkCtx<HD>& cx, bf16x8 (&n)[4]) {
   n[0] = A2D_NAT(0); n[1] = A2D_NAT(1); n[2] = A2D_NAT(2); n[3] = A2D_NAT(3);
   A2D_FENCE
 }
 // `init` is the starting value of the sum (zero for S, -delta for dP - delta).  Two accumulators
 // (even / odd 16-wide slices of H): an MFMA that accumulates onto the result of the one issued
 // just before it would wait for that result.
-__device__ __forceinline__ f32x16 dk_first(const DkCtx& cx, bf16x8 (&n)[4], f32x16 init) {
+template <int HD>
+__device__ __forceinline__ f32x16 dk_first(const DkCtx<HD>& cx, bf16x8 (&n)[4], f32x16 init) {
+  constexpr int KS = HD / 16;
   f32x16 sa = init, sb = zero16();
-#define A2D_MM1(X) if ((X) & 1) sb = mma(n[(X) & 3], cx.frag[X], sb); else sa = mma(n[(X) & 3], cx.frag[X], sa);
-  A2D_MM1(0) n[0] = A2D_NAT(4); A2D_FENCE
-  A2D_MM1(1) n[1] = A2D_NAT(5); A2D_FENCE
-  A2D_MM1(2) n[2] = A2D_NAT(6); A2D_FENCE
-  A2D_MM1(3) n[3] = A2D_NAT(7); A2D_FENCE
-  A2D_MM1(4) A2D_MM1(5) A2D_MM1(6) A2D_MM1(7)
-#undef A2D_MM1
+  static_for<0, KS>([&](auto X) {
+    constexpr int x = decltype(X)::value;
+    if constexpr (x & 1) sb = mma(n[x & 3], cx.frag[x], sb); else sa = mma(n[x & 3], cx.frag[x], sa);
+    if constexpr (x + 4 < KS) { n[x & 3] = A2D_NAT(x + 4); A2D_FENCE }
+  });
 #pragma unroll
   for (int r = 0; r < 16; ++r) sa[r] += sb[r];
   return sa;
@@ -129,12 +134,14 @@ __device__ __forceinline__ f32x16 dk_first(const DkCtx& cx, bf16x8 (&n)[4], f32x
 
 // The 32 per-query statistics of the step (lse for the score wave, delta for the gradient wave)
 // and the partner's probabilities, requested ahead of the first contraction.
-__device__ __forceinline__ void dk_stat_pre(const DkCtx& cx, f32x4 (&st)[4]) {
+template <int HD>
+__device__ __forceinline__ void dk_stat_pre(const DkCtx<HD>& cx, f32x4 (&st)[4]) {
 #pragma unroll
   for (int g = 0; g < 4; ++g) st[g] = lds_load_f32x4(cx.stat + 8 * g * 4);
   A2D_FENCE
 }
-__device__ __forceinline__ void dk_mbox_pre(const DkCtx& cx, f32x4 (&pm)[4]) {
+template <int HD>
+__device__ __forceinline__ void dk_mbox_pre(const DkCtx<HD>& cx, f32x4 (&pm)[4]) {
 #pragma unroll
   for (int g = 0; g < 4; ++g) pm[g] = lds_load_f32x4(cx.mbox + g * 1024);
   A2D_FENCE
@@ -142,8 +149,8 @@ __device__ __forceinline__ void dk_mbox_pre(const DkCtx& cx, f32x4 (&pm)[4]) {
 
 // score wave: P = exp2(c S - lse2), masked; handed on in fp32 and kept as bf16 B fragments.
 // register r <-> query qs0 + 8*(r>>2) + 4*half + (r&3); lane <-> key
-template <bool MASK>
-__device__ __forceinline__ void dk_probs(const DkCtx& cx, const f32x4 (&st)[4], f32x16& s,
+template <bool MASK, int HD>
+__device__ __forceinline__ void dk_probs(const DkCtx<HD>& cx, const f32x4 (&st)[4], f32x16& s,
                                          bf16x8 (&bf)[2], int qs0) {
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
@@ -173,27 +180,36 @@ __device__ __forceinline__ void dk_dscores(const f32x4 (&pm)[4], f32x16& dpd, bf
   for (int u = 0; u < 2; ++u) bf[u] = pack8(dp, 8 * u);
 }
 
-// Second contraction of a step (dV^T += dO^T P or dK^T += Q^T dS): eight MFMAs, A operands from
-// the LDS transpose read, again through a ring of four fragments (one per 32-column tile of H):
+// Second contraction of a step (dV^T += dO^T P or dK^T += Q^T dS): 2 * HD / 32 MFMAs, A operands
+// from the LDS transpose read, again through a ring (one fragment per 32-column tile of H):
 // dk_second_pre requests those of the first 16 query rows (before the exponentials, so they
 // arrive meanwhile), the body those of the second 16.
-__device__ __forceinline__ void dk_second_pre(const DkCtx& cx, bf16x8 (&t)[4]) {
-  t[0] = A2D_TR(0, 0); t[1] = A2D_TR(0, 1); t[2] = A2D_TR(0, 2); t[3] = A2D_TR(0, 3);
+template <int HD>
+__device__ __forceinline__ void dk_second_pre(const DkCtx<HD>& cx, bf16x8 (&t)[HD / 32]) {
+  static_for<0, HD / 32>([&](auto HT) { constexpr int ht = decltype(HT)::value; t[ht] = A2D_TR(0, ht); });
   A2D_FENCE
 }
-__device__ __forceinline__ void dk_second(DkCtx& cx, bf16x8 (&t)[4], const bf16x8 (&bf)[2]) {
-#define A2D_MM2(HT, U) cx.acc[HT] = mma(t[HT], bf[U], cx.acc[HT]);
-  A2D_MM2(0, 0) t[0] = A2D_TR(1, 0); A2D_FENCE
-  A2D_MM2(1, 0) t[1] = A2D_TR(1, 1); A2D_FENCE
-  A2D_MM2(2, 0) t[2] = A2D_TR(1, 2); A2D_FENCE
-  A2D_MM2(3, 0) t[3] = A2D_TR(1, 3); A2D_FENCE
-  A2D_MM2(0, 1) A2D_MM2(1, 1) A2D_MM2(2, 1) A2D_MM2(3, 1)
-#undef A2D_MM2
+template <int HD>
+__device__ __forceinline__ void dk_second(DkCtx<HD>& cx, bf16x8 (&t)[HD / 32], const bf16x8 (&bf)[2]) {
+  constexpr int CT = HD / 32;
+  static_for<0, CT>([&](auto HT) {
+    constexpr int ht = decltype(HT)::value;
+    cx.acc[ht] = mma(t[ht], bf[0], cx.acc[ht]);
+    t[ht] = A2D_TR(1, ht);
+    A2D_FENCE
+  });
+  static_for<0, CT>([&](auto HT) {
+    constexpr int ht = decltype(HT)::value;
+    cx.acc[ht] = mma(t[ht], bf[1], cx.acc[ht]);
+  });
 }
 #undef A2D_FENCE
 #undef A2D_TR
 #undef A2D_NAT
 
+// HR: head size = row length in memory (80, 96 or 128); the LDS tiles and fragments are laid out
+// for the padded head size HD = padded_head(HR) (96 or 128).
+template <int HR>
 __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
     a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
@@ -202,6 +218,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
   int head, blk;
   if (!xcd_map(d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS, head, blk)) return;
+  constexpr int HD = padded_head(HR), H = HR, KS = HD / 16, CT = HD / 32;
   const int k0 = blk * DK_KEYS;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -214,7 +231,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   lse += (int64_t)head * d.nq;
   delta += (int64_t)head * d.nq;
 
-  DkCtx cx;
+  DkCtx<HD> cx;
   cx.half = lane >> 5;
   cx.c = d.scale * kLog2e;
   // ---- K^T (score wave) or V^T (gradient wave) B fragments of the pair's 32 keys: lane = key,
@@ -224,11 +241,14 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   {
     const bf16_t* src = (role ? V : K) + (int64_t)min(key, d.nkv - 1) * H + 8 * cx.half;
 #pragma unroll
-    for (int x = 0; x < 8; ++x) cx.frag[x] = *reinterpret_cast<const bf16x8*>(src + 16 * x);
+    for (int x = 0; x < KS; ++x) {
+      if (16 * x < H) cx.frag[x] = *reinterpret_cast<const bf16x8*>(src + 16 * x);
+      else cx.frag[x] = bf16x8{};                              // columns past the head size are zero
+    }
   }
   wait_vmem_all();
 #pragma unroll
-  for (int t = 0; t < 4; ++t) cx.acc[t] = zero16();
+  for (int t = 0; t < CT; ++t) cx.acc[t] = zero16();
 
   // Query i sees key kk of key/value sub-block s iff i >= kk - rel[s].  seg_first_row(sb, r): first
   // local query row that sees local key r of sub-block sb (nq if none does).
@@ -301,10 +321,14 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   u32x4 qreg[2], greg[2];
   float stat[2] = {0.f, 0.f};
   bool stat_ok[2] = {false, false};
+  // (a chunk past the row's end - head sizes below 128 - re-reads the row's last chunk and is
+  // stored as zeros or, past the padded head size, not at all: every lane issues every load)
+  const int ld_ch = min(st_ch, H / 8 - 1);
+  const bool ch_data = st_ch * 8 < H, ch_tile = st_ch * 8 < HD;
   auto load_step = [&](int step, auto set_tag) {
     constexpr int SET = decltype(set_tag)::value;
     const int i0 = i_start + min(step, nsteps - 1) * BQ;
-    const unsigned off = (unsigned)(min(i0 + st_row, d.nq - 1) * (H * 2) + st_ch * 16);
+    const unsigned off = (unsigned)(min(i0 + st_row, d.nq - 1) * (H * 2) + ld_ch * 16);
     qreg[SET] = gload_b128(q_base, off);
     greg[SET] = gload_b128(g_base, off);
     // raw statistic loads only: converting here would make the wave wait for everything just
@@ -317,8 +341,11 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   auto store_step = [&](int buf, auto set_tag) {
     constexpr int SET = decltype(set_tag)::value;
     char* b = lds + buf * DK_BUF;
-    *reinterpret_cast<u32x4*>(b + st_off) = qreg[SET];
-    *reinterpret_cast<u32x4*>(b + DK_TILE + st_off) = greg[SET];
+    if (HD == 128 || ch_tile) {
+      const u32x4 zero = {0, 0, 0, 0};
+      *reinterpret_cast<u32x4*>(b + st_off) = (HD == 128 || ch_data) ? qreg[SET] : zero;
+      *reinterpret_cast<u32x4*>(b + DK_TILE + st_off) = (HD == 128 || ch_data) ? greg[SET] : zero;
+    }
     if (tid < 2 * BQ) {
       float v = stat[SET];
       if (tid < BQ) v = (!stat_ok[SET] || v == -INFINITY) ? INFINITY : v * kLog2e;
@@ -364,7 +391,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
       load_step(j + 4, set_tag);
       if (active(j)) {
         const int i0 = i_start + j * BQ;
-        bf16x8 t[4], bf[2];
+        bf16x8 t[CT], bf[2];
         f32x16 s = dk_first(cx, n, zero16());
         dk_second_pre(cx, t);
         if (i0 >= w_all && i0 + BQ <= d.nq) dk_probs<false>(cx, st, s, bf, i0);
@@ -390,7 +417,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
       store_step((j + 2) % DK_NBUF, set_tag);
       load_step(j + 4, set_tag);
       if (active(j - 1)) {
-        bf16x8 t[4], bf[2];
+        bf16x8 t[CT], bf[2];
         f32x4 pm[4];
         dk_mbox_pre(cx, pm);
         dk_second_pre(cx, t);
@@ -418,23 +445,24 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
 
   if (key < d.nkv) {
     const int64_t row = (int64_t)head * d.nkv + key;
-    if (role == 0) store_acc_t(dV + row * H, cx.acc, cx.half, 1.0f);
-    else store_acc_t(dK + row * H, cx.acc, cx.half, d.scale);
+    if (role == 0) store_acc_t<CT>(dV + row * H, cx.acc, cx.half, 1.0f, H);
+    else store_acc_t<CT>(dK + row * H, cx.acc, cx.half, d.scale, H);
   }
 }
 
 // ---------------------------------------------------------------------- dQ
 constexpr int BKS = 64;           // keys per step
-constexpr int VT_LD = 272;        // V tile row stride (natural reads only)
-// LDS: [buf]{ K tile (dual layout), V tile (272-byte rows) }
+// LDS: [buf]{ K tile (dual layout), V tile (natural reads only: rows of the head's bytes + 16) }
+__host__ __device__ constexpr int vt_ld(int hd) { return hd * 2 + 16; }
 constexpr int DQ_VT = DUAL64_BYTES;
-constexpr int DQ_BUF = DUAL64_BYTES + BKS * VT_LD;
-constexpr int DQ_LDS = 2 * DQ_BUF;
+__host__ __device__ constexpr int dq_buf(int hd) { return DUAL64_BYTES + BKS * vt_ld(hd); }
+__host__ __device__ constexpr int dq_lds(int hd) { return 2 * dq_buf(hd); }
 constexpr int DQ_RING = 2;        // fragment ring depth (registers are tight: 256 per wavefront)
 
+template <int HD>
 struct DqCtx {
-  f32x16 dq[4];
-  bf16x8 qf[8], gf[8];
+  f32x16 dq[HD / 32];
+  bf16x8 qf[HD / 16], gf[HD / 16];
   DualAddr ka;          // K tile of the current buffer
   unsigned vnat;        // natural-fragment base in the V tile of the current buffer
   float c, lse2, del;
@@ -442,35 +470,37 @@ struct DqCtx {
   int half;
 };
 
-// one 32-key x 32-query piece: T selects the half of the 64-key step
-template <int T, bool MASK>
-__device__ __forceinline__ void dq_piece(DqCtx& cx, int key0) {
+// one 32-key x 32-query piece: T selects the half of the 64-key step.  HD / 16 slices of H in the
+// two first contractions (S^T and dP^T, alternating), 2 * HD / 32 MFMAs in dQ^T += K^T dS^T
+// (step I: 16-key group I / CT, column tile I % CT); fragments run two steps ahead of their use.
+template <int T, bool MASK, int HD>
+__device__ __forceinline__ void dq_piece(DqCtx<HD>& cx, int key0) {
+  constexpr int KS = HD / 16, CT = HD / 32, VT_LD = vt_ld(HD);
   constexpr int RB = T * 32 * DUAL_LD;
   constexpr int VB = T * 32 * VT_LD;
-  bf16x8 kr[DQ_RING], vr[DQ_RING];
-#define A2D_LD1(X)                                             \
-  kr[(X) % DQ_RING] = dual_nat<X>(cx.ka, RB);                  \
-  vr[(X) % DQ_RING] = lds_load_b128(cx.vnat + VB + 32 * (X));  \
-  __builtin_amdgcn_sched_barrier(0);
-#define A2D_SDP(X) s = mma(kr[(X) % DQ_RING], cx.qf[X], s); dp = mma(vr[(X) % DQ_RING], cx.gf[X], dp);
-  A2D_LD1(0) A2D_LD1(1)
+  bf16x8 kr[DQ_RING], vr[DQ_RING], kt[DQ_RING];
+  auto ld1 = [&](auto X) {
+    constexpr int x = decltype(X)::value;
+    kr[x % DQ_RING] = dual_nat<x>(cx.ka, RB);
+    vr[x % DQ_RING] = lds_load_b128(cx.vnat + VB + 32 * x);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // K^T fragments; the first ones are on their way during the exponentials
+  auto ld2 = [&](auto I) {
+    constexpr int i = decltype(I)::value;
+    kt[i % DQ_RING] = lds_load_tr(cx.ka.tr_lo + RB + (i / CT) * 16 * DUAL_LD + 64 * (i % CT),
+                                  cx.ka.tr_hi + RB + (i / CT) * 16 * DUAL_LD + 64 * (i % CT));
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  static_for<0, DQ_RING>(ld1);
   f32x16 s = zero16(), dp = zero16();
-  A2D_SDP(0) A2D_LD1(2)
-  A2D_SDP(1) A2D_LD1(3)
-  A2D_SDP(2) A2D_LD1(4)
-  A2D_SDP(3) A2D_LD1(5)
-  A2D_SDP(4) A2D_LD1(6)
-  A2D_SDP(5) A2D_LD1(7)
-  // K^T fragments of the first key rows: on their way during the exponentials
-  bf16x8 kt[DQ_RING];
-#define A2D_LD2(I)                                                                                        \
-  kt[(I) % DQ_RING] = lds_load_tr(cx.ka.tr_lo + RB + ((I) >> 2) * 16 * DUAL_LD + 64 * ((I) & 3),          \
-                                  cx.ka.tr_hi + RB + ((I) >> 2) * 16 * DUAL_LD + 64 * ((I) & 3));         \
-  __builtin_amdgcn_sched_barrier(0);
-  A2D_SDP(6) A2D_LD2(0)
-  A2D_SDP(7) A2D_LD2(1)
-#undef A2D_SDP
-#undef A2D_LD1
+  static_for<0, KS>([&](auto X) {
+    constexpr int x = decltype(X)::value;
+    s = mma(kr[x % DQ_RING], cx.qf[x], s);
+    dp = mma(vr[x % DQ_RING], cx.gf[x], dp);
+    if constexpr (x + DQ_RING < KS) ld1(std::integral_constant<int, x + DQ_RING>{});
+    else ld2(std::integral_constant<int, x + DQ_RING - KS>{});
+  });
   // register r <-> key key0 + 8*(r>>2) + 4*half + (r&3); lane <-> query
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -482,22 +512,18 @@ __device__ __forceinline__ void dq_piece(DqCtx& cx, int key0) {
   dsb[0] = pack8(dp, 0);
   dsb[1] = pack8(dp, 8);
   __builtin_amdgcn_sched_barrier(0);
-#define A2D_DQ(I) cx.dq[(I) & 3] = mma(kt[(I) % DQ_RING], dsb[(I) >> 2], cx.dq[(I) & 3]);
-  A2D_DQ(0) A2D_LD2(2)
-  A2D_DQ(1) A2D_LD2(3)
-  A2D_DQ(2) A2D_LD2(4)
-  A2D_DQ(3) A2D_LD2(5)
-  A2D_DQ(4) A2D_LD2(6)
-  A2D_DQ(5) A2D_LD2(7)
-  A2D_DQ(6) A2D_DQ(7)
-#undef A2D_DQ
-#undef A2D_LD2
+  static_for<0, 2 * CT>([&](auto I) {
+    constexpr int i = decltype(I)::value;
+    cx.dq[i % CT] = mma(kt[i % DQ_RING], dsb[i / CT], cx.dq[i % CT]);
+    if constexpr (i + DQ_RING < 2 * CT) ld2(std::integral_constant<int, i + DQ_RING>{});
+  });
 }
 
 // WAVES wavefronts (32 query rows each) per workgroup: 8 fill a compute unit with one workgroup;
 // 4 (two workgroups per compute unit) are used when there are too few 256-row blocks to give
 // every compute unit one.
-template <int WAVES>
+// HR: head size (80, 96 or 128), HD its padded size, as in the dK/dV kernel.
+template <int WAVES, int HR>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
     a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
@@ -506,6 +532,8 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
   constexpr int DQ_ROWS = 32 * WAVES;      // query rows per workgroup
   constexpr int DQ_THREADS = 64 * WAVES;
+  constexpr int HD = padded_head(HR), H = HR;
+  constexpr int KS = HD / 16, CT = HD / 32, VT_LD = vt_ld(HD), DQ_BUF = dq_buf(HD);
   const int nqb = (d.nq + DQ_ROWS - 1) / DQ_ROWS;
   int head, blk;
   if (!xcd_map(d.heads, nqb, head, blk)) return;
@@ -518,7 +546,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   K += (int64_t)head * d.nkv * H;
   V += (int64_t)head * d.nkv * H;
 
-  DqCtx cx;
+  DqCtx<HD> cx;
   cx.half = lane >> 5;
   cx.c = d.scale * kLog2e;
   const int q_row = q0 + wave * 32 + l32;
@@ -527,9 +555,14 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   {
     const int64_t off = (int64_t)q_ld * H + 8 * cx.half;
 #pragma unroll
-    for (int x = 0; x < 8; ++x) {
-      cx.qf[x] = *reinterpret_cast<const bf16x8*>(Q + off + 16 * x);
-      cx.gf[x] = *reinterpret_cast<const bf16x8*>(dO + off + 16 * x);
+    for (int x = 0; x < KS; ++x) {
+      if (16 * x < H) {
+        cx.qf[x] = *reinterpret_cast<const bf16x8*>(Q + off + 16 * x);
+        cx.gf[x] = *reinterpret_cast<const bf16x8*>(dO + off + 16 * x);
+      } else {                                                 // columns past the head size are zero
+        cx.qf[x] = bf16x8{};
+        cx.gf[x] = bf16x8{};
+      }
     }
     const float v = lse[(int64_t)head * d.nq + q_ld];
     cx.lse2 = (!q_ok || v == -INFINITY) ? INFINITY : v * kLog2e;    // +inf: exp2(s - lse2) = 0
@@ -555,7 +588,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
     cx.my_vis = vis_count(q_ld, s);
   };
 #pragma unroll
-  for (int t = 0; t < 4; ++t) cx.dq[t] = zero16();
+  for (int t = 0; t < CT; ++t) cx.dq[t] = zero16();
 
   cx.ka.init(lane, lds_base);
   cx.vnat = lds_base + DQ_VT + l32 * VT_LD + 16 * cx.half;
@@ -567,6 +600,10 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   const int st_row = tid >> 4, st_ch = tid & 15;
   u32x4 kreg[ST_N], vreg[ST_N];
   // half hf of block j of the sub-block of seg_rows keys that starts at local key seg_start
+  // (a chunk past the row's end - head sizes below 128 - re-reads the row's last chunk and is
+  // stored as zeros or, past the padded head size, not at all)
+  const int ld_ch = min(st_ch, H / 8 - 1);
+  const bool ch_data = st_ch * 8 < H, ch_tile = st_ch * 8 < HD;
   auto load_half = [&](int seg_start, int seg_rows, int j, int hf) {
     const int k0 = seg_start + j * BKS;
     const gptr_t kb = uniform_gptr(K + (int64_t)k0 * H);
@@ -574,18 +611,21 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
     const int last = seg_rows - 1 - j * BKS;       // rows beyond the sub-block re-read its last row
 #pragma unroll
     for (int p = 0; p < ST_N; ++p) {
-      const unsigned off = (unsigned)(min(32 * hf + st_row + ST_ROWS * p, last) * (H * 2) + st_ch * 16);
+      const unsigned off = (unsigned)(min(32 * hf + st_row + ST_ROWS * p, last) * (H * 2) + ld_ch * 16);
       kreg[p] = gload_b128(kb, off);
       vreg[p] = gload_b128(vb, off);
     }
   };
   auto store_half = [&](int buf, int hf) {
     char* b = lds + buf * DQ_BUF;
+    if (HD == 128 || ch_tile) {
+      const u32x4 zero = {0, 0, 0, 0};
 #pragma unroll
-    for (int p = 0; p < ST_N; ++p) {
-      const int row = 32 * hf + st_row + ST_ROWS * p;
-      *reinterpret_cast<u32x4*>(b + dual_store_off(row, st_ch)) = kreg[p];
-      *reinterpret_cast<u32x4*>(b + DQ_VT + row * VT_LD + st_ch * 16) = vreg[p];
+      for (int p = 0; p < ST_N; ++p) {
+        const int row = 32 * hf + st_row + ST_ROWS * p;
+        *reinterpret_cast<u32x4*>(b + dual_store_off(row, st_ch)) = (HD == 128 || ch_data) ? kreg[p] : zero;
+        *reinterpret_cast<u32x4*>(b + DQ_VT + row * VT_LD + st_ch * 16) = (HD == 128 || ch_data) ? vreg[p] : zero;
+      }
     }
   };
 
@@ -630,19 +670,22 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
     sb = nsb; j = nj;
     buf ^= 1;
   }
-  if (q_ok) store_acc_t(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, d.scale, g.acc != 0);
+  if (q_ok) store_acc_t<CT>(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, d.scale, H, g.acc != 0);
 }
 
 }  // namespace
 
 bool bwd_mfma_supported(const a2d_tile_desc& d) {
-  return d.dtype == A2D_BF16 && d.hdim == mfma::H;
+  return d.dtype == A2D_BF16 && (d.hdim == 128 || d.hdim == 96 || d.hdim == 80);
 }
 
-hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
-                           const void* dO, const float* lse, const float* delta, float* dQ,
-                           float* dK, float* dV, hipStream_t s) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_kernel),
+namespace {
+template <int HR>
+hipError_t bwd_launch_hd(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
+                         const void* dO, const float* lse, const float* delta, float* dQ, float* dK,
+                         float* dV, hipStream_t s) {
+  constexpr int DQ_LDS = dq_lds(padded_head(HR));
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_kernel<HR>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, DK_LDS);
   if (e != hipSuccess) return e;
   // dQ kernel: eight wavefronts per workgroup unless that leaves compute units without a workgroup
@@ -651,24 +694,33 @@ hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void*
   if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) return e;
   const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
-  e = hipFuncSetAttribute(big ? reinterpret_cast<const void*>(bwd_dq_kernel<8>)
-                              : reinterpret_cast<const void*>(bwd_dq_kernel<4>),
+  e = hipFuncSetAttribute(big ? reinterpret_cast<const void*>(bwd_dq_kernel<8, HR>)
+                              : reinterpret_cast<const void*>(bwd_dq_kernel<4, HR>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
   if (e != hipSuccess) return e;
   dim3 grid_kv(xcd_grid(d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS));
   const int dq_rows = big ? 256 : 128;
   dim3 grid_q(xcd_grid(d.heads, (d.nq + dq_rows - 1) / dq_rows));
-  hipLaunchKernelGGL(bwd_dkdv_kernel, grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
+  hipLaunchKernelGGL(bwd_dkdv_kernel<HR>, grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (big)
-    hipLaunchKernelGGL(bwd_dq_kernel<8>, grid_q, dim3(512), DQ_LDS, s, d, g, (const bf16_t*)Q,
+    hipLaunchKernelGGL((bwd_dq_kernel<8, HR>), grid_q, dim3(512), DQ_LDS, s, d, g, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
   else
-    hipLaunchKernelGGL(bwd_dq_kernel<4>, grid_q, dim3(256), DQ_LDS, s, d, g, (const bf16_t*)Q,
+    hipLaunchKernelGGL((bwd_dq_kernel<4, HR>), grid_q, dim3(256), DQ_LDS, s, d, g, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
   return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
+                           const void* dO, const float* lse, const float* delta, float* dQ,
+                           float* dK, float* dV, hipStream_t s) {
+  if (d.hdim == 128) return bwd_launch_hd<128>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
+  if (d.hdim == 96) return bwd_launch_hd<96>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
+  return bwd_launch_hd<80>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
 }
 
 }  // namespace a2d

@@ -141,18 +141,18 @@ __device__ __forceinline__ void fwd_block(FwdState<HD>& st, const bf16x8 (&qf)[H
 // WAVES wavefronts (32 query rows each) per workgroup: 8 fill a compute unit with one workgroup;
 // 4 (two workgroups per compute unit) are used when there are too few 256-row blocks to give
 // every compute unit one.
-// HD: padded head size of the LDS tiles and fragments (96 or 128); the true head size d.hdim
-// (80, 96 or 128) is the row length in memory.
-template <int WAVES, int HD>
+// HR: head size = row length in memory (80, 96 or 128); the LDS tiles and fragments are laid out
+// for the padded head size HD = padded_head(HR) (96 or 128).
+template <int WAVES, int HR>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
     a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, float* __restrict__ O_part, float* __restrict__ m_out,
     float* __restrict__ l_out) {
   constexpr int BM = 32 * WAVES;          // query rows per workgroup
   constexpr int kThreads = 64 * WAVES;
+  constexpr int HD = padded_head(HR), H = HR;
   constexpr int KS = HD / 16, CT = HD / 32, KLD = kld(HD), K_BYTES = BN * KLD, BUF_BYTES = buf_bytes(HD);
   constexpr int kLdsBytes = lds_bytes(HD);
-  const int H = d.hdim;                   // row length in memory
   extern __shared__ __attribute__((aligned(16))) char lds[];
   // [buf]{ K tile (BN x KLD), V tile (BN x VLD) }
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
@@ -382,15 +382,15 @@ bool fwd_mfma_supported(const a2d_tile_desc& d) {
 }
 
 namespace {
-template <int WAVES, int HD>
+template <int WAVES, int HR>
 hipError_t fwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                       float* O_part, float* m, float* l, hipStream_t s) {
-  constexpr int bytes = lds_bytes(HD);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_mfma_kernel<WAVES, HD>),
+  constexpr int bytes = lds_bytes(padded_head(HR));
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_mfma_kernel<WAVES, HR>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   if (e != hipSuccess) return e;
   dim3 grid(xcd_grid(d.heads, (d.nq + 32 * WAVES - 1) / (32 * WAVES))), block(64 * WAVES);
-  hipLaunchKernelGGL((fwd_mfma_kernel<WAVES, HD>), grid, block, bytes, s, d, g, (const bf16_t*)Q,
+  hipLaunchKernelGGL((fwd_mfma_kernel<WAVES, HR>), grid, block, bytes, s, d, g, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, O_part, m, l);
   return hipGetLastError();
 }
@@ -404,9 +404,11 @@ hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const SegList& g, const void*
   if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) return e;
   const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
-  if (padded_head(d.hdim) == 128)
+  if (d.hdim == 128)
     return big ? fwd_launch<8, 128>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 128>(d, g, Q, K, V, O_part, m, l, s);
-  return big ? fwd_launch<8, 96>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 96>(d, g, Q, K, V, O_part, m, l, s);
+  if (d.hdim == 96)
+    return big ? fwd_launch<8, 96>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 96>(d, g, Q, K, V, O_part, m, l, s);
+  return big ? fwd_launch<8, 80>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 80>(d, g, Q, K, V, O_part, m, l, s);
 }
 
 }  // namespace a2d
