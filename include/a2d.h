@@ -73,7 +73,7 @@ typedef struct {
   int32_t heads;   /* B * M, >= 1                                                     */
   int32_t nq;      /* query rows of the tile, >= 1                                    */
   int32_t nkv;     /* key/value rows of the tile, >= 1                                */
-  int32_t hdim;    /* H: 64, 80, 96 or 128 (bf16 with H = 80, 96, 128: MFMA kernels)  */
+  int32_t hdim;    /* H: 64, 80, 96 or 128 (bf16: MFMA kernels; fp32: vector-ALU ones) */
   int64_t q_off;   /* global index of query row 0 (used only when causal != 0)        */
   int64_t kv_off;  /* global index of key row 0   (used only when causal != 0)        */
   int32_t causal;  /* 0: no mask; 1: hide key r from query i iff q_off+i < kv_off+r   */

@@ -1,4 +1,4 @@
-// bf16 MFMA backward tile kernels for H = 128, 96 and 80: the per-tile gradient call of Alg. 3
+// bf16 MFMA backward tile kernels for H = 128, 96, 80 and 64: the per-tile gradient call of Alg. 3
 // line 3 with P = exp(S - lse) rebuilt from the FINAL log-sum-exp of the query block,
 //   dV = P^T dO,  dP = dO V^T,  dS = P o (dP - delta),  dQ = scale dS K,  dK = scale dS^T Q.
 //
@@ -676,7 +676,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
 }  // namespace
 
 bool bwd_mfma_supported(const a2d_tile_desc& d) {
-  return d.dtype == A2D_BF16 && (d.hdim == 128 || d.hdim == 96 || d.hdim == 80);
+  return d.dtype == A2D_BF16 && (d.hdim == 128 || d.hdim == 96 || d.hdim == 80 || d.hdim == 64);
 }
 
 namespace {
@@ -720,7 +720,8 @@ hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void*
                            float* dK, float* dV, hipStream_t s) {
   if (d.hdim == 128) return bwd_launch_hd<128>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
   if (d.hdim == 96) return bwd_launch_hd<96>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
-  return bwd_launch_hd<80>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
+  if (d.hdim == 80) return bwd_launch_hd<80>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
+  return bwd_launch_hd<64>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
 }
 
 }  // namespace a2d

@@ -1,4 +1,4 @@
-// bf16 MFMA forward tile kernel for H = 128, 96 and 80 (Sec. 3.1, Eq. (3), evaluated block by
+// bf16 MFMA forward tile kernel for H = 128, 96, 80 and 64 (Sec. 3.1, Eq. (3), evaluated block by
 // block with the recurrence of Sec. 2.2).
 //
 // Work split: one workgroup = 8 wavefronts = 256 query rows of one head; each
@@ -378,7 +378,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
 }  // namespace
 
 bool fwd_mfma_supported(const a2d_tile_desc& d) {
-  return d.dtype == A2D_BF16 && (d.hdim == 128 || d.hdim == 96 || d.hdim == 80);
+  return d.dtype == A2D_BF16 && (d.hdim == 128 || d.hdim == 96 || d.hdim == 80 || d.hdim == 64);
 }
 
 namespace {
@@ -408,7 +408,9 @@ hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const SegList& g, const void*
     return big ? fwd_launch<8, 128>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 128>(d, g, Q, K, V, O_part, m, l, s);
   if (d.hdim == 96)
     return big ? fwd_launch<8, 96>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 96>(d, g, Q, K, V, O_part, m, l, s);
-  return big ? fwd_launch<8, 80>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 80>(d, g, Q, K, V, O_part, m, l, s);
+  if (d.hdim == 80)
+    return big ? fwd_launch<8, 80>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 80>(d, g, Q, K, V, O_part, m, l, s);
+  return big ? fwd_launch<8, 64>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 64>(d, g, Q, K, V, O_part, m, l, s);
 }
 
 }  // namespace a2d

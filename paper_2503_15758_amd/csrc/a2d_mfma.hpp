@@ -18,11 +18,10 @@
 namespace a2d {
 namespace mfma {
 
-// Head sizes of the MFMA kernels: the tiles are laid out for HD = 96 or 128 columns (multiples of
-// the 32-column accumulator tile); a head size of 80 runs as HD = 96 with its last 16 columns
+// Head sizes of the MFMA kernels: the tiles are laid out for HD = 64, 96 or 128 columns (multiples
+// of the 32-column accumulator tile); a head size of 80 runs as HD = 96 with its last 16 columns
 // zero in LDS and in the register fragments and left out of every store.
-constexpr int H = 128;
-__host__ __device__ constexpr int padded_head(int h) { return h > 96 ? 128 : 96; }
+__host__ __device__ constexpr int padded_head(int h) { return h > 96 ? 128 : (h > 64 ? 96 : 64); }
 
 // compile-time loop: f(std::integral_constant<int, B>{}), ..., f(std::integral_constant<int, E - 1>{})
 template <int B, int E, class F>
