@@ -23,12 +23,11 @@ a2d_status fail(a2d_status st, const char* fmt, ...) {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // A2D_FORCE_GENERIC=1 routes every tile call to the generic kernels (debugging aid).
+// A2D_FORCE_GENERIC=1 in the environment routes every tile call to the vector-ALU kernels (read
+// at every call, so a test can switch it)
 bool force_generic() {
-  static const bool v = [] {
-    const char* e = getenv("A2D_FORCE_GENERIC");
-    return e && e[0] == '1';
-  }();
-  return v;
+  const char* e = getenv("A2D_FORCE_GENERIC");
+  return e && e[0] == '1';
 }
 
 a2d_status check_desc(const a2d_tile_desc* d, const char* who) {

@@ -538,3 +538,27 @@ def test_normalised_partial_format(a2d, dt, H):
     Or, lr = oracle.fix_norm([np64(x) for x in Oin], [np64(x) for x in lin])
     assert_close(O2, Or, torch.float32, "fix_norm alone O")
     assert_close(l2, lr, torch.float32, "fix_norm alone lse", rel=False)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("H", [64, 96, 128])
+def test_generic_kernels_on_bf16_inputs(a2d, H, monkeypatch):
+    """The vector-ALU kernels take bf16 inputs too (A2D_FORCE_GENERIC=1); same bar as the MFMA path."""
+    monkeypatch.setenv("A2D_FORCE_GENERIC", "1")
+    heads, nq, nkv = 2, 150, 210
+    scale = 1.0 / math.sqrt(H)
+    Q = synth.normal((heads, nq, H), 71, 0, 1.0, "bf16")
+    K = synth.normal((heads, nkv, H), 71, 1, 1.0, "bf16")
+    V = synth.normal((heads, nkv, H), 71, 2, 1.0, "bf16")
+    dO = synth.normal((heads, nq, H), 71, 3, 1.0, "bf16")
+    Np, m, l = check_partial(a2d, Q, K, V, 80, 0, True, scale, "generic bf16 H=%d" % H)
+    Nr, mr, lr = oracle.partial_fwd(np64(Q), np64(K), np64(V), 80, 0, True, scale)
+    Or, lser = oracle.fix([Nr], [mr], [lr])
+    O_in = torch.from_numpy(Or).to(torch.bfloat16)
+    lse_in = torch.from_numpy(lser).to(torch.float32)
+    dQ, dK, dV = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), 80, 0, True, scale)
+    torch.cuda.synchronize()
+    rq, rk, rv = oracle.partial_bwd(np64(Q), np64(K), np64(V), np64(O_in), np64(dO), np64(lse_in), 80, 0, True, scale)
+    assert_close(dQ, rq, torch.bfloat16, "generic bf16 dQ")
+    assert_close(dK, rk, torch.bfloat16, "generic bf16 dK")
+    assert_close(dV, rv, torch.bfloat16, "generic bf16 dV")
