@@ -35,9 +35,9 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # their kernels (partial_bwd = delta + dK/dV + dQ kernels).  Only the default workload was counted.
 MIB = float(1 << 20)
 TRAFFIC_BYTES = {"c3": {
-    "partial_fwd_diag": (291.0 + 195.0) * MIB, "partial_fwd_full": (291.0 + 195.0) * MIB,
-    "partial_bwd_diag": (192.0 + 387.2 + 412.0 + 1.5 + 384.2 + 193.6) * MIB,
-    "partial_bwd_full": (192.0 + 387.2 + 412.0 + 1.5 + 384.2 + 193.6) * MIB,
+    "partial_fwd_diag": (289.4 + 211.4) * MIB, "partial_fwd_full": (289.4 + 211.4) * MIB,
+    "partial_bwd_diag": (192.0 + 387.5 + 400.8 + 1.5 + 384.0 + 193.0) * MIB,
+    "partial_bwd_full": (192.0 + 387.5 + 400.8 + 1.5 + 384.0 + 193.0) * MIB,
     "fix": (1632.1 + 97.5) * MIB, "fix_bwd_dq": (1536.0 + 96.0) * MIB,
     "fix_bwd_dk": (1536.0 + 96.0) * MIB, "fix_bwd_dv": (1536.0 + 96.0) * MIB}}
 

@@ -65,7 +65,7 @@ __device__ __forceinline__ bool seg_visible(const SegList& g, int i, int c) {
 // ---- launchers (each returns the launch's hipError_t; none synchronises) ----
 
 // Generic tile kernels: fp32 arithmetic on the vector ALUs for fp32 or bf16
-// inputs, any nq / nkv, H in {64, 128}.
+// inputs, any nq / nkv, H in {64, 80, 96, 128}.
 hipError_t launch_fwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                               float* O_part, float* m, float* l, hipStream_t s);
 hipError_t launch_bwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
@@ -76,7 +76,7 @@ hipError_t launch_bwd_generic(const a2d_tile_desc& d, const SegList& g, const vo
 hipError_t launch_delta(int dtype, int64_t rows, int hdim, const void* O, const void* dO,
                         float* delta, hipStream_t s);
 
-// bf16 MFMA tile kernels (H = 128).  `supported` tells whether the shape is covered.
+// bf16 MFMA tile kernels (H in {64, 80, 96, 128}).  `supported` tells whether the shape is covered.
 bool fwd_mfma_supported(const a2d_tile_desc& d);
 hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                            float* O_part, float* m, float* l, hipStream_t s);

@@ -284,6 +284,50 @@ def test_c3_causal_tiles_full_heads(a2d):
             assert_close(got[:1], ref, torch.bfloat16, "c3 bwd tile (7,%d) %s" % (c, name))
 
 
+def test_c3_gathered_row_full_heads(a2d):
+    """The benchmark's gathered launch at full size: query block r = 7 of the GPT-3-like workload
+    against the whole key row (8 sub-blocks, 32768 keys, 96 heads) in ONE call, in the (N, m, l)
+    and in the normalised format; oracle on sampled rows of heads 0 and 95 (full causal attention of
+    those rows, since the gathered row holds every key they may see).  Backward of the two-sub-block
+    tile {block 0, block 7} (one unmasked, one diagonal), head 0 against the oracle."""
+    w = synth.WORKLOADS["c3"]
+    T, scale, G, r = w.tile, 1.0 / math.sqrt(w.hdim), w.grid, w.grid - 1
+    Qr, dOr = synth.q_block(w, r), synth.do_block(w, r)
+    Kb = [synth.k_block(w, c) for c in range(G)]
+    Vb = [synth.v_block(w, c) for c in range(G)]
+    Kall, Vall = torch.cat(Kb, dim=1), torch.cat(Vb, dim=1)
+    Qd, Kd, Vd = dev(Qr), dev(Kall), dev(Vall)
+    segs = [(c * T, T) for c in range(G)]
+    Np, m, l = a2d.partial_fwd(Qd, Kd, Vd, r * T, 0, True, scale, segments=segs)
+    On, lsen = a2d.partial_fwd_norm(Qd, Kd, Vd, r * T, 0, True, scale, segments=segs)
+    O, lse = a2d.fix([Np], [m], [l], torch.bfloat16)
+    torch.cuda.synchronize()
+    rows = _sample_rows(T)[::2]
+    kpos = oracle.segment_positions(segs)
+    for h in (0, w.heads - 1):
+        Kh, Vh = np64(Kall[h:h + 1]), np64(Vall[h:h + 1])
+        Nr = np.empty((1, len(rows), w.hdim)); mr = np.empty((1, len(rows))); lr = np.empty((1, len(rows)))
+        for i, row in enumerate(rows):
+            a, b, c_ = oracle.partial_fwd_pos(np64(Qr[h:h + 1, row:row + 1]), Kh, Vh, r * T + row, kpos, True, scale)
+            Nr[0, i], mr[0, i], lr[0, i] = a[0, 0], b[0, 0], c_[0, 0]
+        Or, lser = oracle.fix([Nr], [mr], [lr])
+        assert_close(np64(m[h:h + 1, rows]), mr, torch.bfloat16, "c3 row m head %d" % h, rel=False)
+        assert_close(np64(O[h:h + 1, rows]), Or, torch.bfloat16, "c3 row O head %d" % h)
+        assert_close(np64(lse[h:h + 1, rows]), lser, torch.bfloat16, "c3 row lse head %d" % h, rel=False)
+        assert_close(np64(On[h:h + 1, rows]), Or, torch.bfloat16, "c3 row O' head %d" % h)
+        assert_close(np64(lsen[h:h + 1, rows]), lser, torch.bfloat16, "c3 row lse' head %d" % h, rel=False)
+    del Kd, Vd, Np, On
+    # backward: sub-blocks 0 and 7, with the final O / lse of the whole row
+    seg2 = [(0, T), (r * T, T)]
+    K2, V2 = torch.cat([Kb[0], Kb[r]], dim=1), torch.cat([Vb[0], Vb[r]], dim=1)
+    dQ, dK, dV = a2d.partial_bwd(Qd, dev(K2), dev(V2), O, dev(dOr), lse, r * T, 0, True, scale, segments=seg2)
+    torch.cuda.synchronize()
+    rq, rk, rv = oracle.partial_bwd_pos(np64(Qr[:1]), np64(K2[:1]), np64(V2[:1]), np64(O[:1]), np64(dOr[:1]),
+                                        np64(lse[:1]), r * T, oracle.segment_positions(seg2), True, scale)
+    for got, ref, name in ((dQ, rq, "dQ"), (dK, rk, "dK"), (dV, rv, "dV")):
+        assert_close(got[:1], ref, torch.bfloat16, "c3 row bwd {0,7} %s" % name)
+
+
 @pytest.mark.parametrize("name", ["c4", "c5"])
 def test_long_context_tiles_sampled(a2d, name):
     """16384 x 16384 tiles at the workload's head count; AttnFix over all sqrt(P) partials of query
