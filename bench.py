@@ -58,7 +58,9 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma-probe", action="store_true")
-    ap.add_argument("--no-gathered", action="store_true")
+    ap.add_argument("--no-gathered", action="store_true",
+                    help="skip the extra measurements appended after the timed steps (gathered key row, "
+                         "normalised partials, grouped-query heads)")
     ap.add_argument("--grid-emulation", action="store_true",
                     help="also time Alg. 1 + Alg. 3 over all P tiles of the c2 sequence (8192 tokens, 4 x 4 grid)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -215,6 +217,8 @@ def main():
         result["gathered"] = gathered_tile(a2d, synth, w, scale, kernels)
     if not args.no_gathered and w.name == "c3":
         result["normalised_partials"] = normalised_format(a2d, synth, w, scale, kernels)
+    if not args.no_gathered and w.name == "c3":
+        result["grouped_query"] = grouped_query(a2d, synth, w, scale, kernels)
     if args.grid_emulation:
         result["grid_emulation"] = grid_emulation(synth)
     if not args.no_mfma_probe:
@@ -317,6 +321,48 @@ def normalised_format(a2d, synth, w, scale, kernels):
     return {"fix_norm_ms": round(t_fix, 4), "fix_norm_gbs": round(nbytes / t_fix / 1e6, 1),
             "fix_norm_frac_hbm": round(nbytes / t_fix / 1e6 / PEAK_HBM_GBS, 4), "fix_norm_bytes": nbytes,
             "fix_fp32_ms": kernels["fix"]["avg_ms"], "partial_fwd_norm_unmasked_tile_ms": round(t_fwd, 4)}
+
+
+def grouped_query(a2d, synth, w, scale, kernels):
+    """The unmasked tile with grouped-query heads (a2d_partial_fwd_gqa / a2d_partial_bwd_gqa): the
+    workload's query heads against 8 and against heads / 8 key/value heads, timed beside the
+    multi-head tile."""
+    import torch
+    T, H, r = w.tile, w.hdim, w.grid - 1
+    dev = lambda t: t.to("cuda")
+    Q, dO = dev(synth.q_block(w, r)), dev(synth.do_block(w, r))
+    K0, V0 = dev(synth.k_block(w, 0)), dev(synth.v_block(w, 0))
+    ws = torch.empty(w.heads * T * 4 + 256, dtype=torch.uint8, device="cuda")
+
+    def timeit(fn, n=10):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    f_fl, b_fl = tile_flops(w, T, T, False)
+    res = {"what": "%d query heads, unmasked tile, key/value heads as listed" % w.heads,
+           "multi_head_fwd_ms": kernels["partial_fwd_full"]["avg_ms"],
+           "multi_head_bwd_ms": kernels["partial_bwd_full"]["avg_ms"], "cases": []}
+    for kvh in sorted({8, w.heads // 8}):
+        if kvh < 1 or w.heads % kvh:
+            continue
+        K, V = K0[:kvh].contiguous(), V0[:kvh].contiguous()
+        out = a2d.partial_fwd(Q, K, V, r * T, 0, True, scale)
+        O, lse = a2d.fix([out[0]], [out[1]], [out[2]], torch.bfloat16)
+        grads = a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, workspace=ws)
+        fwd = lambda: a2d.partial_fwd(Q, K, V, r * T, 0, True, scale, out=out)
+        t_f = min(timeit(fwd), timeit(fwd, 20))     # the first batch still runs at the clock the set-up left
+        t_b = timeit(lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, out=grads, workspace=ws))
+        res["cases"].append({"kv_heads": kvh, "fwd_ms": round(t_f, 4), "fwd_tflops": round(f_fl / t_f / 1e9, 1),
+                             "bwd_ms": round(t_b, 4), "bwd_tflops": round(b_fl / t_b / 1e9, 1)})
+    return res
 
 
 def grid_emulation(synth):

@@ -71,8 +71,8 @@ typedef enum {
 /* One tile problem: a block of nq queries against a block of nkv keys/values. */
 typedef struct {
   int32_t heads;   /* B * M, >= 1                                                     */
-  int32_t nq;      /* query rows of the tile, >= 1                                    */
-  int32_t nkv;     /* key/value rows of the tile, >= 1                                */
+  int32_t nq;      /* query rows of the tile, 1 .. 2^22                               */
+  int32_t nkv;     /* key/value rows of the tile, 1 .. 2^22                           */
   int32_t hdim;    /* H: 64, 80, 96 or 128 (bf16: MFMA kernels; fp32: vector-ALU ones) */
   int64_t q_off;   /* global index of query row 0 (used only when causal != 0)        */
   int64_t kv_off;  /* global index of key row 0   (used only when causal != 0)        */
@@ -214,6 +214,37 @@ a2d_status a2d_partial_fwd_norm(const a2d_tile_desc* desc, int nseg, const a2d_k
 a2d_status a2d_fix_norm(int k, int64_t rows, int32_t hdim, int32_t in_dtype, int32_t out_dtype,
                         const void* const* O_norm_parts, const float* const* lse_parts, void* O,
                         float* lse, void* stream);
+
+/*
+ * Grouped-query attention (the method works head by head, Sec. 2.1 / Sec. 5; with grouped
+ * queries several query heads read the key/value rows of ONE key/value head).  desc->heads
+ * counts QUERY heads; K and V hold kv_heads = desc->heads / group heads, query head h reads
+ * key/value head h / group (the group's query heads are consecutive).  kv_heads must divide
+ * desc->heads; kv_heads == desc->heads is ordinary multi-head attention, kv_heads == 1
+ * multi-query attention.
+ *   a2d_partial_fwd_gqa: K, V [kv_heads][nkv][H]; everything else as in the call `flags` picks:
+ *     0                      a2d_partial_fwd / _seg   (out0 = O_part fp32, out1 = m, out2 = l)
+ *     A2D_TILE_ACCUMULATE    a2d_partial_fwd_acc      (the same three buffers, in/out)
+ *     A2D_TILE_NORMALISED    a2d_partial_fwd_norm     (out0 = O_norm in desc->dtype, out1 = lse_part,
+ *                                                      out2 ignored, may be NULL)
+ *   a2d_partial_bwd_gqa: K, V as above; dK_part, dV_part [kv_heads][nkv][H] fp32: the gradient of
+ *     a key/value head is the SUM over the query heads of its group (taken inside the kernel, in
+ *     head order; one writer per element, no atomics).  flags: 0 or A2D_TILE_ACCUMULATE (dQ +=).
+ *     workspace as for a2d_partial_bwd.
+ * nseg = 0 (segs ignored): the plain tile of desc->kv_off; nseg >= 1: a gathered tile.
+ * group * nq may not exceed 2^22 rows.
+ */
+#define A2D_TILE_ACCUMULATE 1
+#define A2D_TILE_NORMALISED 2
+a2d_status a2d_partial_fwd_gqa(const a2d_tile_desc* desc, int32_t kv_heads, int nseg,
+                               const a2d_kv_segment* segs, int flags, const void* Q, const void* K,
+                               const void* V, void* out0, float* out1, float* out2,
+                               void* workspace, size_t workspace_bytes, void* stream);
+a2d_status a2d_partial_bwd_gqa(const a2d_tile_desc* desc, int32_t kv_heads, int nseg,
+                               const a2d_kv_segment* segs, int flags, const void* Q, const void* K,
+                               const void* V, const void* O, const void* dO, const float* lse,
+                               float* dQ_part, float* dK_part, float* dV_part, void* workspace,
+                               size_t workspace_bytes, void* stream);
 
 /*
  * Sum of k gradient partials (the reduce-scatters of Alg. 3 lines 4-5 use plain

@@ -19,7 +19,7 @@ MAX_PARTS = 32
 
 EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
            "a2d_partial_fwd_seg", "a2d_partial_bwd_seg", "a2d_partial_fwd_acc", "a2d_partial_bwd_acc",
-           "a2d_partial_fwd_norm", "a2d_fix_norm",
+           "a2d_partial_fwd_norm", "a2d_fix_norm", "a2d_partial_fwd_gqa", "a2d_partial_bwd_gqa",
            "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling",
            "a2d_status_str", "a2d_last_error", "a2d_version")
 
@@ -35,6 +35,7 @@ class KvSegment(ctypes.Structure):
 
 
 MAX_SEGMENTS = 32
+TILE_ACCUMULATE, TILE_NORMALISED = 1, 2
 
 
 class A2DError(RuntimeError):
@@ -150,8 +151,7 @@ def partial_fwd(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None, 
     """a2d_partial_fwd. Returns (O_part fp32 [heads][nq][H], m, l fp32 [heads][nq])."""
     for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
         _dev3(t, n)
-    if K.shape != V.shape or K.shape[0] != Q.shape[0] or K.shape[2] != Q.shape[2] or \
-            K.dtype != Q.dtype or V.dtype != Q.dtype:
+    if K.shape != V.shape or K.shape[2] != Q.shape[2] or K.dtype != Q.dtype or V.dtype != Q.dtype:
         raise A2DError(-1, "Q, K, V shapes / dtypes do not match")
     d = tile_desc(Q, K, q_off, kv_off, causal, scale)
     if out is None:
@@ -160,6 +160,14 @@ def partial_fwd(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None, 
         l = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
     else:
         O_part, m, l = out
+    if accumulate and out is None:
+        raise A2DError(-1, "accumulate needs out=(O_part, m, l)")
+    if K.shape[0] != Q.shape[0]:   # grouped queries: K, V hold fewer heads than Q
+        n = len(segments) if segments is not None else 0
+        _check(lib().a2d_partial_fwd_gqa(ctypes.byref(d), int(K.shape[0]), n, _segments(segments) if n else None,
+                                         TILE_ACCUMULATE if accumulate else 0, _ptr(Q), _ptr(K), _ptr(V),
+                                         _ptr(O_part), _ptr(m), _ptr(l), None, 0, _stream()))
+        return O_part, m, l
     if accumulate:                 # out holds a partial triple of the same query block: merged in place
         if out is None:
             raise A2DError(-1, "accumulate needs out=(O_part, m, l)")
@@ -182,8 +190,7 @@ def partial_fwd_norm(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=N
     """a2d_partial_fwd_norm: the normalised partial (O' in Q's dtype, lse' fp32) of a plain or gathered tile."""
     for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
         _dev3(t, n)
-    if K.shape != V.shape or K.shape[0] != Q.shape[0] or K.shape[2] != Q.shape[2] or \
-            K.dtype != Q.dtype or V.dtype != Q.dtype:
+    if K.shape != V.shape or K.shape[2] != Q.shape[2] or K.dtype != Q.dtype or V.dtype != Q.dtype:
         raise A2DError(-1, "Q, K, V shapes / dtypes do not match")
     d = tile_desc(Q, K, q_off, kv_off, causal, scale)
     if out is None:
@@ -192,6 +199,11 @@ def partial_fwd_norm(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=N
     else:
         O_norm, lse = out
     n = len(segments) if segments is not None else 0
+    if K.shape[0] != Q.shape[0]:   # grouped queries
+        _check(lib().a2d_partial_fwd_gqa(ctypes.byref(d), int(K.shape[0]), n, _segments(segments) if n else None,
+                                         TILE_NORMALISED, _ptr(Q), _ptr(K), _ptr(V), _ptr(O_norm), _ptr(lse),
+                                         None, None, 0, _stream()))
+        return O_norm, lse
     _check(lib().a2d_partial_fwd_norm(ctypes.byref(d), n, _segments(segments) if n else None, _ptr(Q),
                                       _ptr(K), _ptr(V), _ptr(O_norm), _ptr(lse), None, 0, _stream()))
     return O_norm, lse
@@ -253,9 +265,17 @@ def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None
         dV = torch.empty(K.shape, dtype=torch.float32, device=Q.device)
     else:
         dQ, dK, dV = out
+    if accumulate and out is None:
+        raise A2DError(-1, "accumulate needs out=(dQ_part, dK_part, dV_part)")
+    if K.shape[0] != Q.shape[0]:   # grouped queries: dK_part, dV_part have K's heads
+        n = len(segments) if segments is not None else 0
+        _check(lib().a2d_partial_bwd_gqa(ctypes.byref(d), int(K.shape[0]), n, _segments(segments) if n else None,
+                                         TILE_ACCUMULATE if accumulate else 0, _ptr(Q), _ptr(K), _ptr(V),
+                                         _ptr(O), _ptr(dO), _ptr(lse), _ptr(dQ), _ptr(dK), _ptr(dV),
+                                         _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                         _stream()))
+        return dQ, dK, dV
     if accumulate:                 # out[0] (dQ_part) is added to
-        if out is None:
-            raise A2DError(-1, "accumulate needs out=(dQ_part, dK_part, dV_part)")
         n = len(segments) if segments is not None else 0
         _check(lib().a2d_partial_bwd_acc(ctypes.byref(d), n, _segments(segments) if n else None, _ptr(Q),
                                          _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse), _ptr(dQ),

@@ -44,6 +44,8 @@ a2d_status check_desc(const a2d_tile_desc* d, const char* who) {
   if (d->causal != 0 && d->causal != 1)
     return fail(A2D_ERR_INVALID_ARG, "%s: causal must be 0 or 1", who);
   if (d->heads > 65535) return fail(A2D_ERR_INVALID_ARG, "%s: heads=%d exceeds 65535", who, d->heads);
+  if (d->nq > (1 << 22) || d->nkv > (1 << 22))   // the kernels address a head's rows with 32-bit byte offsets
+    return fail(A2D_ERR_INVALID_ARG, "%s: nq=%d / nkv=%d exceed 2^22 rows", who, d->nq, d->nkv);
   const int64_t lim = (int64_t)1 << 40;
   if (d->q_off < -lim || d->q_off > lim || d->kv_off < -lim || d->kv_off > lim)
     return fail(A2D_ERR_INVALID_ARG, "%s: offsets out of range", who);
@@ -72,6 +74,8 @@ a2d::SegList one_segment(const a2d_tile_desc* d) {
   a2d::SegList g;
   memset(&g, 0, sizeof(g));
   g.n = 1;
+  g.group = 1;
+  g.split = 1;
   g.start[0] = 0;
   g.rows[0] = d->nkv;
   g.rel[0] = d->q_off - d->kv_off;
@@ -85,6 +89,8 @@ a2d_status make_segments(const a2d_tile_desc* d, int nseg, const a2d_kv_segment*
   if (!segs) return fail(A2D_ERR_INVALID_ARG, "%s: segs is NULL", who);
   memset(g, 0, sizeof(*g));
   g->n = nseg;
+  g->group = 1;
+  g->split = 1;
   int64_t total = 0;
   for (int s = 0; s < nseg; ++s) {
     if (segs[s].rows < 1 || segs[s].pad != 0)
@@ -207,6 +213,53 @@ a2d_status a2d_fix_norm(int k, int64_t rows, int32_t hdim, int32_t in_dtype, int
   }
   return hip_result(a2d::launch_fix_norm(k, rows, hdim, in_dtype, out_dtype, p, O, lse,
                                          static_cast<hipStream_t>(stream)), who);
+}
+
+// query heads per key/value head, or an error
+static a2d_status group_of(const a2d_tile_desc* desc, int kv_heads, const char* who, a2d::SegList* g) {
+  int* group = &g->group;
+  if (kv_heads < 1 || desc->heads % kv_heads != 0)
+    return fail(A2D_ERR_INVALID_ARG, "%s: kv_heads=%d must be >= 1 and divide heads=%d", who, kv_heads,
+                desc->heads);
+  *group = desc->heads / kv_heads;
+  if ((int64_t)*group * desc->nq > ((int64_t)1 << 22))
+    return fail(A2D_ERR_INVALID_ARG, "%s: group * nq = %lld exceeds 2^22 rows", who,
+                (long long)*group * desc->nq);
+  g->split = a2d::group_split(kv_heads, *group);
+  return A2D_OK;
+}
+
+a2d_status a2d_partial_fwd_gqa(const a2d_tile_desc* desc, int32_t kv_heads, int nseg,
+                               const a2d_kv_segment* segs, int flags, const void* Q, const void* K,
+                               const void* V, void* out0, float* out1, float* out2,
+                               void* /*workspace*/, size_t /*workspace_bytes*/, void* stream) {
+  const char* who = "a2d_partial_fwd_gqa";
+  A2D_TRY(check_desc(desc, who));
+  if (flags != 0 && flags != A2D_TILE_ACCUMULATE && flags != A2D_TILE_NORMALISED)
+    return fail(A2D_ERR_INVALID_ARG, "%s: flags=%d must be 0, A2D_TILE_ACCUMULATE or A2D_TILE_NORMALISED", who, flags);
+  a2d::SegList g = one_segment(desc);
+  if (nseg != 0) A2D_TRY(make_segments(desc, nseg, segs, who, &g));
+  A2D_TRY(group_of(desc, kv_heads, who, &g));
+  g.acc = flags == A2D_TILE_ACCUMULATE;
+  g.norm = flags == A2D_TILE_NORMALISED;
+  return partial_fwd_impl(desc, g, Q, K, V, static_cast<float*>(out0), out1, g.norm ? out1 : out2, stream, who);
+}
+
+a2d_status a2d_partial_bwd_gqa(const a2d_tile_desc* desc, int32_t kv_heads, int nseg,
+                               const a2d_kv_segment* segs, int flags, const void* Q, const void* K,
+                               const void* V, const void* O, const void* dO, const float* lse,
+                               float* dQ_part, float* dK_part, float* dV_part, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  const char* who = "a2d_partial_bwd_gqa";
+  A2D_TRY(check_desc(desc, who));
+  if (flags != 0 && flags != A2D_TILE_ACCUMULATE)
+    return fail(A2D_ERR_INVALID_ARG, "%s: flags=%d must be 0 or A2D_TILE_ACCUMULATE", who, flags);
+  a2d::SegList g = one_segment(desc);
+  if (nseg != 0) A2D_TRY(make_segments(desc, nseg, segs, who, &g));
+  A2D_TRY(group_of(desc, kv_heads, who, &g));
+  g.acc = flags == A2D_TILE_ACCUMULATE;
+  return partial_bwd_impl(desc, g, Q, K, V, O, dO, lse, dQ_part, dK_part, dV_part, workspace,
+                          workspace_bytes, stream, who);
 }
 
 a2d_status a2d_partial_fwd_acc(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,

@@ -209,7 +209,9 @@ __device__ __forceinline__ void dk_second(DkCtx<HD>& cx, bf16x8 (&t)[HD / 32], c
 
 // HR: head size = row length in memory (80, 96 or 128); the LDS tiles and fragments are laid out
 // for the padded head size HD = padded_head(HR) (96 or 128).
-template <int HR>
+// GROUPED: several query heads per key/value head (g.group > 1); the plain kernel is compiled
+// without the bookkeeping that walks them.
+template <int HR, bool GROUPED>
 __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
     a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
@@ -217,19 +219,21 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
   int head, blk;
-  if (!xcd_map(d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS, head, blk)) return;
+  // `head` is the KEY/VALUE head; its g.group query heads are consecutive rows of Q, dO, lse, delta
+  const int group = GROUPED ? g.group : 1;
+  if (!xcd_map(GROUPED ? d.heads / group : d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS, head, blk)) return;
   constexpr int HD = padded_head(HR), H = HR, KS = HD / 16, CT = HD / 32;
   const int k0 = blk * DK_KEYS;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int pair = wave & 3, role = wave >> 2;   // wavefronts w and w + 4 share 32 keys
   const int l32 = lane & 31;
-  Q += (int64_t)head * d.nq * H;
-  dO += (int64_t)head * d.nq * H;
+  Q += (int64_t)head * group * d.nq * H;
+  dO += (int64_t)head * group * d.nq * H;
   K += (int64_t)head * d.nkv * H;
   V += (int64_t)head * d.nkv * H;
-  lse += (int64_t)head * d.nq;
-  delta += (int64_t)head * d.nq;
+  lse += (int64_t)head * group * d.nq;
+  delta += (int64_t)head * group * d.nq;
 
   DkCtx<HD> cx;
   cx.half = lane >> 5;
@@ -272,7 +276,8 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   int wg_lo, wg_hi;
   first_row_range(k0, min(k0 + DK_KEYS, d.nkv), wg_lo, wg_hi);
   const int i_start = (wg_lo / BQ) * BQ;
-  const int nsteps = (d.nq - i_start + BQ - 1) / BQ;
+  const int nsteps = (d.nq - i_start + BQ - 1) / BQ;   // steps per query head
+  const int total = nsteps * group;                    // the group's query heads one after the other
   const int wk_first = k0 + pair * 32, wk_end = min(wk_first + 32, d.nkv);
   cx.my_first = d.nq;                                         // padding keys see nothing
   if (key < d.nkv) {
@@ -325,18 +330,28 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   // stored as zeros or, past the padded head size, not at all: every lane issues every load)
   const int ld_ch = min(st_ch, H / 8 - 1);
   const bool ch_data = st_ch * 8 < H, ch_tile = st_ch * 8 < HD;
+  // (load_step is called for steps 0, 1, 2, ... in order; with grouped heads ld_s / ld_row0 /
+  // ld_left follow the next step's position - its step inside the query head, the head's first
+  // row - without a division)
+  int ld_s = 0, ld_row0 = 0, ld_left = total - 1;
   auto load_step = [&](int step, auto set_tag) {
     constexpr int SET = decltype(set_tag)::value;
-    const int i0 = i_start + min(step, nsteps - 1) * BQ;
-    const unsigned off = (unsigned)(min(i0 + st_row, d.nq - 1) * (H * 2) + ld_ch * 16);
+    const int i0 = i_start + (GROUPED ? ld_s : min(step, nsteps - 1)) * BQ;
+    const unsigned off = (unsigned)((ld_row0 + min(i0 + st_row, d.nq - 1)) * (H * 2) + ld_ch * 16);
     qreg[SET] = gload_b128(q_base, off);
     greg[SET] = gload_b128(g_base, off);
     // raw statistic loads only: converting here would make the wave wait for everything just
     // issued.  Every thread loads one (only the first 64 values are used) so that each set is
     // the same number of loads in every wavefront.
-    const int i = min(i0 + (tid & (BQ - 1)), d.nq - 1);
+    const int i = ld_row0 + min(i0 + (tid & (BQ - 1)), d.nq - 1);
     stat[SET] = (tid & BQ) ? delta[i] : lse[i];
     stat_ok[SET] = (i0 + (tid & (BQ - 1))) < d.nq;
+    if constexpr (GROUPED) {   // next step; the last one repeats
+      const bool more = ld_left > 0, wrap = ld_s + 1 == nsteps;
+      ld_left -= more ? 1 : 0;
+      ld_row0 += (more && wrap) ? d.nq : 0;
+      ld_s = more ? (wrap ? 0 : ld_s + 1) : ld_s;
+    }
   };
   auto store_step = [&](int buf, auto set_tag) {
     constexpr int SET = decltype(set_tag)::value;
@@ -365,7 +380,10 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
 
   // A step is skipped (by both wavefronts of its pair) when none of its rows sees any of the
   // pair's keys; it is masked unless every row sees every key.
-  auto active = [&](int step) { return step >= 0 && step < nsteps && i_start + step * BQ + BQ - 1 >= w_any; };
+  // (step = position in the whole walk, s = its step inside its query head)
+  auto active = [&](int step, int s) { return step >= 0 && step < total && i_start + s * BQ + BQ - 1 >= w_any; };
+  int cs = 0;                                                   // s of the iteration's step j
+  auto next_s = [&](int s) { return (GROUPED && s + 1 == nsteps) ? 0 : s + 1; };
   auto advance = [&](int slot_delta) {   // to this wave's next step: tile buffer and mailbox slot
     const int adv = (cur == DK_NBUF - 1) ? -(DK_NBUF - 1) : 1;
     cur += adv;
@@ -389,8 +407,8 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
       constexpr int SET = decltype(set_tag)::value;
       store_step((j + 2) % DK_NBUF, set_tag);
       load_step(j + 4, set_tag);
-      if (active(j)) {
-        const int i0 = i_start + j * BQ;
+      if (active(j, cs)) {
+        const int i0 = i_start + cs * BQ;
         bf16x8 t[CT], bf[2];
         f32x16 s = dk_first(cx, n, zero16());
         dk_second_pre(cx, t);
@@ -399,6 +417,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
         dk_second(cx, t, bf);
       }
       advance(SET ? -DK_MBOX_SLOT : DK_MBOX_SLOT);
+      cs = next_s(cs);
       dk_first_pre(cx, n);
       dk_stat_pre(cx, st);
       __syncthreads();
@@ -406,17 +425,18 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
     // nsteps + 1 iterations (the gradient wave's last step), rounded up to an even number: an
     // iteration beyond that finds no step to compute, and straight-line control flow keeps the
     // wait counters exact
-    for (int j = 0; j <= nsteps; j += 2) {
+    for (int j = 0; j <= total; j += 2) {
       iteration(j, set0{});
       iteration(j + 1, set1{});
     }
   } else if (nsteps > 0) {
     f32x16 dp = zero16();   // dP - delta of the step whose dS, dK come next iteration
+    int ps = 0;             // s of step j - 1
     auto iteration = [&](int j, auto set_tag) {
       constexpr int SET = decltype(set_tag)::value;
       store_step((j + 2) % DK_NBUF, set_tag);
       load_step(j + 4, set_tag);
-      if (active(j - 1)) {
+      if (active(j - 1, ps)) {
         bf16x8 t[CT], bf[2];
         f32x4 pm[4];
         dk_mbox_pre(cx, pm);
@@ -425,7 +445,9 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
         dk_second(cx, t, bf);
       }
       advance(SET ? DK_MBOX_SLOT : -DK_MBOX_SLOT);
-      if (active(j)) {
+      ps = cs;
+      cs = next_s(cs);
+      if (active(j, ps)) {
         bf16x8 n[4];
         f32x4 st[4];
         dk_first_pre(cx, n);
@@ -437,7 +459,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
       }
       __syncthreads();
     };
-    for (int j = 0; j <= nsteps; j += 2) {
+    for (int j = 0; j <= total; j += 2) {
       iteration(j, set0{});
       iteration(j + 1, set1{});
     }
@@ -535,16 +557,21 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   constexpr int HD = padded_head(HR), H = HR;
   constexpr int KS = HD / 16, CT = HD / 32, VT_LD = vt_ld(HD), DQ_BUF = dq_buf(HD);
   const int nqb = (d.nq + DQ_ROWS - 1) / DQ_ROWS;
-  int head, blk;
-  if (!xcd_map(d.heads, nqb, head, blk)) return;
+  // the query blocks of the query heads that share a key/value head go to one XCD (to g.split
+  // XCDs, an equal share of the heads each, when that is what spreads the load evenly)
+  int unit, blk;
+  const int per_unit = g.group / g.split;
+  if (!xcd_map(d.heads / per_unit, per_unit * nqb, unit, blk)) return;
+  const int head = unit * per_unit + blk / nqb, kvh = head / g.group;
+  blk %= nqb;
   const int q0 = (nqb - 1 - blk) * DQ_ROWS;            // heavy blocks first under a causal mask
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31;
   Q += (int64_t)head * d.nq * H;
   dO += (int64_t)head * d.nq * H;
-  K += (int64_t)head * d.nkv * H;
-  V += (int64_t)head * d.nkv * H;
+  K += (int64_t)kvh * d.nkv * H;
+  V += (int64_t)kvh * d.nkv * H;
 
   DqCtx<HD> cx;
   cx.half = lane >> 5;
@@ -685,7 +712,9 @@ hipError_t bwd_launch_hd(const a2d_tile_desc& d, const SegList& g, const void* Q
                          const void* dO, const float* lse, const float* delta, float* dQ, float* dK,
                          float* dV, hipStream_t s) {
   constexpr int DQ_LDS = dq_lds(padded_head(HR));
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_kernel<HR>),
+  const bool grouped = g.group > 1;
+  hipError_t e = hipFuncSetAttribute(grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true>)
+                                             : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, DK_LDS);
   if (e != hipSuccess) return e;
   // dQ kernel: eight wavefronts per workgroup unless that leaves compute units without a workgroup
@@ -698,11 +727,16 @@ hipError_t bwd_launch_hd(const a2d_tile_desc& d, const SegList& g, const void* Q
                               : reinterpret_cast<const void*>(bwd_dq_kernel<4, HR>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
   if (e != hipSuccess) return e;
-  dim3 grid_kv(xcd_grid(d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS));
+  dim3 grid_kv(xcd_grid(d.heads / g.group, (d.nkv + DK_KEYS - 1) / DK_KEYS));
   const int dq_rows = big ? 256 : 128;
-  dim3 grid_q(xcd_grid(d.heads, (d.nq + dq_rows - 1) / dq_rows));
-  hipLaunchKernelGGL(bwd_dkdv_kernel<HR>, grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
-                     (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV);
+  const int per_unit = g.group / g.split;
+  dim3 grid_q(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + dq_rows - 1) / dq_rows)));
+  if (grouped)
+    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, true>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
+                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV);
+  else
+    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, false>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
+                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (big)

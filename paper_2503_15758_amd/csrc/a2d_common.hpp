@@ -41,14 +41,28 @@ template <> struct dtype_of<bf16_t> { static constexpr int value = A2D_BF16; };
 // buffers and the backward add to the dQ partial already in its output buffer.
 // `norm` != 0: the forward writes the NORMALISED partial O' = N / l in the input dtype (into the
 // buffer passed as O_part) and lse' = m + ln l (into the buffer passed as m) instead of (N, m, l).
+// `group` >= 1: query heads per key/value head (grouped-query attention: query head h reads
+// key/value head h / group; K, V, dK, dV have heads / group heads).  `split` divides `group`:
+// kernels that own query blocks place the query heads of a key/value head on XCDs in `split`
+// separate runs (1 = all of them on one XCD; chosen by group_split()).
 struct SegList {
   int n;
   int acc;
   int norm;
+  int group;
+  int split;
   int start[A2D_MAX_SEGMENTS];
   int rows[A2D_MAX_SEGMENTS];
   int64_t rel[A2D_MAX_SEGMENTS];
 };
+
+// Smallest divisor s of `group` that makes kv_heads * s a multiple of the 8 XCDs (an even load per
+// XCD); `group` itself (one run per query head) when there is none.
+inline int group_split(int kv_heads, int group) {
+  for (int s = 1; s <= group; ++s)
+    if (group % s == 0 && (kv_heads * s) % 8 == 0) return s;
+  return group;
+}
 
 // sub-block that holds local key c (c < nkv)
 __device__ __forceinline__ int seg_of_key(const SegList& g, int c) {

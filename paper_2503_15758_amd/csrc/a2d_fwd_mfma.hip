@@ -158,16 +158,21 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
   const int nqb = (d.nq + BM - 1) / BM;
-  int head, blk;
-  if (!xcd_map(d.heads, nqb, head, blk)) return;
+  // the query blocks of the query heads that share a key/value head go to one XCD (to g.split
+  // XCDs, an equal share of the heads each, when that is what spreads the load evenly)
+  int unit, blk;
+  const int per_unit = g.group / g.split;
+  if (!xcd_map(d.heads / per_unit, per_unit * nqb, unit, blk)) return;
+  const int head = unit * per_unit + blk / nqb, kvh = head / g.group;
+  blk %= nqb;
   // heavy (late) query blocks first: under a causal mask they walk more key blocks
   const int q0 = (nqb - 1 - blk) * BM;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int half = lane >> 5, l32 = lane & 31;
   Q += (int64_t)head * d.nq * H;
-  K += (int64_t)head * d.nkv * H;
-  V += (int64_t)head * d.nkv * H;
+  K += (int64_t)kvh * d.nkv * H;
+  V += (int64_t)kvh * d.nkv * H;
 
   // ---- Q^T fragments: lane holds query row (l32), h = 16*step + 8*half + 0..7.
   // Rows beyond nq re-read the last row (their results are never stored).
@@ -389,7 +394,8 @@ hipError_t fwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, c
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_mfma_kernel<WAVES, HR>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   if (e != hipSuccess) return e;
-  dim3 grid(xcd_grid(d.heads, (d.nq + 32 * WAVES - 1) / (32 * WAVES))), block(64 * WAVES);
+  const int per_unit = g.group / g.split;
+  dim3 grid(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + 32 * WAVES - 1) / (32 * WAVES)))), block(64 * WAVES);
   hipLaunchKernelGGL((fwd_mfma_kernel<WAVES, HR>), grid, block, bytes, s, d, g, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, O_part, m, l);
   return hipGetLastError();

@@ -72,8 +72,8 @@ __global__ __launch_bounds__(kThreads) void fwd_generic_kernel(
   const int q0 = blockIdx.x * BM;
   const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;
   Q += (int64_t)head * d.nq * H;
-  K += (int64_t)head * d.nkv * H;
-  V += (int64_t)head * d.nkv * H;
+  K += (int64_t)(head / g.group) * d.nkv * H;
+  V += (int64_t)(head / g.group) * d.nkv * H;
 
   load_tile<T, H>(Qs, LD, Q, q0, d.nq, BM);
 
@@ -192,15 +192,15 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_generic_kernel(
   float* dOs = Qs + BQ * LD;       // [BQ][LD]
   float* Ps = dOs + BQ * LD;       // [BQ][LP]
   float* dSs = Ps + BQ * LP;       // [BQ][LP]
-  const int head = blockIdx.y;
+  const int head = blockIdx.y;     // key/value head: its g.group query heads follow one another in Q, dO, lse, delta
   const int k0 = blockIdx.x * BK;
   const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;
-  Q += (int64_t)head * d.nq * H;
-  dO += (int64_t)head * d.nq * H;
+  Q += (int64_t)head * g.group * d.nq * H;
+  dO += (int64_t)head * g.group * d.nq * H;
   K += (int64_t)head * d.nkv * H;
   V += (int64_t)head * d.nkv * H;
-  lse += (int64_t)head * d.nq;
-  delta += (int64_t)head * d.nq;
+  lse += (int64_t)head * g.group * d.nq;
+  delta += (int64_t)head * g.group * d.nq;
 
   load_tile<T, H>(Ks, LD, K, k0, d.nkv, BK);
   load_tile<T, H>(Vs, LD, V, k0, d.nkv, BK);
@@ -225,6 +225,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_generic_kernel(
       i_first = min(i_first, fr);
     }
   }
+  for (int qh = 0; qh < g.group; ++qh, Q += (int64_t)d.nq * H, dO += (int64_t)d.nq * H, lse += d.nq, delta += d.nq)
   for (int i0 = (i_first / BQ) * BQ; i0 < d.nq; i0 += BQ) {
     __syncthreads();
     load_tile<T, H>(Qs, LD, Q, i0, d.nq, BQ);
@@ -313,8 +314,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_generic_kernel(
   const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;
   Q += (int64_t)head * d.nq * H;
   dO += (int64_t)head * d.nq * H;
-  K += (int64_t)head * d.nkv * H;
-  V += (int64_t)head * d.nkv * H;
+  K += (int64_t)(head / g.group) * d.nkv * H;
+  V += (int64_t)(head / g.group) * d.nkv * H;
   lse += (int64_t)head * d.nq;
   delta += (int64_t)head * d.nq;
 
@@ -454,7 +455,7 @@ hipError_t bwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, c
   e = set_lds(bwd_dq_generic_kernel<T, H>, lds_q);
   if (e != hipSuccess) return e;
   dim3 block(kThreads);
-  dim3 grid_kv((d.nkv + 63) / 64, d.heads), grid_q((d.nq + 63) / 64, d.heads);
+  dim3 grid_kv((d.nkv + 63) / 64, d.heads / g.group), grid_q((d.nq + 63) / 64, d.heads);
   hipLaunchKernelGGL((bwd_dkdv_generic_kernel<T, H>), grid_kv, block, lds_kv, s, d, g, (const T*)Q,
                      (const T*)K, (const T*)V, (const T*)dO, lse, delta, dK, dV);
   e = hipGetLastError();

@@ -539,6 +539,77 @@ def test_grid_emulation_matches_full_attention(a2d, layout, dt, H, grid):
     assert torch.equal(O, O1) and torch.equal(lse, lse1)
 
 
+# ----------------------------------------------------------------------------- grouped queries
+GQA_CASES = [
+    # heads, kv_heads, nq, nkv, H, q_off, kv_off, causal, segments
+    (4, 2, 200, 300, 128, 150, 0, True, None),
+    (6, 2, 130, 130, 128, 0, 0, True, None),
+    (3, 1, 96, 260, 64, 0, 0, False, None),                       # multi-query
+    (8, 2, 64, 192, 96, 100, 0, True, [(0, 64), (96, 64), (40, 64)]),
+    (4, 1, 33, 70, 80, 40, 10, True, None),
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("case", GQA_CASES, ids=lambda c: "%dq%dkv_%dx%dxH%d" % c[:5])
+def test_grouped_query_heads(a2d, dt, case):
+    """a2d_partial_fwd_gqa / a2d_partial_bwd_gqa against the oracle run on K, V repeated per query
+    head (the definition of grouped-query attention); dK, dV against the oracle's per-query-head
+    gradients summed over each group."""
+    heads, kvh, nq, nkv, H, q_off, kv_off, causal, segs = case
+    grp = heads // kvh
+    scale = 1.0 / math.sqrt(H)
+    Q = synth.normal((heads, nq, H), 71, 0, 1.0, dt)
+    K = synth.normal((kvh, nkv, H), 71, 1, 1.0, dt)
+    V = synth.normal((kvh, nkv, H), 71, 2, 1.0, dt)
+    dO = synth.normal((heads, nq, H), 71, 3, 1.0, dt)
+    Kr, Vr = np.repeat(np64(K), grp, axis=0), np.repeat(np64(V), grp, axis=0)
+    kpos = oracle.segment_positions(segs) if segs else np.arange(kv_off, kv_off + nkv, dtype=np.int64)
+    what = "gqa %s %s" % (dt, case[:8])
+    Np, m, l = a2d.partial_fwd(dev(Q), dev(K), dev(V), q_off, kv_off, causal, scale, segments=segs)
+    On, lsen = a2d.partial_fwd_norm(dev(Q), dev(K), dev(V), q_off, kv_off, causal, scale, segments=segs)
+    torch.cuda.synchronize()
+    Nr, mr, lr = oracle.partial_fwd_pos(np64(Q), Kr, Vr, q_off, kpos, causal, scale)
+    Ng, mg, lg = np64(Np), np64(m), np64(l)
+    empty = np.isinf(mr)
+    assert np.array_equal(np.isinf(mg) & (mg < 0), empty), what + ": set of empty rows differs"
+    ok = ~empty
+    assert_close(mg[ok], mr[ok], DT[dt], what + " m", rel=False)
+    assert_close(Ng[ok] / lg[ok][:, None], Nr[ok] / lr[ok][:, None], DT[dt], what + " N/l")
+    Or, lser = oracle.fix([Nr], [mr], [lr])
+    assert_close(np64(On)[ok], Or[ok], DT[dt], what + " O'")
+    assert_close(np64(lsen)[ok], lser[ok], DT[dt], what + " lse'", rel=False)
+    # accumulating form: the same tile merged into an empty triple gives the plain result bit for bit
+    acc = (torch.zeros_like(Np), torch.full_like(m, -float("inf")), torch.zeros_like(l))
+    a2d.partial_fwd(dev(Q), dev(K), dev(V), q_off, kv_off, causal, scale, out=acc, segments=segs, accumulate=True)
+    torch.cuda.synchronize()
+    assert_close(np64(acc[1])[ok], mr[ok], DT[dt], what + " acc m", rel=False)
+    assert_close(np64(acc[0])[ok] / np64(acc[2])[ok][:, None], Nr[ok] / lr[ok][:, None], DT[dt], what + " acc N/l")
+    # backward
+    O_in = torch.from_numpy(Or).to(DT[dt])
+    lse_in = torch.from_numpy(lser).to(torch.float32)
+    dQ, dK, dV = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, kv_off, causal,
+                                 scale, segments=segs)
+    torch.cuda.synchronize()
+    assert dK.shape == K.shape and dV.shape == V.shape
+    with np.errstate(invalid="ignore"):
+        rq, rk, rv = oracle.partial_bwd_pos(np64(Q), Kr, Vr, np64(O_in), np64(dO), np64(lse_in), q_off, kpos,
+                                            causal, scale)
+    rk = rk.reshape(kvh, grp, nkv, H).sum(axis=1)
+    rv = rv.reshape(kvh, grp, nkv, H).sum(axis=1)
+    assert_close(dQ, rq, DT[dt], what + " dQ")
+    assert_close(dK, rk, DT[dt], what + " dK")
+    assert_close(dV, rv, DT[dt], what + " dV")
+    # kv_heads == heads through the same entry point is the plain call, bit for bit
+    if grp > 1 and segs is None:
+        Kf, Vf = dev(torch.from_numpy(Kr).to(DT[dt])), dev(torch.from_numpy(Vr).to(DT[dt]))
+        a = a2d.partial_fwd(dev(Q), Kf, Vf, q_off, kv_off, causal, scale)
+        torch.cuda.synchronize()
+        for x, y in zip(a, (Np, m, l)):
+            assert torch.equal(x, y), what + ": grouped forward differs from the repeated-head forward"
+
+
 # ----------------------------------------------------------------------------- normalised partials
 @pytest.mark.gpu
 @pytest.mark.parametrize("dt,H", [("bf16", 128), ("f32", 64), ("bf16", 96)])

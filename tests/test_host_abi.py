@@ -161,3 +161,29 @@ def test_normalised_format_argument_errors(binding):
     assert fix(2, 10, 128, 5, b.A2D_BF16) == -2
     assert fix(2, 10, 128, b.A2D_BF16, 5) == -2
     assert fix(2, 10, 128, b.A2D_BF16, b.A2D_BF16, None) == -1
+
+
+def test_grouped_query_argument_errors(binding):
+    b, L = binding, binding.lib()
+    P = ctypes.c_void_p(0x10000)
+    d = _desc(b)                      # heads as _desc sets them
+    heads = d.heads
+    fwd = lambda kvh, flags, o0=P, o2=P: L.a2d_partial_fwd_gqa(ctypes.byref(d), kvh, 0, None, flags, P, P, P, o0, P, o2,
+                                                               None, 0, None)
+    assert fwd(0, 0) == -1 and fwd(heads + 1, 0) == -1           # kv_heads must divide heads
+    if heads % 3:
+        assert fwd(3, 0) == -1 and b"divide" in L.a2d_last_error()
+    assert fwd(heads, 4) == -1 and fwd(heads, 3) == -1            # unknown / combined flags
+    assert fwd(heads, 0, None) == -1                              # NULL output
+    assert fwd(1, b.TILE_NORMALISED, ctypes.c_void_p(0x10002), None) == -3
+    bwd = lambda kvh, flags: L.a2d_partial_bwd_gqa(ctypes.byref(d), kvh, 0, None, flags, P, P, P, P, P, P, P, P, P,
+                                                   None, 0, None)
+    assert bwd(heads + 1, 0) == -1
+    assert bwd(1, b.TILE_NORMALISED) == -1                        # the backward has no normalised form
+    assert bwd(1, 0) == -4                                        # first failing check: the workspace
+    big = _desc(b, nq=1 << 22)
+    big.heads = 4
+    assert L.a2d_partial_fwd_gqa(ctypes.byref(big), 2, 0, None, 0, P, P, P, P, P, P, None, 0, None) == -1
+    assert b"2^22" in L.a2d_last_error()
+    too = _desc(b, nq=(1 << 22) + 1)
+    assert L.a2d_partial_fwd(ctypes.byref(too), P, P, P, P, P, P, None, 0, None) == -1
