@@ -33,11 +33,16 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of each call, from rocprofv3 PMC runs of this script (FETCH_SIZE and WRITE_SIZE,
 # each scaled by the reading of a 1 GiB copy: profiles/bench_c3_hbm_traffic.txt).  The tile calls sum
 # their kernels (partial_bwd = delta + dK/dV + dQ kernels).  Only the default workload was counted.
+# The default backward hands dS (bf16, 2 bytes per visible score) from the dK/dV kernel to the dQ
+# kernel through the workspace: bytes traded for the dQ kernel's recomputation of S and dP; the
+# "_recompute" entries are the --recompute-bwd path (traffic = the algorithmic minimum).
 MIB = float(1 << 20)
 TRAFFIC_BYTES = {"c3": {
     "partial_fwd_diag": (289.4 + 211.4) * MIB, "partial_fwd_full": (289.4 + 211.4) * MIB,
-    "partial_bwd_diag": (192.0 + 387.5 + 400.8 + 1.5 + 384.0 + 193.0) * MIB,
-    "partial_bwd_full": (192.0 + 387.5 + 400.8 + 1.5 + 384.0 + 193.0) * MIB,
+    "partial_bwd_diag": (192.0 + 387.2 + 1812.8 + 1.5 + 1932.0 + 192.0) * MIB,
+    "partial_bwd_full": (192.0 + 387.2 + 3273.6 + 1.5 + 3456.5 + 194.0) * MIB,
+    "partial_bwd_diag_recompute": (192.0 + 387.5 + 400.8 + 1.5 + 384.0 + 193.0) * MIB,
+    "partial_bwd_full_recompute": (192.0 + 387.5 + 400.8 + 1.5 + 384.0 + 193.0) * MIB,
     "fix": (1632.1 + 97.5) * MIB, "fix_bwd_dq": (1536.0 + 96.0) * MIB,
     "fix_bwd_dk": (1536.0 + 96.0) * MIB, "fix_bwd_dv": (1536.0 + 96.0) * MIB}}
 
@@ -61,6 +66,9 @@ def main():
     ap.add_argument("--no-gathered", action="store_true",
                     help="skip the extra measurements appended after the timed steps (gathered key row, "
                          "normalised partials, grouped-query heads)")
+    ap.add_argument("--recompute-bwd", action="store_true",
+                    help="give a2d_partial_bwd only its minimum workspace: the dQ kernel then recomputes S and dP "
+                         "instead of reading the dS the dK/dV kernel left in the larger workspace")
     ap.add_argument("--grid-emulation", action="store_true",
                     help="also time Alg. 1 + Alg. 3 over all P tiles of the c2 sequence (8192 tokens, 4 x 4 grid)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -105,8 +113,10 @@ def main():
     O = torch.empty(w.heads, T, H, dtype=dt, device="cuda")
     lse = torch.empty(w.heads, T, **f32)
     if w.backward:
-        ws = torch.empty(a2d.workspace_bytes(a2d.tile_desc(Q, Kc[tiles[0][0]], 0, 0, w.causal, scale),
-                                             a2d.OP_PARTIAL_BWD), dtype=torch.uint8, device="cuda")
+        # the larger workspace (delta + dS, 2 T^2 bytes per head more) selects the dS hand-over
+        ws_op = a2d.OP_PARTIAL_BWD if args.recompute_bwd else a2d.OP_PARTIAL_BWD_DS
+        ws = torch.empty(a2d.workspace_bytes(a2d.tile_desc(Q, Kc[tiles[0][0]], 0, 0, w.causal, scale), ws_op),
+                         dtype=torch.uint8, device="cuda")
         # gradient partials: dQ over the grid row (one per key block), dK / dV over the grid column
         dq_parts = [torch.zeros(w.heads, T, H, **f32) for _ in range(G)]
         dk_parts = [torch.zeros(w.heads, T, H, **f32) for _ in range(G)]
@@ -198,7 +208,10 @@ def main():
     roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["achieved"],
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": kernels[dom]["frac"],
                 "avg_ms": kernels[dom]["avg_ms"],
-                "traffic": TRAFFIC_BYTES.get(w.name, {}).get(dom)}
+                "traffic": TRAFFIC_BYTES.get(w.name, {}).get(dom + ("_recompute" if args.recompute_bwd else ""),
+                                                             TRAFFIC_BYTES.get(w.name, {}).get(dom))}
+    if w.backward:
+        roofline["bwd_path"] = "recompute" if args.recompute_bwd else "dS hand-over"
 
     result = {
         "metric": "fwd+bwd attention TFLOP/s per tile + % bf16 MFMA peak; AttnFix GB/s",
@@ -249,7 +262,9 @@ def gathered_tile(a2d, synth, w, scale, kernels):
     out = a2d.partial_fwd(Q, K, V, r * T, 0, True, scale, segments=segs)
     O, lse = a2d.fix([out[0]], [out[1]], [out[2]])
     o3 = a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, segments=segs)
-    ws = torch.empty(w.heads * T * 4 + 256, dtype=torch.uint8, device="cuda")
+    # the workspace size that selects the dS hand-over, as in the timed steps (2 bytes per score: 24 GiB here)
+    ws = torch.empty(a2d.workspace_bytes(a2d.tile_desc(Q, K, r * T, 0, True, scale), a2d.OP_PARTIAL_BWD_DS),
+                     dtype=torch.uint8, device="cuda")
 
     def timeit(fn, n=5):
         fn(); fn()

@@ -59,7 +59,8 @@ typedef enum {
   A2D_OP_PARTIAL_FWD = 0,
   A2D_OP_FIX = 1,
   A2D_OP_PARTIAL_BWD = 2,
-  A2D_OP_FIX_BWD = 3
+  A2D_OP_FIX_BWD = 3,
+  A2D_OP_PARTIAL_BWD_DS = 4 /* workspace query only: a2d_partial_bwd with the dS hand-over */
 } a2d_op;
 
 /* Most partials one a2d_fix / a2d_fix_bwd call can merge (sqrt(P) in the paper). */
@@ -83,7 +84,13 @@ typedef struct {
 
 /*
  * Bytes of device workspace the given op needs for this tile (0 if none).
- * Only A2D_OP_PARTIAL_BWD needs any (the per-row sums delta = rowsum(dO o O)).
+ * A2D_OP_PARTIAL_BWD: the minimum (the per-row sums delta = rowsum(dO o O)).
+ * A2D_OP_PARTIAL_BWD_DS: the size from which the backward calls ALSO keep dS (bf16, one value
+ * per score: about 2 nq nkv bytes per head) in the workspace, so that dQ is one contraction over
+ * the stored dS instead of a second recomputation of S and dP (bf16 inputs, one query head per
+ * key/value head, sub-blocks of a gathered tile starting at multiples of 64 keys, less than
+ * 4 GiB of dS per head; otherwise the extra bytes are ignored).  Same results up to fp32
+ * summation order; faster when the memory is there.
  * `k` is ignored for the tile ops.  Returns 0 for a NULL or invalid descriptor.
  */
 size_t a2d_workspace_bytes(const a2d_tile_desc* desc, int op, int k);
@@ -124,9 +131,10 @@ a2d_status a2d_fix(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
  *        P = exp(S - lse), delta = rowsum(dO o O), dV = P^T dO, dP = dO V^T,
  *        dS = P o (dP - delta), dQ = scale dS K, dK = scale dS^T Q.
  * bf16 inputs: P and dS are rounded to bf16 before their contractions.
- * workspace: a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD, 0) bytes, contents
- * undefined on entry and exit; calls sharing one workspace must be ordered on
- * one stream.
+ * workspace: at least a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD, 0) bytes (from
+ * a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD_DS, 0) bytes on, the faster dS hand-over
+ * is used), contents undefined on entry and exit; calls sharing one workspace must be
+ * ordered on one stream.
  */
 a2d_status a2d_partial_bwd(const a2d_tile_desc* desc, const void* Q, const void* K,
                            const void* V, const void* O, const void* dO,

@@ -14,7 +14,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "liba2d.so")
 
 A2D_F32, A2D_BF16 = 0, 1
-OP_PARTIAL_FWD, OP_FIX, OP_PARTIAL_BWD, OP_FIX_BWD = 0, 1, 2, 3
+OP_PARTIAL_FWD, OP_FIX, OP_PARTIAL_BWD, OP_FIX_BWD, OP_PARTIAL_BWD_DS = 0, 1, 2, 3, 4
 MAX_PARTS = 32
 
 EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
@@ -248,15 +248,17 @@ def fix(O_parts, ms, ls, out_dtype=torch.bfloat16, out=None):
 
 
 def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None, out=None,
-                workspace=None, segments=None, accumulate=False):
-    """a2d_partial_bwd. Returns (dQ_part, dK_part, dV_part), all fp32."""
+                workspace=None, segments=None, accumulate=False, ds_handover=False):
+    """a2d_partial_bwd. Returns (dQ_part, dK_part, dV_part), all fp32.  With no `workspace` given,
+    ds_handover=True allocates the larger one (a2d_workspace_bytes(A2D_OP_PARTIAL_BWD_DS)) that
+    makes the library keep dS for the dQ contraction instead of recomputing it."""
     for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
         _dev3(t, n)
     if O.shape != Q.shape or dO.shape != Q.shape or O.dtype != Q.dtype or dO.dtype != Q.dtype or \
             lse.shape != Q.shape[:2] or lse.dtype != torch.float32 or K.shape != V.shape:
         raise A2DError(-1, "O, dO, lse do not match Q")
     d = tile_desc(Q, K, q_off, kv_off, causal, scale)
-    need = workspace_bytes(d, OP_PARTIAL_BWD)
+    need = workspace_bytes(d, OP_PARTIAL_BWD_DS if ds_handover else OP_PARTIAL_BWD)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     if out is None:

@@ -39,7 +39,8 @@ def _stale(target, deps):
 
 def build(force=False, verbose=True):
     os.makedirs(OBJ, exist_ok=True)
-    headers = [os.path.join(CSRC, "a2d_common.hpp"), os.path.join(ROOT, "include", "a2d.h")]
+    headers = [os.path.join(CSRC, "a2d_common.hpp"), os.path.join(CSRC, "a2d_mfma.hpp"),
+               os.path.join(ROOT, "include", "a2d.h")]
     jobs, objs = [], []
     for src in SOURCES:
         s = os.path.join(CSRC, src)

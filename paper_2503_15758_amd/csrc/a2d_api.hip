@@ -146,9 +146,13 @@ a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
   float* delta = static_cast<float*>(workspace);
   A2D_TRY(hip_result(a2d::launch_delta(desc->dtype, (int64_t)desc->heads * desc->nq, desc->hdim, O,
                                        dO, delta, s), who));
-  if (!force_generic() && a2d::bwd_mfma_supported(*desc))
+  if (!force_generic() && a2d::bwd_mfma_supported(*desc)) {
+    // a workspace large enough for dS as well switches to the hand-over path
+    const size_t ds_bytes = a2d::bwd_ds_bytes(*desc, g);
+    void* ds_ws = (ds_bytes > 0 && workspace_bytes >= need + ds_bytes) ? static_cast<char*>(workspace) + need : nullptr;
     return hip_result(a2d::launch_bwd_mfma(*desc, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
-                                           dV_part, s), who);
+                                           dV_part, ds_ws, s), who);
+  }
   return hip_result(a2d::launch_bwd_generic(*desc, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
                                             dV_part, s), who);
 }
@@ -159,9 +163,11 @@ extern "C" {
 
 size_t a2d_workspace_bytes(const a2d_tile_desc* desc, int op, int /*k*/) {
   if (!desc || desc->heads < 1 || desc->nq < 1) return 0;
-  if (op != A2D_OP_PARTIAL_BWD) return 0;
+  if (op != A2D_OP_PARTIAL_BWD && op != A2D_OP_PARTIAL_BWD_DS) return 0;
   const size_t rows = (size_t)desc->heads * (size_t)desc->nq;
-  return ((rows * sizeof(float) + 255) / 256) * 256;
+  const size_t delta_bytes = ((rows * sizeof(float) + 255) / 256) * 256;
+  if (op == A2D_OP_PARTIAL_BWD || desc->nkv < 1) return delta_bytes;
+  return delta_bytes + a2d::bwd_ds_bytes(*desc, one_segment(desc));
 }
 
 a2d_status a2d_partial_fwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,

@@ -207,15 +207,69 @@ __device__ __forceinline__ void dk_second(DkCtx<HD>& cx, bf16x8 (&t)[HD / 32], c
 #undef A2D_TR
 #undef A2D_NAT
 
+// ---- dS hand-over to the dQ kernel (optional).  The dK/dV kernel can leave dS (bf16, already
+// multiplied out: P o (dP - delta)) in a workspace, so that the dQ kernel is a plain contraction
+// dQ = scale dS K instead of recomputing S and dP.  Workspace layout: per head, per 32-row tile rt,
+// per 64-key block kb one 4 KiB tile [piece T = 0, 1 (32 keys each)][u = 0, 1 (16 keys each)]
+// [lane 0..63][8 bf16]: lane (row = lane & 31, half = lane >> 5) holds, for the 16 keys
+// 64 kb + 32 T + 16 u + .., the keys 4 half + {0..3} and 8 + 4 half + {0..3} - exactly the B
+// fragment of the dQ kernel's MFMA, so the consumer reads it with one coalesced 16-byte load per
+// lane and the producer writes it with one coalesced 16-byte store per lane.
+constexpr int DS_TILE_BYTES = 4096;
+__host__ __device__ inline int ds_row_tiles(int nq) { return (nq + 31) / 32; }
+__host__ __device__ inline int ds_key_blocks(int nkv) { return (nkv + 63) / 64; }
+__host__ __device__ inline size_t ds_head_bytes(int nq, int nkv) {
+  return (size_t)ds_row_tiles(nq) * ds_key_blocks(nkv) * DS_TILE_BYTES;
+}
+
+typedef __attribute__((address_space(1))) char* gwptr_t;
+__device__ __forceinline__ gwptr_t uniform_gwptr(void* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<gwptr_t>(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ void gstore_b128(gwptr_t base, unsigned byte_off, bf16x8 v) {
+  // streamed once, read back by another kernel: keep it from displacing the Q / dO tiles in L2
+  __builtin_nontemporal_store(v, reinterpret_cast<__attribute__((address_space(1))) bf16x8*>(base + byte_off));
+}
+
+// The gradient wave holds dS with lane = key and registers = query rows; the dQ kernel needs
+// lane = query row and registers = keys.  The wave turns its 32 x 32 piece around through LDS (its
+// own mailbox piece, free once the probabilities have been read): each lane writes its four
+// 4-row groups as 8-byte pieces of a [key][row] tile (rows of 72 bytes: conflict-free), and the
+// transposing read returns, per lane, four keys of one row.
+constexpr int DS_TR_LD = 72;
+__device__ __forceinline__ void ds_turn_write(unsigned piece, int l32, int half, const bf16x8 (&bf)[2]) {
+  const unsigned a = piece + l32 * DS_TR_LD + 8 * half;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const u32x4 w = __builtin_bit_cast(u32x4, bf[u]);
+    // register group g = 2u (w.x, w.y) and g = 2u + 1 (w.z, w.w): rows 8g + 4 half + 0..3
+    *reinterpret_cast<__attribute__((address_space(3))) u32x2*>((uintptr_t)(a + 16 * (2 * u))) = u32x2{w[0], w[1]};
+    *reinterpret_cast<__attribute__((address_space(3))) u32x2*>((uintptr_t)(a + 16 * (2 * u + 1))) = u32x2{w[2], w[3]};
+  }
+}
+__device__ __forceinline__ void ds_turn_read(unsigned piece, int lane, bf16x8 (&out)[2]) {
+  const int g16 = lane >> 4, j16 = lane & 15;
+  const unsigned a = piece + (4 * (g16 >> 1) + (j16 >> 2)) * DS_TR_LD + (16 * (g16 & 1) + 4 * (j16 & 3)) * 2;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) out[u] = lds_load_tr(a + 16 * u * DS_TR_LD, a + (16 * u + 8) * DS_TR_LD);
+}
+
 // HR: head size = row length in memory (80, 96 or 128); the LDS tiles and fragments are laid out
 // for the padded head size HD = padded_head(HR) (96 or 128).
 // GROUPED: several query heads per key/value head (g.group > 1); the plain kernel is compiled
 // without the bookkeeping that walks them.
-template <int HR, bool GROUPED>
+// WRITE_DS: the gradient waves also leave dS in the workspace `dS` (layout above) for the
+// contraction-only dQ kernel.
+template <int HR, bool GROUPED, bool WRITE_DS>
 __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
     a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
-    const float* __restrict__ delta, float* __restrict__ dK, float* __restrict__ dV) {
+    const float* __restrict__ delta, float* __restrict__ dK, float* __restrict__ dV,
+    bf16_t* __restrict__ dS) {
+  static_assert(!(GROUPED && WRITE_DS), "the dS hand-over is built for one query head per key/value head");
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
   int head, blk;
@@ -378,10 +432,21 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   }
   __syncthreads();
 
+  // dS hand-over: this pair's 32 keys are piece T = pair & 1 of key block 2 blk + (pair >> 1)
+  const unsigned ds_row_stride = (unsigned)ds_key_blocks(d.nkv) * DS_TILE_BYTES;
+  const unsigned ds_lane_off = (unsigned)(2 * blk + (pair >> 1)) * DS_TILE_BYTES + (pair & 1) * 2048 + lane * 16;
+  gwptr_t ds_base = nullptr;
+  if constexpr (WRITE_DS)
+    ds_base = uniform_gwptr(reinterpret_cast<char*>(dS) + (int64_t)head * ds_head_bytes(d.nq, d.nkv));
+
   // A step is skipped (by both wavefronts of its pair) when none of its rows sees any of the
   // pair's keys; it is masked unless every row sees every key.
   // (step = position in the whole walk, s = its step inside its query head)
-  auto active = [&](int step, int s) { return step >= 0 && step < total && i_start + s * BQ + BQ - 1 >= w_any; };
+  // (rows past nq do not count: a pair without keys, w_any = nq, is never active - it has no
+  // place in the dS workspace either)
+  auto active = [&](int step, int s) {
+    return step >= 0 && step < total && min(i_start + s * BQ + BQ - 1, d.nq - 1) >= w_any;
+  };
   int cs = 0;                                                   // s of the iteration's step j
   auto next_s = [&](int s) { return (GROUPED && s + 1 == nsteps) ? 0 : s + 1; };
   auto advance = [&](int slot_delta) {   // to this wave's next step: tile buffer and mailbox slot
@@ -442,7 +507,22 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
         dk_mbox_pre(cx, pm);
         dk_second_pre(cx, t);
         dk_dscores(pm, dp, bf);
+        bf16x8 ds_out[2];
+        if constexpr (WRITE_DS) {
+          // turned around through LDS; requested BEFORE the contraction's own fragments are
+          // waited for (LDS answers in order), so the stores below find their data arrived
+          ds_turn_write(cx.mbox - lane * 16, l32, cx.half, bf);
+          ds_turn_read(cx.mbox - lane * 16, lane, ds_out);
+          __builtin_amdgcn_sched_barrier(0);
+        }
         dk_second(cx, t, bf);
+        if constexpr (WRITE_DS) {
+          // (measured: making these stores unconditional - skipped steps writing to a spill slot,
+          // which keeps the compiler's load wait counts exact - is not faster)
+          const unsigned off = (unsigned)(i_start / BQ + ps) * ds_row_stride + ds_lane_off;
+          gstore_b128(ds_base, off, ds_out[0]);
+          gstore_b128(ds_base, off + 1024, ds_out[1]);
+        }
       }
       advance(SET ? DK_MBOX_SLOT : -DK_MBOX_SLOT);
       ps = cs;
@@ -700,21 +780,275 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   if (q_ok) store_acc_t<CT>(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, d.scale, H, g.acc != 0);
 }
 
+// ---------------------------------------------------------------------- dQ from a stored dS
+// Contraction-only dQ kernel: dQ^T += K^T dS^T with dS read back from the workspace the dK/dV
+// kernel filled (layout at ds_row_tiles above).  Workgroup = WAVES wavefronts of 32 query rows;
+// 64 keys per step: the K tile goes through LDS (dual layout, transposing reads only), the dS
+// fragments come straight from global memory, one contiguous 4 KiB tile per wavefront and step,
+// requested DSQ_SETS - 1 steps ahead through DSQ_SETS register sets (the stream is HBM-bound: 2 bytes per
+// score).  The sub-blocks of a gathered tile must start at multiples of 64 keys, so that a 64-key
+// block never straddles two of them.
+constexpr int DSQ_RING = 4;
+constexpr int DSQ_SETS = 3;  // register sets of dS fragments: requests run DSQ_SETS - 1 steps ahead
+template <int HD>
+struct DsqCtx {
+  f32x16 dq[HD / 32];
+  DualAddr ka;          // K tile of the current buffer
+  int my_vis;           // number of leading keys of the current sub-block this lane's query row sees
+  int half;
+};
+
+// one 32-key piece (T = 0, 1) of the step: ds[2T], ds[2T + 1] are the two 16-key B fragments;
+// key0 = the piece's first key, local to its sub-block
+template <int T, bool MASK, int HD>
+__device__ __forceinline__ void dsq_piece(DsqCtx<HD>& cx, const u32x4 (&ds)[4], int key0) {
+  constexpr int CT = HD / 32;
+  constexpr int RB = T * 32 * DUAL_LD;
+  bf16x8 kt[DSQ_RING];
+  auto ld = [&](auto I) {
+    constexpr int i = decltype(I)::value;
+    kt[i % DSQ_RING] = lds_load_tr(cx.ka.tr_lo + RB + (i / CT) * 16 * DUAL_LD + 64 * (i % CT),
+                                   cx.ka.tr_hi + RB + (i / CT) * 16 * DUAL_LD + 64 * (i % CT));
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  static_for<0, (DSQ_RING < 2 * CT ? DSQ_RING : 2 * CT)>(ld);
+  bf16x8 dsb[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    u32x4 w = ds[2 * T + u];
+    if (MASK) {
+      // element e of the fragment <-> key key0 + 16u + 8 (e >> 2) + 4 half + (e & 3); two per word
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const int k = key0 + 16 * u + 8 * (x >> 1) + 4 * cx.half + 2 * (x & 1);
+        const unsigned keep = (k < cx.my_vis ? 0x0000FFFFu : 0u) | (k + 1 < cx.my_vis ? 0xFFFF0000u : 0u);
+        w[x] &= keep;
+      }
+    }
+    dsb[u] = __builtin_bit_cast(bf16x8, w);
+  }
+  static_for<0, 2 * CT>([&](auto I) {
+    constexpr int i = decltype(I)::value;
+    cx.dq[i % CT] = mma(kt[i % DSQ_RING], dsb[i / CT], cx.dq[i % CT]);
+    if constexpr (i + DSQ_RING < 2 * CT) ld(std::integral_constant<int, i + DSQ_RING>{});
+  });
+}
+
+template <int WAVES, int HR>
+__global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
+    a2d_tile_desc d, SegList g, const bf16_t* __restrict__ K, const bf16_t* __restrict__ dS,
+    float* __restrict__ dQ) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+  constexpr int DQ_ROWS = 32 * WAVES, DQ_THREADS = 64 * WAVES;
+  constexpr int HD = padded_head(HR), H = HR, CT = HD / 32;
+  const int nqb = (d.nq + DQ_ROWS - 1) / DQ_ROWS;
+  int head, blk;
+  if (!xcd_map(d.heads, nqb, head, blk)) return;
+  const int q0 = (nqb - 1 - blk) * DQ_ROWS;            // heavy blocks first under a causal mask
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int l32 = lane & 31;
+  K += (int64_t)head * d.nkv * H;
+
+  DsqCtx<HD> cx;
+  cx.half = lane >> 5;
+  const int q_row = q0 + wave * 32 + l32;
+  const bool q_ok = q_row < d.nq;
+  const int q_ld = min(q_row, d.nq - 1);
+#pragma unroll
+  for (int t = 0; t < CT; ++t) cx.dq[t] = zero16();
+  cx.ka.init(lane, lds_base);
+
+  // this wavefront's row tile of dS (a wavefront past the last row reads the last tile; its
+  // results are never stored)
+  const int n_rt = ds_row_tiles(d.nq), n_kb = ds_key_blocks(d.nkv);
+  const int rt = min((q0 + wave * 32) / 32, n_rt - 1);
+  const gptr_t ds_base = uniform_gptr(reinterpret_cast<const char*>(dS) + (int64_t)head * ds_head_bytes(d.nq, d.nkv) +
+                                      (int64_t)rt * n_kb * DS_TILE_BYTES);
+
+  // visibility per key/value sub-block s: query i sees the first vis_count(i, s) keys of it
+  auto vis_count = [&](int i, int s) -> int {
+    if (!d.causal) return g.rows[s];
+    const int64_t v = (int64_t)i + g.rel[s] + 1;
+    return v <= 0 ? 0 : (v < g.rows[s] ? (int)v : g.rows[s]);
+  };
+  const int blk_last = min(q0 + DQ_ROWS, d.nq) - 1;
+  const int w_first = min(q0 + wave * 32, d.nq - 1);
+  const int w_last = min(q0 + wave * 32 + 31, d.nq - 1);
+  auto seg_blocks = [&](int s) { return (vis_count(blk_last, s) + BKS - 1) / BKS; };
+  int count = 0;                                   // 64-key blocks the workgroup walks
+  for (int s = 0; s < g.n; ++s) count += seg_blocks(s);
+
+  // Walk over the visible blocks, as global block numbers (start of the sub-block / 64 + block
+  // inside it).  The fetch walker runs ahead of the compute walker; once it has run out it keeps
+  // returning its last block (loads stay unconditional).
+  int f_sb = -1, f_j = 0, f_nblk = 0, f_base = 0, f_id = 0;
+  auto fetch_next = [&]() {
+    if (f_j + 1 < f_nblk) { ++f_j; f_id = f_base + f_j; return; }
+    int s = f_sb + 1;
+    while (s < g.n && seg_blocks(s) == 0) ++s;
+    if (s < g.n) { f_sb = s; f_j = 0; f_nblk = seg_blocks(s); f_base = g.start[s] / BKS; f_id = f_base; }
+  };
+  int c_sb = -1, c_j = 0, c_nblk = 0;              // compute walker: sub-block, block inside it
+  int nvis_wave = 0, nfull_wave = 0;
+  auto compute_next = [&]() {
+    if (c_j + 1 < c_nblk) { ++c_j; return; }
+    int s = c_sb + 1;
+    while (s < g.n && seg_blocks(s) == 0) ++s;
+    if (s < g.n) {
+      c_sb = s; c_j = 0; c_nblk = seg_blocks(s);
+      nvis_wave = vis_count(w_last, s);
+      nfull_wave = vis_count(w_first, s);
+      cx.my_vis = vis_count(q_ld, s);
+    } else {
+      nvis_wave = 0;                               // past the last block: nothing to compute
+    }
+  };
+
+  // ---- K staging: thread moves chunk (tid & 15) of rows (tid >> 4) + ST_ROWS p of the 64-row tile
+  constexpr int ST_ROWS = DQ_THREADS / 16, ST_N = BKS / ST_ROWS;
+  const int st_row = tid >> 4, st_ch = tid & 15;
+  const int ld_ch = min(st_ch, H / 8 - 1);
+  const bool ch_data = st_ch * 8 < H, ch_tile = st_ch * 8 < HD;
+  const gptr_t k_base = uniform_gptr(K);
+  u32x4 kreg[ST_N];
+  auto load_k = [&](int id) {
+#pragma unroll
+    for (int p = 0; p < ST_N; ++p) {
+      const int row = min(id * BKS + st_row + ST_ROWS * p, d.nkv - 1);   // rows past the end re-read the last key
+      kreg[p] = gload_b128(k_base, (unsigned)(row * (H * 2) + ld_ch * 16));
+    }
+  };
+  auto store_k = [&](int buf) {
+    char* b = lds + buf * DUAL64_BYTES;
+    if (HD == 128 || ch_tile) {
+      const u32x4 zero = {0, 0, 0, 0};
+#pragma unroll
+      for (int p = 0; p < ST_N; ++p)
+        *reinterpret_cast<u32x4*>(b + dual_store_off(st_row + ST_ROWS * p, st_ch)) = (HD == 128 || ch_data) ? kreg[p] : zero;
+    }
+  };
+  u32x4 ds[DSQ_SETS][4];
+  auto load_ds = [&](int id, auto set_tag) {
+    constexpr int SET = decltype(set_tag)::value;
+    const unsigned off = (unsigned)id * DS_TILE_BYTES + lane * 16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      // read once: keep the stream from displacing the K tiles in L2
+      ds[SET][i] = __builtin_nontemporal_load(
+          reinterpret_cast<const __attribute__((address_space(1))) u32x4*>(ds_base + off + 1024 * i));
+    }
+  };
+
+  if (count == 0) {                                // no visible key: dQ share is zero
+    if (q_ok && !g.acc) store_acc_t<CT>(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, 0.f, H, false);
+    return;
+  }
+  fetch_next();                                    // block 0
+  load_k(f_id);
+  load_ds(f_id, std::integral_constant<int, 0>{});
+  store_k(0);
+  int idq[DSQ_SETS - 2];                           // blocks t + 1 .. t + DSQ_SETS - 2 of iteration t
+  static_for<1, DSQ_SETS - 1>([&](auto S) {        // blocks 1 .. DSQ_SETS - 2
+    fetch_next();
+    idq[decltype(S)::value - 1] = f_id;
+    load_ds(f_id, S);
+  });
+  compute_next();
+  __syncthreads();
+
+  int buf = 0;
+  // iteration t: K of block t + 1 and dS of block t + DSQ_SETS - 1 are requested (K first: the
+  // wait for it at the end of the iteration must not cover the dS loads behind it), block t is
+  // computed.
+  auto iteration = [&](auto cur_tag) {
+    constexpr int CUR = decltype(cur_tag)::value;
+    load_k(idq[0]);
+    fetch_next();
+    load_ds(f_id, std::integral_constant<int, (CUR + DSQ_SETS - 1) % DSQ_SETS>{});
+    const int k0 = c_j * BKS;                      // local to the sub-block
+    if (k0 < nvis_wave) {
+      if (k0 + 32 > nfull_wave) dsq_piece<0, true>(cx, ds[CUR], k0); else dsq_piece<0, false>(cx, ds[CUR], k0);
+    }
+    if (k0 + 32 < nvis_wave) {
+      if (k0 + 64 > nfull_wave) dsq_piece<1, true>(cx, ds[CUR], k0 + 32); else dsq_piece<1, false>(cx, ds[CUR], k0 + 32);
+    }
+    store_k(buf ^ 1);
+#pragma unroll
+    for (int x = 0; x + 1 < DSQ_SETS - 2; ++x) idq[x] = idq[x + 1];
+    idq[DSQ_SETS - 3] = f_id;
+    cx.ka.shift(buf ? -DUAL64_BYTES : DUAL64_BYTES);
+    buf ^= 1;
+    compute_next();
+    __syncthreads();
+  };
+  for (int t = 0; t < count; t += DSQ_SETS)        // blocks past the last find nvis_wave = 0
+    static_for<0, DSQ_SETS>([&](auto S) { iteration(S); });
+  if (q_ok) store_acc_t<CT>(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, d.scale, H, g.acc != 0);
+}
+
 }  // namespace
 
 bool bwd_mfma_supported(const a2d_tile_desc& d) {
   return d.dtype == A2D_BF16 && (d.hdim == 128 || d.hdim == 96 || d.hdim == 80 || d.hdim == 64);
 }
 
+// Bytes of the dS workspace of a tile (0 when the hand-over does not apply: grouped heads, a
+// sub-block that does not start at a multiple of 64 keys, or more than 4 GiB per head)
+size_t bwd_ds_bytes(const a2d_tile_desc& d, const SegList& g) {
+  if (!bwd_mfma_supported(d) || g.group != 1) return 0;
+  for (int s = 0; s < g.n; ++s)
+    if (g.start[s] % 64 != 0) return 0;
+  const size_t per_head = ds_head_bytes(d.nq, d.nkv);
+  if (per_head >= ((size_t)1 << 32)) return 0;
+  return per_head * (size_t)d.heads;
+}
+
 namespace {
+template <int HR>
+hipError_t bwd_launch_ds(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
+                         const void* dO, const float* lse, const float* delta, float* dQ, float* dK,
+                         float* dV, void* ds_ws, hipStream_t s) {
+  constexpr int DSQ_LDS = 2 * DUAL64_BYTES;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, true>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, DK_LDS);
+  if (e != hipSuccess) return e;
+  int dev = 0, cus = 0;
+  e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return e;
+  const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
+  e = hipFuncSetAttribute(big ? reinterpret_cast<const void*>(bwd_dq_ds_kernel<8, HR>)
+                              : reinterpret_cast<const void*>(bwd_dq_ds_kernel<4, HR>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, DSQ_LDS);
+  if (e != hipSuccess) return e;
+  dim3 grid_kv(xcd_grid(d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS));
+  const int dq_rows = big ? 256 : 128;
+  dim3 grid_q(xcd_grid(d.heads, (d.nq + dq_rows - 1) / dq_rows));
+  hipLaunchKernelGGL((bwd_dkdv_kernel<HR, false, true>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g,
+                     (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV,
+                     (bf16_t*)ds_ws);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (big)
+    hipLaunchKernelGGL((bwd_dq_ds_kernel<8, HR>), grid_q, dim3(512), DSQ_LDS, s, d, g, (const bf16_t*)K,
+                       (const bf16_t*)ds_ws, dQ);
+  else
+    hipLaunchKernelGGL((bwd_dq_ds_kernel<4, HR>), grid_q, dim3(256), DSQ_LDS, s, d, g, (const bf16_t*)K,
+                       (const bf16_t*)ds_ws, dQ);
+  return hipGetLastError();
+}
+
 template <int HR>
 hipError_t bwd_launch_hd(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                          const void* dO, const float* lse, const float* delta, float* dQ, float* dK,
-                         float* dV, hipStream_t s) {
+                         float* dV, void* ds_ws, hipStream_t s) {
+  if (ds_ws) return bwd_launch_ds<HR>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
   constexpr int DQ_LDS = dq_lds(padded_head(HR));
   const bool grouped = g.group > 1;
-  hipError_t e = hipFuncSetAttribute(grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true>)
-                                             : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false>),
+  hipError_t e = hipFuncSetAttribute(grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, false>)
+                                             : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, false>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, DK_LDS);
   if (e != hipSuccess) return e;
   // dQ kernel: eight wavefronts per workgroup unless that leaves compute units without a workgroup
@@ -732,11 +1066,11 @@ hipError_t bwd_launch_hd(const a2d_tile_desc& d, const SegList& g, const void* Q
   const int per_unit = g.group / g.split;
   dim3 grid_q(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + dq_rows - 1) / dq_rows)));
   if (grouped)
-    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, true>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
-                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV);
+    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, true, false>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
+                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV, (bf16_t*)nullptr);
   else
-    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, false>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
-                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV);
+    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, false, false>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
+                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV, (bf16_t*)nullptr);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (big)
@@ -749,13 +1083,15 @@ hipError_t bwd_launch_hd(const a2d_tile_desc& d, const SegList& g, const void* Q
 }
 }  // namespace
 
+// ds_ws != NULL: a workspace of bwd_ds_bytes(d, g) bytes; the dK/dV kernel leaves dS there and the
+// dQ kernel is the contraction-only one.
 hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                            const void* dO, const float* lse, const float* delta, float* dQ,
-                           float* dK, float* dV, hipStream_t s) {
-  if (d.hdim == 128) return bwd_launch_hd<128>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
-  if (d.hdim == 96) return bwd_launch_hd<96>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
-  if (d.hdim == 80) return bwd_launch_hd<80>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
-  return bwd_launch_hd<64>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s);
+                           float* dK, float* dV, void* ds_ws, hipStream_t s) {
+  if (d.hdim == 128) return bwd_launch_hd<128>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
+  if (d.hdim == 96) return bwd_launch_hd<96>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
+  if (d.hdim == 80) return bwd_launch_hd<80>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
+  return bwd_launch_hd<64>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
 }
 
 }  // namespace a2d

@@ -95,9 +95,12 @@ bool fwd_mfma_supported(const a2d_tile_desc& d);
 hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                            float* O_part, float* m, float* l, hipStream_t s);
 bool bwd_mfma_supported(const a2d_tile_desc& d);
+// ds_ws: NULL, or a workspace of bwd_ds_bytes(d, g) (> 0) bytes through which the dK/dV kernel
+// hands dS to a contraction-only dQ kernel (instead of the dQ kernel recomputing S and dP)
+size_t bwd_ds_bytes(const a2d_tile_desc& d, const SegList& g);
 hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                            const void* dO, const float* lse, const float* delta, float* dQ,
-                           float* dK, float* dV, hipStream_t s);
+                           float* dK, float* dV, void* ds_ws, hipStream_t s);
 
 struct FixPtrs {
   const float* o[A2D_MAX_PARTS];

@@ -95,8 +95,11 @@ def forward(Q, K, V, grid, causal=True, layout="cyclic", scale=None, streams=4):
     return O, lse
 
 
-def backward(Q, K, V, O, dO, lse, grid, causal=True, layout="cyclic", scale=None, streams=4):
-    """Alg. 3: dQ, dK, dV [heads][n][H] in the input dtype from the saved O and lse."""
+def backward(Q, K, V, O, dO, lse, grid, causal=True, layout="cyclic", scale=None, streams=4,
+             ds_handover=True):
+    """Alg. 3: dQ, dK, dV [heads][n][H] in the input dtype from the saved O and lse.
+    ds_handover: give every stream the larger workspace with which the tile call keeps dS for its dQ
+    contraction instead of recomputing the scores (about 2 T^2 bytes per head and stream more)."""
     heads, n, H = Q.shape
     scale = float(scale if scale is not None else 1.0 / math.sqrt(H))
     idx = block_indices(n, grid, layout, Q.device)
@@ -107,8 +110,9 @@ def backward(Q, K, V, O, dO, lse, grid, causal=True, layout="cyclic", scale=None
     tiles = _tiles(grid, causal, layout)
     parts = {t: tuple(torch.empty(heads, T, H, **f32) for _ in range(3)) for t in tiles}
     st = _Streams(streams)
-    # one delta workspace per stream: calls that share a workspace must be ordered on one stream
-    need = a2d.workspace_bytes(a2d.tile_desc(Qb[0], Kb[0], 0, 0, causal, scale), a2d.OP_PARTIAL_BWD)
+    # one workspace per stream: calls that share a workspace must be ordered on one stream
+    need = a2d.workspace_bytes(a2d.tile_desc(Qb[0], Kb[0], 0, 0, causal, scale),
+                               a2d.OP_PARTIAL_BWD_DS if ds_handover else a2d.OP_PARTIAL_BWD)
     ws = [torch.empty(need, dtype=torch.uint8, device=Q.device) for _ in st.side]
     for i, (r, c) in enumerate(tiles):                 # Alg. 3 line 3
         qo, ko = tile_offsets(r, c, T, layout)

@@ -539,6 +539,74 @@ def test_grid_emulation_matches_full_attention(a2d, layout, dt, H, grid):
     assert torch.equal(O, O1) and torch.equal(lse, lse1)
 
 
+# ----------------------------------------------------------------------------- dS hand-over
+DS_CASES = [
+    # heads, nq, nkv, H, q_off, kv_off, causal, segments (starts at multiples of 64 keys)
+    (2, 256, 256, 128, 0, 0, True, None),
+    (2, 300, 500, 128, 200, 0, True, None),
+    (1, 700, 900, 128, 300, 100, True, None),
+    (2, 130, 170, 96, 0, 0, False, None),
+    (2, 150, 200, 80, 60, 0, True, None),
+    (3, 97, 64, 64, 10, 0, True, None),
+    (1, 33, 1, 128, 0, 0, True, None),
+    (2, 200, 448, 128, 300, 0, True, [(0, 128), (250, 192), (100, 128)]),
+    (1, 64, 100, 128, 0, 500, True, None),                      # nothing visible
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", DS_CASES, ids=lambda c: "%dx%dx%dxH%d_q%d_k%d_%s" % c[:7])
+def test_partial_bwd_ds_handover(a2d, case):
+    """a2d_partial_bwd with the larger workspace (dS kept by the dK/dV kernel, dQ as one
+    contraction over it) against the oracle, and against the recomputing path: dK, dV bit for bit
+    (same kernel arithmetic), dQ to rounding.  Also the accumulating form."""
+    heads, nq, nkv, H, q_off, kv_off, causal, segs = case
+    dt = "bf16"
+    scale = 1.0 / math.sqrt(H)
+    Q = synth.normal((heads, nq, H), 81, 0, 1.0, dt)
+    K = synth.normal((heads, nkv, H), 81, 1, 1.0, dt)
+    V = synth.normal((heads, nkv, H), 81, 2, 1.0, dt)
+    dO = synth.normal((heads, nq, H), 81, 3, 1.0, dt)
+    kpos = oracle.segment_positions(segs) if segs else np.arange(kv_off, kv_off + nkv, dtype=np.int64)
+    what = "ds %s" % (case[:7],)
+    Nr, mr, lr = oracle.partial_fwd_pos(np64(Q), np64(K), np64(V), q_off, kpos, causal, scale)
+    Or, lser = oracle.fix([Nr], [mr], [lr])
+    O_in = torch.from_numpy(Or).to(DT[dt])
+    lse_in = torch.from_numpy(lser).to(torch.float32)
+    args = (dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, kv_off, causal, scale)
+    d = a2d.tile_desc(args[0], args[1], q_off, kv_off, causal, scale)
+    big, small = a2d.workspace_bytes(d, a2d.OP_PARTIAL_BWD_DS), a2d.workspace_bytes(d, a2d.OP_PARTIAL_BWD)
+    assert big == small + heads * ((nq + 31) // 32) * ((nkv + 63) // 64) * 4096
+    # poison the workspace: parts of dS the dK/dV kernel skips must never reach dQ
+    # (and a guard band behind it that must stay untouched)
+    guard = 8192
+    ws_all = torch.full(((big + guard) // 2,), float("nan"), dtype=torch.bfloat16, device="cuda").view(torch.uint8)
+    ws, band = ws_all[:big], ws_all[big:]
+    band_before = band.clone()
+    dQ, dK, dV = a2d.partial_bwd(*args, segments=segs, workspace=ws)
+    dQ0, dK0, dV0 = a2d.partial_bwd(*args, segments=segs)
+    torch.cuda.synchronize()
+    with np.errstate(invalid="ignore"):
+        rq, rk, rv = oracle.partial_bwd_pos(np64(Q), np64(K), np64(V), np64(O_in), np64(dO), np64(lse_in),
+                                            q_off, kpos, causal, scale)
+    assert_close(dQ, rq, DT[dt], what + " dQ")
+    assert_close(dK, rk, DT[dt], what + " dK")
+    assert_close(dV, rv, DT[dt], what + " dV")
+    assert torch.equal(dK, dK0) and torch.equal(dV, dV0), what + ": dK / dV differ from the recomputing path"
+    assert_close(dQ, np64(dQ0), DT[dt], what + " dQ vs recomputing path", rel=False)   # (one key: dQ is rounding noise)
+    # accumulating form on top of a known dQ
+    base = torch.full_like(dQ, 0.5)
+    acc = (base.clone(), torch.empty_like(dK), torch.empty_like(dV))
+    a2d.partial_bwd(*args, segments=segs, workspace=ws, out=acc, accumulate=True)
+    torch.cuda.synchronize()
+    assert_close(acc[0], np64(dQ) + 0.5, DT[dt], what + " dQ +=")
+    # same call twice: bitwise the same
+    dQ2, _, _ = a2d.partial_bwd(*args, segments=segs, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dQ, dQ2)
+    assert torch.equal(band, band_before), what + ": bytes behind the workspace were written"
+
+
 # ----------------------------------------------------------------------------- grouped queries
 GQA_CASES = [
     # heads, kv_heads, nq, nkv, H, q_off, kv_off, causal, segments

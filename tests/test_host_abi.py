@@ -48,6 +48,10 @@ def test_workspace_bytes(binding):
     assert b.workspace_bytes(_desc(b), b.OP_PARTIAL_BWD) == 2 * 128 * 4
     assert b.workspace_bytes(_desc(b, heads=3, nq=5), b.OP_PARTIAL_BWD) == 256
     assert b.lib().a2d_workspace_bytes(None, b.OP_PARTIAL_BWD, 0) == 0
+    # with the dS hand-over: + one 4 KiB tile per head, 32-row tile and 64-key block (bf16 MFMA path only)
+    assert b.workspace_bytes(_desc(b), b.OP_PARTIAL_BWD_DS) == 2 * 128 * 4 + 2 * 4 * 2 * 4096
+    assert b.workspace_bytes(_desc(b, nq=33, nkv=65), b.OP_PARTIAL_BWD_DS) == 512 + 2 * 2 * 2 * 4096
+    assert b.workspace_bytes(_desc(b, dtype=b.A2D_F32), b.OP_PARTIAL_BWD_DS) == 2 * 128 * 4
 
 
 def test_argument_errors_enqueue_nothing(binding):
