@@ -275,13 +275,18 @@ def test_c3_causal_tiles_full_heads(a2d):
             assert_close(np64(parts[c][0][h:h + 1, rows]) / np64(parts[c][2][h:h + 1, rows])[..., None],
                          trip[c][0] / trip[c][2][..., None], torch.bfloat16, "c3 N/l tile %d" % c)
     # backward of the diagonal tile and of the unmasked tile (r, 0), all heads on the GPU, head 0 checked
+    # (once with the minimum workspace - the dQ kernel recomputes the scores - and once with the
+    # larger one that makes the dK/dV kernel hand dS over, the path the benchmark times)
     for c in (r, 0):
-        dQ, dK, dV = a2d.partial_bwd(Qd, Kd[c], Vd[c], O, dOd, lse, r * T, c * T, True, scale)
-        torch.cuda.synchronize()
         rQ, rK, rV = oracle.partial_bwd(np64(Qr[:1]), np64(Kb[c][:1]), np64(Vb[c][:1]), np64(O[:1]), np64(dOr[:1]),
                                         np64(lse[:1]), r * T, c * T, True, scale)
-        for got, ref, name in ((dQ, rQ, "dQ"), (dK, rK, "dK"), (dV, rV, "dV")):
-            assert_close(got[:1], ref, torch.bfloat16, "c3 bwd tile (7,%d) %s" % (c, name))
+        for handover in (False, True):
+            dQ, dK, dV = a2d.partial_bwd(Qd, Kd[c], Vd[c], O, dOd, lse, r * T, c * T, True, scale,
+                                         ds_handover=handover)
+            torch.cuda.synchronize()
+            for got, ref, name in ((dQ, rQ, "dQ"), (dK, rK, "dK"), (dV, rV, "dV")):
+                assert_close(got[:1], ref, torch.bfloat16, "c3 bwd tile (7,%d) %s%s" % (c, name, " (dS hand-over)" if handover else ""))
+            del dQ, dK, dV
 
 
 def test_c3_gathered_row_full_heads(a2d):
@@ -360,7 +365,7 @@ def test_long_context_tiles_sampled(a2d, name):
     # valid sub-problem (gradients couple all rows), so check dQ on sampled query rows (needs all keys
     # of the tile) and dK/dV through their sums over keys, which need only per-row quantities.
     dO0 = synth.do_block(w, 0)
-    dQ, dK, dV = a2d.partial_bwd(Qd, dev(K0), dev(V0), O, dev(dO0), lse, 0, 0, False, scale)
+    dQ, dK, dV = a2d.partial_bwd(Qd, dev(K0), dev(V0), O, dev(dO0), lse, 0, 0, False, scale, ds_handover=True)
     torch.cuda.synchronize()
     sub = rows[:48]
     rQ, _, _ = oracle.partial_bwd(np64(Q0[:1, sub]), np64(K0[:1]), np64(V0[:1]), np64(O[:1, sub]), np64(dO0[:1, sub]),
