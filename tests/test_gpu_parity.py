@@ -402,6 +402,8 @@ SEG_CASES = [
     (2, 130, 128, 0, False, [(5, 70), (0, 190)]),                          # no mask: offsets are irrelevant
     (1, 96, 64, 40, True, [(0, 50), (30, 70)]),                            # generic (H = 64) kernels
     (1, 8, 128, 0, True, [(100, 16), (200, 16)]),                          # nothing visible at all
+    (1, 150, 128, 120, True, [((37 * i) % 256, 8 + (i % 3)) for i in range(32)]),  # the most sub-blocks a call takes
+    (2, 100, 96, 90, True, [(0, 64), (128, 40), (60, 64)]),                 # head size 96 on the MFMA kernels
 ]
 
 
@@ -457,7 +459,7 @@ def test_gathered_tile_fwd_bwd(a2d, dt, case):
 
 # ----------------------------------------------------------------------------- accumulating calls
 @pytest.mark.gpu
-@pytest.mark.parametrize("dt,H", [("bf16", 128), ("f32", 64)])
+@pytest.mark.parametrize("dt,H", [("bf16", 128), ("f32", 64), ("bf16", 96), ("bf16", 80), ("bf16", 64)])
 def test_accumulating_tile_calls(a2d, dt, H):
     """a2d_partial_fwd_acc walks a query block over its key blocks into ONE triple (plain tiles and
     a gathered one); a2d_partial_bwd_acc adds the dQ shares into one buffer."""
