@@ -347,7 +347,9 @@ def grouped_query(a2d, synth, w, scale, kernels):
     dev = lambda t: t.to("cuda")
     Q, dO = dev(synth.q_block(w, r)), dev(synth.do_block(w, r))
     K0, V0 = dev(synth.k_block(w, 0)), dev(synth.v_block(w, 0))
-    ws = torch.empty(w.heads * T * 4 + 256, dtype=torch.uint8, device="cuda")
+    # the workspace size that selects the dS hand-over, as in the timed steps
+    ws = torch.empty(a2d.workspace_bytes(a2d.tile_desc(Q, K0, r * T, 0, True, scale), a2d.OP_PARTIAL_BWD_DS),
+                     dtype=torch.uint8, device="cuda")
 
     def timeit(fn, n=10):
         for _ in range(3):

@@ -87,9 +87,9 @@ typedef struct {
  * A2D_OP_PARTIAL_BWD: the minimum (the per-row sums delta = rowsum(dO o O)).
  * A2D_OP_PARTIAL_BWD_DS: the size from which the backward calls ALSO keep dS (bf16, one value
  * per score: about 2 nq nkv bytes per head) in the workspace, so that dQ is one contraction over
- * the stored dS instead of a second recomputation of S and dP (bf16 inputs, one query head per
- * key/value head, sub-blocks of a gathered tile starting at multiples of 64 keys, less than
- * 4 GiB of dS per head; otherwise the extra bytes are ignored).  Same results up to fp32
+ * the stored dS instead of a second recomputation of S and dP (bf16 inputs, sub-blocks of a
+ * gathered tile starting at multiples of 64 keys, less than 4 GiB of dS per key/value head
+ * - all the query heads of its group together; otherwise the extra bytes are ignored).  Same results up to fp32
  * summation order; faster when the memory is there.
  * `k` is ignored for the tile ops.  Returns 0 for a NULL or invalid descriptor.
  */

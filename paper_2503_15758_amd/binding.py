@@ -74,6 +74,17 @@ def lib():
         L.a2d_partial_fwd_norm.restype = ctypes.c_int
         L.a2d_partial_fwd_norm.argtypes = [ctypes.POINTER(TileDesc), ctypes.c_int, ctypes.POINTER(KvSegment),
                                            vp, vp, vp, vp, fp, vp, ctypes.c_size_t, vp]
+        # (every argument is typed: an untyped Python int travels as a 32-bit C int, and one that lands
+        # on the stack - these calls have more arguments than registers - reaches a size_t parameter
+        # with undefined upper bits)
+        L.a2d_partial_fwd_gqa.restype = ctypes.c_int
+        L.a2d_partial_fwd_gqa.argtypes = [ctypes.POINTER(TileDesc), ctypes.c_int32, ctypes.c_int,
+                                          ctypes.POINTER(KvSegment), ctypes.c_int, vp, vp, vp, vp, fp, fp, vp,
+                                          ctypes.c_size_t, vp]
+        L.a2d_partial_bwd_gqa.restype = ctypes.c_int
+        L.a2d_partial_bwd_gqa.argtypes = [ctypes.POINTER(TileDesc), ctypes.c_int32, ctypes.c_int,
+                                          ctypes.POINTER(KvSegment), ctypes.c_int, vp, vp, vp, vp, vp, fp,
+                                          fp, fp, fp, vp, ctypes.c_size_t, vp]
         L.a2d_fix_norm.restype = ctypes.c_int
         L.a2d_fix_norm.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                    ctypes.POINTER(vp), ctypes.POINTER(vp), vp, fp, vp]
@@ -94,7 +105,9 @@ def lib():
         L.a2d_status_str.restype = ctypes.c_char_p
         L.a2d_status_str.argtypes = [ctypes.c_int]
         L.a2d_last_error.restype = ctypes.c_char_p
+        L.a2d_last_error.argtypes = []
         L.a2d_version.restype = ctypes.c_char_p
+        L.a2d_version.argtypes = []
         _lib = L
     return _lib
 

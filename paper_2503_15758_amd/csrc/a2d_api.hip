@@ -138,6 +138,11 @@ a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
   A2D_TRY(check_ptr(dK_part, who, "dK_part"));
   A2D_TRY(check_ptr(dV_part, who, "dV_part"));
   const size_t need = a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD, 0);
+  // the size decides how much of the workspace is used: a value no allocation can have (a foreign
+  // caller that passed a 32-bit integer for the size_t, leaving the upper half undefined) is refused
+  if (workspace_bytes > ((size_t)1 << 46))
+    return fail(A2D_ERR_INVALID_ARG, "%s: workspace_bytes = %zu is not a plausible size (size_t expected)", who,
+                workspace_bytes);
   if (!workspace || workspace_bytes < need)
     return fail(A2D_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need,
                 workspace ? workspace_bytes : (size_t)0);

@@ -269,7 +269,6 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ delta, float* __restrict__ dK, float* __restrict__ dV,
     bf16_t* __restrict__ dS) {
-  static_assert(!(GROUPED && WRITE_DS), "the dS hand-over is built for one query head per key/value head");
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
   int head, blk;
@@ -437,7 +436,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   const unsigned ds_lane_off = (unsigned)(2 * blk + (pair >> 1)) * DS_TILE_BYTES + (pair & 1) * 2048 + lane * 16;
   gwptr_t ds_base = nullptr;
   if constexpr (WRITE_DS)
-    ds_base = uniform_gwptr(reinterpret_cast<char*>(dS) + (int64_t)head * ds_head_bytes(d.nq, d.nkv));
+    ds_base = uniform_gwptr(reinterpret_cast<char*>(dS) + (int64_t)head * group * ds_head_bytes(d.nq, d.nkv));
 
   // A step is skipped (by both wavefronts of its pair) when none of its rows sees any of the
   // pair's keys; it is masked unless every row sees every key.
@@ -449,6 +448,9 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   };
   int cs = 0;                                                   // s of the iteration's step j
   auto next_s = [&](int s) { return (GROUPED && s + 1 == nsteps) ? 0 : s + 1; };
+  int c_rt = i_start / BQ;                                      // dS row tile of step j, counted over the group's heads
+  // (a head's steps end at its last row tile; the next head's start i_start / BQ tiles into its own)
+  auto next_rt = [&](int rt, int s) { return (GROUPED && s + 1 == nsteps) ? rt + 1 + i_start / BQ : rt + 1; };
   auto advance = [&](int slot_delta) {   // to this wave's next step: tile buffer and mailbox slot
     const int adv = (cur == DK_NBUF - 1) ? -(DK_NBUF - 1) : 1;
     cur += adv;
@@ -497,6 +499,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   } else if (nsteps > 0) {
     f32x16 dp = zero16();   // dP - delta of the step whose dS, dK come next iteration
     int ps = 0;             // s of step j - 1
+    int p_rt = 0;           // and its dS row tile
     auto iteration = [&](int j, auto set_tag) {
       constexpr int SET = decltype(set_tag)::value;
       store_step((j + 2) % DK_NBUF, set_tag);
@@ -519,12 +522,14 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
         if constexpr (WRITE_DS) {
           // (measured: making these stores unconditional - skipped steps writing to a spill slot,
           // which keeps the compiler's load wait counts exact - is not faster)
-          const unsigned off = (unsigned)(i_start / BQ + ps) * ds_row_stride + ds_lane_off;
+          const unsigned off = (unsigned)p_rt * ds_row_stride + ds_lane_off;
           gstore_b128(ds_base, off, ds_out[0]);
           gstore_b128(ds_base, off + 1024, ds_out[1]);
         }
       }
       advance(SET ? DK_MBOX_SLOT : -DK_MBOX_SLOT);
+      p_rt = c_rt;
+      c_rt = next_rt(c_rt, cs);
       ps = cs;
       cs = next_s(cs);
       if (active(j, ps)) {
@@ -843,13 +848,17 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
   constexpr int DQ_ROWS = 32 * WAVES, DQ_THREADS = 64 * WAVES;
   constexpr int HD = padded_head(HR), H = HR, CT = HD / 32;
   const int nqb = (d.nq + DQ_ROWS - 1) / DQ_ROWS;
-  int head, blk;
-  if (!xcd_map(d.heads, nqb, head, blk)) return;
+  // placement as in bwd_dq_kernel (grouped heads: the query heads of a key/value head share an XCD)
+  int unit, blk;
+  const int per_unit = g.group / g.split;
+  if (!xcd_map(d.heads / per_unit, per_unit * nqb, unit, blk)) return;
+  const int head = unit * per_unit + blk / nqb, kvh = head / g.group;
+  blk %= nqb;
   const int q0 = (nqb - 1 - blk) * DQ_ROWS;            // heavy blocks first under a causal mask
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31;
-  K += (int64_t)head * d.nkv * H;
+  K += (int64_t)kvh * d.nkv * H;
 
   DsqCtx<HD> cx;
   cx.half = lane >> 5;
@@ -994,14 +1003,14 @@ bool bwd_mfma_supported(const a2d_tile_desc& d) {
   return d.dtype == A2D_BF16 && (d.hdim == 128 || d.hdim == 96 || d.hdim == 80 || d.hdim == 64);
 }
 
-// Bytes of the dS workspace of a tile (0 when the hand-over does not apply: grouped heads, a
-// sub-block that does not start at a multiple of 64 keys, or more than 4 GiB per head)
+// Bytes of the dS workspace of a tile (0 when the hand-over does not apply: a sub-block that does
+// not start at a multiple of 64 keys, or 4 GiB or more per key/value head)
 size_t bwd_ds_bytes(const a2d_tile_desc& d, const SegList& g) {
-  if (!bwd_mfma_supported(d) || g.group != 1) return 0;
+  if (!bwd_mfma_supported(d)) return 0;
   for (int s = 0; s < g.n; ++s)
     if (g.start[s] % 64 != 0) return 0;
   const size_t per_head = ds_head_bytes(d.nq, d.nkv);
-  if (per_head >= ((size_t)1 << 32)) return 0;
+  if (per_head * (size_t)g.group >= ((size_t)1 << 32)) return 0;   // 32-bit offsets inside a key/value head's share
   return per_head * (size_t)d.heads;
 }
 
@@ -1011,7 +1020,9 @@ hipError_t bwd_launch_ds(const a2d_tile_desc& d, const SegList& g, const void* Q
                          const void* dO, const float* lse, const float* delta, float* dQ, float* dK,
                          float* dV, void* ds_ws, hipStream_t s) {
   constexpr int DSQ_LDS = 2 * DUAL64_BYTES;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, true>),
+  const bool grouped = g.group > 1;
+  hipError_t e = hipFuncSetAttribute(grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, true>)
+                                             : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, true>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, DK_LDS);
   if (e != hipSuccess) return e;
   int dev = 0, cus = 0;
@@ -1023,12 +1034,18 @@ hipError_t bwd_launch_ds(const a2d_tile_desc& d, const SegList& g, const void* Q
                               : reinterpret_cast<const void*>(bwd_dq_ds_kernel<4, HR>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, DSQ_LDS);
   if (e != hipSuccess) return e;
-  dim3 grid_kv(xcd_grid(d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS));
+  dim3 grid_kv(xcd_grid(d.heads / g.group, (d.nkv + DK_KEYS - 1) / DK_KEYS));
   const int dq_rows = big ? 256 : 128;
-  dim3 grid_q(xcd_grid(d.heads, (d.nq + dq_rows - 1) / dq_rows));
-  hipLaunchKernelGGL((bwd_dkdv_kernel<HR, false, true>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g,
-                     (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV,
-                     (bf16_t*)ds_ws);
+  const int per_unit = g.group / g.split;
+  dim3 grid_q(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + dq_rows - 1) / dq_rows)));
+  if (grouped)
+    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, true, true>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g,
+                       (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV,
+                       (bf16_t*)ds_ws);
+  else
+    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, false, true>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g,
+                       (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV,
+                       (bf16_t*)ds_ws);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (big)

@@ -666,7 +666,12 @@ def test_grouped_query_heads(a2d, dt, case):
     lse_in = torch.from_numpy(lser).to(torch.float32)
     dQ, dK, dV = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, kv_off, causal,
                                  scale, segments=segs)
+    # with the larger workspace (bf16: dS handed from the dK/dV kernel to the dQ kernel, per query head)
+    dQh, dKh, dVh = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, kv_off, causal,
+                                    scale, segments=segs, ds_handover=True)
     torch.cuda.synchronize()
+    assert torch.equal(dKh, dK) and torch.equal(dVh, dV), what + ": dK / dV with the larger workspace differ"
+    assert_close(dQh, np64(dQ), DT[dt], what + " dQ with the larger workspace", rel=False)
     assert dK.shape == K.shape and dV.shape == V.shape
     with np.errstate(invalid="ignore"):
         rq, rk, rv = oracle.partial_bwd_pos(np64(Q), Kr, Vr, np64(O_in), np64(dO), np64(lse_in), q_off, kpos,

@@ -185,9 +185,36 @@ def test_grouped_query_argument_errors(binding):
     assert bwd(heads + 1, 0) == -1
     assert bwd(1, b.TILE_NORMALISED) == -1                        # the backward has no normalised form
     assert bwd(1, 0) == -4                                        # first failing check: the workspace
+    assert L.a2d_partial_bwd_gqa(ctypes.byref(d), 1, 0, None, 0, P, P, P, P, P, P, P, P, P, P, 1 << 50, None) == -1
+    assert b"plausible" in L.a2d_last_error()                    # a size no allocation can have
     big = _desc(b, nq=1 << 22)
     big.heads = 4
     assert L.a2d_partial_fwd_gqa(ctypes.byref(big), 2, 0, None, 0, P, P, P, P, P, P, None, 0, None) == -1
     assert b"2^22" in L.a2d_last_error()
     too = _desc(b, nq=(1 << 22) + 1)
     assert L.a2d_partial_fwd(ctypes.byref(too), P, P, P, P, P, P, None, 0, None) == -1
+
+
+def test_every_export_has_typed_arguments(binding):
+    """ctypes passes an untyped Python int as a 32-bit C int; as a stack argument that leaves the
+    upper half of a size_t parameter (a workspace size) undefined.  Every export must therefore
+    declare its argument and result types, with as many arguments as the header's prototype."""
+    import re
+    L = binding.lib()
+    header = open(os.path.join(ROOT, "include", "a2d.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    for name in binding.EXPORTS:
+        fn = getattr(L, name)
+        assert fn.argtypes is not None, name + ": argtypes not declared in the binding"
+        assert fn.restype is not ctypes.c_int or name.startswith("a2d_"), name
+        m = re.search(r"\b%s\s*\(([^;]*?)\)\s*;" % name, header, flags=re.S)
+        assert m, name + ": prototype not found in include/a2d.h"
+        params = m.group(1).strip()
+        n = 0 if params in ("", "void") else params.count(",") + 1
+        assert len(fn.argtypes) == n, "%s: %d argument types declared, the header has %d" % (name, len(fn.argtypes), n)
+        # sizes travel as size_t, row counts as int64
+        for i, p_ in enumerate(x.strip() for x in params.split(",")) if n else []:
+            if p_.startswith("size_t"):
+                assert fn.argtypes[i] is ctypes.c_size_t, "%s: argument %d must be c_size_t" % (name, i)
+            if p_.startswith("int64_t"):
+                assert fn.argtypes[i] is ctypes.c_int64, "%s: argument %d must be c_int64" % (name, i)
