@@ -226,6 +226,39 @@ def main():
         "attnfix_gbs": kernels["fix"]["achieved"], "attnfix_frac_hbm": kernels["fix"]["frac"],
         "roofline": roofline, "kernels": kernels,
     }
+    if not args.no_gathered and w.backward and len(tiles) == 2:
+        # the same step with the two backward tile calls on two streams (their own workspaces): the
+        # HBM-bound dQ-from-dS kernel of one tile then runs beside the MFMA-bound dK/dV kernel of the other
+        side = torch.cuda.Stream()
+        ws2 = torch.empty_like(ws)
+        fork, join = torch.cuda.Event(), torch.cuda.Event()
+        (c_a, _), (c_b, _) = tiles
+
+        def step_two_streams():
+            for name, fn in calls:
+                if name.startswith("partial_bwd_") and name.endswith("full"):
+                    fork.record()
+                    side.wait_event(fork)
+                    with torch.cuda.stream(side):
+                        a2d.partial_bwd(Q, Kc[c_b], Vc[c_b], O, dO, lse, r * T, c_b * T, w.causal, scale,
+                                        out=(dq_parts[c_b], dk_parts[1], dv_parts[1]), workspace=ws2)
+                        join.record()
+                elif name == "fix_bwd_dq":
+                    torch.cuda.current_stream().wait_event(join)
+                    fn()
+                else:
+                    fn()
+
+        for _ in range(args.warmup):
+            step_two_streams()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_two_streams()
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t0) * 1e3 / args.steps
+        result["two_stream_step"] = {"ms_per_step": round(ms2, 4), "tflops": round(total_flops / (ms2 * 1e-3) / 1e12, 2),
+                                     "what": "the timed step with its two backward tile calls on two streams"}
     if not args.no_gathered and w.causal and w.name == "c3":
         result["gathered"] = gathered_tile(a2d, synth, w, scale, kernels)
     if not args.no_gathered and w.name == "c3":
