@@ -226,6 +226,28 @@ def main():
         "attnfix_gbs": kernels["fix"]["achieved"], "attnfix_frac_hbm": kernels["fix"]["frac"],
         "roofline": roofline, "kernels": kernels,
     }
+    if not args.no_gathered:
+        # the same step replayed from a HIP graph (the calls only enqueue kernels, so a step captures as is)
+        side_g = torch.cuda.Stream()
+        side_g.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side_g):
+            step()
+        torch.cuda.current_stream().wait_stream(side_g)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side_g):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        msg = (time.perf_counter() - t0) * 1e3 / args.steps
+        result["hip_graph_step"] = {"ms_per_step": round(msg, 4), "tflops": round(total_flops / (msg * 1e-3) / 1e12, 2),
+                                    "launches_per_step": len(calls) + (2 * len(tiles) if w.backward else 0),
+                                    "what": "the timed step captured once into a HIP graph and replayed"}
     if not args.no_gathered and w.backward and len(tiles) == 2:
         # the same step with the two backward tile calls on two streams (their own workspaces): the
         # HBM-bound dQ-from-dS kernel of one tile then runs beside the MFMA-bound dK/dV kernel of the other

@@ -757,3 +757,58 @@ def test_generic_kernels_on_bf16_inputs(a2d, H, monkeypatch):
     assert_close(dQ, rq, torch.bfloat16, "generic bf16 dQ")
     assert_close(dK, rk, torch.bfloat16, "generic bf16 dK")
     assert_close(dV, rv, torch.bfloat16, "generic bf16 dV")
+
+
+# ----------------------------------------------------------------------------- HIP graph capture
+@pytest.mark.gpu
+def test_step_replays_from_a_hip_graph(a2d):
+    """The calls only enqueue kernels on the given stream (no allocation, no memset, no
+    synchronisation), so a whole step - tiles, merge, gradient tiles, gradient sums - can be
+    captured into a HIP graph.  Several replays, with eager work and synchronisations between
+    them, must each reproduce the eager results bit for bit."""
+    heads, T, H, G = 2, 256, 128, 2
+    scale = 1.0 / math.sqrt(H)
+    r = G - 1
+    Q = dev(synth.normal((heads, T, H), 91, 0, 1.0, "bf16"))
+    dO = dev(synth.normal((heads, T, H), 91, 1, 1.0, "bf16"))
+    Ks = [dev(synth.normal((heads, T, H), 91, 10 + c, 1.0, "bf16")) for c in range(G)]
+    Vs = [dev(synth.normal((heads, T, H), 91, 20 + c, 1.0, "bf16")) for c in range(G)]
+    f32 = dict(dtype=torch.float32, device="cuda")
+    parts = [(torch.empty(heads, T, H, **f32), torch.empty(heads, T, **f32), torch.empty(heads, T, **f32)) for _ in range(G)]
+    grads = [(torch.empty(heads, T, H, **f32), torch.empty(heads, T, H, **f32), torch.empty(heads, T, H, **f32)) for _ in range(G)]
+    O = torch.empty(heads, T, H, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(heads, T, **f32)
+    dQ = torch.empty(heads, T, H, dtype=torch.bfloat16, device="cuda")
+    d = a2d.tile_desc(Q, Ks[0], 0, 0, True, scale)
+    ws = [torch.empty(a2d.workspace_bytes(d, a2d.OP_PARTIAL_BWD_DS if c == 0 else a2d.OP_PARTIAL_BWD),
+                      dtype=torch.uint8, device="cuda") for c in range(G)]          # both backward paths
+    outs = [O, lse, dQ] + [t for p in parts for t in p] + [t for g_ in grads for t in g_]
+
+    def step():
+        for c in range(G):
+            a2d.partial_fwd(Q, Ks[c], Vs[c], r * T, c * T, True, scale, out=parts[c])
+        a2d.fix([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], out=(O, lse))
+        for c in range(G):
+            a2d.partial_bwd(Q, Ks[c], Vs[c], O, dO, lse, r * T, c * T, True, scale, out=grads[c], workspace=ws[c])
+        a2d.fix_bwd([g_[0] for g_ in grads], out=dQ)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in outs]
+    side = torch.cuda.Stream()                 # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                 # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for replay in range(3):
+        for t in outs:
+            t.fill_(float("nan")) if t.is_floating_point() else t.zero_()    # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(outs, want):
+            assert torch.equal(got, ref), "replay %d differs from the eager step" % replay
