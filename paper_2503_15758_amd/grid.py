@@ -108,7 +108,9 @@ def backward(Q, K, V, O, dO, lse, grid, causal=True, layout="cyclic", scale=None
     Qb, Kb, Vb, Ob, dOb, lb = gather(Q), gather(K), gather(V), gather(O), gather(dO), gather(lse)
     f32 = dict(dtype=torch.float32, device=Q.device)
     tiles = _tiles(grid, causal, layout)
-    parts = {t: tuple(torch.empty(heads, T, H, **f32) for _ in range(3)) for t in tiles}
+    kvh = K.shape[0]                                   # fewer than `heads` with grouped-query heads
+    parts = {t: (torch.empty(heads, T, H, **f32), torch.empty(kvh, T, H, **f32), torch.empty(kvh, T, H, **f32))
+             for t in tiles}
     st = _Streams(streams)
     # one workspace per stream: calls that share a workspace must be ordered on one stream
     need = a2d.workspace_bytes(a2d.tile_desc(Qb[0], Kb[0], 0, 0, causal, scale),

@@ -546,6 +546,33 @@ def test_grid_emulation_matches_full_attention(a2d, layout, dt, H, grid):
     assert torch.equal(O, O1) and torch.equal(lse, lse1)
 
 
+@pytest.mark.gpu
+def test_grid_emulation_grouped_query_heads(a2d):
+    """The whole grid (cyclic layout, several streams) with 4 query heads on 2 key/value heads
+    against full causal attention on the repeated K, V; dK, dV summed over each group."""
+    from paper_2503_15758_amd import grid as g2d
+    heads, kvh, grid, H, dt = 4, 2, 3, 128, "bf16"
+    n, grp = 128 * grid, heads // kvh
+    scale = 1.0 / math.sqrt(H)
+    Q, dO = synth.normal((heads, n, H), 53, 0, 1.0, dt), synth.normal((heads, n, H), 53, 3, 1.0, dt)
+    K, V = synth.normal((kvh, n, H), 53, 1, 1.0, dt), synth.normal((kvh, n, H), 53, 2, 1.0, dt)
+    Kr, Vr = np.repeat(np64(K), grp, axis=0), np.repeat(np64(V), grp, axis=0)
+    O, lse = g2d.forward(dev(Q), dev(K), dev(V), grid, True, "cyclic", scale, streams=2)
+    torch.cuda.synchronize()
+    Or, lr = oracle.attention_fwd(np64(Q), Kr, Vr, scale, True)
+    assert_close(O, Or, DT[dt], "gqa grid O")
+    assert_close(lse, lr, DT[dt], "gqa grid lse", rel=False)
+    O_in, lse_in = torch.from_numpy(Or).to(DT[dt]), torch.from_numpy(lr).to(torch.float32)
+    dQ, dK, dV = g2d.backward(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), grid, True, "cyclic", scale,
+                              streams=2)
+    torch.cuda.synchronize()
+    assert dK.shape == K.shape and dV.shape == V.shape
+    rq, rk, rv = oracle.attention_bwd(np64(Q), Kr, Vr, np64(dO), scale, True)
+    assert_close(dQ, rq, DT[dt], "gqa grid dQ")
+    assert_close(dK, rk.reshape(kvh, grp, n, H).sum(axis=1), DT[dt], "gqa grid dK")
+    assert_close(dV, rv.reshape(kvh, grp, n, H).sum(axis=1), DT[dt], "gqa grid dV")
+
+
 # ----------------------------------------------------------------------------- dS hand-over
 DS_CASES = [
     # heads, nq, nkv, H, q_off, kv_off, causal, segments (starts at multiples of 64 keys)
