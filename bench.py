@@ -468,14 +468,14 @@ def grid_emulation(synth):
 
 def cpu_baseline(w, scale):
     """The fp64 oracle, as it stands, on the host cores: partial forward + AttnFix (k = 1) + partial
-    backward of an unmasked tile for a bounded number of heads (about 6e11 algorithmic FLOPs, some
-    10-20 s on 16 cores)."""
+    backward of an unmasked tile for a bounded number of heads (about 1.2e12 algorithmic FLOPs, some
+    15 s on 16 cores)."""
     import oracle
     from paper_2503_15758_amd import synth
     T, H = w.tile, w.hdim
     per_head = (14.0 if w.backward else 4.0) * T * T * H
-    nh = int(max(1, min(w.heads, round(6.0e11 / per_head))))
-    nq_s = T if per_head <= 6.0e11 else max(64, int(6.0e11 / ((14.0 if w.backward else 4.0) * T * H)))
+    nh = int(max(1, min(w.heads, round(1.2e12 / per_head))))
+    nq_s = T if per_head <= 1.2e12 else max(64, int(1.2e12 / ((14.0 if w.backward else 4.0) * T * H)))
     sub = synth.Workload(w.name, w.dtype, nh, H, w.seq, w.grid, w.causal, w.backward, w.sigma_qk, w.seed)
     n64 = lambda t: t.double().numpy()
     Q = n64(synth.q_block(sub, w.grid - 1, nq_s)); K = n64(synth.k_block(sub, 0)); V = n64(synth.v_block(sub, 0))
