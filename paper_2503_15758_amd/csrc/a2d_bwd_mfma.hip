@@ -23,9 +23,12 @@
 //                    SIMD; walks the key blocks, 64 keys per step.  S^T = K Q^T
 //                    and dP^T = V dO^T leave a lane holding ONE query column;
 //                    dQ^T += K^T dS^T with K^T from the LDS transpose read.
+//   bwd_dq_ds_kernel owns query rows like bwd_dq_kernel, but reads dS from a workspace the
+//                    dK/dV kernel filled (its WRITE_DS variant) and only contracts it with K:
+//                    used when the caller's workspace is large enough, so that S and dP are
+//                    computed once (5 contractions for 5 counted ones instead of 7).
 // Tiles that are read both ways (natural and transposed fragments) live in the "dual" LDS
-// layout of a2d_mfma.hpp: every fragment address is a per-lane base plus an immediate.  The
-// score recomputation is done in both kernels (7 contractions for 5 counted ones).
+// layout of a2d_mfma.hpp: every fragment address is a per-lane base plus an immediate.
 #include <type_traits>
 
 #include "a2d_mfma.hpp"
