@@ -226,7 +226,14 @@ def main():
         "attnfix_gbs": kernels["fix"]["achieved"], "attnfix_frac_hbm": kernels["fix"]["frac"],
         "roofline": roofline, "kernels": kernels,
     }
-    if not args.no_gathered:
+    # ---- extra measurements after the timed steps; none of them may cost the line above
+    def extra(key, fn):
+        try:
+            result[key] = fn()
+        except Exception as e:                       # report and go on
+            result[key] = {"error": "%s: %s" % (type(e).__name__, str(e)[:200])}
+
+    def graph_step():
         # the same step replayed from a HIP graph (the calls only enqueue kernels, so a step captures as is)
         side_g = torch.cuda.Stream()
         side_g.wait_stream(torch.cuda.current_stream())
@@ -245,10 +252,11 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         msg = (time.perf_counter() - t0) * 1e3 / args.steps
-        result["hip_graph_step"] = {"ms_per_step": round(msg, 4), "tflops": round(total_flops / (msg * 1e-3) / 1e12, 2),
-                                    "launches_per_step": len(calls) + (2 * len(tiles) if w.backward else 0),
-                                    "what": "the timed step captured once into a HIP graph and replayed"}
-    if not args.no_gathered and w.backward and len(tiles) == 2:
+        return {"ms_per_step": round(msg, 4), "tflops": round(total_flops / (msg * 1e-3) / 1e12, 2),
+                "launches_per_step": len(calls) + (2 * len(tiles) if w.backward else 0),
+                "what": "the timed step captured once into a HIP graph and replayed"}
+
+    def two_stream_step():
         # the same step with the two backward tile calls on two streams (their own workspaces): the
         # HBM-bound dQ-from-dS kernel of one tile then runs beside the MFMA-bound dK/dV kernel of the other
         side = torch.cuda.Stream()
@@ -279,22 +287,29 @@ def main():
             step_two_streams()
         torch.cuda.synchronize()
         ms2 = (time.perf_counter() - t0) * 1e3 / args.steps
-        result["two_stream_step"] = {"ms_per_step": round(ms2, 4), "tflops": round(total_flops / (ms2 * 1e-3) / 1e12, 2),
-                                     "what": "the timed step with its two backward tile calls on two streams"}
-    if not args.no_gathered and w.causal and w.name == "c3":
-        result["gathered"] = gathered_tile(a2d, synth, w, scale, kernels)
-    if not args.no_gathered and w.name == "c3":
-        result["normalised_partials"] = normalised_format(a2d, synth, w, scale, kernels)
-    if not args.no_gathered and w.name == "c3":
-        result["grouped_query"] = grouped_query(a2d, synth, w, scale, kernels)
-    if args.grid_emulation:
-        result["grid_emulation"] = grid_emulation(synth)
-    if not args.no_mfma_probe:
+        return {"ms_per_step": round(ms2, 4), "tflops": round(total_flops / (ms2 * 1e-3) / 1e12, 2),
+                "what": "the timed step with its two backward tile calls on two streams"}
+
+    def mfma_ceiling():
         tf_r, mhz_r = a2d.mfma_ceiling(20000, True)
         tf_c, mhz_c = a2d.mfma_ceiling(20000, False)
-        result["mfma_ceiling"] = {"random_operands": {"tflops": round(tf_r, 1), "shader_mhz": round(mhz_r)},
-                                  "constant_operands": {"tflops": round(tf_c, 1), "shader_mhz": round(mhz_c)},
-                                  "unit": "TFLOP/s", "kind": "MFMA-only probe, register operands"}
+        return {"random_operands": {"tflops": round(tf_r, 1), "shader_mhz": round(mhz_r)},
+                "constant_operands": {"tflops": round(tf_c, 1), "shader_mhz": round(mhz_c)},
+                "unit": "TFLOP/s", "kind": "MFMA-only probe, register operands"}
+
+    if not args.no_gathered:
+        extra("hip_graph_step", graph_step)
+        if w.backward and len(tiles) == 2:
+            extra("two_stream_step", two_stream_step)
+        if w.name == "c3":
+            if w.causal:
+                extra("gathered", lambda: gathered_tile(a2d, synth, w, scale, kernels))
+            extra("normalised_partials", lambda: normalised_format(a2d, synth, w, scale, kernels))
+            extra("grouped_query", lambda: grouped_query(a2d, synth, w, scale, kernels))
+    if args.grid_emulation:
+        extra("grid_emulation", lambda: grid_emulation(synth))
+    if not args.no_mfma_probe:
+        extra("mfma_ceiling", mfma_ceiling)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, scale)
     print(json.dumps(result))
