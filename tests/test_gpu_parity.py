@@ -71,6 +71,7 @@ FWD_CASES = [
     (1, 700, 900, 128, True, 300, 100),      # more keys than queries, offset diagonal
     (2, 150, 200, 80, True, 60, 0),          # the head sizes of the paper's smaller models
     (2, 130, 170, 96, False, 0, 0),
+    (1, 130, 200, 128, True, (1 << 39) + 60, 1 << 39),   # global offsets far beyond 32 bits
 ]
 
 
@@ -143,6 +144,8 @@ BWD_CASES = [
     (1, 700, 900, 128, True, 300, 100),
     (2, 150, 200, 80, True, 60, 0),
     (2, 130, 170, 96, False, 0, 0),
+    (1, 1, 1, 128, False, 0, 0),
+    (1, 130, 200, 128, True, (1 << 39) + 60, 1 << 39),   # global offsets far beyond 32 bits
 ]
 
 
