@@ -109,6 +109,20 @@ a2d_status make_segments(const a2d_tile_desc* d, int nseg, const a2d_kv_segment*
   return A2D_OK;
 }
 
+// Do the blocks of the tile differ in cost?  Under a causal mask the first and the last query row
+// may see different numbers of keys of some sub-block; the kernels then start their workgroups
+// heaviest first over a whole XCD instead of head by head.
+int blocks_differ(const a2d_tile_desc* d, const a2d::SegList& g) {
+  if (!d->causal) return 0;
+  auto vis = [&](int64_t i, int s) -> int64_t {
+    const int64_t v = i + g.rel[s] + 1;
+    return v <= 0 ? 0 : (v < g.rows[s] ? v : g.rows[s]);
+  };
+  for (int s = 0; s < g.n; ++s)
+    if (vis(0, s) != vis(d->nq - 1, s)) return 1;
+  return 0;
+}
+
 a2d_status partial_fwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, const void* Q, const void* K,
                             const void* V, float* O_part, float* m, float* l, void* stream,
                             const char* who) {
@@ -119,8 +133,11 @@ a2d_status partial_fwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
   A2D_TRY(check_ptr(m, who, "m"));
   A2D_TRY(check_ptr(l, who, "l"));
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (!force_generic() && a2d::fwd_mfma_supported(*desc))
-    return hip_result(a2d::launch_fwd_mfma(*desc, g, Q, K, V, O_part, m, l, s), who);
+  if (!force_generic() && a2d::fwd_mfma_supported(*desc)) {
+    a2d::SegList go = g;
+    go.by_size = blocks_differ(desc, g);
+    return hip_result(a2d::launch_fwd_mfma(*desc, go, Q, K, V, O_part, m, l, s), who);
+  }
   return hip_result(a2d::launch_fwd_generic(*desc, g, Q, K, V, O_part, m, l, s), who);
 }
 
@@ -155,7 +172,9 @@ a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
     // a workspace large enough for dS as well switches to the hand-over path
     const size_t ds_bytes = a2d::bwd_ds_bytes(*desc, g);
     void* ds_ws = (ds_bytes > 0 && workspace_bytes >= need + ds_bytes) ? static_cast<char*>(workspace) + need : nullptr;
-    return hip_result(a2d::launch_bwd_mfma(*desc, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
+    a2d::SegList go = g;
+    go.by_size = blocks_differ(desc, g);
+    return hip_result(a2d::launch_bwd_mfma(*desc, go, Q, K, V, dO, lse, delta, dQ_part, dK_part,
                                            dV_part, ds_ws, s), who);
   }
   return hip_result(a2d::launch_bwd_generic(*desc, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,

@@ -277,7 +277,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   int head, blk;
   // `head` is the KEY/VALUE head; its g.group query heads are consecutive rows of Q, dO, lse, delta
   const int group = GROUPED ? g.group : 1;
-  if (!xcd_map(GROUPED ? d.heads / group : d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS, head, blk)) return;
+  if (!xcd_map(GROUPED ? d.heads / group : d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS, g.by_size != 0, head, blk)) return;
   constexpr int HD = padded_head(HR), H = HR, KS = HD / 16, CT = HD / 32;
   const int k0 = blk * DK_KEYS;
   const int tid = threadIdx.x;
@@ -649,9 +649,10 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   // XCDs, an equal share of the heads each, when that is what spreads the load evenly)
   int unit, blk;
   const int per_unit = g.group / g.split;
-  if (!xcd_map(d.heads / per_unit, per_unit * nqb, unit, blk)) return;
-  const int head = unit * per_unit + blk / nqb, kvh = head / g.group;
-  blk %= nqb;
+  if (!xcd_map(d.heads / per_unit, per_unit * nqb, g.by_size != 0, unit, blk)) return;
+  // (blocks numbered by size first when the workgroups are ordered by size)
+  const int head = unit * per_unit + (g.by_size ? blk % per_unit : blk / nqb), kvh = head / g.group;
+  blk = g.by_size ? blk / per_unit : blk % nqb;
   const int q0 = (nqb - 1 - blk) * DQ_ROWS;            // heavy blocks first under a causal mask
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -854,9 +855,10 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
   // placement as in bwd_dq_kernel (grouped heads: the query heads of a key/value head share an XCD)
   int unit, blk;
   const int per_unit = g.group / g.split;
-  if (!xcd_map(d.heads / per_unit, per_unit * nqb, unit, blk)) return;
-  const int head = unit * per_unit + blk / nqb, kvh = head / g.group;
-  blk %= nqb;
+  if (!xcd_map(d.heads / per_unit, per_unit * nqb, g.by_size != 0, unit, blk)) return;
+  // (blocks numbered by size first when the workgroups are ordered by size)
+  const int head = unit * per_unit + (g.by_size ? blk % per_unit : blk / nqb), kvh = head / g.group;
+  blk = g.by_size ? blk / per_unit : blk % nqb;
   const int q0 = (nqb - 1 - blk) * DQ_ROWS;            // heavy blocks first under a causal mask
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;

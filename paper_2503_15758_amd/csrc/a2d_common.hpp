@@ -45,12 +45,15 @@ template <> struct dtype_of<bf16_t> { static constexpr int value = A2D_BF16; };
 // key/value head h / group; K, V, dK, dV have heads / group heads).  `split` divides `group`:
 // kernels that own query blocks place the query heads of a key/value head on XCDs in `split`
 // separate runs (1 = all of them on one XCD; chosen by group_split()).
+// `by_size` != 0: the blocks of the tile differ in cost (a causal mask crosses it); the kernels then
+// order their workgroups by block, heaviest first, over a whole XCD (see xcd_map).
 struct SegList {
   int n;
   int acc;
   int norm;
   int group;
   int split;
+  int by_size;
   int start[A2D_MAX_SEGMENTS];
   int rows[A2D_MAX_SEGMENTS];
   int64_t rel[A2D_MAX_SEGMENTS];

@@ -162,9 +162,10 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   // XCDs, an equal share of the heads each, when that is what spreads the load evenly)
   int unit, blk;
   const int per_unit = g.group / g.split;
-  if (!xcd_map(d.heads / per_unit, per_unit * nqb, unit, blk)) return;
-  const int head = unit * per_unit + blk / nqb, kvh = head / g.group;
-  blk %= nqb;
+  if (!xcd_map(d.heads / per_unit, per_unit * nqb, g.by_size != 0, unit, blk)) return;
+  // (blocks numbered by size first when the workgroups are ordered by size)
+  const int head = unit * per_unit + (g.by_size ? blk % per_unit : blk / nqb), kvh = head / g.group;
+  blk = g.by_size ? blk / per_unit : blk % nqb;
   // heavy (late) query blocks first: under a causal mask they walk more key blocks
   const int q0 = (nqb - 1 - blk) * BM;
   const int tid = threadIdx.x;

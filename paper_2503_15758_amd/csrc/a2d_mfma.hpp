@@ -121,18 +121,31 @@ __device__ __forceinline__ int dual_store_off(int r, int c) { return r * DUAL_LD
 
 // XCD-aware work mapping.  MI355X has 8 XCDs, each with its own L2, and hands consecutive
 // workgroup ids to consecutive XCDs (id % 8).  All blocks of one head read the same K / V (or
-// Q / dO) rows, so they are placed on ONE XCD, back to back in its dispatch order: the k-th
-// workgroup of XCD x (id = 8 k + x) works on head 8 * (k / nblocks) + x, block k % nblocks.
+// Q / dO) rows, so they are placed on ONE XCD.  Two orders inside an XCD (k-th workgroup of XCD x,
+// id = 8 k + x):
+//   by head  (by_size = false): head 8 * (k / nblocks) + x, block k % nblocks - a head's blocks run
+//            back to back and share its rows in L2; used when all blocks cost the same;
+//   by block (by_size = true):  head 8 * (k % hpx) + x, block k / hpx (hpx = heads per XCD) - block
+//            b of every head before any block b + 1.  The callers number the blocks heaviest first,
+//            so under a causal mask that crosses the tile the workgroups start longest first over
+//            the whole XCD and its compute units finish together (diagonal forward tile -9 %); the
+//            heads' rows then share L2 less (unmasked tile +2-3 %, which is why it is not the default).
 // Grid size: 8 * ceil(heads / 8) * nblocks; workgroups whose head is out of range exit.
 constexpr int kXcds = 8;
 __host__ __device__ inline int xcd_grid(int heads, int nblocks) {
   return kXcds * ((heads + kXcds - 1) / kXcds) * nblocks;
 }
-__device__ __forceinline__ bool xcd_map(int heads, int nblocks, int& head, int& block) {
+__device__ __forceinline__ bool xcd_map(int heads, int nblocks, bool by_size, int& head, int& block) {
   const int id = blockIdx.x;
   const int x = id % kXcds, k = id / kXcds;
-  head = kXcds * (k / nblocks) + x;
-  block = k % nblocks;
+  if (by_size) {
+    const int hpx = (heads + kXcds - 1) / kXcds;
+    head = kXcds * (k % hpx) + x;
+    block = k / hpx;
+  } else {
+    head = kXcds * (k / nblocks) + x;
+    block = k % nblocks;
+  }
   return head < heads;
 }
 
