@@ -109,18 +109,20 @@ a2d_status make_segments(const a2d_tile_desc* d, int nseg, const a2d_kv_segment*
   return A2D_OK;
 }
 
-// Do the blocks of the tile differ in cost?  Under a causal mask the first and the last query row
-// may see different numbers of keys of some sub-block; the kernels then start their workgroups
-// heaviest first over a whole XCD instead of head by head.
+// Do the blocks of the tile differ much in cost?  Under a causal mask the last query row may see
+// many more keys than the first (at least twice as many: a tile the diagonal crosses); the kernels
+// then start their workgroups heaviest first over a whole XCD instead of head by head.  (A
+// gathered key row whose last sub-block alone is cut by the diagonal stays head by head: its
+// blocks cost nearly the same and the heads' rows are worth more in L2.)
 int blocks_differ(const a2d_tile_desc* d, const a2d::SegList& g) {
   if (!d->causal) return 0;
   auto vis = [&](int64_t i, int s) -> int64_t {
     const int64_t v = i + g.rel[s] + 1;
     return v <= 0 ? 0 : (v < g.rows[s] ? v : g.rows[s]);
   };
-  for (int s = 0; s < g.n; ++s)
-    if (vis(0, s) != vis(d->nq - 1, s)) return 1;
-  return 0;
+  int64_t first = 0, last = 0;
+  for (int s = 0; s < g.n; ++s) { first += vis(0, s); last += vis(d->nq - 1, s); }
+  return last >= 2 * first && last > first;
 }
 
 a2d_status partial_fwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, const void* Q, const void* K,
