@@ -35,14 +35,15 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # their kernels (partial_bwd = delta + dK/dV + dQ kernels).  Only the default workload was counted.
 # The default backward hands dS (bf16, 2 bytes per visible score) from the dK/dV kernel to the dQ
 # kernel through the workspace: bytes traded for the dQ kernel's recomputation of S and dP; the
-# "_recompute" entries are the --recompute-bwd path (traffic = the algorithmic minimum).
+# "_recompute" entries are the --recompute-bwd path (traffic = the algorithmic minimum for the unmasked
+# tile; the diagonal tiles order their workgroups by size and share their inputs in L2 less).
 MIB = float(1 << 20)
 TRAFFIC_BYTES = {"c3": {
-    "partial_fwd_diag": (289.4 + 211.4) * MIB, "partial_fwd_full": (289.4 + 211.4) * MIB,
-    "partial_bwd_diag": (192.0 + 387.2 + 1812.8 + 1.5 + 1932.0 + 192.0) * MIB,
-    "partial_bwd_full": (192.0 + 387.2 + 3273.6 + 1.5 + 3456.5 + 194.0) * MIB,
-    "partial_bwd_diag_recompute": (192.0 + 387.5 + 400.8 + 1.5 + 384.0 + 193.0) * MIB,
-    "partial_bwd_full_recompute": (192.0 + 387.5 + 400.8 + 1.5 + 384.0 + 193.0) * MIB,
+    "partial_fwd_diag": (909.1 + 195.6) * MIB, "partial_fwd_full": (288.1 + 228.2) * MIB,
+    "partial_bwd_diag": (192.0 + 1459.7 + 2076.8 + 1.5 + 1932.1 + 193.2) * MIB,
+    "partial_bwd_full": (192.0 + 387.2 + 3269.5 + 1.5 + 3456.3 + 193.1) * MIB,
+    "partial_bwd_diag_recompute": (192.0 + 1459.9 + 963.9 + 1.5 + 384.3 + 192.2) * MIB,
+    "partial_bwd_full_recompute": (192.0 + 387.2 + 387.2 + 1.5 + 384.1 + 192.9) * MIB,
     "fix": (1632.1 + 97.5) * MIB, "fix_bwd_dq": (1536.0 + 96.0) * MIB,
     "fix_bwd_dk": (1536.0 + 96.0) * MIB, "fix_bwd_dv": (1536.0 + 96.0) * MIB}}
 
