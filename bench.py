@@ -39,11 +39,11 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # tile; the diagonal tiles order their workgroups by size and share their inputs in L2 less).
 MIB = float(1 << 20)
 TRAFFIC_BYTES = {"c3": {
-    "partial_fwd_diag": (909.1 + 195.6) * MIB, "partial_fwd_full": (288.1 + 228.2) * MIB,
-    "partial_bwd_diag": (192.0 + 1459.7 + 2076.8 + 1.5 + 1932.1 + 193.2) * MIB,
-    "partial_bwd_full": (192.0 + 387.2 + 3269.5 + 1.5 + 3456.3 + 193.1) * MIB,
-    "partial_bwd_diag_recompute": (192.0 + 1459.9 + 963.9 + 1.5 + 384.3 + 192.2) * MIB,
-    "partial_bwd_full_recompute": (192.0 + 387.2 + 387.2 + 1.5 + 384.1 + 192.9) * MIB,
+    "partial_fwd_diag": (470.1 + 215.9) * MIB, "partial_fwd_full": (288.2 + 227.7) * MIB,
+    "partial_bwd_diag": (192.0 + 675.9 + 1874.9 + 1.5 + 1932.0 + 192.8) * MIB,
+    "partial_bwd_full": (192.0 + 387.2 + 3268.5 + 1.5 + 3456.1 + 193.8) * MIB,
+    "partial_bwd_diag_recompute": (192.0 + 659.9 + 633.8 + 1.5 + 384.6 + 194.7) * MIB,
+    "partial_bwd_full_recompute": (192.0 + 387.2 + 387.2 + 1.5 + 384.6 + 196.2) * MIB,
     "fix": (1632.1 + 97.5) * MIB, "fix_bwd_dq": (1536.0 + 96.0) * MIB,
     "fix_bwd_dk": (1536.0 + 96.0) * MIB, "fix_bwd_dv": (1536.0 + 96.0) * MIB}}
 

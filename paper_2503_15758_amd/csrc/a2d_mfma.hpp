@@ -125,13 +125,15 @@ __device__ __forceinline__ int dual_store_off(int r, int c) { return r * DUAL_LD
 // id = 8 k + x):
 //   by head  (by_size = false): head 8 * (k / nblocks) + x, block k % nblocks - a head's blocks run
 //            back to back and share its rows in L2; used when all blocks cost the same;
-//   by block (by_size = true):  head 8 * (k % hpx) + x, block k / hpx (hpx = heads per XCD) - block
-//            b of every head before any block b + 1.  The callers number the blocks heaviest first,
-//            so under a causal mask that crosses the tile the workgroups start longest first over
-//            the whole XCD and its compute units finish together (diagonal forward tile -9 %); the
-//            heads' rows then share L2 less (unmasked tile +2-3 %, which is why it is not the default).
+//   by block (by_size = true):  the XCD's heads in chunks of kSizeChunk; inside a chunk block b of
+//            every head before any block b + 1.  The callers number the blocks heaviest first, so
+//            under a causal mask that crosses the tile the workgroups start longest first and the
+//            compute units finish together (diagonal forward tile -7 %); chunks of 2 to 12 heads
+//            all gave the same time, 4 keeps most of a head's rows shared in L2 (the unmasked
+//            tile loses 2-3 % with this order, which is why it is not the default).
 // Grid size: 8 * ceil(heads / 8) * nblocks; workgroups whose head is out of range exit.
 constexpr int kXcds = 8;
+constexpr int kSizeChunk = 4;
 __host__ __device__ inline int xcd_grid(int heads, int nblocks) {
   return kXcds * ((heads + kXcds - 1) / kXcds) * nblocks;
 }
@@ -140,8 +142,10 @@ __device__ __forceinline__ bool xcd_map(int heads, int nblocks, bool by_size, in
   const int x = id % kXcds, k = id / kXcds;
   if (by_size) {
     const int hpx = (heads + kXcds - 1) / kXcds;
-    head = kXcds * (k % hpx) + x;
-    block = k / hpx;
+    const int c = k / (kSizeChunk * nblocks), kk = k - c * (kSizeChunk * nblocks);
+    const int width = min(kSizeChunk, hpx - c * kSizeChunk);   // the last chunk may hold fewer heads
+    head = kXcds * (c * kSizeChunk + kk % width) + x;
+    block = kk / width;
   } else {
     head = kXcds * (k / nblocks) + x;
     block = k % nblocks;
