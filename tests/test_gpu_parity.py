@@ -177,6 +177,57 @@ def test_partial_bwd_small(a2d, dt, case):
         assert_close(got, ref, DT[dt], what + " " + name, rel=bool(np.abs(ref).max() > 0))
 
 
+def _sweep_cases(n, seed):
+    """Seeded random tile shapes: ragged sizes around the 32 / 64 / 128 / 256 block edges, every
+    MFMA head size, diagonals that cross the tile anywhere (or miss it)."""
+    rng = np.random.default_rng(seed)
+    edges = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 383, 511, 512, 640]
+    cases = []
+    for i in range(n):
+        heads = int(rng.integers(1, 5))
+        nq = int(rng.choice(edges)) if rng.random() < 0.5 else int(rng.integers(1, 700))
+        nkv = int(rng.choice(edges)) if rng.random() < 0.5 else int(rng.integers(1, 700))
+        H = int(rng.choice([64, 80, 96, 128]))
+        causal = bool(rng.random() < 0.7)
+        base = int(rng.integers(0, 1 << 20))
+        shift = int(rng.integers(-nq - 8, nkv + 8)) if causal else 0   # kv_off - q_off
+        q_off, kv_off = (base + max(0, -shift), base + max(0, shift)) if causal else (0, 0)
+        cases.append((heads, nq, nkv, H, causal, q_off, kv_off))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(24, 2503), ids=lambda c: "x".join(map(str, c)))
+def test_seeded_shape_sweep_bf16(a2d, case):
+    """Forward, and backward on both paths (recomputing dQ kernel / dS hand-over), on seeded random
+    shapes.  As in test_partial_bwd_small the rows also see a second, always visible key block, so
+    the FINAL lse the backward receives is finite on every row."""
+    heads, nq, nkv, H, causal, q_off, kv_off = case
+    print("sweep case", case, flush=True)
+    scale = 1.0 / math.sqrt(H)
+    Q = synth.normal((heads, nq, H), 91, 0, 1.0, "bf16")
+    K = synth.normal((heads, nkv, H), 91, 1, 1.0, "bf16")
+    V = synth.normal((heads, nkv, H), 91, 2, 1.0, "bf16")
+    dO = synth.normal((heads, nq, H), 91, 3, 1.0, "bf16")
+    what = "sweep %s" % (case,)
+    check_partial(a2d, Q, K, V, q_off, kv_off, causal, scale, what)
+    K2 = synth.normal((heads, 40, H), 91, 4, 1.0, "bf16")
+    V2 = synth.normal((heads, 40, H), 91, 5, 1.0, "bf16")
+    t1 = oracle.partial_fwd(np64(Q), np64(K), np64(V), q_off, kv_off, causal, scale)
+    t2 = oracle.partial_fwd(np64(Q), np64(K2), np64(V2), 0, 0, False, scale)
+    Of, lsef = oracle.fix([t1[0], t2[0]], [t1[1], t2[1]], [t1[2], t2[2]])
+    O_in = torch.from_numpy(Of).to(torch.bfloat16)
+    lse_in = torch.from_numpy(lsef).to(torch.float32)
+    rQ, rK, rV = oracle.partial_bwd(np64(Q), np64(K), np64(V), np64(O_in), np64(dO), np64(lse_in),
+                                    q_off, kv_off, causal, scale)
+    for handover in (False, True):
+        dQ, dK, dV = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, kv_off,
+                                     causal, scale, ds_handover=handover)
+        torch.cuda.synchronize()
+        for got, ref, name in ((dQ, rQ, "dQ"), (dK, rK, "dK"), (dV, rV, "dV")):
+            assert_close(got, ref, torch.bfloat16, "%s %s handover=%s" % (what, name, handover),
+                         rel=bool(np.abs(ref).max() > 1e-3))
+
+
 # ----------------------------------------------------------------------------- workloads
 def test_c1_fp32_grid_forward_all_elements(a2d):
     w = synth.WORKLOADS["c1"]
@@ -458,6 +509,74 @@ def test_gathered_tile_fwd_bwd(a2d, dt, case):
         torch.cuda.synchronize()
         for x, y in zip(a, b):
             assert torch.equal(x, y)
+
+
+def _sweep_seg_cases(n, seed):
+    """Seeded random gathered tiles with grouped heads: 1-6 sub-blocks of ragged sizes at random
+    positions around the query block, 1-3 key/value heads shared by 1, 2 or 4 query heads each."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        kv_heads, group = int(rng.integers(1, 4)), int(rng.choice([1, 2, 4]))
+        nq = int(rng.integers(1, 420))
+        H = int(rng.choice([64, 80, 96, 128]))
+        q_off = int(rng.integers(0, 900))
+        aligned = bool(rng.random() < 0.5)        # sub-block starts on 64-key boundaries: the dS hand-over applies
+        segs = []
+        for _ in range(int(rng.integers(1, 7))):
+            rows = int(rng.integers(1, 4)) * 64 if aligned else int(rng.integers(1, 200))
+            segs.append((int(rng.integers(0, q_off + nq + 100)), rows))
+        if aligned:
+            segs[-1] = (segs[-1][0], int(rng.integers(1, 200)))   # only the last one may be ragged
+        cases.append((kv_heads, group, nq, H, q_off, bool(rng.random() < 0.8), segs))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_seg_cases(16, 15758),
+                         ids=lambda c: "%dkvx%d_%dxH%d_q%d_%s_%dseg" % (c[0], c[1], c[2], c[3], c[4], c[5], len(c[6])))
+def test_seeded_sweep_gathered_grouped_bf16(a2d, case):
+    """Gathered key rows and grouped query heads together, forward and both backward paths, on
+    seeded random shapes; the oracle sees the key/value heads repeated per query head and its
+    dK / dV summed back over each group."""
+    kv_heads, group, nq, H, q_off, causal, segs = case
+    print("sweep case", case, flush=True)
+    heads, nkv = kv_heads * group, sum(r for _, r in segs)
+    scale = 1.0 / math.sqrt(H)
+    Q = synth.normal((heads, nq, H), 92, 0, 1.0, "bf16")
+    K = synth.normal((kv_heads, nkv, H), 92, 1, 1.0, "bf16")
+    V = synth.normal((kv_heads, nkv, H), 92, 2, 1.0, "bf16")
+    dO = synth.normal((heads, nq, H), 92, 3, 1.0, "bf16")
+    Kx, Vx = (np.repeat(np64(t), group, axis=0) for t in (K, V))
+    kpos = oracle.segment_positions(segs)
+    what = "sweep %s" % (case,)
+    Np, m, l = a2d.partial_fwd(dev(Q), dev(K), dev(V), q_off, 0, causal, scale, segments=segs)
+    torch.cuda.synchronize()
+    Nr, mr, lr = oracle.partial_fwd_pos(np64(Q), Kx, Vx, q_off, kpos, causal, scale)
+    Ng, mg, lg = np64(Np), np64(m), np64(l)
+    empty = np.isinf(mr)
+    assert np.array_equal(np.isinf(mg) & (mg < 0), empty), what + ": set of empty rows differs"
+    assert np.all(lg[empty] == 0.0) and np.all(Ng[empty] == 0.0)
+    ok = ~empty
+    if ok.any():
+        assert_close(mg[ok], mr[ok], torch.bfloat16, what + " m", rel=False)
+        assert_close(Ng[ok] / lg[ok][:, None], Nr[ok] / lr[ok][:, None], torch.bfloat16, what + " N/l")
+    # the rows also see a second, always visible key block: the FINAL lse is finite everywhere
+    K2 = np.repeat(np64(synth.normal((kv_heads, 24, H), 92, 4, 1.0, "bf16")), group, axis=0)
+    V2 = np.repeat(np64(synth.normal((kv_heads, 24, H), 92, 5, 1.0, "bf16")), group, axis=0)
+    t2 = oracle.partial_fwd(np64(Q), K2, V2, 0, 0, False, scale)
+    Of, lsef = oracle.fix([Nr, t2[0]], [mr, t2[1]], [lr, t2[2]])
+    O_in = torch.from_numpy(Of).to(torch.bfloat16)
+    lse_in = torch.from_numpy(lsef).to(torch.float32)
+    rq, rk, rv = oracle.partial_bwd_pos(np64(Q), Kx, Vx, np64(O_in), np64(dO), np64(lse_in), q_off, kpos, causal, scale)
+    rk = rk.reshape(kv_heads, group, nkv, H).sum(axis=1)
+    rv = rv.reshape(kv_heads, group, nkv, H).sum(axis=1)
+    for handover in (False, True):
+        dQ, dK, dV = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, 0, causal,
+                                     scale, segments=segs, ds_handover=handover)
+        torch.cuda.synchronize()
+        for got, ref, name in ((dQ, rq, "dQ"), (dK, rk, "dK"), (dV, rv, "dV")):
+            assert_close(got, ref, torch.bfloat16, "%s %s handover=%s" % (what, name, handover),
+                         rel=bool(np.abs(ref).max() > 1e-3))
 
 
 # ----------------------------------------------------------------------------- accumulating calls
