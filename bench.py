@@ -307,6 +307,7 @@ def main():
                 extra("gathered", lambda: gathered_tile(a2d, synth, w, scale, kernels))
             extra("normalised_partials", lambda: normalised_format(a2d, synth, w, scale, kernels))
             extra("grouped_query", lambda: grouped_query(a2d, synth, w, scale, kernels))
+            extra("strided_inputs", lambda: strided_inputs(a2d, synth, w, scale, kernels))
     if args.grid_emulation:
         extra("grid_emulation", lambda: grid_emulation(synth))
     if not args.no_mfma_probe:
@@ -407,6 +408,49 @@ def normalised_format(a2d, synth, w, scale, kernels):
     return {"fix_norm_ms": round(t_fix, 4), "fix_norm_gbs": round(nbytes / t_fix / 1e6, 1),
             "fix_norm_frac_hbm": round(nbytes / t_fix / 1e6 / PEAK_HBM_GBS, 4), "fix_norm_bytes": nbytes,
             "fix_fp32_ms": kernels["fix"]["avg_ms"], "partial_fwd_norm_unmasked_tile_ms": round(t_fwd, 4)}
+
+
+def strided_inputs(a2d, synth, w, scale, kernels):
+    """The unmasked tile with Q, K, V read in place from a [rows][3][heads][H] buffer (a fused QKV
+    projection) and O, dO from [rows][heads][H] ones, through the descriptor's strides, timed beside
+    the plain-layout tile of the timed steps."""
+    import torch
+    if not w.backward:
+        return None
+    T, H, r = w.tile, w.hdim, w.grid - 1
+    dev = lambda t: t.to("cuda")
+    packed = torch.stack([dev(synth.q_block(w, r)), dev(synth.k_block(w, 0)), dev(synth.v_block(w, 0))], 0)
+    packed = packed.permute(2, 0, 1, 3).contiguous()                 # [rows][3][heads][H]
+    Q, K0, V0 = (packed[:, i].permute(1, 0, 2) for i in range(3))    # [heads][rows][H] views
+    dO = dev(synth.do_block(w, r)).permute(1, 0, 2).contiguous().permute(1, 0, 2)
+    out = a2d.partial_fwd(Q, K0, V0, r * T, 0, True, scale)
+    O, lse = a2d.fix([out[0]], [out[1]], [out[2]])
+    O = O.permute(1, 0, 2).contiguous().permute(1, 0, 2)
+    o3 = tuple(torch.empty(w.heads, T, H, dtype=torch.float32, device="cuda") for _ in range(3))
+    ws = torch.empty(a2d.workspace_bytes(a2d.tile_desc(Q, K0, r * T, 0, True, scale), a2d.OP_PARTIAL_BWD_DS),
+                     dtype=torch.uint8, device="cuda")
+
+    def timeit(fn, n=10):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    t_f = timeit(lambda: a2d.partial_fwd(Q, K0, V0, r * T, 0, True, scale, out=out))
+    t_b = timeit(lambda: a2d.partial_bwd(Q, K0, V0, O, dO, lse, r * T, 0, True, scale, out=o3, workspace=ws))
+    Qc, Kc, Vc, Oc, dOc = (t.contiguous() for t in (Q, K0, V0, O, dO))     # plain copies, timed the same way
+    p_f = timeit(lambda: a2d.partial_fwd(Qc, Kc, Vc, r * T, 0, True, scale, out=out))
+    p_b = timeit(lambda: a2d.partial_bwd(Qc, Kc, Vc, Oc, dOc, lse, r * T, 0, True, scale, out=o3, workspace=ws))
+    return {"what": "unmasked tile, Q / K / V views of one [rows][3][heads][H] buffer, O / dO [rows][heads][H]; "
+                    "plain_*: the same calls on plain copies, timed back to back in the same way",
+            "row_stride_bytes": int(Q.stride(1) * Q.element_size()), "fwd_ms": round(t_f, 4), "bwd_ms": round(t_b, 4),
+            "plain_fwd_ms": round(p_f, 4), "plain_bwd_ms": round(p_b, 4)}
 
 
 def grouped_query(a2d, synth, w, scale, kernels):

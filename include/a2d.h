@@ -14,8 +14,9 @@
  * Conventions shared by every call
  *  - Every pointer is caller-owned DEVICE memory unless stated otherwise; the
  *    library allocates nothing and keeps no pointer after a call returns.
- *  - Matrices are row-major [heads][rows][H] with H contiguous and no padding;
- *    per-row statistics are [heads][rows].  heads = batch * number of heads (the
+ *  - Matrices are row-major [heads][rows][H] with H contiguous and no padding
+ *    (the tile calls' inputs in the model's dtype may instead be strided, see
+ *    a2d_layout); per-row statistics are [heads][rows].  heads = batch * number of heads (the
  *    method works per head, Sec. 2.1 / Sec. 5).
  *  - Scores are s = scale * <q, k> (the 1/sqrt(H) factor the paper's footnote in
  *    Sec. 2.1 leaves out is the explicit `scale`), then the causal mask of
@@ -69,6 +70,23 @@ typedef enum {
 /* Most key/value sub-blocks of one gathered tile (a2d_partial_fwd_seg / a2d_partial_bwd_seg). */
 #define A2D_MAX_SEGMENTS 32
 
+/*
+ * Where the rows of a [heads][rows][H] tensor of the model's dtype (Q, K, V, O, dO) lie: element
+ * (h, r, j) is at base + h * head + r * row + j, strides in ELEMENTS; the H elements of a row are
+ * always contiguous.  {0, 0} means the plain layout (row = H, head = rows * H).  Otherwise
+ * row >= H, head >= 1, both multiples of 16 bytes' worth of elements (8 for bf16, 4 for fp32), a
+ * row stride below 16 MiB, and what one call addresses through one base pointer (the rows of one
+ * key/value head; of the query heads that share it) must span less than 4 GiB - e.g. the
+ * [rows][heads][H] layout of a fused QKV projection is head = H, row = heads * H (times 3 when
+ * Q, K and V are interleaved), with the tensor's base pointer moved to its first element.  The
+ * library reads heads * rows rows through these strides and cannot check that they exist.
+ * The fp32 partials, statistics and gradient partials the calls write are always plain.
+ */
+typedef struct {
+  int64_t head;
+  int64_t row;
+} a2d_layout;
+
 /* One tile problem: a block of nq queries against a block of nkv keys/values. */
 typedef struct {
   int32_t heads;   /* B * M, >= 1                                                     */
@@ -80,6 +98,12 @@ typedef struct {
   int32_t causal;  /* 0: no mask; 1: hide key r from query i iff q_off+i < kv_off+r   */
   float scale;     /* multiplies <q, k>; 1/sqrt(H) in the paper's setting             */
   int32_t dtype;   /* a2d_dtype of Q, K, V, O, dO                                     */
+  int32_t pad;     /* must be 0                                                       */
+  a2d_layout lq;   /* layout of Q                                                     */
+  a2d_layout lk;   /* layout of K (its heads are the key/value heads)                 */
+  a2d_layout lv;   /* layout of V                                                     */
+  a2d_layout lo;   /* layout of O  (backward calls)                                   */
+  a2d_layout ldo;  /* layout of dO (backward calls)                                   */
 } a2d_tile_desc;
 
 /*

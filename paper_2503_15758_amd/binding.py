@@ -24,10 +24,17 @@ EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd
            "a2d_status_str", "a2d_last_error", "a2d_version")
 
 
+class Layout(ctypes.Structure):
+    """a2d_layout: element strides of a [heads][rows][H] tensor; (0, 0) = plain."""
+    _fields_ = [("head", ctypes.c_int64), ("row", ctypes.c_int64)]
+
+
 class TileDesc(ctypes.Structure):
     _fields_ = [("heads", ctypes.c_int32), ("nq", ctypes.c_int32), ("nkv", ctypes.c_int32),
                 ("hdim", ctypes.c_int32), ("q_off", ctypes.c_int64), ("kv_off", ctypes.c_int64),
-                ("causal", ctypes.c_int32), ("scale", ctypes.c_float), ("dtype", ctypes.c_int32)]
+                ("causal", ctypes.c_int32), ("scale", ctypes.c_float), ("dtype", ctypes.c_int32),
+                ("pad", ctypes.c_int32), ("lq", Layout), ("lk", Layout), ("lv", Layout), ("lo", Layout),
+                ("ldo", Layout)]
 
 
 class KvSegment(ctypes.Structure):
@@ -138,14 +145,35 @@ def _ptr_array(ts):
 
 
 def _dev3(t, name):
-    if not (t.is_cuda and t.is_contiguous() and t.dim() == 3):
-        raise A2DError(-1, "%s must be a contiguous [heads][rows][H] device tensor" % name)
+    """The tile calls' inputs: [heads][rows][H] device tensors (or views) whose rows of H elements are
+    contiguous; the head and row strides travel in the descriptor."""
+    if not (t.is_cuda and t.dim() == 3 and (t.stride(2) == 1 or t.shape[2] == 1)):
+        raise A2DError(-1, "%s must be a [heads][rows][H] device tensor with contiguous rows" % name)
 
 
-def tile_desc(Q, K, q_off, kv_off, causal, scale):
+def _plain(ts, name):
+    """What the library writes is always in the plain layout."""
+    for t in ts:
+        if not (t.is_cuda and t.is_contiguous()):
+            raise A2DError(-1, "%s must be contiguous device tensors" % name)
+
+
+def _layout(t):
+    """a2d_layout of a tensor or view accepted by _dev3 ((0, 0) for the plain layout)."""
+    if t is None or t.is_contiguous():
+        return Layout(0, 0)
+    heads, rows, H = t.shape
+    row = t.stride(1) if rows > 1 else H             # a stride over a dimension of extent 1 is arbitrary
+    head = t.stride(0) if heads > 1 else rows * row
+    return Layout(int(head), int(row))
+
+
+def tile_desc(Q, K, q_off, kv_off, causal, scale, V=None, O=None, dO=None):
+    """Descriptor of the tile; the strides of Q, K (and V, O, dO when given) are taken from the tensors."""
     heads, nq, H = Q.shape
     return TileDesc(heads, nq, K.shape[1], H, int(q_off), int(kv_off), int(bool(causal)),
-                    float(scale if scale is not None else 1.0 / math.sqrt(H)), _dtype_code(Q.dtype))
+                    float(scale if scale is not None else 1.0 / math.sqrt(H)), _dtype_code(Q.dtype), 0,
+                    _layout(Q), _layout(K), _layout(V if V is not None else K), _layout(O), _layout(dO))
 
 
 def workspace_bytes(desc, op, k=0):
@@ -166,13 +194,14 @@ def partial_fwd(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=None, 
         _dev3(t, n)
     if K.shape != V.shape or K.shape[2] != Q.shape[2] or K.dtype != Q.dtype or V.dtype != Q.dtype:
         raise A2DError(-1, "Q, K, V shapes / dtypes do not match")
-    d = tile_desc(Q, K, q_off, kv_off, causal, scale)
+    d = tile_desc(Q, K, q_off, kv_off, causal, scale, V)
     if out is None:
         O_part = torch.empty(Q.shape, dtype=torch.float32, device=Q.device)
         m = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
         l = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
     else:
         O_part, m, l = out
+        _plain(out, "out=(O_part, m, l)")
     if accumulate and out is None:
         raise A2DError(-1, "accumulate needs out=(O_part, m, l)")
     if K.shape[0] != Q.shape[0]:   # grouped queries: K, V hold fewer heads than Q
@@ -205,12 +234,13 @@ def partial_fwd_norm(Q, K, V, q_off=0, kv_off=0, causal=False, scale=None, out=N
         _dev3(t, n)
     if K.shape != V.shape or K.shape[2] != Q.shape[2] or K.dtype != Q.dtype or V.dtype != Q.dtype:
         raise A2DError(-1, "Q, K, V shapes / dtypes do not match")
-    d = tile_desc(Q, K, q_off, kv_off, causal, scale)
+    d = tile_desc(Q, K, q_off, kv_off, causal, scale, V)
     if out is None:
         O_norm = torch.empty(Q.shape, dtype=Q.dtype, device=Q.device)
         lse = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
     else:
         O_norm, lse = out
+        _plain(out, "out=(O_norm, lse)")
     n = len(segments) if segments is not None else 0
     if K.shape[0] != Q.shape[0]:   # grouped queries
         _check(lib().a2d_partial_fwd_gqa(ctypes.byref(d), int(K.shape[0]), n, _segments(segments) if n else None,
@@ -268,9 +298,10 @@ def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None
     for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
         _dev3(t, n)
     if O.shape != Q.shape or dO.shape != Q.shape or O.dtype != Q.dtype or dO.dtype != Q.dtype or \
-            lse.shape != Q.shape[:2] or lse.dtype != torch.float32 or K.shape != V.shape:
-        raise A2DError(-1, "O, dO, lse do not match Q")
-    d = tile_desc(Q, K, q_off, kv_off, causal, scale)
+            lse.shape != Q.shape[:2] or lse.dtype != torch.float32 or K.shape != V.shape or \
+            not lse.is_contiguous():
+        raise A2DError(-1, "O, dO, lse do not match Q (lse: plain fp32 [heads][nq])")
+    d = tile_desc(Q, K, q_off, kv_off, causal, scale, V, O, dO)
     need = workspace_bytes(d, OP_PARTIAL_BWD_DS if ds_handover else OP_PARTIAL_BWD)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
@@ -280,6 +311,7 @@ def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None
         dV = torch.empty(K.shape, dtype=torch.float32, device=Q.device)
     else:
         dQ, dK, dV = out
+        _plain(out, "out=(dQ_part, dK_part, dV_part)")
     if accumulate and out is None:
         raise A2DError(-1, "accumulate needs out=(dQ_part, dK_part, dV_part)")
     if K.shape[0] != Q.shape[0]:   # grouped queries: dK_part, dV_part have K's heads

@@ -20,6 +20,12 @@ a2d_status fail(a2d_status st, const char* fmt, ...) {
   return st;
 }
 
+#define A2D_TRY_(expr)                  \
+  do {                                  \
+    a2d_status st__ = (expr);           \
+    if (st__ != A2D_OK) return st__;    \
+  } while (0)
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // A2D_FORCE_GENERIC=1 routes every tile call to the generic kernels (debugging aid).
@@ -49,6 +55,47 @@ a2d_status check_desc(const a2d_tile_desc* d, const char* who) {
   const int64_t lim = (int64_t)1 << 40;
   if (d->q_off < -lim || d->q_off > lim || d->kv_off < -lim || d->kv_off > lim)
     return fail(A2D_ERR_INVALID_ARG, "%s: offsets out of range", who);
+  if (d->pad != 0) return fail(A2D_ERR_INVALID_ARG, "%s: desc->pad must be 0", who);
+  return A2D_OK;
+}
+
+// One layout of the descriptor: {0, 0} becomes the plain one; anything else is checked.  `heads`
+// consecutive heads of `rows` rows are addressed through one base pointer with 32-bit byte offsets.
+a2d_status resolve_layout(a2d_layout* l, const char* name, int64_t heads, int64_t rows, const a2d_tile_desc* d,
+                          const char* who) {
+  const int64_t esize = d->dtype == A2D_BF16 ? 2 : 4, unit = 16 / esize;
+  if (l->head == 0 && l->row == 0) {
+    l->row = d->hdim;
+    l->head = rows * d->hdim;
+    return A2D_OK;
+  }
+  if (l->row < d->hdim || l->head < 1 || l->row > ((int64_t)1 << 40) || l->head > ((int64_t)1 << 40))
+    return fail(A2D_ERR_INVALID_ARG, "%s: layout of %s: head=%lld row=%lld (row >= H and head >= 1 needed)", who,
+                name, (long long)l->head, (long long)l->row);
+  if (l->row % unit != 0 || l->head % unit != 0)
+    return fail(A2D_ERR_MISALIGNED, "%s: layout of %s: head=%lld row=%lld must be multiples of %lld elements", who,
+                name, (long long)l->head, (long long)l->row, (long long)unit);
+  // (the kernels form row offsets with 24-bit multiplies: rows < 2^22, row stride < 16 MiB)
+  if (l->row * esize >= ((int64_t)1 << 24))
+    return fail(A2D_ERR_UNSUPPORTED, "%s: layout of %s: row stride of %lld bytes (16 MiB or more)", who, name,
+                (long long)(l->row * esize));
+  const int64_t span = ((heads - 1) * l->head + (rows - 1) * l->row + d->hdim) * esize;
+  if (span >= ((int64_t)1 << 32))
+    return fail(A2D_ERR_UNSUPPORTED, "%s: layout of %s: %lld head(s) of %lld rows span %lld bytes (4 GiB or more)",
+                who, name, (long long)heads, (long long)rows, (long long)span);
+  return A2D_OK;
+}
+
+// The descriptor with every layout the call uses filled in (group = query heads per key/value head)
+a2d_status resolve_layouts(const a2d_tile_desc* desc, int group, bool backward, const char* who, a2d_tile_desc* out) {
+  *out = *desc;
+  A2D_TRY_(resolve_layout(&out->lq, "Q", group, desc->nq, desc, who));
+  A2D_TRY_(resolve_layout(&out->lk, "K", 1, desc->nkv, desc, who));
+  A2D_TRY_(resolve_layout(&out->lv, "V", 1, desc->nkv, desc, who));
+  if (backward) {
+    A2D_TRY_(resolve_layout(&out->lo, "O", group, desc->nq, desc, who));
+    A2D_TRY_(resolve_layout(&out->ldo, "dO", group, desc->nq, desc, who));
+  }
   return A2D_OK;
 }
 
@@ -135,12 +182,14 @@ a2d_status partial_fwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
   A2D_TRY(check_ptr(m, who, "m"));
   A2D_TRY(check_ptr(l, who, "l"));
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (!force_generic() && a2d::fwd_mfma_supported(*desc)) {
+  a2d_tile_desc dd;
+  A2D_TRY(resolve_layouts(desc, g.group, false, who, &dd));
+  if (!force_generic() && a2d::fwd_mfma_supported(dd)) {
     a2d::SegList go = g;
     go.by_size = blocks_differ(desc, g);
-    return hip_result(a2d::launch_fwd_mfma(*desc, go, Q, K, V, O_part, m, l, s), who);
+    return hip_result(a2d::launch_fwd_mfma(dd, go, Q, K, V, O_part, m, l, s), who);
   }
-  return hip_result(a2d::launch_fwd_generic(*desc, g, Q, K, V, O_part, m, l, s), who);
+  return hip_result(a2d::launch_fwd_generic(dd, g, Q, K, V, O_part, m, l, s), who);
 }
 
 a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, const void* Q, const void* K,
@@ -167,19 +216,20 @@ a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
                 workspace ? workspace_bytes : (size_t)0);
   if (!aligned16(workspace)) return fail(A2D_ERR_MISALIGNED, "%s: workspace is not 16-byte aligned", who);
   hipStream_t s = static_cast<hipStream_t>(stream);
+  a2d_tile_desc dd;
+  A2D_TRY(resolve_layouts(desc, g.group, true, who, &dd));
   float* delta = static_cast<float*>(workspace);
-  A2D_TRY(hip_result(a2d::launch_delta(desc->dtype, (int64_t)desc->heads * desc->nq, desc->hdim, O,
-                                       dO, delta, s), who));
-  if (!force_generic() && a2d::bwd_mfma_supported(*desc)) {
+  A2D_TRY(hip_result(a2d::launch_delta(dd, O, dO, delta, s), who));
+  if (!force_generic() && a2d::bwd_mfma_supported(dd)) {
     // a workspace large enough for dS as well switches to the hand-over path
-    const size_t ds_bytes = a2d::bwd_ds_bytes(*desc, g);
+    const size_t ds_bytes = a2d::bwd_ds_bytes(dd, g);
     void* ds_ws = (ds_bytes > 0 && workspace_bytes >= need + ds_bytes) ? static_cast<char*>(workspace) + need : nullptr;
     a2d::SegList go = g;
     go.by_size = blocks_differ(desc, g);
-    return hip_result(a2d::launch_bwd_mfma(*desc, go, Q, K, V, dO, lse, delta, dQ_part, dK_part,
+    return hip_result(a2d::launch_bwd_mfma(dd, go, Q, K, V, dO, lse, delta, dQ_part, dK_part,
                                            dV_part, ds_ws, s), who);
   }
-  return hip_result(a2d::launch_bwd_generic(*desc, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
+  return hip_result(a2d::launch_bwd_generic(dd, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
                                             dV_part, s), who);
 }
 

@@ -266,7 +266,9 @@ __device__ __forceinline__ void ds_turn_read(unsigned piece, int lane, bf16x8 (&
 // without the bookkeeping that walks them.
 // WRITE_DS: the gradient waves also leave dS in the workspace `dS` (layout above) for the
 // contraction-only dQ kernel.
-template <int HR, bool GROUPED, bool WRITE_DS>
+// PLAIN: Q and dO are in the plain layout (row stride H, head stride nq * H): the staging offsets
+// are then compile-time multiples and one offset serves both tensors (3 % on the recomputing path).
+template <int HR, bool GROUPED, bool WRITE_DS, bool PLAIN = false>
 __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
     a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
@@ -284,10 +286,10 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int pair = wave & 3, role = wave >> 2;   // wavefronts w and w + 4 share 32 keys
   const int l32 = lane & 31;
-  Q += (int64_t)head * group * d.nq * H;
-  dO += (int64_t)head * group * d.nq * H;
-  K += (int64_t)head * d.nkv * H;
-  V += (int64_t)head * d.nkv * H;
+  Q += (int64_t)head * group * d.lq.head;
+  dO += (int64_t)head * group * d.ldo.head;
+  K += (int64_t)head * d.lk.head;
+  V += (int64_t)head * d.lv.head;
   lse += (int64_t)head * group * d.nq;
   delta += (int64_t)head * group * d.nq;
 
@@ -299,7 +301,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   // probabilities.
   const int key = k0 + pair * 32 + l32;
   {
-    const bf16_t* src = (role ? V : K) + (int64_t)min(key, d.nkv - 1) * H + 8 * cx.half;
+    const bf16_t* src = (role ? V : K) + (int64_t)min(key, d.nkv - 1) * (role ? d.lv.row : d.lk.row) + 8 * cx.half;
 #pragma unroll
     for (int x = 0; x < KS; ++x) {
       if (16 * x < H) cx.frag[x] = *reinterpret_cast<const bf16x8*>(src + 16 * x);
@@ -389,13 +391,25 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   // (load_step is called for steps 0, 1, 2, ... in order; with grouped heads ld_s / ld_row0 /
   // ld_left follow the next step's position - its step inside the query head, the head's first
   // row - without a division)
+  // (ld_qh / ld_gh: byte offset of the query head's first row of Q / dO from the group's first head)
   int ld_s = 0, ld_row0 = 0, ld_left = total - 1;
+  unsigned ld_qh = 0, ld_gh = 0;
+  const unsigned q_row_bytes = __builtin_amdgcn_readfirstlane((unsigned)d.lq.row * 2);
+  const unsigned g_row_bytes = __builtin_amdgcn_readfirstlane((unsigned)d.ldo.row * 2);
+  const unsigned q_head_bytes = __builtin_amdgcn_readfirstlane((unsigned)d.lq.head * 2);
+  const unsigned g_head_bytes = __builtin_amdgcn_readfirstlane((unsigned)d.ldo.head * 2);
   auto load_step = [&](int step, auto set_tag) {
     constexpr int SET = decltype(set_tag)::value;
     const int i0 = i_start + (GROUPED ? ld_s : min(step, nsteps - 1)) * BQ;
-    const unsigned off = (unsigned)((ld_row0 + min(i0 + st_row, d.nq - 1)) * (H * 2) + ld_ch * 16);
-    qreg[SET] = gload_b128(q_base, off);
-    greg[SET] = gload_b128(g_base, off);
+    if constexpr (PLAIN) {
+      const unsigned off = (unsigned)((ld_row0 + min(i0 + st_row, d.nq - 1)) * (H * 2) + ld_ch * 16);
+      qreg[SET] = gload_b128(q_base, off);
+      greg[SET] = gload_b128(g_base, off);
+    } else {
+      const unsigned r = (unsigned)min(i0 + st_row, d.nq - 1);
+      qreg[SET] = gload_b128(q_base, ld_qh + __umul24(r, q_row_bytes) + ld_ch * 16);
+      greg[SET] = gload_b128(g_base, ld_gh + __umul24(r, g_row_bytes) + ld_ch * 16);
+    }
     // raw statistic loads only: converting here would make the wave wait for everything just
     // issued.  Every thread loads one (only the first 64 values are used) so that each set is
     // the same number of loads in every wavefront.
@@ -406,6 +420,8 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
       const bool more = ld_left > 0, wrap = ld_s + 1 == nsteps;
       ld_left -= more ? 1 : 0;
       ld_row0 += (more && wrap) ? d.nq : 0;
+      ld_qh += (more && wrap) ? q_head_bytes : 0u;
+      ld_gh += (more && wrap) ? g_head_bytes : 0u;
       ld_s = more ? (wrap ? 0 : ld_s + 1) : ld_s;
     }
   };
@@ -657,10 +673,10 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31;
-  Q += (int64_t)head * d.nq * H;
-  dO += (int64_t)head * d.nq * H;
-  K += (int64_t)kvh * d.nkv * H;
-  V += (int64_t)kvh * d.nkv * H;
+  Q += (int64_t)head * d.lq.head;
+  dO += (int64_t)head * d.ldo.head;
+  K += (int64_t)kvh * d.lk.head;
+  V += (int64_t)kvh * d.lv.head;
 
   DqCtx<HD> cx;
   cx.half = lane >> 5;
@@ -669,12 +685,12 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   const bool q_ok = q_row < d.nq;
   const int q_ld = min(q_row, d.nq - 1);         // rows beyond nq re-read the last row, lse2 = +inf
   {
-    const int64_t off = (int64_t)q_ld * H + 8 * cx.half;
+    const int64_t off = (int64_t)q_ld * d.lq.row + 8 * cx.half, goff = (int64_t)q_ld * d.ldo.row + 8 * cx.half;
 #pragma unroll
     for (int x = 0; x < KS; ++x) {
       if (16 * x < H) {
         cx.qf[x] = *reinterpret_cast<const bf16x8*>(Q + off + 16 * x);
-        cx.gf[x] = *reinterpret_cast<const bf16x8*>(dO + off + 16 * x);
+        cx.gf[x] = *reinterpret_cast<const bf16x8*>(dO + goff + 16 * x);
       } else {                                                 // columns past the head size are zero
         cx.qf[x] = bf16x8{};
         cx.gf[x] = bf16x8{};
@@ -720,16 +736,21 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   // stored as zeros or, past the padded head size, not at all)
   const int ld_ch = min(st_ch, H / 8 - 1);
   const bool ch_data = st_ch * 8 < H, ch_tile = st_ch * 8 < HD;
+  // (row strides in bytes, pinned in registers: read from the kernel arguments inside the loop they
+  // would be scalar loads, which share a wait counter with the LDS reads in flight.  A head's rows
+  // span less than 4 GiB - the API layer checks it - so row index times stride fits 32 bits.)
+  const unsigned k_row_bytes = __builtin_amdgcn_readfirstlane((unsigned)d.lk.row * 2);
+  const unsigned v_row_bytes = __builtin_amdgcn_readfirstlane((unsigned)d.lv.row * 2);
   auto load_half = [&](int seg_start, int seg_rows, int j, int hf) {
     const int k0 = seg_start + j * BKS;
-    const gptr_t kb = uniform_gptr(K + (int64_t)k0 * H);
-    const gptr_t vb = uniform_gptr(V + (int64_t)k0 * H);
+    const gptr_t kb = uniform_gptr(reinterpret_cast<const char*>(K) + (unsigned)k0 * k_row_bytes);
+    const gptr_t vb = uniform_gptr(reinterpret_cast<const char*>(V) + (unsigned)k0 * v_row_bytes);
     const int last = seg_rows - 1 - j * BKS;       // rows beyond the sub-block re-read its last row
 #pragma unroll
     for (int p = 0; p < ST_N; ++p) {
-      const unsigned off = (unsigned)(min(32 * hf + st_row + ST_ROWS * p, last) * (H * 2) + ld_ch * 16);
-      kreg[p] = gload_b128(kb, off);
-      vreg[p] = gload_b128(vb, off);
+      const unsigned r = (unsigned)min(32 * hf + st_row + ST_ROWS * p, last);
+      kreg[p] = gload_b128(kb, __umul24(r, k_row_bytes) + ld_ch * 16);
+      vreg[p] = gload_b128(vb, __umul24(r, v_row_bytes) + ld_ch * 16);
     }
   };
   auto store_half = [&](int buf, int hf) {
@@ -863,7 +884,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31;
-  K += (int64_t)kvh * d.nkv * H;
+  K += (int64_t)kvh * d.lk.head;
 
   DsqCtx<HD> cx;
   cx.half = lane >> 5;
@@ -926,12 +947,13 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
   const int ld_ch = min(st_ch, H / 8 - 1);
   const bool ch_data = st_ch * 8 < H, ch_tile = st_ch * 8 < HD;
   const gptr_t k_base = uniform_gptr(K);
+  const unsigned k_row_bytes = __builtin_amdgcn_readfirstlane((unsigned)d.lk.row * 2);
   u32x4 kreg[ST_N];
   auto load_k = [&](int id) {
 #pragma unroll
     for (int p = 0; p < ST_N; ++p) {
       const int row = min(id * BKS + st_row + ST_ROWS * p, d.nkv - 1);   // rows past the end re-read the last key
-      kreg[p] = gload_b128(k_base, (unsigned)(row * (H * 2) + ld_ch * 16));
+      kreg[p] = gload_b128(k_base, __umul24((unsigned)row, k_row_bytes) + ld_ch * 16);
     }
   };
   auto store_k = [&](int buf) {
@@ -1069,9 +1091,13 @@ hipError_t bwd_launch_hd(const a2d_tile_desc& d, const SegList& g, const void* Q
   if (ds_ws) return bwd_launch_ds<HR>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
   constexpr int DQ_LDS = dq_lds(padded_head(HR));
   const bool grouped = g.group > 1;
-  hipError_t e = hipFuncSetAttribute(grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, false>)
-                                             : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, false>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, DK_LDS);
+  // Q and dO in the plain layout: the variant with compile-time staging offsets
+  const bool plain = d.lq.row == HR && d.ldo.row == HR && d.lq.head == (int64_t)d.nq * HR && d.ldo.head == d.lq.head;
+  const void* dkdv = plain ? (grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, false, true>)
+                                      : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, false, true>))
+                           : (grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, false, false>)
+                                      : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, false, false>));
+  hipError_t e = hipFuncSetAttribute(dkdv, hipFuncAttributeMaxDynamicSharedMemorySize, DK_LDS);
   if (e != hipSuccess) return e;
   // dQ kernel: eight wavefronts per workgroup unless that leaves compute units without a workgroup
   int dev = 0, cus = 0;
@@ -1087,12 +1113,14 @@ hipError_t bwd_launch_hd(const a2d_tile_desc& d, const SegList& g, const void* Q
   const int dq_rows = big ? 256 : 128;
   const int per_unit = g.group / g.split;
   dim3 grid_q(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + dq_rows - 1) / dq_rows)));
-  if (grouped)
-    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, true, false>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
-                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV, (bf16_t*)nullptr);
-  else
-    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, false, false>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q,
-                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV, (bf16_t*)nullptr);
+#define A2D_DKDV(GR, PL)                                                                                          \
+  hipLaunchKernelGGL((bwd_dkdv_kernel<HR, GR, false, PL>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q, \
+                     (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV, (bf16_t*)nullptr)
+  if (grouped && plain) A2D_DKDV(true, true);
+  else if (grouped) A2D_DKDV(true, false);
+  else if (plain) A2D_DKDV(false, true);
+  else A2D_DKDV(false, false);
+#undef A2D_DKDV
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (big)

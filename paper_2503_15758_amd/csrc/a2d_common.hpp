@@ -89,9 +89,8 @@ hipError_t launch_bwd_generic(const a2d_tile_desc& d, const SegList& g, const vo
                               const void* dO, const float* lse, const float* delta, float* dQ,
                               float* dK, float* dV, hipStream_t s);
 
-// delta[row] = sum_j dO[row][j] * O[row][j]
-hipError_t launch_delta(int dtype, int64_t rows, int hdim, const void* O, const void* dO,
-                        float* delta, hipStream_t s);
+// delta[head][row] = sum_j dO[head][row][j] * O[head][row][j]  (O, dO with the layouts d.lo, d.ldo)
+hipError_t launch_delta(const a2d_tile_desc& d, const void* O, const void* dO, float* delta, hipStream_t s);
 
 // bf16 MFMA tile kernels (H in {64, 80, 96, 128}).  `supported` tells whether the shape is covered.
 bool fwd_mfma_supported(const a2d_tile_desc& d);

@@ -171,16 +171,16 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int half = lane >> 5, l32 = lane & 31;
-  Q += (int64_t)head * d.nq * H;
-  K += (int64_t)kvh * d.nkv * H;
-  V += (int64_t)kvh * d.nkv * H;
+  Q += (int64_t)head * d.lq.head;
+  K += (int64_t)kvh * d.lk.head;
+  V += (int64_t)kvh * d.lv.head;
 
   // ---- Q^T fragments: lane holds query row (l32), h = 16*step + 8*half + 0..7.
   // Rows beyond nq re-read the last row (their results are never stored).
   const int q_row = q0 + wave * 32 + l32;
   bf16x8 qf[KS];
   {
-    const bf16_t* qp = Q + (int64_t)min(q_row, d.nq - 1) * H + 8 * half;
+    const bf16_t* qp = Q + (int64_t)min(q_row, d.nq - 1) * d.lq.row + 8 * half;
 #pragma unroll
     for (int x = 0; x < KS; ++x) {
       if (16 * x < H) qf[x] = *reinterpret_cast<const bf16x8*>(qp + 16 * x);
@@ -278,17 +278,22 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   for (int p = 0; p < ST_N; ++p) { kreg[p] = u32x4{0, 0, 0, 0}; vreg[p] = u32x4{0, 0, 0, 0}; }
   // block j of the sub-block of seg_rows keys that starts at local key seg_start; rows beyond its
   // end re-read its last row
+  // (row strides in bytes, pinned in registers: read from the kernel arguments inside the loop they
+  // would be scalar loads, which share a wait counter with the LDS reads in flight.  A head's rows
+  // span less than 4 GiB - the API layer checks it - so row index times stride fits 32 bits.)
+  const unsigned k_row_bytes = __builtin_amdgcn_readfirstlane((unsigned)d.lk.row * 2);
+  const unsigned v_row_bytes = __builtin_amdgcn_readfirstlane((unsigned)d.lv.row * 2);
   auto load_tile = [&](int seg_start, int seg_rows, int j) {
     const int k0 = seg_start + j * BN;
-    const gptr_t kb = uniform_gptr(K + (int64_t)k0 * H);   // scalar bases
-    const gptr_t vb = uniform_gptr(V + (int64_t)k0 * H);
+    const gptr_t kb = uniform_gptr(reinterpret_cast<const char*>(K) + (unsigned)k0 * k_row_bytes);   // scalar bases
+    const gptr_t vb = uniform_gptr(reinterpret_cast<const char*>(V) + (unsigned)k0 * v_row_bytes);
     const int last = seg_rows - 1 - j * BN;
     if (ld_ok) {
 #pragma unroll
       for (int p = 0; p < ST_N; ++p) {
-        const unsigned off = (unsigned)(min(ld_row + ST_ROWS * p, last) * (H * 2) + ld_chunk * 16);
-        kreg[p] = gload_b128(kb, off);
-        vreg[p] = gload_b128(vb, off);
+        const unsigned r = (unsigned)min(ld_row + ST_ROWS * p, last);
+        kreg[p] = gload_b128(kb, __umul24(r, k_row_bytes) + ld_chunk * 16);
+        vreg[p] = gload_b128(vb, __umul24(r, v_row_bytes) + ld_chunk * 16);
       }
     }
   };

@@ -18,13 +18,14 @@ namespace {
 constexpr int kThreads = 256;
 
 // dst[r][h] (row stride ld floats) = src row (row0 + r) widened to fp32, zero for rows >= nrows
+// (src rows are `stride` elements apart)
 template <typename T, int H>
-__device__ __forceinline__ void load_tile(float* dst, int ld, const T* __restrict__ src,
+__device__ __forceinline__ void load_tile(float* dst, int ld, const T* __restrict__ src, int64_t stride,
                                           int row0, int nrows, int tile_rows) {
   for (int idx = threadIdx.x; idx < tile_rows * H; idx += kThreads) {
     const int r = idx / H, h = idx - r * H;
     const int g = row0 + r;
-    dst[r * ld + h] = (g < nrows) ? to_f32(src[(int64_t)g * H + h]) : 0.f;
+    dst[r * ld + h] = (g < nrows) ? to_f32(src[(int64_t)g * stride + h]) : 0.f;
   }
 }
 
@@ -71,11 +72,11 @@ __global__ __launch_bounds__(kThreads) void fwd_generic_kernel(
   const int head = blockIdx.y;
   const int q0 = blockIdx.x * BM;
   const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;
-  Q += (int64_t)head * d.nq * H;
-  K += (int64_t)(head / g.group) * d.nkv * H;
-  V += (int64_t)(head / g.group) * d.nkv * H;
+  Q += (int64_t)head * d.lq.head;
+  K += (int64_t)(head / g.group) * d.lk.head;
+  V += (int64_t)(head / g.group) * d.lv.head;
 
-  load_tile<T, H>(Qs, LD, Q, q0, d.nq, BM);
+  load_tile<T, H>(Qs, LD, Q, d.lq.row, q0, d.nq, BM);
 
   float o[4][HB];
   float mi[4], li[4];
@@ -98,8 +99,8 @@ __global__ __launch_bounds__(kThreads) void fwd_generic_kernel(
 
   for (int k0 = 0; k0 < nvis; k0 += BN) {
     __syncthreads();
-    load_tile<T, H>(Ks, LD, K, k0, d.nkv, BN);
-    load_tile<T, H>(Vs, H, V, k0, d.nkv, BN);
+    load_tile<T, H>(Ks, LD, K, d.lk.row, k0, d.nkv, BN);
+    load_tile<T, H>(Vs, H, V, d.lv.row, k0, d.nkv, BN);
     __syncthreads();
     float s[4][4];
 #pragma unroll
@@ -195,15 +196,15 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_generic_kernel(
   const int head = blockIdx.y;     // key/value head: its g.group query heads follow one another in Q, dO, lse, delta
   const int k0 = blockIdx.x * BK;
   const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;
-  Q += (int64_t)head * g.group * d.nq * H;
-  dO += (int64_t)head * g.group * d.nq * H;
-  K += (int64_t)head * d.nkv * H;
-  V += (int64_t)head * d.nkv * H;
+  Q += (int64_t)head * g.group * d.lq.head;
+  dO += (int64_t)head * g.group * d.ldo.head;
+  K += (int64_t)head * d.lk.head;
+  V += (int64_t)head * d.lv.head;
   lse += (int64_t)head * g.group * d.nq;
   delta += (int64_t)head * g.group * d.nq;
 
-  load_tile<T, H>(Ks, LD, K, k0, d.nkv, BK);
-  load_tile<T, H>(Vs, LD, V, k0, d.nkv, BK);
+  load_tile<T, H>(Ks, LD, K, d.lk.row, k0, d.nkv, BK);
+  load_tile<T, H>(Vs, LD, V, d.lv.row, k0, d.nkv, BK);
 
   float dk[4][HB], dv[4][HB];
 #pragma unroll
@@ -225,11 +226,11 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_generic_kernel(
       i_first = min(i_first, fr);
     }
   }
-  for (int qh = 0; qh < g.group; ++qh, Q += (int64_t)d.nq * H, dO += (int64_t)d.nq * H, lse += d.nq, delta += d.nq)
+  for (int qh = 0; qh < g.group; ++qh, Q += d.lq.head, dO += d.ldo.head, lse += d.nq, delta += d.nq)
   for (int i0 = (i_first / BQ) * BQ; i0 < d.nq; i0 += BQ) {
     __syncthreads();
-    load_tile<T, H>(Qs, LD, Q, i0, d.nq, BQ);
-    load_tile<T, H>(dOs, LD, dO, i0, d.nq, BQ);
+    load_tile<T, H>(Qs, LD, Q, d.lq.row, i0, d.nq, BQ);
+    load_tile<T, H>(dOs, LD, dO, d.ldo.row, i0, d.nq, BQ);
     __syncthreads();
     float s[2][4], dp[2][4];
 #pragma unroll
@@ -312,15 +313,15 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_generic_kernel(
   const int head = blockIdx.y;
   const int q0 = blockIdx.x * BQ;
   const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;
-  Q += (int64_t)head * d.nq * H;
-  dO += (int64_t)head * d.nq * H;
-  K += (int64_t)(head / g.group) * d.nkv * H;
-  V += (int64_t)(head / g.group) * d.nkv * H;
+  Q += (int64_t)head * d.lq.head;
+  dO += (int64_t)head * d.ldo.head;
+  K += (int64_t)(head / g.group) * d.lk.head;
+  V += (int64_t)(head / g.group) * d.lv.head;
   lse += (int64_t)head * d.nq;
   delta += (int64_t)head * d.nq;
 
-  load_tile<T, H>(Qs, LD, Q, q0, d.nq, BQ);
-  load_tile<T, H>(dOs, LD, dO, q0, d.nq, BQ);
+  load_tile<T, H>(Qs, LD, Q, d.lq.row, q0, d.nq, BQ);
+  load_tile<T, H>(dOs, LD, dO, d.ldo.row, q0, d.nq, BQ);
 
   float dq[4][HB];
   float lse_i[4], del_i[4];
@@ -337,8 +338,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_generic_kernel(
 
   for (int k0 = 0; k0 < nvis; k0 += BK) {
     __syncthreads();
-    load_tile<T, H>(Ks, LD, K, k0, d.nkv, BK);
-    load_tile<T, H>(Vs, LD, V, k0, d.nkv, BK);
+    load_tile<T, H>(Ks, LD, K, d.lk.row, k0, d.nkv, BK);
+    load_tile<T, H>(Vs, LD, V, d.lv.row, k0, d.nkv, BK);
     __syncthreads();
     float s[4][2], dp[4][2];
 #pragma unroll
@@ -399,9 +400,10 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_generic_kernel(
 
 // --------------------------------------------------- delta = rowsum(dO o O)
 // LPR lanes share a row, each reading 16 bytes of O and of dO per step.
+// (O and dO are [heads][nq][H] tensors with the strides lo / ldo; delta is plain [heads][nq])
 template <typename T>
-__global__ __launch_bounds__(kThreads) void delta_kernel(int64_t rows, int H, int lpr,
-                                                         const T* __restrict__ O,
+__global__ __launch_bounds__(kThreads) void delta_kernel(int64_t rows, int nq, int H, int lpr, a2d_layout lo,
+                                                         a2d_layout ldo, const T* __restrict__ O,
                                                          const T* __restrict__ dO,
                                                          float* __restrict__ delta) {
   constexpr int EPL = 16 / sizeof(T);          // elements per lane per load
@@ -413,8 +415,9 @@ __global__ __launch_bounds__(kThreads) void delta_kernel(int64_t rows, int H, in
   const int c = (int)(idx - row * lpr);
   float acc = 0.f;
   if (row < rows && c < nload) {
-    const T* o = O + row * H + c * EPL;
-    const T* g = dO + row * H + c * EPL;
+    const int64_t head = row / nq, r = row - head * nq;
+    const T* o = O + head * lo.head + r * lo.row + c * EPL;
+    const T* g = dO + head * ldo.head + r * ldo.row + c * EPL;
     const u32x4 ow = *reinterpret_cast<const u32x4*>(o);
     const u32x4 gw = *reinterpret_cast<const u32x4*>(g);
     const T* ov = reinterpret_cast<const T*>(&ow);
@@ -490,19 +493,20 @@ hipError_t launch_bwd_generic(const a2d_tile_desc& d, const SegList& g, const vo
 }
 #undef A2D_DISPATCH_H
 
-hipError_t launch_delta(int dtype, int64_t rows, int hdim, const void* O, const void* dO,
-                        float* delta, hipStream_t s) {
+hipError_t launch_delta(const a2d_tile_desc& d, const void* O, const void* dO, float* delta, hipStream_t s) {
+  const int dtype = d.dtype, hdim = d.hdim;
+  const int64_t rows = (int64_t)d.heads * d.nq;
   const int epl = dtype == A2D_BF16 ? 8 : 4;
   int lpr = 1;
   while (lpr < hdim / epl) lpr <<= 1;
   const int64_t threads = rows * lpr;
   dim3 grid((unsigned)((threads + kThreads - 1) / kThreads)), block(kThreads);
   if (dtype == A2D_BF16)
-    hipLaunchKernelGGL((delta_kernel<bf16_t>), grid, block, 0, s, rows, hdim, lpr, (const bf16_t*)O,
-                       (const bf16_t*)dO, delta);
+    hipLaunchKernelGGL((delta_kernel<bf16_t>), grid, block, 0, s, rows, d.nq, hdim, lpr, d.lo, d.ldo,
+                       (const bf16_t*)O, (const bf16_t*)dO, delta);
   else
-    hipLaunchKernelGGL((delta_kernel<float>), grid, block, 0, s, rows, hdim, lpr, (const float*)O,
-                       (const float*)dO, delta);
+    hipLaunchKernelGGL((delta_kernel<float>), grid, block, 0, s, rows, d.nq, hdim, lpr, d.lo, d.ldo,
+                       (const float*)O, (const float*)dO, delta);
   return hipGetLastError();
 }
 

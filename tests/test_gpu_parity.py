@@ -579,6 +579,71 @@ def test_seeded_sweep_gathered_grouped_bf16(a2d, case):
                          rel=bool(np.abs(ref).max() > 1e-3))
 
 
+# ----------------------------------------------------------------------------- strided inputs
+STRIDED_CASES = [
+    # dt, q heads, kv heads, nq, nkv, H, causal, q_off, kv_off, segments or None
+    ("bf16", 3, 3, 200, 200, 128, True, 0, 0, None),            # packed [rows][3][heads][H] projection
+    ("bf16", 2, 2, 300, 300, 96, True, 64, 0, None),
+    ("bf16", 4, 2, 130, 260, 128, True, 200, 0, None),          # grouped heads, K / V in their own buffer
+    ("bf16", 2, 1, 150, 320, 80, True, 100, 0, [(0, 128), (300, 64), (64, 128)]),
+    ("bf16", 2, 2, 513, 130, 64, False, 0, 0, None),
+    ("f32", 2, 2, 100, 100, 64, True, 0, 0, None),              # vector-ALU kernels
+    ("f32", 4, 2, 70, 90, 128, False, 0, 0, None),
+]
+
+
+@pytest.mark.parametrize("case", STRIDED_CASES, ids=lambda c: "%s_%dq%dkv_%dx%dxH%d" % c[:6])
+def test_strided_inputs(a2d, case):
+    """Q, K, V, O, dO as [heads][rows][H] VIEWS of [rows][heads][H] buffers (a fused QKV projection
+    when the lengths allow it): the calls must give bit for bit what they give on plain copies."""
+    dt, hq, hkv, nq, nkv, H, causal, q_off, kv_off, segs = case
+    scale = 1.0 / math.sqrt(H)
+    kw = dict(segments=segs) if segs else {}
+    if hq == hkv and nq == nkv:
+        packed = dev(synth.normal((nq, 3, hq, H), 95, 0, 1.0, dt))
+        Qv, Kv, Vv = (packed[:, i].permute(1, 0, 2) for i in range(3))
+    else:
+        Qv = dev(synth.normal((nq, hq, H), 95, 0, 1.0, dt)).permute(1, 0, 2)
+        kvbuf = dev(synth.normal((nkv, 2, hkv, H), 95, 1, 1.0, dt))
+        Kv, Vv = kvbuf[:, 0].permute(1, 0, 2), kvbuf[:, 1].permute(1, 0, 2)
+    assert not Qv.is_contiguous() and not Kv.is_contiguous() and not Vv.is_contiguous()
+    Qc, Kc, Vc = Qv.contiguous(), Kv.contiguous(), Vv.contiguous()
+    got = a2d.partial_fwd(Qv, Kv, Vv, q_off, kv_off, causal, scale, **kw)
+    ref = a2d.partial_fwd(Qc, Kc, Vc, q_off, kv_off, causal, scale, **kw)
+    torch.cuda.synchronize()
+    for x, y, name in zip(got, ref, ("N", "m", "l")):
+        assert torch.equal(x, y), "strided forward: %s differs" % name
+    gn = a2d.partial_fwd_norm(Qv, Kv, Vv, q_off, kv_off, causal, scale, **kw)
+    rn = a2d.partial_fwd_norm(Qc, Kc, Vc, q_off, kv_off, causal, scale, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(gn[0], rn[0]) and torch.equal(gn[1], rn[1])
+    # backward: O and dO in a [rows][2][heads][H] buffer; lse made finite by an always visible key
+    N, m, l = ref
+    lse = torch.logaddexp(m + torch.log(l), torch.zeros_like(m))
+    odo = dev(synth.normal((nq, 2, hq, H), 95, 2, 1.0, dt))
+    Ov, dOv = odo[:, 0].permute(1, 0, 2), odo[:, 1].permute(1, 0, 2)
+    Oc, dOc = Ov.contiguous(), dOv.contiguous()
+    for handover in (False, True):
+        g3 = a2d.partial_bwd(Qv, Kv, Vv, Ov, dOv, lse, q_off, kv_off, causal, scale, ds_handover=handover, **kw)
+        r3 = a2d.partial_bwd(Qc, Kc, Vc, Oc, dOc, lse, q_off, kv_off, causal, scale, ds_handover=handover, **kw)
+        torch.cuda.synchronize()
+        for x, y, name in zip(g3, r3, ("dQ", "dK", "dV")):
+            assert torch.equal(x, y), "strided backward (handover=%s): %s differs" % (handover, name)
+    # the vector-ALU kernels on the same views
+    import os
+    os.environ["A2D_FORCE_GENERIC"] = "1"
+    try:
+        g1 = a2d.partial_fwd(Qv, Kv, Vv, q_off, kv_off, causal, scale, **kw)
+        r1 = a2d.partial_fwd(Qc, Kc, Vc, q_off, kv_off, causal, scale, **kw)
+        g3 = a2d.partial_bwd(Qv, Kv, Vv, Ov, dOv, lse, q_off, kv_off, causal, scale, **kw)
+        r3 = a2d.partial_bwd(Qc, Kc, Vc, Oc, dOc, lse, q_off, kv_off, causal, scale, **kw)
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["A2D_FORCE_GENERIC"]
+    for x, y in zip(g1 + g3, r1 + r3):
+        assert torch.equal(x, y), "strided inputs, vector-ALU kernels: results differ"
+
+
 # ----------------------------------------------------------------------------- accumulating calls
 @pytest.mark.gpu
 @pytest.mark.parametrize("dt,H", [("bf16", 128), ("f32", 64), ("bf16", 96), ("bf16", 80), ("bf16", 64)])

@@ -2,6 +2,7 @@
 header declares, and rejects bad arguments before anything is enqueued."""
 import ctypes
 import os
+import subprocess
 import re
 
 import pytest
@@ -30,9 +31,26 @@ def test_header_symbols_are_exported(binding):
     assert binding.version() == "0.1"
 
 
-def test_descriptor_layout(binding):
-    assert ctypes.sizeof(binding.TileDesc) == 48
-    assert binding.TileDesc.q_off.offset == 16 and binding.TileDesc.dtype.offset == 40
+def test_descriptor_layout(binding, tmp_path):
+    """The ctypes mirror of a2d_tile_desc against what the C compiler makes of include/a2d.h."""
+    T = binding.TileDesc
+    assert ctypes.sizeof(T) == 128
+    assert T.q_off.offset == 16 and T.dtype.offset == 40 and T.pad.offset == 44
+    assert T.lq.offset == 48 and T.ldo.offset == 112 and ctypes.sizeof(binding.Layout) == 16
+    fields = ["heads", "nq", "nkv", "hdim", "q_off", "kv_off", "causal", "scale", "dtype", "pad",
+              "lq", "lk", "lv", "lo", "ldo"]
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "a2d.h"\nint main(void) {\n'
+                   '  printf("%zu", sizeof(a2d_tile_desc));\n' +
+                   "".join('  printf(" %%zu", offsetof(a2d_tile_desc, %s));\n' % f for f in fields) +
+                   '  printf(" %zu %zu", sizeof(a2d_kv_segment), sizeof(a2d_layout));\n  return 0;\n}\n')
+    exe = tmp_path / "layout"
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run(["gcc", "-I", inc, str(src), "-o", str(exe)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    want = [ctypes.sizeof(T)] + [getattr(T, f).offset for f in fields] + \
+           [ctypes.sizeof(binding.KvSegment), ctypes.sizeof(binding.Layout)]
+    assert got == want
 
 
 def _desc(b, **kw):
@@ -70,11 +88,26 @@ def test_argument_errors_enqueue_nothing(binding):
     assert fwd(_desc(b), q=None) == -1
     assert fwd(_desc(b), q=odd) == -3 and b"aligned" in L.a2d_last_error()
     assert fwd(_desc(b), o=odd) == -3
+    # layouts: pad, row stride below H, misaligned strides, more than 4 GiB through one base pointer
+    assert fwd(_desc(b, pad=1)) == -1 and b"pad" in L.a2d_last_error()
+    assert fwd(_desc(b, lq=b.Layout(128 * 128, 64))) == -1 and b"layout of Q" in L.a2d_last_error()
+    assert fwd(_desc(b, lk=b.Layout(0, 128))) == -1 and b"layout of K" in L.a2d_last_error()
+    assert fwd(_desc(b, lv=b.Layout(-128, 256))) == -1
+    assert fwd(_desc(b, lv=b.Layout(128 * 132, 132))) == -3 and b"layout of V" in L.a2d_last_error()
+    assert fwd(_desc(b, lq=b.Layout(132, 256))) == -3
+    assert fwd(_desc(b, dtype=b.A2D_F32, lq=b.Layout(130, 256))) == -3      # fp32: multiples of 4 elements
+    assert fwd(_desc(b, lk=b.Layout(128, 1 << 25))) == -2 and b"16 MiB" in L.a2d_last_error()
+    assert fwd(_desc(b, nkv=1 << 12, lk=b.Layout(128, 1 << 20))) == -2 and b"4 GiB" in L.a2d_last_error()
     # backward: workspace missing / too small
     d = _desc(b)
     bwd = lambda ws, n: L.a2d_partial_bwd(ctypes.byref(d), P, P, P, P, P, P, P, P, P, ws, n, None)
     assert bwd(None, 0) == -4
     assert bwd(P, 16) == -4 and b"1024" in L.a2d_last_error()
+    d = _desc(b, ldo=b.Layout(128, 120))
+    assert bwd(P, 1 << 20) == -1 and b"layout of dO" in L.a2d_last_error()
+    d = _desc(b, lo=b.Layout(4, 256))
+    assert bwd(P, 1 << 20) == -3 and b"layout of O" in L.a2d_last_error()
+    d = _desc(b)
     # fix / fix_bwd
     arr = (ctypes.c_void_p * 2)(0x10000, 0x20000)
     assert L.a2d_fix(0, 10, 128, b.A2D_BF16, arr, arr, arr, P, P, None) == -1
