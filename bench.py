@@ -39,11 +39,11 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # tile; the diagonal tiles order their workgroups by size and share their inputs in L2 less).
 MIB = float(1 << 20)
 TRAFFIC_BYTES = {"c3": {
-    "partial_fwd_diag": (470.1 + 215.9) * MIB, "partial_fwd_full": (288.2 + 227.7) * MIB,
-    "partial_bwd_diag": (192.0 + 675.9 + 1874.9 + 1.5 + 1932.0 + 192.8) * MIB,
-    "partial_bwd_full": (192.0 + 387.2 + 3268.5 + 1.5 + 3456.1 + 193.8) * MIB,
-    "partial_bwd_diag_recompute": (192.0 + 659.9 + 633.8 + 1.5 + 384.6 + 194.7) * MIB,
-    "partial_bwd_full_recompute": (192.0 + 387.2 + 387.2 + 1.5 + 384.6 + 196.2) * MIB,
+    "partial_fwd_diag": (465.7 + 214.9) * MIB, "partial_fwd_full": (288.2 + 224.6) * MIB,
+    "partial_bwd_diag": (192.0 + 676.3 + 1873.8 + 1.5 + 1932.1 + 192.8) * MIB,
+    "partial_bwd_full": (192.0 + 387.6 + 3269.9 + 1.5 + 3456.1 + 194.1) * MIB,
+    "partial_bwd_diag_recompute": (192.0 + 666.0 + 621.9 + 1.5 + 384.2 + 192.8) * MIB,
+    "partial_bwd_full_recompute": (192.0 + 388.4 + 387.2 + 1.5 + 384.0 + 193.3) * MIB,
     "fix": (1632.1 + 97.5) * MIB, "fix_bwd_dq": (1536.0 + 96.0) * MIB,
     "fix_bwd_dk": (1536.0 + 96.0) * MIB, "fix_bwd_dv": (1536.0 + 96.0) * MIB}}
 
