@@ -341,13 +341,16 @@ def gathered_tile(a2d, synth, w, scale, kernels):
     def timeit(fn, n=5):
         fn(); fn()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(n):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n
+        ts = []
+        for _ in range(3):      # median of three loops: the first one after an idle stretch runs at lower clocks
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) / n)
+        return sorted(ts)[1]
 
     t_f = timeit(lambda: a2d.partial_fwd(Q, K, V, r * T, 0, True, scale, out=out, segments=segs))
     t_b = timeit(lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, out=o3, workspace=ws,
@@ -393,13 +396,16 @@ def normalised_format(a2d, synth, w, scale, kernels):
         for _ in range(3):
             fn()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(n):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n
+        ts = []
+        for _ in range(3):      # median of three loops: the first one after an idle stretch runs at lower clocks
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) / n)
+        return sorted(ts)[1]
 
     t_fix = timeit(lambda: a2d.fix_norm([p[0] for p in parts], [p[1] for p in parts], out=(O, lse)))
     t_fwd = timeit(lambda: a2d.partial_fwd_norm(Q, K0, V0, r * T, 0, True, scale, out=parts[0]), n=10)
@@ -434,21 +440,30 @@ def strided_inputs(a2d, synth, w, scale, kernels):
         for _ in range(3):
             fn()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(n):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n
+        ts = []
+        for _ in range(3):      # median of three loops: the first one after an idle stretch runs at lower clocks
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) / n)
+        return sorted(ts)[1]
 
-    t_f = timeit(lambda: a2d.partial_fwd(Q, K0, V0, r * T, 0, True, scale, out=out))
-    t_b = timeit(lambda: a2d.partial_bwd(Q, K0, V0, O, dO, lse, r * T, 0, True, scale, out=o3, workspace=ws))
     Qc, Kc, Vc, Oc, dOc = (t.contiguous() for t in (Q, K0, V0, O, dO))     # plain copies, timed the same way
-    p_f = timeit(lambda: a2d.partial_fwd(Qc, Kc, Vc, r * T, 0, True, scale, out=out))
-    p_b = timeit(lambda: a2d.partial_bwd(Qc, Kc, Vc, Oc, dOc, lse, r * T, 0, True, scale, out=o3, workspace=ws))
+    # alternating, median of three: the first loop after an idle stretch runs at lower clocks
+    med = lambda v: sorted(v)[len(v) // 2]
+    tf, pf, tb, pb = [], [], [], []
+    for _ in range(3):
+        tf.append(timeit(lambda: a2d.partial_fwd(Q, K0, V0, r * T, 0, True, scale, out=out)))
+        pf.append(timeit(lambda: a2d.partial_fwd(Qc, Kc, Vc, r * T, 0, True, scale, out=out)))
+    for _ in range(3):
+        tb.append(timeit(lambda: a2d.partial_bwd(Q, K0, V0, O, dO, lse, r * T, 0, True, scale, out=o3, workspace=ws)))
+        pb.append(timeit(lambda: a2d.partial_bwd(Qc, Kc, Vc, Oc, dOc, lse, r * T, 0, True, scale, out=o3, workspace=ws)))
+    t_f, p_f, t_b, p_b = med(tf), med(pf), med(tb), med(pb)
     return {"what": "unmasked tile, Q / K / V views of one [rows][3][heads][H] buffer, O / dO [rows][heads][H]; "
-                    "plain_*: the same calls on plain copies, timed back to back in the same way",
+                    "plain_*: the same calls on plain copies, alternating, medians of three",
             "row_stride_bytes": int(Q.stride(1) * Q.element_size()), "fwd_ms": round(t_f, 4), "bwd_ms": round(t_b, 4),
             "plain_fwd_ms": round(p_f, 4), "plain_bwd_ms": round(p_b, 4)}
 
@@ -470,13 +485,16 @@ def grouped_query(a2d, synth, w, scale, kernels):
         for _ in range(3):
             fn()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(n):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n
+        ts = []
+        for _ in range(3):      # median of three loops: the first one after an idle stretch runs at lower clocks
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) / n)
+        return sorted(ts)[1]
 
     f_fl, b_fl = tile_flops(w, T, T, False)
     res = {"what": "%d query heads, unmasked tile, key/value heads as listed" % w.heads,
