@@ -289,6 +289,22 @@ a2d_status a2d_fix_bwd(int k, int64_t n, int32_t out_dtype, const float* const* 
                        void* out, void* stream);
 
 /*
+ * a2d_fix and a2d_fix_bwd with the merged output written through a layout, so that O, dQ, dK, dV
+ * land where the model keeps them (e.g. [rows][heads][H] activations, or the Q / K / V slots of a
+ * packed gradient buffer) without a transposing copy.  The inputs are the plain fp32 partials of
+ * heads * nq (heads * rows) rows as before, lse stays plain [heads][nq]; row r of head h of the
+ * output starts h * lo->head + r * lo->row elements from O (multiples of 16 bytes, row >= hdim).
+ * lo = NULL or {0, 0}: the plain layout, i.e. exactly a2d_fix / a2d_fix_bwd.  Same arithmetic and
+ * same results as those calls; nothing is enqueued on an error.
+ */
+a2d_status a2d_fix_strided(int k, int32_t heads, int32_t nq, int32_t hdim, int32_t out_dtype,
+                           const float* const* O_parts, const float* const* m, const float* const* l,
+                           void* O, const a2d_layout* lo, float* lse, void* stream);
+a2d_status a2d_fix_bwd_strided(int k, int32_t heads, int32_t rows, int32_t hdim, int32_t out_dtype,
+                               const float* const* parts, void* out, const a2d_layout* lout,
+                               void* stream);
+
+/*
  * Diagnostic, not part of the method: the rate the bf16 MFMA units of the current device
  * sustain on their own (register operands only, several wavefronts per SIMD, four independent
  * accumulators per wavefront), for pricing the tile kernels against what the chip delivers

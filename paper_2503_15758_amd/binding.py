@@ -20,6 +20,7 @@ MAX_PARTS = 32
 EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
            "a2d_partial_fwd_seg", "a2d_partial_bwd_seg", "a2d_partial_fwd_acc", "a2d_partial_bwd_acc",
            "a2d_partial_fwd_norm", "a2d_fix_norm", "a2d_partial_fwd_gqa", "a2d_partial_bwd_gqa",
+           "a2d_fix_strided", "a2d_fix_bwd_strided",
            "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling",
            "a2d_status_str", "a2d_last_error", "a2d_version")
 
@@ -104,6 +105,13 @@ def lib():
         L.a2d_fix_bwd.restype = ctypes.c_int
         L.a2d_fix_bwd.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(vp),
                                   vp, vp]
+        L.a2d_fix_strided.restype = ctypes.c_int
+        L.a2d_fix_strided.argtypes = [ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                      ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
+                                      ctypes.POINTER(Layout), vp, vp]
+        L.a2d_fix_bwd_strided.restype = ctypes.c_int
+        L.a2d_fix_bwd_strided.argtypes = [ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.POINTER(vp), vp, ctypes.POINTER(Layout), vp]
         L.a2d_mfma_ceiling_scratch_bytes.restype = ctypes.c_size_t
         L.a2d_mfma_ceiling_scratch_bytes.argtypes = []
         L.a2d_mfma_ceiling.restype = ctypes.c_int
@@ -285,6 +293,14 @@ def fix(O_parts, ms, ls, out_dtype=torch.bfloat16, out=None):
         lse = torch.empty(shape[:-1], dtype=torch.float32, device=O_parts[0].device)
     else:
         O, lse = out
+    _plain(list(O_parts) + list(ms) + list(ls) + [lse], "the partials and lse")
+    if not O.is_contiguous():      # a [heads][nq][H] view: written in place through its strides
+        _dev3(O, "O")
+        lo = _layout(O)
+        _check(lib().a2d_fix_strided(k, O.shape[0], O.shape[1], shape[-1], _dtype_code(O.dtype),
+                                     _ptr_array(O_parts), _ptr_array(ms), _ptr_array(ls), _ptr(O),
+                                     ctypes.byref(lo), _ptr(lse), _stream()))
+        return O, lse
     _check(lib().a2d_fix(k, rows, shape[-1], _dtype_code(O.dtype), _ptr_array(O_parts),
                          _ptr_array(ms), _ptr_array(ls), _ptr(O), _ptr(lse), _stream()))
     return O, lse
@@ -348,6 +364,13 @@ def fix_bwd(parts, out_dtype=torch.bfloat16, out=None):
         raise A2DError(-1, "need k >= 1 partials")
     if out is None:
         out = torch.empty(parts[0].shape, dtype=out_dtype, device=parts[0].device)
+    _plain(parts, "the partials")
+    if not out.is_contiguous():    # a [heads][rows][H] view: written in place through its strides
+        _dev3(out, "out")
+        lo = _layout(out)
+        _check(lib().a2d_fix_bwd_strided(k, out.shape[0], out.shape[1], out.shape[2], _dtype_code(out.dtype),
+                                         _ptr_array(parts), _ptr(out), ctypes.byref(lo), _stream()))
+        return out
     _check(lib().a2d_fix_bwd(k, parts[0].numel(), _dtype_code(out.dtype), _ptr_array(parts), _ptr(out),
                              _stream()))
     return out

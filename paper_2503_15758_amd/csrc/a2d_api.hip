@@ -364,10 +364,28 @@ a2d_status a2d_partial_fwd(const a2d_tile_desc* desc, const void* Q, const void*
   return partial_fwd_impl(desc, one_segment(desc), Q, K, V, O_part, m, l, stream, who);
 }
 
-a2d_status a2d_fix(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
-                   const float* const* O_parts, const float* const* m, const float* const* l,
-                   void* O, float* lse, void* stream) {
-  const char* who = "a2d_fix";
+}  // extern "C"
+
+namespace {
+
+// layout of a merge's output: NULL or {0, 0} = plain
+a2d_status out_map(const a2d_layout* lo, int64_t nq, int32_t hdim, int32_t out_dtype, const char* who, a2d::OutMap* om) {
+  *om = a2d::plain_out();
+  if (!lo || (lo->head == 0 && lo->row == 0)) return A2D_OK;
+  const int64_t unit = out_dtype == A2D_BF16 ? 8 : 4;
+  if (lo->row < hdim || lo->head < 1 || lo->row > ((int64_t)1 << 40) || lo->head > ((int64_t)1 << 40))
+    return fail(A2D_ERR_INVALID_ARG, "%s: output layout: head=%lld row=%lld (row >= H and head >= 1 needed)", who,
+                (long long)lo->head, (long long)lo->row);
+  if (lo->row % unit != 0 || lo->head % unit != 0)
+    return fail(A2D_ERR_MISALIGNED, "%s: output layout: head=%lld row=%lld must be multiples of %lld elements", who,
+                (long long)lo->head, (long long)lo->row, (long long)unit);
+  om->head = lo->head; om->row = lo->row; om->nq = (int)nq; om->plain = 0;
+  return A2D_OK;
+}
+
+a2d_status fix_impl(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
+                    const float* const* O_parts, const float* const* m, const float* const* l,
+                    void* O, const a2d::OutMap& om, float* lse, void* stream, const char* who) {
   if (k < 1 || k > A2D_MAX_PARTS)
     return fail(A2D_ERR_INVALID_ARG, "%s: k=%d outside 1..%d", who, k, A2D_MAX_PARTS);
   if (rows < 1) return fail(A2D_ERR_INVALID_ARG, "%s: rows=%lld must be >= 1", who, (long long)rows);
@@ -388,8 +406,59 @@ a2d_status a2d_fix(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
     A2D_TRY(check_ptr(l[x], who, "l[x]"));
     p.o[x] = O_parts[x]; p.m[x] = m[x]; p.l[x] = l[x];
   }
-  return hip_result(a2d::launch_fix(k, rows, hdim, out_dtype, p, O, lse,
+  return hip_result(a2d::launch_fix(k, rows, hdim, out_dtype, p, om, O, lse,
                                     static_cast<hipStream_t>(stream)), who);
+}
+
+a2d_status fix_bwd_impl(int k, int64_t n, int32_t hdim, int32_t out_dtype, const float* const* parts, void* out,
+                        const a2d::OutMap& om, void* stream, const char* who) {
+  if (k < 1 || k > A2D_MAX_PARTS)
+    return fail(A2D_ERR_INVALID_ARG, "%s: k=%d outside 1..%d", who, k, A2D_MAX_PARTS);
+  if (n < 4 || n % 4 != 0)
+    return fail(A2D_ERR_INVALID_ARG, "%s: n=%lld must be a positive multiple of 4", who, (long long)n);
+  if (n > ((int64_t)1 << 41)) return fail(A2D_ERR_INVALID_ARG, "%s: n too large", who);
+  if (out_dtype != A2D_F32 && out_dtype != A2D_BF16)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: out_dtype %d not supported", who, out_dtype);
+  if (!parts) return fail(A2D_ERR_INVALID_ARG, "%s: parts is NULL", who);
+  A2D_TRY(check_ptr(out, who, "out"));
+  a2d::SumPtrs p;
+  memset(&p, 0, sizeof(p));
+  for (int x = 0; x < k; ++x) {
+    A2D_TRY(check_ptr(parts[x], who, "parts[x]"));
+    p.p[x] = parts[x];
+  }
+  return hip_result(a2d::launch_fix_bwd(k, n, hdim / 4, out_dtype, p, om, out, static_cast<hipStream_t>(stream)), who);
+}
+
+}  // namespace
+
+extern "C" {
+
+a2d_status a2d_fix(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
+                   const float* const* O_parts, const float* const* m, const float* const* l,
+                   void* O, float* lse, void* stream) {
+  return fix_impl(k, rows, hdim, out_dtype, O_parts, m, l, O, a2d::plain_out(), lse, stream, "a2d_fix");
+}
+
+a2d_status a2d_fix_strided(int k, int32_t heads, int32_t nq, int32_t hdim, int32_t out_dtype,
+                           const float* const* O_parts, const float* const* m, const float* const* l,
+                           void* O, const a2d_layout* lo, float* lse, void* stream) {
+  const char* who = "a2d_fix_strided";
+  if (heads < 1 || nq < 1) return fail(A2D_ERR_INVALID_ARG, "%s: heads=%d nq=%d must be >= 1", who, heads, nq);
+  a2d::OutMap om;
+  A2D_TRY(out_map(lo, nq, hdim, out_dtype, who, &om));
+  return fix_impl(k, (int64_t)heads * nq, hdim, out_dtype, O_parts, m, l, O, om, lse, stream, who);
+}
+
+a2d_status a2d_fix_bwd_strided(int k, int32_t heads, int32_t rows, int32_t hdim, int32_t out_dtype,
+                               const float* const* parts, void* out, const a2d_layout* lout, void* stream) {
+  const char* who = "a2d_fix_bwd_strided";
+  if (heads < 1 || rows < 1) return fail(A2D_ERR_INVALID_ARG, "%s: heads=%d rows=%d must be >= 1", who, heads, rows);
+  if (hdim < 4 || hdim % 4 != 0 || hdim > 1024)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: hdim=%d must be a multiple of 4 in 4..1024", who, hdim);
+  a2d::OutMap om;
+  A2D_TRY(out_map(lout, rows, hdim, out_dtype, who, &om));
+  return fix_bwd_impl(k, (int64_t)heads * rows * hdim, hdim, out_dtype, parts, out, om, stream, who);
 }
 
 a2d_status a2d_partial_bwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
@@ -431,23 +500,7 @@ a2d_status a2d_partial_bwd(const a2d_tile_desc* desc, const void* Q, const void*
 
 a2d_status a2d_fix_bwd(int k, int64_t n, int32_t out_dtype, const float* const* parts, void* out,
                        void* stream) {
-  const char* who = "a2d_fix_bwd";
-  if (k < 1 || k > A2D_MAX_PARTS)
-    return fail(A2D_ERR_INVALID_ARG, "%s: k=%d outside 1..%d", who, k, A2D_MAX_PARTS);
-  if (n < 4 || n % 4 != 0)
-    return fail(A2D_ERR_INVALID_ARG, "%s: n=%lld must be a positive multiple of 4", who, (long long)n);
-  if (n > ((int64_t)1 << 41)) return fail(A2D_ERR_INVALID_ARG, "%s: n too large", who);
-  if (out_dtype != A2D_F32 && out_dtype != A2D_BF16)
-    return fail(A2D_ERR_UNSUPPORTED, "%s: out_dtype %d not supported", who, out_dtype);
-  if (!parts) return fail(A2D_ERR_INVALID_ARG, "%s: parts is NULL", who);
-  A2D_TRY(check_ptr(out, who, "out"));
-  a2d::SumPtrs p;
-  memset(&p, 0, sizeof(p));
-  for (int x = 0; x < k; ++x) {
-    A2D_TRY(check_ptr(parts[x], who, "parts[x]"));
-    p.p[x] = parts[x];
-  }
-  return hip_result(a2d::launch_fix_bwd(k, n, out_dtype, p, out, static_cast<hipStream_t>(stream)), who);
+  return fix_bwd_impl(k, n, 4, out_dtype, parts, out, a2d::plain_out(), stream, "a2d_fix_bwd");
 }
 
 const char* a2d_status_str(a2d_status status) {

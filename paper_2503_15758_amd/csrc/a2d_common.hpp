@@ -112,9 +112,19 @@ struct FixPtrs {
 struct SumPtrs {
   const float* p[A2D_MAX_PARTS];
 };
-hipError_t launch_fix(int k, int64_t rows, int hdim, int out_dtype, const FixPtrs& p, void* O,
+// Layout of a merge's output in the model's dtype: plain != 0 -> [rows][H] contiguous; else row r of
+// head h (nq rows per head) starts h * head + r * row elements from the base.
+struct OutMap {
+  int64_t head;
+  int64_t row;
+  int nq;
+  int plain;
+};
+inline OutMap plain_out() { return OutMap{0, 0, 1, 1}; }
+hipError_t launch_fix(int k, int64_t rows, int hdim, int out_dtype, const FixPtrs& p, const OutMap& om, void* O,
                       float* lse, hipStream_t s);
-hipError_t launch_fix_bwd(int k, int64_t n, int out_dtype, const SumPtrs& p, void* out,
+// (hv = 4-column groups per row, used only when the output is not plain)
+hipError_t launch_fix_bwd(int k, int64_t n, int hv, int out_dtype, const SumPtrs& p, const OutMap& om, void* out,
                           hipStream_t s);
 // merge of k NORMALISED partials (O'_k in in_dtype, lse_k)
 struct NormPtrs {

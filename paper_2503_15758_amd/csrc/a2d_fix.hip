@@ -16,6 +16,14 @@ __device__ __forceinline__ void store_out4(bf16_t* O, int64_t off, f32x4 v) {
   *reinterpret_cast<bf16x4*>(O + off) = b;
 }
 
+// Where column group idx (4 columns, hv groups per row) of the merged output goes: plain, or row
+// r of head h (nq rows per head) at h * head + r * row elements.
+__device__ __forceinline__ int64_t out_offset(const OutMap& om, int64_t idx, int hv) {
+  if (om.plain) return idx * 4;
+  const int64_t row = idx / hv, h = row / om.nq;
+  return h * om.head + (row - h * om.nq) * om.row + (idx - row * hv) * 4;
+}
+
 // Each thread handles CPT 16-byte column groups, one per grid-sized stride, and issues the
 // loads of all of them (CPT * k 128-bit loads) before the first use: the amount of data in
 // flight per thread, not the arithmetic, decides how close these kernels get to the HBM rate.
@@ -25,7 +33,7 @@ constexpr int chunks_per_thread(int kmax) { return kmax >= kLoadsInFlight ? 1 : 
 // A column group = 4 consecutive columns of one row; hv = H / 4 groups per row.
 // KMAX is the unroll bound (k <= KMAX); loads of absent partials are predicated off.
 template <typename OutT, int KMAX, int CPT>
-__global__ __launch_bounds__(256) void fix_kernel(FixPtrs p, int k, int64_t rows, int hv,
+__global__ __launch_bounds__(256) void fix_kernel(FixPtrs p, int k, int64_t rows, int hv, OutMap om,
                                                   OutT* __restrict__ O, float* __restrict__ lse) {
   const int64_t base = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * 256;
@@ -72,13 +80,13 @@ __global__ __launch_bounds__(256) void fix_kernel(FixPtrs p, int k, int64_t rows
     }
     const float inv = (D > 0.f) ? 1.0f / D : 0.f;
     acc[0] *= inv; acc[1] *= inv; acc[2] *= inv; acc[3] *= inv;
-    store_out4(O, idx * 4, acc);
+    store_out4(O, out_offset(om, idx, hv), acc);
     if (idx == row * hv) lse[row] = (D > 0.f) ? M + logf(D) : -INFINITY;
   }
 }
 
 template <typename OutT, int KMAX, int CPT>
-__global__ __launch_bounds__(256) void sum_kernel(SumPtrs p, int k, int64_t n4,
+__global__ __launch_bounds__(256) void sum_kernel(SumPtrs p, int k, int64_t n4, int hv, OutMap om,
                                                   OutT* __restrict__ out) {
   const int64_t base = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * 256;
@@ -102,7 +110,7 @@ __global__ __launch_bounds__(256) void sum_kernel(SumPtrs p, int k, int64_t n4,
     for (int x = 1; x < KMAX; ++x) {
       acc[0] += v[c][x][0]; acc[1] += v[c][x][1]; acc[2] += v[c][x][2]; acc[3] += v[c][x][3];
     }
-    store_out4(out, idx * 4, acc);
+    store_out4(out, out_offset(om, idx, hv), acc);
   }
 }
 
@@ -160,41 +168,41 @@ __global__ __launch_bounds__(256) void fix_norm_kernel(NormPtrs p, int k, int64_
 }
 
 template <typename OutT, int KMAX>
-void fix_launch(int k, int64_t rows, int hv, const FixPtrs& p, OutT* O, float* lse, hipStream_t s) {
+void fix_launch(int k, int64_t rows, int hv, const FixPtrs& p, const OutMap& om, OutT* O, float* lse, hipStream_t s) {
   constexpr int CPT = chunks_per_thread(KMAX);
   const int64_t per_block = 256 * CPT;
   const dim3 grid((unsigned)((rows * hv + per_block - 1) / per_block)), block(256);
-  hipLaunchKernelGGL((fix_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, rows, hv, O, lse);
+  hipLaunchKernelGGL((fix_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, rows, hv, om, O, lse);
 }
 
 template <typename OutT, int KMAX>
-void sum_launch(int k, int64_t n4, const SumPtrs& p, OutT* out, hipStream_t s) {
+void sum_launch(int k, int64_t n4, int hv, const SumPtrs& p, const OutMap& om, OutT* out, hipStream_t s) {
   constexpr int CPT = chunks_per_thread(KMAX);
   const int64_t per_block = 256 * CPT;
   const dim3 grid((unsigned)((n4 + per_block - 1) / per_block)), block(256);
-  hipLaunchKernelGGL((sum_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, n4, out);
+  hipLaunchKernelGGL((sum_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, n4, hv, om, out);
 }
 
 template <typename OutT>
-hipError_t fix_dispatch(int k, int64_t rows, int hdim, const FixPtrs& p, OutT* O, float* lse,
+hipError_t fix_dispatch(int k, int64_t rows, int hdim, const FixPtrs& p, const OutMap& om, OutT* O, float* lse,
                         hipStream_t s) {
   const int hv = hdim / 4;
-  if (k <= 2) fix_launch<OutT, 2>(k, rows, hv, p, O, lse, s);
-  else if (k <= 4) fix_launch<OutT, 4>(k, rows, hv, p, O, lse, s);
-  else if (k <= 8) fix_launch<OutT, 8>(k, rows, hv, p, O, lse, s);
-  else if (k <= 16) fix_launch<OutT, 16>(k, rows, hv, p, O, lse, s);
-  else fix_launch<OutT, 32>(k, rows, hv, p, O, lse, s);
+  if (k <= 2) fix_launch<OutT, 2>(k, rows, hv, p, om, O, lse, s);
+  else if (k <= 4) fix_launch<OutT, 4>(k, rows, hv, p, om, O, lse, s);
+  else if (k <= 8) fix_launch<OutT, 8>(k, rows, hv, p, om, O, lse, s);
+  else if (k <= 16) fix_launch<OutT, 16>(k, rows, hv, p, om, O, lse, s);
+  else fix_launch<OutT, 32>(k, rows, hv, p, om, O, lse, s);
   return hipGetLastError();
 }
 
 template <typename OutT>
-hipError_t sum_dispatch(int k, int64_t n, const SumPtrs& p, OutT* out, hipStream_t s) {
+hipError_t sum_dispatch(int k, int64_t n, int hv, const SumPtrs& p, const OutMap& om, OutT* out, hipStream_t s) {
   const int64_t n4 = n / 4;
-  if (k <= 2) sum_launch<OutT, 2>(k, n4, p, out, s);
-  else if (k <= 4) sum_launch<OutT, 4>(k, n4, p, out, s);
-  else if (k <= 8) sum_launch<OutT, 8>(k, n4, p, out, s);
-  else if (k <= 16) sum_launch<OutT, 16>(k, n4, p, out, s);
-  else sum_launch<OutT, 32>(k, n4, p, out, s);
+  if (k <= 2) sum_launch<OutT, 2>(k, n4, hv, p, om, out, s);
+  else if (k <= 4) sum_launch<OutT, 4>(k, n4, hv, p, om, out, s);
+  else if (k <= 8) sum_launch<OutT, 8>(k, n4, hv, p, om, out, s);
+  else if (k <= 16) sum_launch<OutT, 16>(k, n4, hv, p, om, out, s);
+  else sum_launch<OutT, 32>(k, n4, hv, p, om, out, s);
   return hipGetLastError();
 }
 
@@ -231,16 +239,17 @@ hipError_t launch_fix_norm(int k, int64_t rows, int hdim, int in_dtype, int out_
   return fix_norm_dispatch<float, float>(k, rows, hdim, p, (float*)O, lse, s);
 }
 
-hipError_t launch_fix(int k, int64_t rows, int hdim, int out_dtype, const FixPtrs& p, void* O,
+hipError_t launch_fix(int k, int64_t rows, int hdim, int out_dtype, const FixPtrs& p, const OutMap& om, void* O,
                       float* lse, hipStream_t s) {
-  if (out_dtype == A2D_BF16) return fix_dispatch<bf16_t>(k, rows, hdim, p, (bf16_t*)O, lse, s);
-  return fix_dispatch<float>(k, rows, hdim, p, (float*)O, lse, s);
+  if (out_dtype == A2D_BF16) return fix_dispatch<bf16_t>(k, rows, hdim, p, om, (bf16_t*)O, lse, s);
+  return fix_dispatch<float>(k, rows, hdim, p, om, (float*)O, lse, s);
 }
 
-hipError_t launch_fix_bwd(int k, int64_t n, int out_dtype, const SumPtrs& p, void* out,
+// hv = column groups per row (only used when the output is not plain)
+hipError_t launch_fix_bwd(int k, int64_t n, int hv, int out_dtype, const SumPtrs& p, const OutMap& om, void* out,
                           hipStream_t s) {
-  if (out_dtype == A2D_BF16) return sum_dispatch<bf16_t>(k, n, p, (bf16_t*)out, s);
-  return sum_dispatch<float>(k, n, p, (float*)out, s);
+  if (out_dtype == A2D_BF16) return sum_dispatch<bf16_t>(k, n, hv, p, om, (bf16_t*)out, s);
+  return sum_dispatch<float>(k, n, hv, p, om, (float*)out, s);
 }
 
 }  // namespace a2d

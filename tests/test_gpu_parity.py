@@ -644,6 +644,35 @@ def test_strided_inputs(a2d, case):
         assert torch.equal(x, y), "strided inputs, vector-ALU kernels: results differ"
 
 
+@pytest.mark.parametrize("dt,H,k", [("bf16", 128, 3), ("f32", 64, 2), ("bf16", 80, 8)])
+def test_strided_merge_outputs(a2d, dt, H, k):
+    """a2d_fix_strided / a2d_fix_bwd_strided write O and the gradient sums into [heads][rows][H]
+    VIEWS of [rows][heads][H] buffers: bit for bit what the plain calls give, nothing written
+    outside the views' elements."""
+    heads, nq = 3, 70
+    g = torch.Generator().manual_seed(300 + k)
+    Ns = [dev(torch.randn(heads, nq, H, generator=g)) for _ in range(k)]
+    ms = [dev(torch.randn(heads, nq, generator=g) * 5) for _ in range(k)]
+    ls = [dev(torch.rand(heads, nq, generator=g) * 9 + 1) for _ in range(k)]
+    O_ref, lse_ref = a2d.fix(Ns, ms, ls, DT[dt])
+    buf = torch.full((nq, 2, heads, H), 7.0, dtype=DT[dt], device="cuda")     # slot 1 must stay untouched
+    view = buf[:, 0].permute(1, 0, 2)
+    lse = torch.empty(heads, nq, dtype=torch.float32, device="cuda")
+    O, _ = a2d.fix(Ns, ms, ls, out=(view, lse))
+    torch.cuda.synchronize()
+    assert O.data_ptr() == buf.data_ptr() and not view.is_contiguous()
+    assert torch.equal(view, O_ref) and torch.equal(lse, lse_ref)
+    assert bool((buf[:, 1] == 7.0).all()), "a2d_fix_strided wrote outside its rows"
+    parts = [dev(torch.randn(heads, nq, H, generator=g)) for _ in range(k)]
+    s_ref = a2d.fix_bwd(parts, DT[dt])
+    buf.fill_(7.0)
+    view = buf[:, 1].permute(1, 0, 2)
+    a2d.fix_bwd(parts, out=view)
+    torch.cuda.synchronize()
+    assert torch.equal(view, s_ref)
+    assert bool((buf[:, 0] == 7.0).all()), "a2d_fix_bwd_strided wrote outside its rows"
+
+
 # ----------------------------------------------------------------------------- accumulating calls
 @pytest.mark.gpu
 @pytest.mark.parametrize("dt,H", [("bf16", 128), ("f32", 64), ("bf16", 96), ("bf16", 80), ("bf16", 64)])

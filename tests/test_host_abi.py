@@ -121,6 +121,17 @@ def test_argument_errors_enqueue_nothing(binding):
     assert L.a2d_fix_bwd(2, 10, b.A2D_BF16, arr, P, None) == -1          # n not a multiple of 4
     assert L.a2d_fix_bwd(2, 16, b.A2D_BF16, arr, None, None) == -1
     assert L.a2d_fix_bwd(40, 16, b.A2D_BF16, arr, P, None) == -1
+    # the merges with a strided output
+    lay = lambda h, r: ctypes.byref(b.Layout(h, r))
+    assert L.a2d_fix_strided(2, 0, 10, 128, b.A2D_BF16, arr, arr, arr, P, lay(128, 256), P, None) == -1
+    assert L.a2d_fix_strided(2, 2, 10, 128, b.A2D_BF16, arr, arr, arr, P, lay(128, 64), P, None) == -1
+    assert L.a2d_fix_strided(2, 2, 10, 128, b.A2D_BF16, arr, arr, arr, P, lay(132, 256), P, None) == -3
+    assert L.a2d_fix_strided(40, 2, 10, 128, b.A2D_BF16, arr, arr, arr, P, lay(128, 256), P, None) == -1
+    assert L.a2d_fix_strided(2, 2, 10, 128, b.A2D_BF16, arr, arr, arr, None, lay(128, 256), P, None) == -1
+    assert L.a2d_fix_bwd_strided(2, 2, 0, 128, b.A2D_BF16, arr, P, lay(128, 256), None) == -1
+    assert L.a2d_fix_bwd_strided(2, 2, 10, 126, b.A2D_BF16, arr, P, lay(128, 256), None) == -2
+    assert L.a2d_fix_bwd_strided(2, 2, 10, 128, b.A2D_F32, arr, P, lay(130, 256), None) == -3
+    assert L.a2d_fix_bwd_strided(2, 2, 10, 128, b.A2D_BF16, arr, odd, lay(128, 256), None) == -3
     assert L.a2d_status_str(-4) == b"workspace missing or too small"
     assert L.a2d_status_str(0) == b"ok"
 
