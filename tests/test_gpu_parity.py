@@ -5,6 +5,7 @@ launch configuration the benchmark times and compare whole heads or sampled rows
 Tolerances (the benchmark spec): max abs error <= 1e-4 (fp32), <= 2e-2 (bf16 in / fp32 accumulate).
 """
 import math
+import os
 
 import numpy as np
 import pytest
@@ -196,7 +197,11 @@ def _sweep_cases(n, seed):
     return cases
 
 
-@pytest.mark.parametrize("case", _sweep_cases(24, 2503), ids=lambda c: "x".join(map(str, c)))
+# (A2D_SWEEP_CASES in the environment widens both sweeps for an occasional longer hunt)
+_SWEEP_N = int(os.environ.get("A2D_SWEEP_CASES", "0"))
+
+
+@pytest.mark.parametrize("case", _sweep_cases(_SWEEP_N or 24, 2503), ids=lambda c: "x".join(map(str, c)))
 def test_seeded_shape_sweep_bf16(a2d, case):
     """Forward, and backward on both paths (recomputing dQ kernel / dS hand-over), on seeded random
     shapes.  As in test_partial_bwd_small the rows also see a second, always visible key block, so
@@ -532,7 +537,7 @@ def _sweep_seg_cases(n, seed):
     return cases
 
 
-@pytest.mark.parametrize("case", _sweep_seg_cases(16, 15758),
+@pytest.mark.parametrize("case", _sweep_seg_cases(_SWEEP_N or 16, 15758),
                          ids=lambda c: "%dkvx%d_%dxH%d_q%d_%s_%dseg" % (c[0], c[1], c[2], c[3], c[4], c[5], len(c[6])))
 def test_seeded_sweep_gathered_grouped_bf16(a2d, case):
     """Gathered key rows and grouped query heads together, forward and both backward paths, on
