@@ -303,6 +303,11 @@ a2d_status a2d_fix_strided(int k, int32_t heads, int32_t nq, int32_t hdim, int32
 a2d_status a2d_fix_bwd_strided(int k, int32_t heads, int32_t rows, int32_t hdim, int32_t out_dtype,
                                const float* const* parts, void* out, const a2d_layout* lout,
                                void* stream);
+/* a2d_fix_norm with O written through a layout, as a2d_fix_strided. */
+a2d_status a2d_fix_norm_strided(int k, int32_t heads, int32_t nq, int32_t hdim, int32_t in_dtype,
+                                int32_t out_dtype, const void* const* O_norm_parts,
+                                const float* const* lse_parts, void* O, const a2d_layout* lo,
+                                float* lse, void* stream);
 
 /*
  * Diagnostic, not part of the method: the rate the bf16 MFMA units of the current device

@@ -20,7 +20,7 @@ MAX_PARTS = 32
 EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
            "a2d_partial_fwd_seg", "a2d_partial_bwd_seg", "a2d_partial_fwd_acc", "a2d_partial_bwd_acc",
            "a2d_partial_fwd_norm", "a2d_fix_norm", "a2d_partial_fwd_gqa", "a2d_partial_bwd_gqa",
-           "a2d_fix_strided", "a2d_fix_bwd_strided",
+           "a2d_fix_strided", "a2d_fix_bwd_strided", "a2d_fix_norm_strided",
            "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling",
            "a2d_status_str", "a2d_last_error", "a2d_version")
 
@@ -109,6 +109,10 @@ def lib():
         L.a2d_fix_strided.argtypes = [ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                       ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
                                       ctypes.POINTER(Layout), vp, vp]
+        L.a2d_fix_norm_strided.restype = ctypes.c_int
+        L.a2d_fix_norm_strided.argtypes = [ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
+                                           ctypes.POINTER(Layout), vp, vp]
         L.a2d_fix_bwd_strided.restype = ctypes.c_int
         L.a2d_fix_bwd_strided.argtypes = [ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                           ctypes.POINTER(vp), vp, ctypes.POINTER(Layout), vp]
@@ -274,6 +278,14 @@ def fix_norm(O_norms, lses, out_dtype=torch.bfloat16, out=None):
         lse = torch.empty(shape[:-1], dtype=torch.float32, device=O_norms[0].device)
     else:
         O, lse = out
+    _plain(list(O_norms) + list(lses) + [lse], "the partials and lse")
+    if not O.is_contiguous():      # a [heads][nq][H] view: written in place through its strides
+        _dev3(O, "O")
+        lo = _layout(O)
+        _check(lib().a2d_fix_norm_strided(k, O.shape[0], O.shape[1], shape[-1], _dtype_code(O_norms[0].dtype),
+                                          _dtype_code(O.dtype), _ptr_array(O_norms), _ptr_array(lses), _ptr(O),
+                                          ctypes.byref(lo), _ptr(lse), _stream()))
+        return O, lse
     _check(lib().a2d_fix_norm(k, rows, shape[-1], _dtype_code(O_norms[0].dtype), _dtype_code(O.dtype),
                               _ptr_array(O_norms), _ptr_array(lses), _ptr(O), _ptr(lse), _stream()))
     return O, lse

@@ -270,10 +270,14 @@ a2d_status a2d_partial_fwd_norm(const a2d_tile_desc* desc, int nseg, const a2d_k
   return partial_fwd_impl(desc, g, Q, K, V, static_cast<float*>(O_norm), lse_part, lse_part, stream, who);
 }
 
-a2d_status a2d_fix_norm(int k, int64_t rows, int32_t hdim, int32_t in_dtype, int32_t out_dtype,
-                        const void* const* O_norm_parts, const float* const* lse_parts, void* O,
-                        float* lse, void* stream) {
-  const char* who = "a2d_fix_norm";
+}  // extern "C"
+
+namespace {
+a2d_status out_map(const a2d_layout* lo, int64_t nq, int32_t hdim, int32_t out_dtype, const char* who, a2d::OutMap* om);
+
+a2d_status fix_norm_impl(int k, int64_t rows, int32_t hdim, int32_t in_dtype, int32_t out_dtype,
+                         const void* const* O_norm_parts, const float* const* lse_parts, void* O,
+                         const a2d::OutMap& om, float* lse, void* stream, const char* who) {
   if (k < 1 || k > A2D_MAX_PARTS)
     return fail(A2D_ERR_INVALID_ARG, "%s: k=%d outside 1..%d", who, k, A2D_MAX_PARTS);
   if (rows < 1) return fail(A2D_ERR_INVALID_ARG, "%s: rows=%lld must be >= 1", who, (long long)rows);
@@ -293,8 +297,30 @@ a2d_status a2d_fix_norm(int k, int64_t rows, int32_t hdim, int32_t in_dtype, int
     A2D_TRY(check_ptr(lse_parts[x], who, "lse_parts[x]"));
     p.o[x] = O_norm_parts[x]; p.lse[x] = lse_parts[x];
   }
-  return hip_result(a2d::launch_fix_norm(k, rows, hdim, in_dtype, out_dtype, p, O, lse,
+  return hip_result(a2d::launch_fix_norm(k, rows, hdim, in_dtype, out_dtype, p, om, O, lse,
                                          static_cast<hipStream_t>(stream)), who);
+}
+}  // namespace
+
+extern "C" {
+
+a2d_status a2d_fix_norm(int k, int64_t rows, int32_t hdim, int32_t in_dtype, int32_t out_dtype,
+                        const void* const* O_norm_parts, const float* const* lse_parts, void* O,
+                        float* lse, void* stream) {
+  return fix_norm_impl(k, rows, hdim, in_dtype, out_dtype, O_norm_parts, lse_parts, O, a2d::plain_out(), lse,
+                       stream, "a2d_fix_norm");
+}
+
+a2d_status a2d_fix_norm_strided(int k, int32_t heads, int32_t nq, int32_t hdim, int32_t in_dtype,
+                                int32_t out_dtype, const void* const* O_norm_parts,
+                                const float* const* lse_parts, void* O, const a2d_layout* lo, float* lse,
+                                void* stream) {
+  const char* who = "a2d_fix_norm_strided";
+  if (heads < 1 || nq < 1) return fail(A2D_ERR_INVALID_ARG, "%s: heads=%d nq=%d must be >= 1", who, heads, nq);
+  a2d::OutMap om;
+  A2D_TRY(out_map(lo, nq, hdim, out_dtype, who, &om));
+  return fix_norm_impl(k, (int64_t)heads * nq, hdim, in_dtype, out_dtype, O_norm_parts, lse_parts, O, om, lse,
+                       stream, who);
 }
 
 // query heads per key/value head, or an error

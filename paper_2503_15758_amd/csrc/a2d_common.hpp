@@ -132,7 +132,7 @@ struct NormPtrs {
   const float* lse[A2D_MAX_PARTS];
 };
 hipError_t launch_fix_norm(int k, int64_t rows, int hdim, int in_dtype, int out_dtype, const NormPtrs& p,
-                           void* O, float* lse, hipStream_t s);
+                           const OutMap& om, void* O, float* lse, hipStream_t s);
 
 // MFMA-only ceiling probe (diagnostic)
 hipError_t launch_mfma_probe(int blocks, int iters, int random_data, float* scratch, hipStream_t s);

@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void sum_kernel(SumPtrs p, int k, int64_t n4, 
 // Merge of k NORMALISED partials: L = log sum_k exp(lse_k), O = sum_k exp(lse_k - L) O'_k.  A
 // column group = 4 consecutive columns of one row, as in fix_kernel; InT is the partials' dtype.
 template <typename InT, typename OutT, int KMAX, int CPT>
-__global__ __launch_bounds__(256) void fix_norm_kernel(NormPtrs p, int k, int64_t rows, int hv,
+__global__ __launch_bounds__(256) void fix_norm_kernel(NormPtrs p, int k, int64_t rows, int hv, OutMap om,
                                                        OutT* __restrict__ O, float* __restrict__ lse) {
   const int64_t base = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * 256;
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(256) void fix_norm_kernel(NormPtrs p, int k, int64_
     }
     const float inv = (D > 0.f) ? 1.0f / D : 0.f;
     acc[0] *= inv; acc[1] *= inv; acc[2] *= inv; acc[3] *= inv;
-    store_out4(O, idx * 4, acc);
+    store_out4(O, out_offset(om, idx, hv), acc);
     if (idx == row * hv) lse[row] = (D > 0.f) ? M + logf(D) : -INFINITY;
   }
 }
@@ -208,35 +208,35 @@ hipError_t sum_dispatch(int k, int64_t n, int hv, const SumPtrs& p, const OutMap
 
 
 template <typename InT, typename OutT, int KMAX>
-void fix_norm_launch(int k, int64_t rows, int hv, const NormPtrs& p, OutT* O, float* lse, hipStream_t s) {
+void fix_norm_launch(int k, int64_t rows, int hv, const NormPtrs& p, const OutMap& om, OutT* O, float* lse, hipStream_t s) {
   constexpr int CPT = chunks_per_thread(KMAX);
   const int64_t per_block = 256 * CPT;
   const dim3 grid((unsigned)((rows * hv + per_block - 1) / per_block)), block(256);
-  hipLaunchKernelGGL((fix_norm_kernel<InT, OutT, KMAX, CPT>), grid, block, 0, s, p, k, rows, hv, O, lse);
+  hipLaunchKernelGGL((fix_norm_kernel<InT, OutT, KMAX, CPT>), grid, block, 0, s, p, k, rows, hv, om, O, lse);
 }
 
 template <typename InT, typename OutT>
-hipError_t fix_norm_dispatch(int k, int64_t rows, int hdim, const NormPtrs& p, OutT* O, float* lse,
+hipError_t fix_norm_dispatch(int k, int64_t rows, int hdim, const NormPtrs& p, const OutMap& om, OutT* O, float* lse,
                              hipStream_t s) {
   const int hv = hdim / 4;
-  if (k <= 2) fix_norm_launch<InT, OutT, 2>(k, rows, hv, p, O, lse, s);
-  else if (k <= 4) fix_norm_launch<InT, OutT, 4>(k, rows, hv, p, O, lse, s);
-  else if (k <= 8) fix_norm_launch<InT, OutT, 8>(k, rows, hv, p, O, lse, s);
-  else if (k <= 16) fix_norm_launch<InT, OutT, 16>(k, rows, hv, p, O, lse, s);
-  else fix_norm_launch<InT, OutT, 32>(k, rows, hv, p, O, lse, s);
+  if (k <= 2) fix_norm_launch<InT, OutT, 2>(k, rows, hv, p, om, O, lse, s);
+  else if (k <= 4) fix_norm_launch<InT, OutT, 4>(k, rows, hv, p, om, O, lse, s);
+  else if (k <= 8) fix_norm_launch<InT, OutT, 8>(k, rows, hv, p, om, O, lse, s);
+  else if (k <= 16) fix_norm_launch<InT, OutT, 16>(k, rows, hv, p, om, O, lse, s);
+  else fix_norm_launch<InT, OutT, 32>(k, rows, hv, p, om, O, lse, s);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_fix_norm(int k, int64_t rows, int hdim, int in_dtype, int out_dtype, const NormPtrs& p,
-                           void* O, float* lse, hipStream_t s) {
+                           const OutMap& om, void* O, float* lse, hipStream_t s) {
   if (in_dtype == A2D_BF16) {
-    if (out_dtype == A2D_BF16) return fix_norm_dispatch<bf16_t, bf16_t>(k, rows, hdim, p, (bf16_t*)O, lse, s);
-    return fix_norm_dispatch<bf16_t, float>(k, rows, hdim, p, (float*)O, lse, s);
+    if (out_dtype == A2D_BF16) return fix_norm_dispatch<bf16_t, bf16_t>(k, rows, hdim, p, om, (bf16_t*)O, lse, s);
+    return fix_norm_dispatch<bf16_t, float>(k, rows, hdim, p, om, (float*)O, lse, s);
   }
-  if (out_dtype == A2D_BF16) return fix_norm_dispatch<float, bf16_t>(k, rows, hdim, p, (bf16_t*)O, lse, s);
-  return fix_norm_dispatch<float, float>(k, rows, hdim, p, (float*)O, lse, s);
+  if (out_dtype == A2D_BF16) return fix_norm_dispatch<float, bf16_t>(k, rows, hdim, p, om, (bf16_t*)O, lse, s);
+  return fix_norm_dispatch<float, float>(k, rows, hdim, p, om, (float*)O, lse, s);
 }
 
 hipError_t launch_fix(int k, int64_t rows, int hdim, int out_dtype, const FixPtrs& p, const OutMap& om, void* O,

@@ -651,7 +651,7 @@ def test_strided_inputs(a2d, case):
 
 @pytest.mark.parametrize("dt,H,k", [("bf16", 128, 3), ("f32", 64, 2), ("bf16", 80, 8)])
 def test_strided_merge_outputs(a2d, dt, H, k):
-    """a2d_fix_strided / a2d_fix_bwd_strided write O and the gradient sums into [heads][rows][H]
+    """a2d_fix_strided / a2d_fix_norm_strided / a2d_fix_bwd_strided write O and the gradient sums into [heads][rows][H]
     VIEWS of [rows][heads][H] buffers: bit for bit what the plain calls give, nothing written
     outside the views' elements."""
     heads, nq = 3, 70
@@ -668,6 +668,15 @@ def test_strided_merge_outputs(a2d, dt, H, k):
     assert O.data_ptr() == buf.data_ptr() and not view.is_contiguous()
     assert torch.equal(view, O_ref) and torch.equal(lse, lse_ref)
     assert bool((buf[:, 1] == 7.0).all()), "a2d_fix_strided wrote outside its rows"
+    # the merge of normalised partials, same output view
+    Ons = [dev((torch.randn(heads, nq, H, generator=g)).to(DT[dt])) for _ in range(k)]
+    On_ref, ln_ref = a2d.fix_norm(Ons, ms, DT[dt])
+    buf.fill_(7.0)
+    lse.zero_()
+    a2d.fix_norm(Ons, ms, out=(view, lse))
+    torch.cuda.synchronize()
+    assert torch.equal(view, On_ref) and torch.equal(lse, ln_ref)
+    assert bool((buf[:, 1] == 7.0).all()), "a2d_fix_norm_strided wrote outside its rows"
     parts = [dev(torch.randn(heads, nq, H, generator=g)) for _ in range(k)]
     s_ref = a2d.fix_bwd(parts, DT[dt])
     buf.fill_(7.0)

@@ -128,6 +128,9 @@ def test_argument_errors_enqueue_nothing(binding):
     assert L.a2d_fix_strided(2, 2, 10, 128, b.A2D_BF16, arr, arr, arr, P, lay(132, 256), P, None) == -3
     assert L.a2d_fix_strided(40, 2, 10, 128, b.A2D_BF16, arr, arr, arr, P, lay(128, 256), P, None) == -1
     assert L.a2d_fix_strided(2, 2, 10, 128, b.A2D_BF16, arr, arr, arr, None, lay(128, 256), P, None) == -1
+    assert L.a2d_fix_norm_strided(2, 2, 10, 128, b.A2D_BF16, b.A2D_BF16, arr, arr, P, lay(128, 100), P, None) == -1
+    assert L.a2d_fix_norm_strided(2, 2, 0, 128, b.A2D_BF16, b.A2D_BF16, arr, arr, P, lay(128, 256), P, None) == -1
+    assert L.a2d_fix_norm_strided(2, 2, 10, 128, b.A2D_BF16, b.A2D_F32, arr, arr, P, lay(130, 256), P, None) == -3
     assert L.a2d_fix_bwd_strided(2, 2, 0, 128, b.A2D_BF16, arr, P, lay(128, 256), None) == -1
     assert L.a2d_fix_bwd_strided(2, 2, 10, 126, b.A2D_BF16, arr, P, lay(128, 256), None) == -2
     assert L.a2d_fix_bwd_strided(2, 2, 10, 128, b.A2D_F32, arr, P, lay(130, 256), None) == -3
