@@ -213,6 +213,11 @@ def main():
                                                              TRAFFIC_BYTES.get(w.name, {}).get(dom))}
     if w.backward:
         roofline["bwd_path"] = "recompute" if args.recompute_bwd else "dS hand-over"
+        # the call's inputs and outputs read / written once (Q, K, V, O, dO in the model's dtype, three fp32
+        # gradient partials, lse): what `traffic` is to be held against.  The dS hand-over adds 2 bytes per
+        # visible score written and read back (an intermediate traded for two contractions).
+        esz = 2 if w.dtype == "bf16" else 4
+        roofline["algorithmic_bytes"] = w.heads * (5 * T * H * esz + 3 * T * H * 4 + T * 4)
 
     result = {
         "metric": "fwd+bwd attention TFLOP/s per tile + % bf16 MFMA peak; AttnFix GB/s",
@@ -312,6 +317,9 @@ def main():
         extra("grid_emulation", lambda: grid_emulation(synth))
     if not args.no_mfma_probe:
         extra("mfma_ceiling", mfma_ceiling)
+        ceil = result.get("mfma_ceiling", {}).get("random_operands", {}).get("tflops")
+        if ceil:   # context: the same kernel against what the MFMA units sustain on random operands on this chip
+            result["roofline"]["frac_of_random_operand_mfma_rate"] = round(roofline["achieved"] / ceil, 4)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, scale)
     print(json.dumps(result))
