@@ -197,11 +197,12 @@ def _sweep_cases(n, seed):
     return cases
 
 
-# (A2D_SWEEP_CASES in the environment widens both sweeps for an occasional longer hunt)
+# (A2D_SWEEP_CASES / A2D_SWEEP_SEED in the environment widen / move both sweeps for an occasional longer hunt)
 _SWEEP_N = int(os.environ.get("A2D_SWEEP_CASES", "0"))
+_SWEEP_SEED = int(os.environ.get("A2D_SWEEP_SEED", "0"))      # added to the two fixed seeds
 
 
-@pytest.mark.parametrize("case", _sweep_cases(_SWEEP_N or 24, 2503), ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("case", _sweep_cases(_SWEEP_N or 24, 2503 + _SWEEP_SEED), ids=lambda c: "x".join(map(str, c)))
 def test_seeded_shape_sweep_bf16(a2d, case):
     """Forward, and backward on both paths (recomputing dQ kernel / dS hand-over), on seeded random
     shapes.  As in test_partial_bwd_small the rows also see a second, always visible key block, so
@@ -537,7 +538,7 @@ def _sweep_seg_cases(n, seed):
     return cases
 
 
-@pytest.mark.parametrize("case", _sweep_seg_cases(_SWEEP_N or 16, 15758),
+@pytest.mark.parametrize("case", _sweep_seg_cases(_SWEEP_N or 16, 15758 + _SWEEP_SEED),
                          ids=lambda c: "%dkvx%d_%dxH%d_q%d_%s_%dseg" % (c[0], c[1], c[2], c[3], c[4], c[5], len(c[6])))
 def test_seeded_sweep_gathered_grouped_bf16(a2d, case):
     """Gathered key rows and grouped query heads together, forward and both backward paths, on
