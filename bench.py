@@ -518,8 +518,15 @@ def grouped_query(a2d, synth, w, scale, kernels):
         fwd = lambda: a2d.partial_fwd(Q, K, V, r * T, 0, True, scale, out=out)
         t_f = min(timeit(fwd), timeit(fwd, 20))     # the first batch still runs at the clock the set-up left
         t_b = timeit(lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, out=grads, workspace=ws))
+        # A2D_TILE_SPLIT_GROUPS: key blocks may be shared out over the group's query heads (larger workspace)
+        ws2 = torch.empty(a2d.workspace_bytes(a2d.tile_desc(Q, K, r * T, 0, True, scale), a2d.OP_PARTIAL_BWD_SPLIT, kvh),
+                          dtype=torch.uint8, device="cuda")
+        t_s = timeit(lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, out=grads, workspace=ws2,
+                                             split_groups=True))
+        del ws2
         res["cases"].append({"kv_heads": kvh, "fwd_ms": round(t_f, 4), "fwd_tflops": round(f_fl / t_f / 1e9, 1),
-                             "bwd_ms": round(t_b, 4), "bwd_tflops": round(b_fl / t_b / 1e9, 1)})
+                             "bwd_ms": round(t_b, 4), "bwd_tflops": round(b_fl / t_b / 1e9, 1),
+                             "bwd_split_groups_ms": round(t_s, 4), "bwd_split_groups_tflops": round(b_fl / t_s / 1e9, 1)})
     return res
 
 

@@ -61,7 +61,8 @@ typedef enum {
   A2D_OP_FIX = 1,
   A2D_OP_PARTIAL_BWD = 2,
   A2D_OP_FIX_BWD = 3,
-  A2D_OP_PARTIAL_BWD_DS = 4 /* workspace query only: a2d_partial_bwd with the dS hand-over */
+  A2D_OP_PARTIAL_BWD_DS = 4,   /* workspace query only: a2d_partial_bwd with the dS hand-over */
+  A2D_OP_PARTIAL_BWD_SPLIT = 5 /* workspace query only: a2d_partial_bwd_gqa with A2D_TILE_SPLIT_GROUPS */
 } a2d_op;
 
 /* Most partials one a2d_fix / a2d_fix_bwd call can merge (sqrt(P) in the paper). */
@@ -115,7 +116,10 @@ typedef struct {
  * gathered tile starting at multiples of 64 keys, less than 4 GiB of dS per key/value head
  * - all the query heads of its group together; otherwise the extra bytes are ignored).  Same results up to fp32
  * summation order; faster when the memory is there.
- * `k` is ignored for the tile ops.  Returns 0 for a NULL or invalid descriptor.
+ * A2D_OP_PARTIAL_BWD_SPLIT: the size a2d_partial_bwd_gqa needs with A2D_TILE_SPLIT_GROUPS: that of
+ * A2D_OP_PARTIAL_BWD_DS plus fp32 partial dK / dV buffers (at most 2 * heads * nkv * H floats);
+ * `k` = the number of key/value heads.
+ * `k` is ignored for the other tile ops.  Returns 0 for a NULL or invalid descriptor.
  */
 size_t a2d_workspace_bytes(const a2d_tile_desc* desc, int op, int k);
 
@@ -261,13 +265,20 @@ a2d_status a2d_fix_norm(int k, int64_t rows, int32_t hdim, int32_t in_dtype, int
  *                                                      out2 ignored, may be NULL)
  *   a2d_partial_bwd_gqa: K, V as above; dK_part, dV_part [kv_heads][nkv][H] fp32: the gradient of
  *     a key/value head is the SUM over the query heads of its group (taken inside the kernel, in
- *     head order; one writer per element, no atomics).  flags: 0 or A2D_TILE_ACCUMULATE (dQ +=).
- *     workspace as for a2d_partial_bwd.
+ *     head order; one writer per element, no atomics).  flags: 0 or A2D_TILE_ACCUMULATE (dQ +=),
+ *     optionally | A2D_TILE_SPLIT_GROUPS: the library may then give a key block to several
+ *     workgroups, each summing over a share of the group's query heads into an fp32 partial buffer
+ *     in the workspace, and add the partials up in a fixed order afterwards - for key/value head
+ *     counts that leave compute units idle (few key/value heads, short key rows).  Same results
+ *     up to fp32 summation order, still bitwise reproducible; needs a workspace of
+ *     a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD_SPLIT, kv_heads) bytes.
+ *     workspace otherwise as for a2d_partial_bwd.
  * nseg = 0 (segs ignored): the plain tile of desc->kv_off; nseg >= 1: a gathered tile.
  * group * nq may not exceed 2^22 rows.
  */
 #define A2D_TILE_ACCUMULATE 1
 #define A2D_TILE_NORMALISED 2
+#define A2D_TILE_SPLIT_GROUPS 4
 a2d_status a2d_partial_fwd_gqa(const a2d_tile_desc* desc, int32_t kv_heads, int nseg,
                                const a2d_kv_segment* segs, int flags, const void* Q, const void* K,
                                const void* V, void* out0, float* out1, float* out2,

@@ -14,7 +14,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "liba2d.so")
 
 A2D_F32, A2D_BF16 = 0, 1
-OP_PARTIAL_FWD, OP_FIX, OP_PARTIAL_BWD, OP_FIX_BWD, OP_PARTIAL_BWD_DS = 0, 1, 2, 3, 4
+OP_PARTIAL_FWD, OP_FIX, OP_PARTIAL_BWD, OP_FIX_BWD, OP_PARTIAL_BWD_DS, OP_PARTIAL_BWD_SPLIT = 0, 1, 2, 3, 4, 5
 MAX_PARTS = 32
 
 EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
@@ -43,7 +43,7 @@ class KvSegment(ctypes.Structure):
 
 
 MAX_SEGMENTS = 32
-TILE_ACCUMULATE, TILE_NORMALISED = 1, 2
+TILE_ACCUMULATE, TILE_NORMALISED, TILE_SPLIT_GROUPS = 1, 2, 4
 
 
 class A2DError(RuntimeError):
@@ -319,10 +319,13 @@ def fix(O_parts, ms, ls, out_dtype=torch.bfloat16, out=None):
 
 
 def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None, out=None,
-                workspace=None, segments=None, accumulate=False, ds_handover=False):
+                workspace=None, segments=None, accumulate=False, ds_handover=False, split_groups=False):
     """a2d_partial_bwd. Returns (dQ_part, dK_part, dV_part), all fp32.  With no `workspace` given,
     ds_handover=True allocates the larger one (a2d_workspace_bytes(A2D_OP_PARTIAL_BWD_DS)) that
-    makes the library keep dS for the dQ contraction instead of recomputing it."""
+    makes the library keep dS for the dQ contraction instead of recomputing it.  split_groups=True
+    (grouped heads only) passes A2D_TILE_SPLIT_GROUPS: a key block may go to several workgroups,
+    each summing over a share of the group's query heads (workspace of A2D_OP_PARTIAL_BWD_SPLIT
+    size, which includes the dS area)."""
     for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
         _dev3(t, n)
     if O.shape != Q.shape or dO.shape != Q.shape or O.dtype != Q.dtype or dO.dtype != Q.dtype or \
@@ -331,6 +334,9 @@ def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None
         raise A2DError(-1, "O, dO, lse do not match Q (lse: plain fp32 [heads][nq])")
     d = tile_desc(Q, K, q_off, kv_off, causal, scale, V, O, dO)
     need = workspace_bytes(d, OP_PARTIAL_BWD_DS if ds_handover else OP_PARTIAL_BWD)
+    split_groups = bool(split_groups) and K.shape[0] != Q.shape[0]
+    if split_groups:
+        need = workspace_bytes(d, OP_PARTIAL_BWD_SPLIT, int(K.shape[0]))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     if out is None:
@@ -345,7 +351,8 @@ def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None
     if K.shape[0] != Q.shape[0]:   # grouped queries: dK_part, dV_part have K's heads
         n = len(segments) if segments is not None else 0
         _check(lib().a2d_partial_bwd_gqa(ctypes.byref(d), int(K.shape[0]), n, _segments(segments) if n else None,
-                                         TILE_ACCUMULATE if accumulate else 0, _ptr(Q), _ptr(K), _ptr(V),
+                                         (TILE_ACCUMULATE if accumulate else 0) |
+                                         (TILE_SPLIT_GROUPS if split_groups else 0), _ptr(Q), _ptr(K), _ptr(V),
                                          _ptr(O), _ptr(dO), _ptr(lse), _ptr(dQ), _ptr(dK), _ptr(dV),
                                          _ptr(workspace), workspace.numel() * workspace.element_size(),
                                          _stream()))

@@ -123,6 +123,7 @@ a2d::SegList one_segment(const a2d_tile_desc* d) {
   g.n = 1;
   g.group = 1;
   g.split = 1;
+  g.qsplit = 1;
   g.start[0] = 0;
   g.rows[0] = d->nkv;
   g.rel[0] = d->q_off - d->kv_off;
@@ -138,6 +139,7 @@ a2d_status make_segments(const a2d_tile_desc* d, int nseg, const a2d_kv_segment*
   g->n = nseg;
   g->group = 1;
   g->split = 1;
+  g->qsplit = 1;
   int64_t total = 0;
   for (int s = 0; s < nseg; ++s) {
     if (segs[s].rows < 1 || segs[s].pad != 0)
@@ -195,7 +197,7 @@ a2d_status partial_fwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
 a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, const void* Q, const void* K,
                             const void* V, const void* O, const void* dO, const float* lse,
                             float* dQ_part, float* dK_part, float* dV_part, void* workspace,
-                            size_t workspace_bytes, void* stream, const char* who) {
+                            size_t workspace_bytes, void* stream, const char* who, bool split_groups = false) {
   A2D_TRY(check_ptr(Q, who, "Q"));
   A2D_TRY(check_ptr(K, who, "K"));
   A2D_TRY(check_ptr(V, who, "V"));
@@ -218,6 +220,16 @@ a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
   hipStream_t s = static_cast<hipStream_t>(stream);
   a2d_tile_desc dd;
   A2D_TRY(resolve_layouts(desc, g.group, true, who, &dd));
+  // the partial dK / dV buffers of a split over the group's query heads lie behind the dS area
+  float* split_ws = nullptr;
+  if (split_groups && g.group > 1) {
+    const size_t all = a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD_SPLIT, desc->heads / g.group);
+    if (workspace_bytes < all)
+      return fail(A2D_ERR_WORKSPACE, "%s: A2D_TILE_SPLIT_GROUPS needs a workspace of %zu bytes, %zu given", who, all,
+                  workspace_bytes);
+    split_ws = reinterpret_cast<float*>(static_cast<char*>(workspace) +
+                                        a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD_DS, 0));
+  }
   float* delta = static_cast<float*>(workspace);
   A2D_TRY(hip_result(a2d::launch_delta(dd, O, dO, delta, s), who));
   if (!force_generic() && a2d::bwd_mfma_supported(dd)) {
@@ -227,7 +239,7 @@ a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
     a2d::SegList go = g;
     go.by_size = blocks_differ(desc, g);
     return hip_result(a2d::launch_bwd_mfma(dd, go, Q, K, V, dO, lse, delta, dQ_part, dK_part,
-                                           dV_part, ds_ws, s), who);
+                                           dV_part, ds_ws, split_ws, s), who);
   }
   return hip_result(a2d::launch_bwd_generic(dd, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
                                             dV_part, s), who);
@@ -237,13 +249,21 @@ a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
 
 extern "C" {
 
-size_t a2d_workspace_bytes(const a2d_tile_desc* desc, int op, int /*k*/) {
+size_t a2d_workspace_bytes(const a2d_tile_desc* desc, int op, int k) {
   if (!desc || desc->heads < 1 || desc->nq < 1) return 0;
-  if (op != A2D_OP_PARTIAL_BWD && op != A2D_OP_PARTIAL_BWD_DS) return 0;
+  if (op != A2D_OP_PARTIAL_BWD && op != A2D_OP_PARTIAL_BWD_DS && op != A2D_OP_PARTIAL_BWD_SPLIT) return 0;
   const size_t rows = (size_t)desc->heads * (size_t)desc->nq;
   const size_t delta_bytes = ((rows * sizeof(float) + 255) / 256) * 256;
   if (op == A2D_OP_PARTIAL_BWD || desc->nkv < 1) return delta_bytes;
-  return delta_bytes + a2d::bwd_ds_bytes(*desc, one_segment(desc));
+  // (the dS area is sized for the plain tile whether or not a call ends up using it, so that the
+  // areas behind it have a fixed place)
+  const size_t ds_area = ((a2d::bwd_ds_bytes(*desc, one_segment(desc)) + 255) / 256) * 256;
+  if (op == A2D_OP_PARTIAL_BWD_DS) return delta_bytes + ds_area;
+  // partial dK / dV of a split over the group's query heads: 2 x min(group, A2D_MAX_PARTS) buffers
+  const int kv_heads = (k >= 1 && desc->heads % k == 0) ? k : desc->heads;
+  const int group = desc->heads / kv_heads;
+  const size_t parts = group < A2D_MAX_PARTS ? group : A2D_MAX_PARTS;
+  return delta_bytes + ds_area + 2 * parts * (size_t)kv_heads * desc->nkv * desc->hdim * sizeof(float);
 }
 
 a2d_status a2d_partial_fwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,
@@ -360,14 +380,14 @@ a2d_status a2d_partial_bwd_gqa(const a2d_tile_desc* desc, int32_t kv_heads, int 
                                size_t workspace_bytes, void* stream) {
   const char* who = "a2d_partial_bwd_gqa";
   A2D_TRY(check_desc(desc, who));
-  if (flags != 0 && flags != A2D_TILE_ACCUMULATE)
-    return fail(A2D_ERR_INVALID_ARG, "%s: flags=%d must be 0 or A2D_TILE_ACCUMULATE", who, flags);
+  if ((flags & ~(A2D_TILE_ACCUMULATE | A2D_TILE_SPLIT_GROUPS)) != 0)
+    return fail(A2D_ERR_INVALID_ARG, "%s: flags=%d: only A2D_TILE_ACCUMULATE and A2D_TILE_SPLIT_GROUPS apply", who, flags);
   a2d::SegList g = one_segment(desc);
   if (nseg != 0) A2D_TRY(make_segments(desc, nseg, segs, who, &g));
   A2D_TRY(group_of(desc, kv_heads, who, &g));
-  g.acc = flags == A2D_TILE_ACCUMULATE;
+  g.acc = (flags & A2D_TILE_ACCUMULATE) != 0;
   return partial_bwd_impl(desc, g, Q, K, V, O, dO, lse, dQ_part, dK_part, dV_part, workspace,
-                          workspace_bytes, stream, who);
+                          workspace_bytes, stream, who, (flags & A2D_TILE_SPLIT_GROUPS) != 0);
 }
 
 a2d_status a2d_partial_fwd_acc(const a2d_tile_desc* desc, int nseg, const a2d_kv_segment* segs,

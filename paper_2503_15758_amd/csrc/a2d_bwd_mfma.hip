@@ -277,21 +277,38 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
   int head, blk;
-  // `head` is the KEY/VALUE head; its g.group query heads are consecutive rows of Q, dO, lse, delta
-  const int group = GROUPED ? g.group : 1;
-  if (!xcd_map(GROUPED ? d.heads / group : d.heads, (d.nkv + DK_KEYS - 1) / DK_KEYS, g.by_size != 0, head, blk)) return;
+  // `head` is the KEY/VALUE head; its g.group query heads are consecutive rows of Q, dO, lse, delta.
+  // With g.qsplit = Z > 1 (grouped heads only) Z workgroups share a key block: workgroup z walks the
+  // query heads z * group / Z ... of the group and leaves its sums in partial buffer z (dK, dV then
+  // point at Z buffers of [key/value heads][nkv][H], added up by a sum kernel afterwards).
+  const int qsplit = GROUPED ? g.qsplit : 1;
+  const int group = GROUPED ? g.group / qsplit : 1;          // query heads this workgroup walks
+  int qh0 = 0;                                               // the first of them, as a head of Q
+  {
+    int unit;
+    if (!xcd_map((GROUPED ? d.heads / g.group : d.heads) * qsplit, (d.nkv + DK_KEYS - 1) / DK_KEYS, g.by_size != 0,
+                 unit, blk)) return;
+    head = unit / qsplit;
+    const int z = unit - head * qsplit;
+    qh0 = GROUPED ? head * g.group + z * group : head;
+    if (GROUPED && qsplit > 1) {
+      const int64_t part = (int64_t)z * (d.heads / g.group) * d.nkv * HR;
+      dK += part;
+      dV += part;
+    }
+  }
   constexpr int HD = padded_head(HR), H = HR, KS = HD / 16, CT = HD / 32;
   const int k0 = blk * DK_KEYS;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int pair = wave & 3, role = wave >> 2;   // wavefronts w and w + 4 share 32 keys
   const int l32 = lane & 31;
-  Q += (int64_t)head * group * d.lq.head;
-  dO += (int64_t)head * group * d.ldo.head;
+  Q += (int64_t)qh0 * d.lq.head;
+  dO += (int64_t)qh0 * d.ldo.head;
   K += (int64_t)head * d.lk.head;
   V += (int64_t)head * d.lv.head;
-  lse += (int64_t)head * group * d.nq;
-  delta += (int64_t)head * group * d.nq;
+  lse += (int64_t)qh0 * d.nq;
+  delta += (int64_t)qh0 * d.nq;
 
   DkCtx<HD> cx;
   cx.half = lane >> 5;
@@ -455,7 +472,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
   const unsigned ds_lane_off = (unsigned)(2 * blk + (pair >> 1)) * DS_TILE_BYTES + (pair & 1) * 2048 + lane * 16;
   gwptr_t ds_base = nullptr;
   if constexpr (WRITE_DS)
-    ds_base = uniform_gwptr(reinterpret_cast<char*>(dS) + (int64_t)head * group * ds_head_bytes(d.nq, d.nkv));
+    ds_base = uniform_gwptr(reinterpret_cast<char*>(dS) + (int64_t)qh0 * ds_head_bytes(d.nq, d.nkv));
 
   // A step is skipped (by both wavefronts of its pair) when none of its rows sees any of the
   // pair's keys; it is masked unless every row sees every key.
@@ -1061,7 +1078,7 @@ hipError_t bwd_launch_ds(const a2d_tile_desc& d, const SegList& g, const void* Q
                               : reinterpret_cast<const void*>(bwd_dq_ds_kernel<4, HR>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, DSQ_LDS);
   if (e != hipSuccess) return e;
-  dim3 grid_kv(xcd_grid(d.heads / g.group, (d.nkv + DK_KEYS - 1) / DK_KEYS));
+  dim3 grid_kv(xcd_grid(d.heads / g.group * g.qsplit, (d.nkv + DK_KEYS - 1) / DK_KEYS));
   const int dq_rows = big ? 256 : 128;
   const int per_unit = g.group / g.split;
   dim3 grid_q(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + dq_rows - 1) / dq_rows)));
@@ -1109,7 +1126,7 @@ hipError_t bwd_launch_hd(const a2d_tile_desc& d, const SegList& g, const void* Q
                               : reinterpret_cast<const void*>(bwd_dq_kernel<4, HR>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
   if (e != hipSuccess) return e;
-  dim3 grid_kv(xcd_grid(d.heads / g.group, (d.nkv + DK_KEYS - 1) / DK_KEYS));
+  dim3 grid_kv(xcd_grid(d.heads / g.group * g.qsplit, (d.nkv + DK_KEYS - 1) / DK_KEYS));
   const int dq_rows = big ? 256 : 128;
   const int per_unit = g.group / g.split;
   dim3 grid_q(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + dq_rows - 1) / dq_rows)));
@@ -1133,15 +1150,59 @@ hipError_t bwd_launch_hd(const a2d_tile_desc& d, const SegList& g, const void* Q
 }
 }  // namespace
 
+// How many workgroups should share a key block of a grouped-head dK/dV launch (each walking
+// group / Z of the query heads): the divisor Z of `group` (at most A2D_MAX_PARTS) that minimises
+// rounds of workgroups over the compute units x query heads per workgroup; the smallest on a tie.
+int choose_qsplit(int kv_heads, int group, int key_blocks, int cus) {
+  int best = 1;
+  int64_t best_cost = -1;
+  for (int z = 1; z <= group && z <= A2D_MAX_PARTS; ++z) {
+    if (group % z != 0) continue;
+    const int64_t wgs = (int64_t)kv_heads * z * key_blocks;
+    const int64_t cost = ((wgs + cus - 1) / cus) * (group / z);
+    if (best_cost < 0 || cost < best_cost) { best = z; best_cost = cost; }
+  }
+  return best;
+}
+
 // ds_ws != NULL: a workspace of bwd_ds_bytes(d, g) bytes; the dK/dV kernel leaves dS there and the
 // dQ kernel is the contraction-only one.
+// split_ws != NULL (grouped heads): room for 2 * min(group, A2D_MAX_PARTS) partial buffers of
+// [key/value heads][nkv][H] floats; the query heads of a group may then be split over several
+// workgroups per key block (choose_qsplit) whose dK / dV sums a sum kernel adds up.
 hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                            const void* dO, const float* lse, const float* delta, float* dQ,
-                           float* dK, float* dV, void* ds_ws, hipStream_t s) {
-  if (d.hdim == 128) return bwd_launch_hd<128>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
-  if (d.hdim == 96) return bwd_launch_hd<96>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
-  if (d.hdim == 80) return bwd_launch_hd<80>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
-  return bwd_launch_hd<64>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
+                           float* dK, float* dV, void* ds_ws, float* split_ws, hipStream_t s) {
+  SegList gg = g;
+  gg.qsplit = 1;
+  float* dKo = dK;
+  float* dVo = dV;
+  const int kv_heads = d.heads / g.group;
+  const int64_t n = (int64_t)kv_heads * d.nkv * d.hdim;        // elements of dK (of dV)
+  if (split_ws && g.group > 1) {
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    gg.qsplit = choose_qsplit(kv_heads, g.group, (d.nkv + DK_KEYS - 1) / DK_KEYS, cus > 0 ? cus : 1);
+    if (gg.qsplit > 1) {
+      dKo = split_ws;
+      dVo = split_ws + (int64_t)gg.qsplit * n;
+    }
+  }
+  hipError_t e;
+  if (d.hdim == 128) e = bwd_launch_hd<128>(d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
+  else if (d.hdim == 96) e = bwd_launch_hd<96>(d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
+  else if (d.hdim == 80) e = bwd_launch_hd<80>(d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
+  else e = bwd_launch_hd<64>(d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
+  if (e != hipSuccess || gg.qsplit == 1) return e;
+  // dK = sum_z partial z (in order of z: bitwise reproducible), the same for dV
+  SumPtrs pk, pv;
+  for (int z = 0; z < A2D_MAX_PARTS; ++z) { pk.p[z] = nullptr; pv.p[z] = nullptr; }
+  for (int z = 0; z < gg.qsplit; ++z) { pk.p[z] = dKo + (int64_t)z * n; pv.p[z] = dVo + (int64_t)z * n; }
+  e = launch_fix_bwd(gg.qsplit, n, d.hdim / 4, A2D_F32, pk, plain_out(), dK, s);
+  if (e != hipSuccess) return e;
+  return launch_fix_bwd(gg.qsplit, n, d.hdim / 4, A2D_F32, pv, plain_out(), dV, s);
 }
 
 }  // namespace a2d

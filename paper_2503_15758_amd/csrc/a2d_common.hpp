@@ -54,6 +54,7 @@ struct SegList {
   int group;
   int split;
   int by_size;
+  int qsplit;     // dK/dV kernel, grouped heads: workgroups per key block, each walking group / qsplit query heads
   int start[A2D_MAX_SEGMENTS];
   int rows[A2D_MAX_SEGMENTS];
   int64_t rel[A2D_MAX_SEGMENTS];
@@ -102,7 +103,9 @@ bool bwd_mfma_supported(const a2d_tile_desc& d);
 size_t bwd_ds_bytes(const a2d_tile_desc& d, const SegList& g);
 hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                            const void* dO, const float* lse, const float* delta, float* dQ,
-                           float* dK, float* dV, void* ds_ws, hipStream_t s);
+                           float* dK, float* dV, void* ds_ws, float* split_ws, hipStream_t s);
+// the dK/dV kernel's choice of workgroups per key block for grouped heads (see launch_bwd_mfma)
+int choose_qsplit(int kv_heads, int group, int key_blocks, int cus);
 
 struct FixPtrs {
   const float* o[A2D_MAX_PARTS];

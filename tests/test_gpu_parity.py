@@ -939,6 +939,20 @@ def test_grouped_query_heads(a2d, dt, case):
     assert_close(dQ, rq, DT[dt], what + " dQ")
     assert_close(dK, rk, DT[dt], what + " dK")
     assert_close(dV, rv, DT[dt], what + " dV")
+    # A2D_TILE_SPLIT_GROUPS: the query heads of a group shared out over several workgroups per key
+    # block (on shapes this small: one query head each), partial sums added in a fixed order - the
+    # same gradients to rounding, dQ bit for bit (its kernel is not touched), twice the same bits
+    for handover in (False, True):
+        s3 = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, kv_off, causal,
+                             scale, segments=segs, ds_handover=handover, split_groups=True)
+        s3b = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, kv_off, causal,
+                              scale, segments=segs, ds_handover=handover, split_groups=True)
+        torch.cuda.synchronize()
+        assert torch.equal(s3[0], dQh), what + ": dQ with the split differs"
+        assert_close(s3[1], rk, DT[dt], what + " dK, split groups")
+        assert_close(s3[2], rv, DT[dt], what + " dV, split groups")
+        for x, y in zip(s3, s3b):
+            assert torch.equal(x, y), what + ": split groups not reproducible"
     # kv_heads == heads through the same entry point is the plain call, bit for bit
     if grp > 1 and segs is None:
         Kf, Vf = dev(torch.from_numpy(Kr).to(DT[dt])), dev(torch.from_numpy(Vr).to(DT[dt]))

@@ -70,6 +70,12 @@ def test_workspace_bytes(binding):
     assert b.workspace_bytes(_desc(b), b.OP_PARTIAL_BWD_DS) == 2 * 128 * 4 + 2 * 4 * 2 * 4096
     assert b.workspace_bytes(_desc(b, nq=33, nkv=65), b.OP_PARTIAL_BWD_DS) == 512 + 2 * 2 * 2 * 4096
     assert b.workspace_bytes(_desc(b, dtype=b.A2D_F32), b.OP_PARTIAL_BWD_DS) == 2 * 128 * 4
+    # split over the group's query heads: + 2 x min(group, 32) partial buffers of [kv heads][nkv][H] floats
+    ds = b.workspace_bytes(_desc(b, heads=8), b.OP_PARTIAL_BWD_DS)
+    assert b.workspace_bytes(_desc(b, heads=8), b.OP_PARTIAL_BWD_SPLIT, 2) == ds + 2 * 4 * 2 * 128 * 128 * 4
+    assert b.workspace_bytes(_desc(b, heads=8), b.OP_PARTIAL_BWD_SPLIT, 8) == ds + 2 * 1 * 8 * 128 * 128 * 4
+    assert b.workspace_bytes(_desc(b, heads=64), b.OP_PARTIAL_BWD_SPLIT, 1) == \
+        b.workspace_bytes(_desc(b, heads=64), b.OP_PARTIAL_BWD_DS) + 2 * 32 * 1 * 128 * 128 * 4
 
 
 def test_argument_errors_enqueue_nothing(binding):
@@ -232,6 +238,12 @@ def test_grouped_query_argument_errors(binding):
     assert bwd(heads + 1, 0) == -1
     assert bwd(1, b.TILE_NORMALISED) == -1                        # the backward has no normalised form
     assert bwd(1, 0) == -4                                        # first failing check: the workspace
+    assert bwd(1, 8) == -1 and b"flags" in L.a2d_last_error()     # an unknown flag bit
+    # A2D_TILE_SPLIT_GROUPS with a workspace that only covers the dS hand-over: refused before any launch
+    small = b.workspace_bytes(d, b.OP_PARTIAL_BWD_DS)
+    assert L.a2d_partial_bwd_gqa(ctypes.byref(d), 1, 0, None, b.TILE_SPLIT_GROUPS, P, P, P, P, P, P, P, P, P, P,
+                                 small, None) == -4
+    assert b"SPLIT_GROUPS" in L.a2d_last_error()
     assert L.a2d_partial_bwd_gqa(ctypes.byref(d), 1, 0, None, 0, P, P, P, P, P, P, P, P, P, P, 1 << 50, None) == -1
     assert b"plausible" in L.a2d_last_error()                    # a size no allocation can have
     big = _desc(b, nq=1 << 22)
