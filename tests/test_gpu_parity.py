@@ -576,12 +576,12 @@ def test_seeded_sweep_gathered_grouped_bf16(a2d, case):
     rq, rk, rv = oracle.partial_bwd_pos(np64(Q), Kx, Vx, np64(O_in), np64(dO), np64(lse_in), q_off, kpos, causal, scale)
     rk = rk.reshape(kv_heads, group, nkv, H).sum(axis=1)
     rv = rv.reshape(kv_heads, group, nkv, H).sum(axis=1)
-    for handover in (False, True):
+    for handover, split in ((False, False), (True, False), (True, True)):
         dQ, dK, dV = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, 0, causal,
-                                     scale, segments=segs, ds_handover=handover)
+                                     scale, segments=segs, ds_handover=handover, split_groups=split)
         torch.cuda.synchronize()
         for got, ref, name in ((dQ, rq, "dQ"), (dK, rk, "dK"), (dV, rv, "dV")):
-            assert_close(got, ref, torch.bfloat16, "%s %s handover=%s" % (what, name, handover),
+            assert_close(got, ref, torch.bfloat16, "%s %s handover=%s split=%s" % (what, name, handover, split),
                          rel=bool(np.abs(ref).max() > 1e-3))
 
 
