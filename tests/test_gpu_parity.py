@@ -299,8 +299,10 @@ def _sample_rows(T):
 
 def test_c3_causal_tiles_full_heads(a2d):
     """GPT-3-like causal workload: query block r = 7 against all 8 key blocks at 96 heads (the
-    benchmark's launch shape); oracle on head 0 and head 95 rows sampled, bwd of the diagonal and one
-    unmasked tile on head 0."""
+    benchmark's launch shape).  Forward: oracle on sampled rows of the first, a middle and the last
+    head; every tile re-run and re-merged bit for bit.  Backward of the diagonal and of one
+    unmasked tile, both paths, on the first and a middle head, from the ORACLE's final O / lse of
+    those heads (whole rows of the query block against all 32768 keys)."""
     w = synth.WORKLOADS["c3"]
     T, scale, G, r = w.tile, 1.0 / math.sqrt(w.hdim), w.grid, w.grid - 1
     Qr = synth.q_block(w, r)
@@ -312,12 +314,18 @@ def test_c3_causal_tiles_full_heads(a2d):
     parts = [a2d.partial_fwd(Qd, Kd[c], Vd[c], r * T, c * T, True, scale) for c in range(G)]
     O, lse = a2d.fix([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], torch.bfloat16)
     torch.cuda.synchronize()
-    parts2 = a2d.partial_fwd(Qd, Kd[r], Vd[r], r * T, r * T, True, scale)
-    O2, lse2 = a2d.fix([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], torch.bfloat16)
+    # run to run: every tile and the merge of the re-run tiles, bit for bit
+    parts2 = [a2d.partial_fwd(Qd, Kd[c], Vd[c], r * T, c * T, True, scale) for c in range(G)]
+    O2, lse2 = a2d.fix([p[0] for p in parts2], [p[1] for p in parts2], [p[2] for p in parts2], torch.bfloat16)
     torch.cuda.synchronize()
-    assert torch.equal(lse, lse2) and torch.equal(O, O2) and torch.equal(parts2[1], parts[r][1])
+    assert torch.equal(lse, lse2) and torch.equal(O, O2)
+    for c in range(G):
+        for x, y, name in zip(parts[c], parts2[c], ("N", "m", "l")):
+            assert torch.equal(x, y), "c3 tile %d: %s differs between two runs" % (c, name)
+    del parts2, O2, lse2
     rows = _sample_rows(T)
-    for h in (0, w.heads - 1):
+    mid = 43                                   # 43 mod 8 = 3: neither the first nor the last XCD
+    for h in (0, mid, w.heads - 1):
         trip = [oracle.partial_fwd(np64(Qr[h:h + 1, rows]), np64(Kb[c][h:h + 1]), np64(Vb[c][h:h + 1]),
                                    0, 0, False, scale) if c < r else None for c in range(G)]
         # the diagonal block needs per-row offsets: evaluate the sampled rows one contiguous run at a time
@@ -334,18 +342,32 @@ def test_c3_causal_tiles_full_heads(a2d):
             assert_close(np64(parts[c][1][h:h + 1, rows]), trip[c][1], torch.bfloat16, "c3 m", rel=False)
             assert_close(np64(parts[c][0][h:h + 1, rows]) / np64(parts[c][2][h:h + 1, rows])[..., None],
                          trip[c][0] / trip[c][2][..., None], torch.bfloat16, "c3 N/l tile %d" % c)
-    # backward of the diagonal tile and of the unmasked tile (r, 0), all heads on the GPU, head 0 checked
-    # (once with the minimum workspace - the dQ kernel recomputes the scores - and once with the
-    # larger one that makes the dK/dV kernel hand dS over, the path the benchmark times)
+    del parts
+    # backward of the diagonal tile and of the unmasked tile (r, 0), all heads on the GPU, heads 0 and
+    # `mid` checked (once with the minimum workspace - the dQ kernel recomputes the scores - and once
+    # with the dS hand-over, the path the benchmark times).  Those two heads get the oracle's own
+    # final O / lse (rounded to the storage types) as inputs, on the GPU and in the oracle alike.
+    hb = [0, mid]
+    full = [oracle.partial_fwd(np64(Qr[hb]), np64(Kb[c][hb]), np64(Vb[c][hb]), r * T, c * T, True, scale)
+            for c in range(G)]
+    Of, lsef = oracle.fix([t[0] for t in full], [t[1] for t in full], [t[2] for t in full])
+    assert_close(np64(O[hb]), Of, torch.bfloat16, "c3 O, whole heads")
+    assert_close(np64(lse[hb]), lsef, torch.bfloat16, "c3 lse, whole heads", rel=False)
+    O_in, lse_in = O.clone(), lse.clone()
+    O_h, lse_h = torch.from_numpy(Of).to(torch.bfloat16), torch.from_numpy(lsef).to(torch.float32)
+    O_in[hb] = dev(O_h)
+    lse_in[hb] = dev(lse_h)
+    d = a2d.tile_desc(Qd, Kd[0], r * T, 0, True, scale)
+    assert a2d.workspace_bytes(d, a2d.OP_PARTIAL_BWD_DS) > a2d.workspace_bytes(d, a2d.OP_PARTIAL_BWD)
     for c in (r, 0):
-        rQ, rK, rV = oracle.partial_bwd(np64(Qr[:1]), np64(Kb[c][:1]), np64(Vb[c][:1]), np64(O[:1]), np64(dOr[:1]),
-                                        np64(lse[:1]), r * T, c * T, True, scale)
+        rQ, rK, rV = oracle.partial_bwd(np64(Qr[hb]), np64(Kb[c][hb]), np64(Vb[c][hb]), np64(O_h), np64(dOr[hb]),
+                                        np64(lse_h), r * T, c * T, True, scale)
         for handover in (False, True):
-            dQ, dK, dV = a2d.partial_bwd(Qd, Kd[c], Vd[c], O, dOd, lse, r * T, c * T, True, scale,
+            dQ, dK, dV = a2d.partial_bwd(Qd, Kd[c], Vd[c], O_in, dOd, lse_in, r * T, c * T, True, scale,
                                          ds_handover=handover)
             torch.cuda.synchronize()
             for got, ref, name in ((dQ, rQ, "dQ"), (dK, rK, "dK"), (dV, rV, "dV")):
-                assert_close(got[:1], ref, torch.bfloat16, "c3 bwd tile (7,%d) %s%s" % (c, name, " (dS hand-over)" if handover else ""))
+                assert_close(got[hb], ref, torch.bfloat16, "c3 bwd tile (7,%d) %s%s" % (c, name, " (dS hand-over)" if handover else ""))
             del dQ, dK, dV
 
 
@@ -382,13 +404,20 @@ def test_c3_gathered_row_full_heads(a2d):
         assert_close(np64(On[h:h + 1, rows]), Or, torch.bfloat16, "c3 row O' head %d" % h)
         assert_close(np64(lsen[h:h + 1, rows]), lser, torch.bfloat16, "c3 row lse' head %d" % h, rel=False)
     del Kd, Vd, Np, On
-    # backward: sub-blocks 0 and 7, with the final O / lse of the whole row
+    # backward: sub-blocks 0 and 7, with the final O / lse of the whole row; head 0 is checked and
+    # gets the oracle's own O / lse (rounded to the storage types) as inputs on both sides
+    Nf, mf, lf = oracle.partial_fwd_pos(np64(Qr[:1]), np64(Kall[:1]), np64(Vall[:1]), r * T, kpos, True, scale)
+    Of, lsef = oracle.fix([Nf], [mf], [lf])
+    O_h, lse_h = torch.from_numpy(Of).to(torch.bfloat16), torch.from_numpy(lsef).to(torch.float32)
+    O_in, lse_in = O.clone(), lse.clone()
+    O_in[:1] = dev(O_h)
+    lse_in[:1] = dev(lse_h)
     seg2 = [(0, T), (r * T, T)]
     K2, V2 = torch.cat([Kb[0], Kb[r]], dim=1), torch.cat([Vb[0], Vb[r]], dim=1)
-    dQ, dK, dV = a2d.partial_bwd(Qd, dev(K2), dev(V2), O, dev(dOr), lse, r * T, 0, True, scale, segments=seg2)
+    dQ, dK, dV = a2d.partial_bwd(Qd, dev(K2), dev(V2), O_in, dev(dOr), lse_in, r * T, 0, True, scale, segments=seg2)
     torch.cuda.synchronize()
-    rq, rk, rv = oracle.partial_bwd_pos(np64(Qr[:1]), np64(K2[:1]), np64(V2[:1]), np64(O[:1]), np64(dOr[:1]),
-                                        np64(lse[:1]), r * T, oracle.segment_positions(seg2), True, scale)
+    rq, rk, rv = oracle.partial_bwd_pos(np64(Qr[:1]), np64(K2[:1]), np64(V2[:1]), np64(O_h), np64(dOr[:1]),
+                                        np64(lse_h), r * T, oracle.segment_positions(seg2), True, scale)
     for got, ref, name in ((dQ, rq, "dQ"), (dK, rk, "dK"), (dV, rv, "dV")):
         assert_close(got[:1], ref, torch.bfloat16, "c3 row bwd {0,7} %s" % name)
 
@@ -424,17 +453,27 @@ def test_long_context_tiles_sampled(a2d, name):
     # backward of tile (0, 0) at full head count; oracle on a 2048 x 2048 corner of head 0 is not a
     # valid sub-problem (gradients couple all rows), so check dQ on sampled query rows (needs all keys
     # of the tile) and dK/dV through their sums over keys, which need only per-row quantities.
+    # Head 0 is checked; its O / lse inputs come from the oracle (attention of the query block over
+    # this one key block, as if it were the whole sequence: the gradient formulas only need O and
+    # lse to belong together), rounded to the storage types, on the GPU and in the oracle alike.
     dO0 = synth.do_block(w, 0)
-    dQ, dK, dV = a2d.partial_bwd(Qd, dev(K0), dev(V0), O, dev(dO0), lse, 0, 0, False, scale, ds_handover=True)
+    Of, lsef = oracle.fix(*[[x] for x in oracle.partial_fwd(np64(Q0[:1]), np64(K0[:1]), np64(V0[:1]), 0, 0, False, scale)])
+    O_h, lse_h = torch.from_numpy(Of).to(torch.bfloat16), torch.from_numpy(lsef).to(torch.float32)
+    O_in, lse_in = O.clone(), lse.clone()
+    O_in[:1] = dev(O_h)
+    lse_in[:1] = dev(lse_h)
+    d = a2d.tile_desc(Qd, dev(K0), 0, 0, False, scale)
+    assert a2d.workspace_bytes(d, a2d.OP_PARTIAL_BWD_DS) > a2d.workspace_bytes(d, a2d.OP_PARTIAL_BWD)
+    dQ, dK, dV = a2d.partial_bwd(Qd, dev(K0), dev(V0), O_in, dev(dO0), lse_in, 0, 0, False, scale, ds_handover=True)
     torch.cuda.synchronize()
     sub = rows[:48]
-    rQ, _, _ = oracle.partial_bwd(np64(Q0[:1, sub]), np64(K0[:1]), np64(V0[:1]), np64(O[:1, sub]), np64(dO0[:1, sub]),
-                                  np64(lse[:1, sub]), 0, 0, False, scale)
+    rQ, _, _ = oracle.partial_bwd(np64(Q0[:1, sub]), np64(K0[:1]), np64(V0[:1]), np64(O_h[:, sub]), np64(dO0[:1, sub]),
+                                  np64(lse_h[:, sub]), 0, 0, False, scale)
     assert_close(np64(dQ[:1, sub]), rQ, torch.bfloat16, name + " dQ sampled rows")
     # dK, dV of sampled KEY rows need every query row: oracle with the key block cut to those rows
     ksub = rows[:24]
-    _, rK, rV = oracle.partial_bwd(np64(Q0[:1]), np64(K0[:1, ksub]), np64(V0[:1, ksub]), np64(O[:1]), np64(dO0[:1]),
-                                   np64(lse[:1]), 0, 0, False, scale)
+    _, rK, rV = oracle.partial_bwd(np64(Q0[:1]), np64(K0[:1, ksub]), np64(V0[:1, ksub]), np64(O_h), np64(dO0[:1]),
+                                   np64(lse_h), 0, 0, False, scale)
     assert_close(np64(dK[:1, ksub]), rK, torch.bfloat16, name + " dK sampled keys")
     assert_close(np64(dV[:1, ksub]), rV, torch.bfloat16, name + " dV sampled keys")
 
