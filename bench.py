@@ -142,7 +142,7 @@ def main():
             tag = "diag" if diag else "full"
             calls.append(("partial_bwd_" + tag, lambda c=c, i=i: a2d.partial_bwd(
                 Q, Kc[c], Vc[c], O, dO, lse, r * T, c * T, w.causal, scale,
-                out=(dq_parts[c], dk_parts[i], dv_parts[i]), workspace=ws)))
+                out=(dq_parts[c], dk_parts[i], dv_parts[i]), workspace=ws, ds_handover=not args.recompute_bwd)))
         calls.append(("fix_bwd_dq", lambda: a2d.fix_bwd(dq_parts, out=dQ)))
         calls.append(("fix_bwd_dk", lambda: a2d.fix_bwd(dk_parts, out=dK)))
         calls.append(("fix_bwd_dv", lambda: a2d.fix_bwd(dv_parts, out=dV)))
@@ -277,7 +277,8 @@ def main():
                     side.wait_event(fork)
                     with torch.cuda.stream(side):
                         a2d.partial_bwd(Q, Kc[c_b], Vc[c_b], O, dO, lse, r * T, c_b * T, w.causal, scale,
-                                        out=(dq_parts[c_b], dk_parts[1], dv_parts[1]), workspace=ws2)
+                                        out=(dq_parts[c_b], dk_parts[1], dv_parts[1]), workspace=ws2,
+                                        ds_handover=not args.recompute_bwd)
                         join.record()
                 elif name == "fix_bwd_dq":
                     torch.cuda.current_stream().wait_event(join)
@@ -362,7 +363,7 @@ def gathered_tile(a2d, synth, w, scale, kernels):
 
     t_f = timeit(lambda: a2d.partial_fwd(Q, K, V, r * T, 0, True, scale, out=out, segments=segs))
     t_b = timeit(lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, out=o3, workspace=ws,
-                                         segments=segs))
+                                         segments=segs, ds_handover=True))
     # accumulating form on one unmasked tile: starts from the triple in `acc` and merges in place
     K0, V0 = dev(synth.k_block(w, 0)), dev(synth.v_block(w, 0))
     acc = a2d.partial_fwd(Q, dev(synth.k_block(w, 1)), dev(synth.v_block(w, 1)), r * T, T, True, scale)
@@ -467,8 +468,9 @@ def strided_inputs(a2d, synth, w, scale, kernels):
         tf.append(timeit(lambda: a2d.partial_fwd(Q, K0, V0, r * T, 0, True, scale, out=out)))
         pf.append(timeit(lambda: a2d.partial_fwd(Qc, Kc, Vc, r * T, 0, True, scale, out=out)))
     for _ in range(3):
-        tb.append(timeit(lambda: a2d.partial_bwd(Q, K0, V0, O, dO, lse, r * T, 0, True, scale, out=o3, workspace=ws)))
-        pb.append(timeit(lambda: a2d.partial_bwd(Qc, Kc, Vc, Oc, dOc, lse, r * T, 0, True, scale, out=o3, workspace=ws)))
+        tb.append(timeit(lambda: a2d.partial_bwd(Q, K0, V0, O, dO, lse, r * T, 0, True, scale, out=o3, workspace=ws, ds_handover=True)))
+        pb.append(timeit(lambda: a2d.partial_bwd(Qc, Kc, Vc, Oc, dOc, lse, r * T, 0, True, scale, out=o3, workspace=ws,
+                                                 ds_handover=True)))
     t_f, p_f, t_b, p_b = med(tf), med(pf), med(tb), med(pb)
     return {"what": "unmasked tile, Q / K / V views of one [rows][3][heads][H] buffer, O / dO [rows][heads][H]; "
                     "plain_*: the same calls on plain copies, alternating, medians of three",
@@ -514,15 +516,16 @@ def grouped_query(a2d, synth, w, scale, kernels):
         K, V = K0[:kvh].contiguous(), V0[:kvh].contiguous()
         out = a2d.partial_fwd(Q, K, V, r * T, 0, True, scale)
         O, lse = a2d.fix([out[0]], [out[1]], [out[2]], torch.bfloat16)
-        grads = a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, workspace=ws)
+        grads = a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, workspace=ws, ds_handover=True)
         fwd = lambda: a2d.partial_fwd(Q, K, V, r * T, 0, True, scale, out=out)
         t_f = min(timeit(fwd), timeit(fwd, 20))     # the first batch still runs at the clock the set-up left
-        t_b = timeit(lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, out=grads, workspace=ws))
+        t_b = timeit(lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, out=grads, workspace=ws,
+                                             ds_handover=True))
         # A2D_TILE_SPLIT_GROUPS: key blocks may be shared out over the group's query heads (larger workspace)
         ws2 = torch.empty(a2d.workspace_bytes(a2d.tile_desc(Q, K, r * T, 0, True, scale), a2d.OP_PARTIAL_BWD_SPLIT, kvh),
                           dtype=torch.uint8, device="cuda")
         t_s = timeit(lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, r * T, 0, True, scale, out=grads, workspace=ws2,
-                                             split_groups=True))
+                                             split_groups=True, ds_handover=True))
         del ws2
         res["cases"].append({"kv_heads": kvh, "fwd_ms": round(t_f, 4), "fwd_tflops": round(f_fl / t_f / 1e9, 1),
                              "bwd_ms": round(t_b, 4), "bwd_tflops": round(b_fl / t_b / 1e9, 1),

@@ -30,9 +30,13 @@
  *  - Calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL =
  *    the default stream) and return; they do not synchronise.  Outputs are
  *    fully overwritten.  Same inputs give bitwise identical outputs.
- *  - On error a negative status is returned, nothing has been enqueued, and
- *    a2d_last_error() describes the cause (thread-local, host memory owned by
- *    the library).
+ *  - On error a negative status is returned and a2d_last_error() describes the
+ *    cause (thread-local, host memory owned by the library).  Every check of
+ *    the arguments, and everything else that can fail on the host side, comes
+ *    before the call's first kernel launch: with any status other than
+ *    A2D_ERR_HIP nothing has been enqueued.  A2D_ERR_HIP from a launch the
+ *    runtime refused can leave earlier kernels of the same call on the stream;
+ *    the outputs are then undefined.
  *  - Alignment: every device pointer must be 16-byte aligned.
  */
 #ifndef A2D_H_
@@ -88,6 +92,13 @@ typedef struct {
   int64_t row;
 } a2d_layout;
 
+/*
+ * desc->flags, backward calls: hand dS from the dK/dV kernel to the dQ kernel through the
+ * workspace instead of computing it twice (see a2d_workspace_bytes).  The caller ASKS for this
+ * path; the size of the workspace never selects it.
+ */
+#define A2D_DESC_KEEP_DS 1
+
 /* One tile problem: a block of nq queries against a block of nkv keys/values. */
 typedef struct {
   int32_t heads;   /* B * M, >= 1                                                     */
@@ -99,7 +110,7 @@ typedef struct {
   int32_t causal;  /* 0: no mask; 1: hide key r from query i iff q_off+i < kv_off+r   */
   float scale;     /* multiplies <q, k>; 1/sqrt(H) in the paper's setting             */
   int32_t dtype;   /* a2d_dtype of Q, K, V, O, dO                                     */
-  int32_t pad;     /* must be 0                                                       */
+  int32_t flags;   /* 0 or A2D_DESC_KEEP_DS (backward calls; the forward calls ignore it) */
   a2d_layout lq;   /* layout of Q                                                     */
   a2d_layout lk;   /* layout of K (its heads are the key/value heads)                 */
   a2d_layout lv;   /* layout of V                                                     */
@@ -110,12 +121,14 @@ typedef struct {
 /*
  * Bytes of device workspace the given op needs for this tile (0 if none).
  * A2D_OP_PARTIAL_BWD: the minimum (the per-row sums delta = rowsum(dO o O)).
- * A2D_OP_PARTIAL_BWD_DS: the size from which the backward calls ALSO keep dS (bf16, one value
- * per score: about 2 nq nkv bytes per head) in the workspace, so that dQ is one contraction over
- * the stored dS instead of a second recomputation of S and dP (bf16 inputs, sub-blocks of a
- * gathered tile starting at multiples of 64 keys, less than 4 GiB of dS per key/value head
- * - all the query heads of its group together; otherwise the extra bytes are ignored).  Same results up to fp32
- * summation order; faster when the memory is there.
+ * A2D_OP_PARTIAL_BWD_DS: the size the backward calls need when desc->flags has A2D_DESC_KEEP_DS:
+ * they then ALSO keep dS (bf16, one value per score: about 2 nq nkv bytes per head) in the
+ * workspace, so that dQ is one contraction over the stored dS instead of a second recomputation
+ * of S and dP.  The hand-over exists for bf16 inputs, sub-blocks of a gathered tile that start at
+ * multiples of 64 keys, and less than 4 GiB of dS per key/value head (all the query heads of its
+ * group together); where it does not (this query then returns the minimum size for a plain tile)
+ * the flag is accepted and the recomputing kernels run.  Same results up to fp32 summation
+ * order; faster when the memory is there.
  * A2D_OP_PARTIAL_BWD_SPLIT: the size a2d_partial_bwd_gqa needs with A2D_TILE_SPLIT_GROUPS: that of
  * A2D_OP_PARTIAL_BWD_DS plus fp32 partial dK / dV buffers (at most 2 * heads * nkv * H floats);
  * `k` = the number of key/value heads.
@@ -159,10 +172,11 @@ a2d_status a2d_fix(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
  *        P = exp(S - lse), delta = rowsum(dO o O), dV = P^T dO, dP = dO V^T,
  *        dS = P o (dP - delta), dQ = scale dS K, dK = scale dS^T Q.
  * bf16 inputs: P and dS are rounded to bf16 before their contractions.
- * workspace: at least a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD, 0) bytes (from
- * a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD_DS, 0) bytes on, the faster dS hand-over
- * is used), contents undefined on entry and exit; calls sharing one workspace must be
- * ordered on one stream.
+ * workspace: at least a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD, 0) bytes, or, with
+ * A2D_DESC_KEEP_DS in desc->flags (the faster dS hand-over), at least
+ * a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD_DS, 0) bytes - a smaller one is
+ * A2D_ERR_WORKSPACE; contents undefined on entry and exit; calls sharing one workspace
+ * must be ordered on one stream.
  */
 a2d_status a2d_partial_bwd(const a2d_tile_desc* desc, const void* Q, const void* K,
                            const void* V, const void* O, const void* dO,
@@ -183,9 +197,9 @@ typedef struct {
 /*
  * The tile calls for a gathered key/value tile: one query block against the concatenation
  * of nseg sub-blocks that come from different places of the sequence - the Compute line of
- * the paper's GatherComputeScatter algorithm (Sec. 4), which runs FlashAttn on one query
+ * the paper's GatherComputeScatter algorithm (Sec. 3.4), which runs FlashAttn on one query
  * block and the gathered K_g, V_g in one go.  Under the causal mask this is the step-like
- * pattern Sec. 5 says the paper's own kernel could not express (it ran one call per
+ * pattern Sec. 4.1 says the paper's own kernel could not express (it ran one call per
  * sub-block instead).  K, V, dK_part, dV_part are [heads][nkv][H] with
  * nkv = desc->nkv = sum of segs[s].rows, sub-blocks stored in the order of `segs`
  * (a HOST array, read before the call returns); desc->kv_off is ignored; key kk of
@@ -208,7 +222,7 @@ a2d_status a2d_partial_bwd_seg(const a2d_tile_desc* desc, int nseg, const a2d_kv
 
 /*
  * Accumulating forms of the tile calls: the compute-then-reduce pair of the paper's overlapped
- * algorithms (FlashAttn followed by AttnFix in GatherCompute and GatherComputeScatter, Sec. 4;
+ * algorithms (FlashAttn followed by AttnFix in GatherCompute and GatherComputeScatter, Sec. 3.4;
  * "dQ += ..." in their backward counterparts) fused into the tile kernel.
  *   a2d_partial_fwd_acc: O_part, m, l are IN/OUT.  On entry they hold a partial triple of the same
  *     query block (e.g. written by an earlier tile call; m = -inf, l = 0, N = 0 is the empty
@@ -335,6 +349,13 @@ a2d_status a2d_fix_norm_strided(int k, int32_t heads, int32_t nq, int32_t hdim, 
 size_t a2d_mfma_ceiling_scratch_bytes(void);
 a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t scratch_bytes,
                             double* tflops, double* shader_mhz);
+
+/*
+ * Debugging aid, not part of the method: on != 0 routes every tile call of the process to the
+ * fp32 vector-ALU kernels (also for bf16 inputs), 0 back to the default choice.  The initial
+ * value is 1 when A2D_FORCE_GENERIC=1 is in the environment at the first tile call, else 0.
+ */
+void a2d_debug_force_generic(int on);
 
 /* Static string for a status code. */
 const char* a2d_status_str(a2d_status status);

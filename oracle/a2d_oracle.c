@@ -14,7 +14,7 @@
  *   - partial_fwd_pos / _bwd_pos    : the same tile computations when the keys of the tile
  *                                     carry arbitrary global positions (the gathered K_g, V_g
  *                                     of Alg. GatherComputeScatter line "Compute", whose
- *                                     sub-blocks come from different devices; Sec. 5 names the
+ *                                     sub-blocks come from different devices; Sec. 4.1 names the
  *                                     resulting step-like mask),
  *   - attnfix_pair                  : Alg. 2 (AttnFix),
  *   - fix                           : Alg. 2 folded over k partials followed by
@@ -256,7 +256,9 @@ void a2d_oracle_attnfix_pair(int64_t rows, int H, const double* M1,
   }
 }
 
-/* Alg. 2 folded left to right over k partials, then Alg. 1 line 6 and the     */
+/* Alg. 2 over k partials in ONE pass (M = max over all partials, each weighted  */
+/* exp(M_x - M), sums in index order; by the associativity of Sec. 3.1 this is  */
+/* the pairwise fold of Alg. 2, which a pin checks), then Alg. 1 line 6 and the */
 /* log-sum-exp statistic.  parts are arrays of k pointers.                      */
 void a2d_oracle_fix(int k, int64_t rows, int H, const double* const* Nparts,
                     const double* const* Mparts, const double* const* Dparts,

@@ -21,7 +21,7 @@ EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd
            "a2d_partial_fwd_seg", "a2d_partial_bwd_seg", "a2d_partial_fwd_acc", "a2d_partial_bwd_acc",
            "a2d_partial_fwd_norm", "a2d_fix_norm", "a2d_partial_fwd_gqa", "a2d_partial_bwd_gqa",
            "a2d_fix_strided", "a2d_fix_bwd_strided", "a2d_fix_norm_strided",
-           "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling",
+           "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling", "a2d_debug_force_generic",
            "a2d_status_str", "a2d_last_error", "a2d_version")
 
 
@@ -34,7 +34,7 @@ class TileDesc(ctypes.Structure):
     _fields_ = [("heads", ctypes.c_int32), ("nq", ctypes.c_int32), ("nkv", ctypes.c_int32),
                 ("hdim", ctypes.c_int32), ("q_off", ctypes.c_int64), ("kv_off", ctypes.c_int64),
                 ("causal", ctypes.c_int32), ("scale", ctypes.c_float), ("dtype", ctypes.c_int32),
-                ("pad", ctypes.c_int32), ("lq", Layout), ("lk", Layout), ("lv", Layout), ("lo", Layout),
+                ("flags", ctypes.c_int32), ("lq", Layout), ("lk", Layout), ("lv", Layout), ("lo", Layout),
                 ("ldo", Layout)]
 
 
@@ -44,6 +44,7 @@ class KvSegment(ctypes.Structure):
 
 MAX_SEGMENTS = 32
 TILE_ACCUMULATE, TILE_NORMALISED, TILE_SPLIT_GROUPS = 1, 2, 4
+DESC_KEEP_DS = 1
 
 
 class A2DError(RuntimeError):
@@ -121,6 +122,8 @@ def lib():
         L.a2d_mfma_ceiling.restype = ctypes.c_int
         L.a2d_mfma_ceiling.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t,
                                        ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+        L.a2d_debug_force_generic.restype = None
+        L.a2d_debug_force_generic.argtypes = [ctypes.c_int]
         L.a2d_status_str.restype = ctypes.c_char_p
         L.a2d_status_str.argtypes = [ctypes.c_int]
         L.a2d_last_error.restype = ctypes.c_char_p
@@ -180,11 +183,11 @@ def _layout(t):
     return Layout(int(head), int(row))
 
 
-def tile_desc(Q, K, q_off, kv_off, causal, scale, V=None, O=None, dO=None):
+def tile_desc(Q, K, q_off, kv_off, causal, scale, V=None, O=None, dO=None, flags=0):
     """Descriptor of the tile; the strides of Q, K (and V, O, dO when given) are taken from the tensors."""
     heads, nq, H = Q.shape
     return TileDesc(heads, nq, K.shape[1], H, int(q_off), int(kv_off), int(bool(causal)),
-                    float(scale if scale is not None else 1.0 / math.sqrt(H)), _dtype_code(Q.dtype), 0,
+                    float(scale if scale is not None else 1.0 / math.sqrt(H)), _dtype_code(Q.dtype), int(flags),
                     _layout(Q), _layout(K), _layout(V if V is not None else K), _layout(O), _layout(dO))
 
 
@@ -320,9 +323,10 @@ def fix(O_parts, ms, ls, out_dtype=torch.bfloat16, out=None):
 
 def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None, out=None,
                 workspace=None, segments=None, accumulate=False, ds_handover=False, split_groups=False):
-    """a2d_partial_bwd. Returns (dQ_part, dK_part, dV_part), all fp32.  With no `workspace` given,
-    ds_handover=True allocates the larger one (a2d_workspace_bytes(A2D_OP_PARTIAL_BWD_DS)) that
-    makes the library keep dS for the dQ contraction instead of recomputing it.  split_groups=True
+    """a2d_partial_bwd. Returns (dQ_part, dK_part, dV_part), all fp32.  ds_handover=True sets
+    A2D_DESC_KEEP_DS in the descriptor: the library keeps dS for the dQ contraction instead of
+    recomputing it, and the workspace (allocated here when none is given) must then hold
+    a2d_workspace_bytes(A2D_OP_PARTIAL_BWD_DS) bytes.  split_groups=True
     (grouped heads only) passes A2D_TILE_SPLIT_GROUPS: a key block may go to several workgroups,
     each summing over a share of the group's query heads (workspace of A2D_OP_PARTIAL_BWD_SPLIT
     size, which includes the dS area)."""
@@ -332,7 +336,7 @@ def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None
             lse.shape != Q.shape[:2] or lse.dtype != torch.float32 or K.shape != V.shape or \
             not lse.is_contiguous():
         raise A2DError(-1, "O, dO, lse do not match Q (lse: plain fp32 [heads][nq])")
-    d = tile_desc(Q, K, q_off, kv_off, causal, scale, V, O, dO)
+    d = tile_desc(Q, K, q_off, kv_off, causal, scale, V, O, dO, flags=DESC_KEEP_DS if ds_handover else 0)
     need = workspace_bytes(d, OP_PARTIAL_BWD_DS if ds_handover else OP_PARTIAL_BWD)
     split_groups = bool(split_groups) and K.shape[0] != Q.shape[0]
     if split_groups:
@@ -403,6 +407,11 @@ def mfma_ceiling(iters=20000, random_data=True):
     _check(lib().a2d_mfma_ceiling(int(iters), int(bool(random_data)), _ptr(scratch), scratch.numel(),
                                   ctypes.byref(tf), ctypes.byref(mhz)))
     return tf.value, mhz.value
+
+
+def force_generic(on):
+    """a2d_debug_force_generic: route every tile call to the vector-ALU kernels (debugging aid)."""
+    lib().a2d_debug_force_generic(int(bool(on)))
 
 
 def version():

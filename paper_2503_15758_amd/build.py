@@ -12,7 +12,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liba2d.so")
-SOURCES = ["a2d_api.hip", "a2d_fix.hip", "a2d_generic.hip", "a2d_fwd_mfma.hip", "a2d_bwd_mfma.hip",
+SOURCES = ["a2d_api.hip", "a2d_device.hip", "a2d_fix.hip", "a2d_generic.hip", "a2d_fwd_mfma.hip", "a2d_bwd_mfma.hip",
            "a2d_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

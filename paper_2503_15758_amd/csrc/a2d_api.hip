@@ -20,21 +20,13 @@ a2d_status fail(a2d_status st, const char* fmt, ...) {
   return st;
 }
 
-#define A2D_TRY_(expr)                  \
+#define A2D_TRY(expr)                   \
   do {                                  \
     a2d_status st__ = (expr);           \
     if (st__ != A2D_OK) return st__;    \
   } while (0)
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-// A2D_FORCE_GENERIC=1 routes every tile call to the generic kernels (debugging aid).
-// A2D_FORCE_GENERIC=1 in the environment routes every tile call to the vector-ALU kernels (read
-// at every call, so a test can switch it)
-bool force_generic() {
-  const char* e = getenv("A2D_FORCE_GENERIC");
-  return e && e[0] == '1';
-}
 
 a2d_status check_desc(const a2d_tile_desc* d, const char* who) {
   if (!d) return fail(A2D_ERR_INVALID_ARG, "%s: descriptor is NULL", who);
@@ -55,7 +47,8 @@ a2d_status check_desc(const a2d_tile_desc* d, const char* who) {
   const int64_t lim = (int64_t)1 << 40;
   if (d->q_off < -lim || d->q_off > lim || d->kv_off < -lim || d->kv_off > lim)
     return fail(A2D_ERR_INVALID_ARG, "%s: offsets out of range", who);
-  if (d->pad != 0) return fail(A2D_ERR_INVALID_ARG, "%s: desc->pad must be 0", who);
+  if ((d->flags & ~A2D_DESC_KEEP_DS) != 0)
+    return fail(A2D_ERR_INVALID_ARG, "%s: desc->flags=%d: only A2D_DESC_KEEP_DS is defined", who, d->flags);
   return A2D_OK;
 }
 
@@ -89,12 +82,12 @@ a2d_status resolve_layout(a2d_layout* l, const char* name, int64_t heads, int64_
 // The descriptor with every layout the call uses filled in (group = query heads per key/value head)
 a2d_status resolve_layouts(const a2d_tile_desc* desc, int group, bool backward, const char* who, a2d_tile_desc* out) {
   *out = *desc;
-  A2D_TRY_(resolve_layout(&out->lq, "Q", group, desc->nq, desc, who));
-  A2D_TRY_(resolve_layout(&out->lk, "K", 1, desc->nkv, desc, who));
-  A2D_TRY_(resolve_layout(&out->lv, "V", 1, desc->nkv, desc, who));
+  A2D_TRY(resolve_layout(&out->lq, "Q", group, desc->nq, desc, who));
+  A2D_TRY(resolve_layout(&out->lk, "K", 1, desc->nkv, desc, who));
+  A2D_TRY(resolve_layout(&out->lv, "V", 1, desc->nkv, desc, who));
   if (backward) {
-    A2D_TRY_(resolve_layout(&out->lo, "O", group, desc->nq, desc, who));
-    A2D_TRY_(resolve_layout(&out->ldo, "dO", group, desc->nq, desc, who));
+    A2D_TRY(resolve_layout(&out->lo, "O", group, desc->nq, desc, who));
+    A2D_TRY(resolve_layout(&out->ldo, "dO", group, desc->nq, desc, who));
   }
   return A2D_OK;
 }
@@ -104,12 +97,6 @@ a2d_status check_ptr(const void* p, const char* who, const char* name) {
   if (!aligned16(p)) return fail(A2D_ERR_MISALIGNED, "%s: %s is not 16-byte aligned", who, name);
   return A2D_OK;
 }
-
-#define A2D_TRY(expr)                   \
-  do {                                  \
-    a2d_status st__ = (expr);           \
-    if (st__ != A2D_OK) return st__;    \
-  } while (0)
 
 a2d_status hip_result(hipError_t e, const char* who) {
   if (e == hipSuccess) return A2D_OK;
@@ -186,12 +173,14 @@ a2d_status partial_fwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
   hipStream_t s = static_cast<hipStream_t>(stream);
   a2d_tile_desc dd;
   A2D_TRY(resolve_layouts(desc, g.group, false, who, &dd));
-  if (!force_generic() && a2d::fwd_mfma_supported(dd)) {
+  if (!a2d::force_generic() && a2d::fwd_mfma_supported(dd)) {
     a2d::SegList go = g;
     go.by_size = blocks_differ(desc, g);
-    return hip_result(a2d::launch_fwd_mfma(dd, go, Q, K, V, O_part, m, l, s), who);
+    A2D_TRY(hip_result(a2d::launch_fwd_mfma(a2d::PREPARE, dd, go, Q, K, V, O_part, m, l, s), who));
+    return hip_result(a2d::launch_fwd_mfma(a2d::LAUNCH, dd, go, Q, K, V, O_part, m, l, s), who);
   }
-  return hip_result(a2d::launch_fwd_generic(dd, g, Q, K, V, O_part, m, l, s), who);
+  A2D_TRY(hip_result(a2d::launch_fwd_generic(a2d::PREPARE, dd, g, Q, K, V, O_part, m, l, s), who));
+  return hip_result(a2d::launch_fwd_generic(a2d::LAUNCH, dd, g, Q, K, V, O_part, m, l, s), who);
 }
 
 a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, const void* Q, const void* K,
@@ -207,9 +196,11 @@ a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
   A2D_TRY(check_ptr(dQ_part, who, "dQ_part"));
   A2D_TRY(check_ptr(dK_part, who, "dK_part"));
   A2D_TRY(check_ptr(dV_part, who, "dV_part"));
-  const size_t need = a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD, 0);
-  // the size decides how much of the workspace is used: a value no allocation can have (a foreign
-  // caller that passed a 32-bit integer for the size_t, leaving the upper half undefined) is refused
+  const bool keep_ds = (desc->flags & A2D_DESC_KEEP_DS) != 0;
+  const size_t delta_bytes = a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD, 0);
+  const size_t need = keep_ds ? a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD_DS, 0) : delta_bytes;
+  // a value no allocation can have (a foreign caller that passed a 32-bit integer for the size_t,
+  // leaving the upper half undefined) is refused
   if (workspace_bytes > ((size_t)1 << 46))
     return fail(A2D_ERR_INVALID_ARG, "%s: workspace_bytes = %zu is not a plausible size (size_t expected)", who,
                 workspace_bytes);
@@ -231,17 +222,24 @@ a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
                                         a2d_workspace_bytes(desc, A2D_OP_PARTIAL_BWD_DS, 0));
   }
   float* delta = static_cast<float*>(workspace);
-  A2D_TRY(hip_result(a2d::launch_delta(dd, O, dO, delta, s), who));
-  if (!force_generic() && a2d::bwd_mfma_supported(dd)) {
-    // a workspace large enough for dS as well switches to the hand-over path
-    const size_t ds_bytes = a2d::bwd_ds_bytes(dd, g);
-    void* ds_ws = (ds_bytes > 0 && workspace_bytes >= need + ds_bytes) ? static_cast<char*>(workspace) + need : nullptr;
+  if (!a2d::force_generic() && a2d::bwd_mfma_supported(dd)) {
+    // the dS hand-over when the caller asked for it and this tile allows it (`need` covers the
+    // plain tile's dS area; a gathered tile of the same nkv has the same size or none)
+    const size_t ds_bytes = keep_ds ? a2d::bwd_ds_bytes(dd, g) : 0;
+    void* ds_ws = (ds_bytes > 0 && workspace_bytes >= delta_bytes + ds_bytes) ? static_cast<char*>(workspace) + delta_bytes
+                                                                              : nullptr;
     a2d::SegList go = g;
     go.by_size = blocks_differ(desc, g);
-    return hip_result(a2d::launch_bwd_mfma(dd, go, Q, K, V, dO, lse, delta, dQ_part, dK_part,
+    A2D_TRY(hip_result(a2d::launch_bwd_mfma(a2d::PREPARE, dd, go, Q, K, V, dO, lse, delta, dQ_part, dK_part,
+                                            dV_part, ds_ws, split_ws, s), who));
+    A2D_TRY(hip_result(a2d::launch_delta(dd, O, dO, delta, s), who));
+    return hip_result(a2d::launch_bwd_mfma(a2d::LAUNCH, dd, go, Q, K, V, dO, lse, delta, dQ_part, dK_part,
                                            dV_part, ds_ws, split_ws, s), who);
   }
-  return hip_result(a2d::launch_bwd_generic(dd, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
+  A2D_TRY(hip_result(a2d::launch_bwd_generic(a2d::PREPARE, dd, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
+                                             dV_part, s), who));
+  A2D_TRY(hip_result(a2d::launch_delta(dd, O, dO, delta, s), who));
+  return hip_result(a2d::launch_bwd_generic(a2d::LAUNCH, dd, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
                                             dV_part, s), who);
 }
 
@@ -562,10 +560,8 @@ const char* a2d_status_str(a2d_status status) {
 }
 
 size_t a2d_mfma_ceiling_scratch_bytes(void) {
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-    return 0;
+  int cus = 0;
+  if (a2d::device_cus(&cus) != hipSuccess) return 0;
   // four workgroups per compute unit: enough wavefronts to keep every SIMD's MFMA pipe full
   // however the dispatcher spreads them
   return (size_t)4 * cus * a2d::mfma_probe_threads() * sizeof(float) + 16;
@@ -607,6 +603,8 @@ a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t sc
   *shader_mhz = clocks[1] ? (double)clocks[0] / ((double)clocks[1] / 100.0) : 0.0;   // 100 MHz wall counter
   return A2D_OK;
 }
+
+void a2d_debug_force_generic(int on) { a2d::set_force_generic(on != 0); }
 
 const char* a2d_last_error(void) { return g_err; }
 

@@ -1060,24 +1060,22 @@ size_t bwd_ds_bytes(const a2d_tile_desc& d, const SegList& g) {
 
 namespace {
 template <int HR>
-hipError_t bwd_launch_ds(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
-                         const void* dO, const float* lse, const float* delta, float* dQ, float* dK,
+hipError_t bwd_launch_ds(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K,
+                         const void* V, const void* dO, const float* lse, const float* delta, float* dQ, float* dK,
                          float* dV, void* ds_ws, hipStream_t s) {
   constexpr int DSQ_LDS = 2 * DUAL64_BYTES;
   const bool grouped = g.group > 1;
-  hipError_t e = hipFuncSetAttribute(grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, true>)
-                                             : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, true>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, DK_LDS);
-  if (e != hipSuccess) return e;
-  int dev = 0, cus = 0;
-  e = hipGetDevice(&dev);
-  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  int cus = 0;
+  hipError_t e = device_cus(&cus);
   if (e != hipSuccess) return e;
   const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
-  e = hipFuncSetAttribute(big ? reinterpret_cast<const void*>(bwd_dq_ds_kernel<8, HR>)
-                              : reinterpret_cast<const void*>(bwd_dq_ds_kernel<4, HR>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, DSQ_LDS);
-  if (e != hipSuccess) return e;
+  if (ph == PREPARE) {
+    e = ensure_dynamic_lds(grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, true>)
+                                   : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, true>), DK_LDS);
+    if (e != hipSuccess) return e;
+    return ensure_dynamic_lds(big ? reinterpret_cast<const void*>(bwd_dq_ds_kernel<8, HR>)
+                                  : reinterpret_cast<const void*>(bwd_dq_ds_kernel<4, HR>), DSQ_LDS);
+  }
   dim3 grid_kv(xcd_grid(d.heads / g.group * g.qsplit, (d.nkv + DK_KEYS - 1) / DK_KEYS));
   const int dq_rows = big ? 256 : 128;
   const int per_unit = g.group / g.split;
@@ -1102,30 +1100,29 @@ hipError_t bwd_launch_ds(const a2d_tile_desc& d, const SegList& g, const void* Q
 }
 
 template <int HR>
-hipError_t bwd_launch_hd(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
-                         const void* dO, const float* lse, const float* delta, float* dQ, float* dK,
+hipError_t bwd_launch_hd(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K,
+                         const void* V, const void* dO, const float* lse, const float* delta, float* dQ, float* dK,
                          float* dV, void* ds_ws, hipStream_t s) {
-  if (ds_ws) return bwd_launch_ds<HR>(d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
+  if (ds_ws) return bwd_launch_ds<HR>(ph, d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, ds_ws, s);
   constexpr int DQ_LDS = dq_lds(padded_head(HR));
   const bool grouped = g.group > 1;
   // Q and dO in the plain layout: the variant with compile-time staging offsets
   const bool plain = d.lq.row == HR && d.ldo.row == HR && d.lq.head == (int64_t)d.nq * HR && d.ldo.head == d.lq.head;
-  const void* dkdv = plain ? (grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, false, true>)
-                                      : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, false, true>))
-                           : (grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, false, false>)
-                                      : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, false, false>));
-  hipError_t e = hipFuncSetAttribute(dkdv, hipFuncAttributeMaxDynamicSharedMemorySize, DK_LDS);
-  if (e != hipSuccess) return e;
   // dQ kernel: eight wavefronts per workgroup unless that leaves compute units without a workgroup
-  int dev = 0, cus = 0;
-  e = hipGetDevice(&dev);
-  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  int cus = 0;
+  hipError_t e = device_cus(&cus);
   if (e != hipSuccess) return e;
   const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
-  e = hipFuncSetAttribute(big ? reinterpret_cast<const void*>(bwd_dq_kernel<8, HR>)
-                              : reinterpret_cast<const void*>(bwd_dq_kernel<4, HR>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
-  if (e != hipSuccess) return e;
+  if (ph == PREPARE) {
+    const void* dkdv = plain ? (grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, false, true>)
+                                        : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, false, true>))
+                             : (grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, false, false>)
+                                        : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, false, false>));
+    e = ensure_dynamic_lds(dkdv, DK_LDS);
+    if (e != hipSuccess) return e;
+    return ensure_dynamic_lds(big ? reinterpret_cast<const void*>(bwd_dq_kernel<8, HR>)
+                                  : reinterpret_cast<const void*>(bwd_dq_kernel<4, HR>), DQ_LDS);
+  }
   dim3 grid_kv(xcd_grid(d.heads / g.group * g.qsplit, (d.nkv + DK_KEYS - 1) / DK_KEYS));
   const int dq_rows = big ? 256 : 128;
   const int per_unit = g.group / g.split;
@@ -1170,8 +1167,8 @@ int choose_qsplit(int kv_heads, int group, int key_blocks, int cus) {
 // split_ws != NULL (grouped heads): room for 2 * min(group, A2D_MAX_PARTS) partial buffers of
 // [key/value heads][nkv][H] floats; the query heads of a group may then be split over several
 // workgroups per key block (choose_qsplit) whose dK / dV sums a sum kernel adds up.
-hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
-                           const void* dO, const float* lse, const float* delta, float* dQ,
+hipError_t launch_bwd_mfma(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K,
+                           const void* V, const void* dO, const float* lse, const float* delta, float* dQ,
                            float* dK, float* dV, void* ds_ws, float* split_ws, hipStream_t s) {
   SegList gg = g;
   gg.qsplit = 1;
@@ -1180,22 +1177,21 @@ hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void*
   const int kv_heads = d.heads / g.group;
   const int64_t n = (int64_t)kv_heads * d.nkv * d.hdim;        // elements of dK (of dV)
   if (split_ws && g.group > 1) {
-    int dev = 0, cus = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    int cus = 0;
+    const hipError_t e = device_cus(&cus);
     if (e != hipSuccess) return e;
-    gg.qsplit = choose_qsplit(kv_heads, g.group, (d.nkv + DK_KEYS - 1) / DK_KEYS, cus > 0 ? cus : 1);
+    gg.qsplit = choose_qsplit(kv_heads, g.group, (d.nkv + DK_KEYS - 1) / DK_KEYS, cus);
     if (gg.qsplit > 1) {
       dKo = split_ws;
       dVo = split_ws + (int64_t)gg.qsplit * n;
     }
   }
   hipError_t e;
-  if (d.hdim == 128) e = bwd_launch_hd<128>(d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
-  else if (d.hdim == 96) e = bwd_launch_hd<96>(d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
-  else if (d.hdim == 80) e = bwd_launch_hd<80>(d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
-  else e = bwd_launch_hd<64>(d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
-  if (e != hipSuccess || gg.qsplit == 1) return e;
+  if (d.hdim == 128) e = bwd_launch_hd<128>(ph, d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
+  else if (d.hdim == 96) e = bwd_launch_hd<96>(ph, d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
+  else if (d.hdim == 80) e = bwd_launch_hd<80>(ph, d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
+  else e = bwd_launch_hd<64>(ph, d, gg, Q, K, V, dO, lse, delta, dQ, dKo, dVo, ds_ws, s);
+  if (e != hipSuccess || gg.qsplit == 1 || ph == PREPARE) return e;   // (the sum kernel needs no preparation)
   // dK = sum_z partial z (in order of z: bitwise reproducible), the same for dV
   SumPtrs pk, pv;
   for (int z = 0; z < A2D_MAX_PARTS; ++z) { pk.p[z] = nullptr; pv.p[z] = nullptr; }

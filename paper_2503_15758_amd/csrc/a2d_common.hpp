@@ -80,14 +80,29 @@ __device__ __forceinline__ bool seg_visible(const SegList& g, int i, int c) {
   return (int64_t)(c - g.start[s]) <= (int64_t)i + g.rel[s];
 }
 
-// ---- launchers (each returns the launch's hipError_t; none synchronises) ----
+// ---- per-process caches of HIP runtime queries (a2d_device.hip; thread-safe) ----
+// compute units of the current device
+hipError_t device_cus(int* cus);
+// raises the kernel's dynamic-LDS limit to `bytes` once per (device, kernel)
+hipError_t ensure_dynamic_lds(const void* kernel, int bytes);
+// Debugging aid: route every tile call to the vector-ALU kernels.  The default comes from
+// A2D_FORCE_GENERIC=1 in the environment, read once per process; a2d_debug_force_generic() sets it.
+bool force_generic();
+void set_force_generic(bool on);
+
+// ---- launchers (none synchronises) ----
+// Every tile launcher runs in two phases so that a call can finish everything that may fail on the
+// host side before its first kernel is enqueued: PREPARE only raises the dynamic-LDS limits of the
+// kernels the LAUNCH phase of the same arguments will use (cached per device), LAUNCH only
+// launches and returns the launch's hipError_t.
+enum Phase { PREPARE = 0, LAUNCH = 1 };
 
 // Generic tile kernels: fp32 arithmetic on the vector ALUs for fp32 or bf16
 // inputs, any nq / nkv, H in {64, 80, 96, 128}.
-hipError_t launch_fwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
-                              float* O_part, float* m, float* l, hipStream_t s);
-hipError_t launch_bwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
-                              const void* dO, const float* lse, const float* delta, float* dQ,
+hipError_t launch_fwd_generic(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K,
+                              const void* V, float* O_part, float* m, float* l, hipStream_t s);
+hipError_t launch_bwd_generic(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K,
+                              const void* V, const void* dO, const float* lse, const float* delta, float* dQ,
                               float* dK, float* dV, hipStream_t s);
 
 // delta[head][row] = sum_j dO[head][row][j] * O[head][row][j]  (O, dO with the layouts d.lo, d.ldo)
@@ -95,14 +110,14 @@ hipError_t launch_delta(const a2d_tile_desc& d, const void* O, const void* dO, f
 
 // bf16 MFMA tile kernels (H in {64, 80, 96, 128}).  `supported` tells whether the shape is covered.
 bool fwd_mfma_supported(const a2d_tile_desc& d);
-hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
-                           float* O_part, float* m, float* l, hipStream_t s);
+hipError_t launch_fwd_mfma(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K,
+                           const void* V, float* O_part, float* m, float* l, hipStream_t s);
 bool bwd_mfma_supported(const a2d_tile_desc& d);
 // ds_ws: NULL, or a workspace of bwd_ds_bytes(d, g) (> 0) bytes through which the dK/dV kernel
 // hands dS to a contraction-only dQ kernel (instead of the dQ kernel recomputing S and dP)
 size_t bwd_ds_bytes(const a2d_tile_desc& d, const SegList& g);
-hipError_t launch_bwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
-                           const void* dO, const float* lse, const float* delta, float* dQ,
+hipError_t launch_bwd_mfma(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K,
+                           const void* V, const void* dO, const float* lse, const float* delta, float* dQ,
                            float* dK, float* dV, void* ds_ws, float* split_ws, hipStream_t s);
 // the dK/dV kernel's choice of workgroups per key block for grouped heads (see launch_bwd_mfma)
 int choose_qsplit(int kv_heads, int group, int key_blocks, int cus);

@@ -394,12 +394,11 @@ bool fwd_mfma_supported(const a2d_tile_desc& d) {
 
 namespace {
 template <int WAVES, int HR>
-hipError_t fwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
+hipError_t fwd_launch(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                       float* O_part, float* m, float* l, hipStream_t s) {
   constexpr int bytes = lds_bytes(padded_head(HR));
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_mfma_kernel<WAVES, HR>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e != hipSuccess) return e;
+  if (ph == PREPARE)
+    return ensure_dynamic_lds(reinterpret_cast<const void*>(fwd_mfma_kernel<WAVES, HR>), bytes);
   const int per_unit = g.group / g.split;
   dim3 grid(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + 32 * WAVES - 1) / (32 * WAVES)))), block(64 * WAVES);
   hipLaunchKernelGGL((fwd_mfma_kernel<WAVES, HR>), grid, block, bytes, s, d, g, (const bf16_t*)Q,
@@ -408,21 +407,20 @@ hipError_t fwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, c
 }
 }  // namespace
 
-hipError_t launch_fwd_mfma(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
-                           float* O_part, float* m, float* l, hipStream_t s) {
+hipError_t launch_fwd_mfma(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K,
+                           const void* V, float* O_part, float* m, float* l, hipStream_t s) {
   // eight wavefronts per workgroup unless that leaves compute units without a workgroup
-  int dev = 0, cus = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  int cus = 0;
+  const hipError_t e = device_cus(&cus);
   if (e != hipSuccess) return e;
   const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
-  if (d.hdim == 128)
-    return big ? fwd_launch<8, 128>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 128>(d, g, Q, K, V, O_part, m, l, s);
-  if (d.hdim == 96)
-    return big ? fwd_launch<8, 96>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 96>(d, g, Q, K, V, O_part, m, l, s);
-  if (d.hdim == 80)
-    return big ? fwd_launch<8, 80>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 80>(d, g, Q, K, V, O_part, m, l, s);
-  return big ? fwd_launch<8, 64>(d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, 64>(d, g, Q, K, V, O_part, m, l, s);
+#define A2D_FWD(HR) \
+  return big ? fwd_launch<8, HR>(ph, d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, HR>(ph, d, g, Q, K, V, O_part, m, l, s)
+  if (d.hdim == 128) { A2D_FWD(128); }
+  if (d.hdim == 96) { A2D_FWD(96); }
+  if (d.hdim == 80) { A2D_FWD(80); }
+  A2D_FWD(64);
+#undef A2D_FWD
 }
 
 }  // namespace a2d

@@ -1,5 +1,5 @@
 // Generic tile kernels: fp32 arithmetic on the vector ALUs, for fp32 or bf16
-// inputs, any nq / nkv, H in {64, 128}.  They serve the fp32 path and every shape
+// inputs, any nq / nkv, H in {64, 80, 96, 128}.  They serve the fp32 path and every shape
 // the MFMA kernels do not cover.  Structure: a 16 x 16 thread grid computes
 // register-blocked score tiles out of LDS-resident operand tiles (all widened to
 // fp32, rows padded by one word against bank conflicts); probabilities go through
@@ -431,16 +431,14 @@ __global__ __launch_bounds__(kThreads) void delta_kernel(int64_t rows, int nq, i
 
 template <typename K>
 hipError_t set_lds(K kernel, size_t bytes) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  return ensure_dynamic_lds(reinterpret_cast<const void*>(kernel), (int)bytes);
 }
 
 template <typename T, int H>
-hipError_t fwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
+hipError_t fwd_launch(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                       float* O_part, float* m, float* l, hipStream_t s) {
   constexpr size_t lds = sizeof(float) * (64 * (H + 1) * 2 + 64 * H + 64 * 65);
-  hipError_t e = set_lds(fwd_generic_kernel<T, H>, lds);
-  if (e != hipSuccess) return e;
+  if (ph == PREPARE) return set_lds(fwd_generic_kernel<T, H>, lds);
   dim3 grid((d.nq + 63) / 64, d.heads), block(kThreads);
   hipLaunchKernelGGL((fwd_generic_kernel<T, H>), grid, block, lds, s, d, g, (const T*)Q, (const T*)K,
                      (const T*)V, O_part, m, l);
@@ -448,20 +446,20 @@ hipError_t fwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, c
 }
 
 template <typename T, int H>
-hipError_t bwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
+hipError_t bwd_launch(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                       const void* dO, const float* lse, const float* delta, float* dQ, float* dK,
                       float* dV, hipStream_t s) {
   constexpr size_t lds_kv = sizeof(float) * (2 * 64 * (H + 1) + 2 * 32 * (H + 1) + 2 * 32 * 65);
   constexpr size_t lds_q = sizeof(float) * (2 * 64 * (H + 1) + 2 * 32 * (H + 1) + 64 * 33);
-  hipError_t e = set_lds(bwd_dkdv_generic_kernel<T, H>, lds_kv);
-  if (e != hipSuccess) return e;
-  e = set_lds(bwd_dq_generic_kernel<T, H>, lds_q);
-  if (e != hipSuccess) return e;
+  if (ph == PREPARE) {
+    const hipError_t e = set_lds(bwd_dkdv_generic_kernel<T, H>, lds_kv);
+    return e != hipSuccess ? e : set_lds(bwd_dq_generic_kernel<T, H>, lds_q);
+  }
   dim3 block(kThreads);
   dim3 grid_kv((d.nkv + 63) / 64, d.heads / g.group), grid_q((d.nq + 63) / 64, d.heads);
   hipLaunchKernelGGL((bwd_dkdv_generic_kernel<T, H>), grid_kv, block, lds_kv, s, d, g, (const T*)Q,
                      (const T*)K, (const T*)V, (const T*)dO, lse, delta, dK, dV);
-  e = hipGetLastError();
+  const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((bwd_dq_generic_kernel<T, H>), grid_q, block, lds_q, s, d, g, (const T*)Q,
                      (const T*)K, (const T*)V, (const T*)dO, lse, delta, dQ);
@@ -479,17 +477,17 @@ hipError_t bwd_launch(const a2d_tile_desc& d, const SegList& g, const void* Q, c
     default: return FN<T, 64>(__VA_ARGS__);         \
   }
 
-hipError_t launch_fwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
-                              float* O_part, float* m, float* l, hipStream_t s) {
-  if (d.dtype == A2D_BF16) { A2D_DISPATCH_H(fwd_launch, bf16_t, d, g, Q, K, V, O_part, m, l, s) }
-  A2D_DISPATCH_H(fwd_launch, float, d, g, Q, K, V, O_part, m, l, s)
+hipError_t launch_fwd_generic(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K,
+                              const void* V, float* O_part, float* m, float* l, hipStream_t s) {
+  if (d.dtype == A2D_BF16) { A2D_DISPATCH_H(fwd_launch, bf16_t, ph, d, g, Q, K, V, O_part, m, l, s) }
+  A2D_DISPATCH_H(fwd_launch, float, ph, d, g, Q, K, V, O_part, m, l, s)
 }
 
-hipError_t launch_bwd_generic(const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
-                              const void* dO, const float* lse, const float* delta, float* dQ,
+hipError_t launch_bwd_generic(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K,
+                              const void* V, const void* dO, const float* lse, const float* delta, float* dQ,
                               float* dK, float* dV, hipStream_t s) {
-  if (d.dtype == A2D_BF16) { A2D_DISPATCH_H(bwd_launch, bf16_t, d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s) }
-  A2D_DISPATCH_H(bwd_launch, float, d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s)
+  if (d.dtype == A2D_BF16) { A2D_DISPATCH_H(bwd_launch, bf16_t, ph, d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s) }
+  A2D_DISPATCH_H(bwd_launch, float, ph, d, g, Q, K, V, dO, lse, delta, dQ, dK, dV, s)
 }
 #undef A2D_DISPATCH_H
 

@@ -1,4 +1,4 @@
-// Building blocks shared by the bf16 MFMA tile kernels (H = 128): the MFMA wrapper and its
+// Building blocks shared by the bf16 MFMA tile kernels (H = 128, 96, 80, 64): the MFMA wrapper and its
 // fragment layouts, LDS fragment reads, the "dual" LDS tile layout, scalar-base global loads and
 // the XCD-aware work mapping.
 //
@@ -6,7 +6,7 @@
 //   A fragment: lane holds row (lane & 31), contraction indices 8*(lane>>5) + 0..7
 //   B fragment: lane holds column (lane & 31), contraction indices 8*(lane>>5) + 0..7
 //   D: lane holds column (lane & 31); register r is row 8*(r>>2) + 4*(lane>>5) + (r&3)
-// Two kinds of fragment reads from a row-major LDS tile (rows x 128 bf16):
+// Two kinds of fragment reads from a row-major LDS tile (rows x padded head size, bf16):
 //   - "natural" fragments (contraction along H): one 128-bit read per lane;
 //   - "transposed" fragments (contraction along the row index): two ds_read_b64_tr_b16, where a
 //     16-lane group reads 4 consecutive rows x 16 columns and every lane receives a column.

@@ -120,7 +120,7 @@ def backward(Q, K, V, O, dO, lse, grid, causal=True, layout="cyclic", scale=None
         qo, ko = tile_offsets(r, c, T, layout)
         with torch.cuda.stream(st.of(i)):
             a2d.partial_bwd(Qb[r], Kb[c], Vb[c], Ob[r], dOb[r], lb[r], qo, ko, causal, scale,
-                            out=parts[(r, c)], workspace=ws[i % len(ws)])
+                            out=parts[(r, c)], workspace=ws[i % len(ws)], ds_handover=ds_handover)
     st.join()
     dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
     for b in range(grid):                              # Alg. 3 lines 4-5: sums over the grid row / column

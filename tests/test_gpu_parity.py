@@ -675,8 +675,7 @@ def test_strided_inputs(a2d, case):
         for x, y, name in zip(g3, r3, ("dQ", "dK", "dV")):
             assert torch.equal(x, y), "strided backward (handover=%s): %s differs" % (handover, name)
     # the vector-ALU kernels on the same views
-    import os
-    os.environ["A2D_FORCE_GENERIC"] = "1"
+    a2d.force_generic(True)
     try:
         g1 = a2d.partial_fwd(Qv, Kv, Vv, q_off, kv_off, causal, scale, **kw)
         r1 = a2d.partial_fwd(Qc, Kc, Vc, q_off, kv_off, causal, scale, **kw)
@@ -684,7 +683,7 @@ def test_strided_inputs(a2d, case):
         r3 = a2d.partial_bwd(Qc, Kc, Vc, Oc, dOc, lse, q_off, kv_off, causal, scale, **kw)
         torch.cuda.synchronize()
     finally:
-        del os.environ["A2D_FORCE_GENERIC"]
+        a2d.force_generic(False)
     for x, y in zip(g1 + g3, r1 + r3):
         assert torch.equal(x, y), "strided inputs, vector-ALU kernels: results differ"
 
@@ -887,7 +886,7 @@ def test_partial_bwd_ds_handover(a2d, case):
     ws_all = torch.full(((big + guard) // 2,), float("nan"), dtype=torch.bfloat16, device="cuda").view(torch.uint8)
     ws, band = ws_all[:big], ws_all[big:]
     band_before = band.clone()
-    dQ, dK, dV = a2d.partial_bwd(*args, segments=segs, workspace=ws)
+    dQ, dK, dV = a2d.partial_bwd(*args, segments=segs, workspace=ws, ds_handover=True)
     dQ0, dK0, dV0 = a2d.partial_bwd(*args, segments=segs)
     torch.cuda.synchronize()
     with np.errstate(invalid="ignore"):
@@ -901,11 +900,11 @@ def test_partial_bwd_ds_handover(a2d, case):
     # accumulating form on top of a known dQ
     base = torch.full_like(dQ, 0.5)
     acc = (base.clone(), torch.empty_like(dK), torch.empty_like(dV))
-    a2d.partial_bwd(*args, segments=segs, workspace=ws, out=acc, accumulate=True)
+    a2d.partial_bwd(*args, segments=segs, workspace=ws, out=acc, accumulate=True, ds_handover=True)
     torch.cuda.synchronize()
     assert_close(acc[0], np64(dQ) + 0.5, DT[dt], what + " dQ +=")
     # same call twice: bitwise the same
-    dQ2, _, _ = a2d.partial_bwd(*args, segments=segs, workspace=ws)
+    dQ2, _, _ = a2d.partial_bwd(*args, segments=segs, workspace=ws, ds_handover=True)
     torch.cuda.synchronize()
     assert torch.equal(dQ, dQ2)
     assert torch.equal(band, band_before), what + ": bytes behind the workspace were written"
@@ -987,7 +986,7 @@ def test_grouped_query_heads(a2d, dt, case):
         s3b = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), q_off, kv_off, causal,
                               scale, segments=segs, ds_handover=handover, split_groups=True)
         torch.cuda.synchronize()
-        assert torch.equal(s3[0], dQh), what + ": dQ with the split differs"
+        assert torch.equal(s3[0], dQh if handover else dQ), what + ": dQ with the split differs"
         assert_close(s3[1], rk, DT[dt], what + " dK, split groups")
         assert_close(s3[2], rv, DT[dt], what + " dV, split groups")
         for x, y in zip(s3, s3b):
@@ -1048,22 +1047,25 @@ def test_normalised_partial_format(a2d, dt, H):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("H", [64, 96, 128])
-def test_generic_kernels_on_bf16_inputs(a2d, H, monkeypatch):
-    """The vector-ALU kernels take bf16 inputs too (A2D_FORCE_GENERIC=1); same bar as the MFMA path."""
-    monkeypatch.setenv("A2D_FORCE_GENERIC", "1")
+def test_generic_kernels_on_bf16_inputs(a2d, H):
+    """The vector-ALU kernels take bf16 inputs too (a2d_debug_force_generic); same bar as the MFMA path."""
     heads, nq, nkv = 2, 150, 210
     scale = 1.0 / math.sqrt(H)
     Q = synth.normal((heads, nq, H), 71, 0, 1.0, "bf16")
     K = synth.normal((heads, nkv, H), 71, 1, 1.0, "bf16")
     V = synth.normal((heads, nkv, H), 71, 2, 1.0, "bf16")
     dO = synth.normal((heads, nq, H), 71, 3, 1.0, "bf16")
-    Np, m, l = check_partial(a2d, Q, K, V, 80, 0, True, scale, "generic bf16 H=%d" % H)
     Nr, mr, lr = oracle.partial_fwd(np64(Q), np64(K), np64(V), 80, 0, True, scale)
     Or, lser = oracle.fix([Nr], [mr], [lr])
     O_in = torch.from_numpy(Or).to(torch.bfloat16)
     lse_in = torch.from_numpy(lser).to(torch.float32)
-    dQ, dK, dV = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), 80, 0, True, scale)
-    torch.cuda.synchronize()
+    a2d.force_generic(True)
+    try:
+        check_partial(a2d, Q, K, V, 80, 0, True, scale, "generic bf16 H=%d" % H)
+        dQ, dK, dV = a2d.partial_bwd(dev(Q), dev(K), dev(V), dev(O_in), dev(dO), dev(lse_in), 80, 0, True, scale)
+        torch.cuda.synchronize()
+    finally:
+        a2d.force_generic(False)
     rq, rk, rv = oracle.partial_bwd(np64(Q), np64(K), np64(V), np64(O_in), np64(dO), np64(lse_in), 80, 0, True, scale)
     assert_close(dQ, rq, torch.bfloat16, "generic bf16 dQ")
     assert_close(dK, rk, torch.bfloat16, "generic bf16 dK")
@@ -1100,7 +1102,8 @@ def test_step_replays_from_a_hip_graph(a2d):
             a2d.partial_fwd(Q, Ks[c], Vs[c], r * T, c * T, True, scale, out=parts[c])
         a2d.fix([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], out=(O, lse))
         for c in range(G):
-            a2d.partial_bwd(Q, Ks[c], Vs[c], O, dO, lse, r * T, c * T, True, scale, out=grads[c], workspace=ws[c])
+            a2d.partial_bwd(Q, Ks[c], Vs[c], O, dO, lse, r * T, c * T, True, scale, out=grads[c], workspace=ws[c],
+                            ds_handover=(c == 0))
         a2d.fix_bwd([g_[0] for g_ in grads], out=dQ)
 
     step()

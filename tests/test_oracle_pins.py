@@ -472,7 +472,7 @@ def test_fig2_index_sets_and_coverage():
 
 # ----------------------------------------------------------------------------
 # gathered key/value tiles: sub-blocks with their own global offsets (the Compute line of
-# Alg. GatherComputeScatter; Sec. 5 calls the resulting mask step-like)
+# Alg. GatherComputeScatter; Sec. 4.1 calls the resulting mask step-like)
 # ----------------------------------------------------------------------------
 def brute_positions(Q, K, V, scale, q_off, kpos):
     """Pure Python: attention of each query over the keys whose position does not exceed its own."""
@@ -593,7 +593,7 @@ def test_gathered_tile_cyclic_layout_reproduces_full_attention(grid):
 
 # ----------------------------------------------------------------------------
 # accumulating tile call = FlashAttn followed by AttnFix (Compute and Reduce lines of the
-# overlapped algorithms, Sec. 4)
+# overlapped algorithms, Sec. 3.4)
 # ----------------------------------------------------------------------------
 def test_accumulating_partial_walks_to_full_attention():
     g = rng(50)
