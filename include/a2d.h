@@ -185,6 +185,23 @@ a2d_status a2d_partial_bwd(const a2d_tile_desc* desc, const void* Q, const void*
                            void* stream);
 
 /*
+ * a2d_partial_bwd for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus
+ * the workspace), same kernels and bitwise the same results as a2d_partial_bwd with its minimum
+ * workspace (A2D_DESC_KEEP_DS is refused: A2D_ERR_UNSUPPORTED).  The per-row sums delta live in
+ * a device array inside the library (4 MiB per GPU the library runs on, held until the process
+ * ends) of A2D_STATIC_MAX_ROWS floats: heads * nq beyond that is A2D_ERR_WORKSPACE.  The call
+ * itself allocates and frees nothing; its first call on a device looks the array's address up.
+ * All calls on one GPU share the array: calls that may overlap on that GPU (different streams,
+ * different host threads) race and must be ordered by the caller.
+ */
+#define A2D_STATIC_MAX_ROWS (1 << 20)
+a2d_status a2d_partial_bwd_static(const a2d_tile_desc* desc, const void* Q, const void* K,
+                                  const void* V, const void* O, const void* dO,
+                                  const float* lse, float* dQ_part, float* dK_part,
+                                  float* dV_part, void* stream);
+
+/*
  * One sub-block of a GATHERED key/value tile: `rows` consecutive tokens starting at global
  * token index kv_off.
  */

@@ -18,6 +18,7 @@ OP_PARTIAL_FWD, OP_FIX, OP_PARTIAL_BWD, OP_FIX_BWD, OP_PARTIAL_BWD_DS, OP_PARTIA
 MAX_PARTS = 32
 
 EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
+           "a2d_partial_bwd_static",
            "a2d_partial_fwd_seg", "a2d_partial_bwd_seg", "a2d_partial_fwd_acc", "a2d_partial_bwd_acc",
            "a2d_partial_fwd_norm", "a2d_fix_norm", "a2d_partial_fwd_gqa", "a2d_partial_bwd_gqa",
            "a2d_fix_strided", "a2d_fix_bwd_strided", "a2d_fix_norm_strided",
@@ -103,6 +104,8 @@ def lib():
         L.a2d_partial_bwd.restype = ctypes.c_int
         L.a2d_partial_bwd.argtypes = [ctypes.POINTER(TileDesc), vp, vp, vp, vp, vp, fp, fp, fp, fp,
                                       vp, ctypes.c_size_t, vp]
+        L.a2d_partial_bwd_static.restype = ctypes.c_int
+        L.a2d_partial_bwd_static.argtypes = [ctypes.POINTER(TileDesc), vp, vp, vp, vp, vp, fp, fp, fp, fp, vp]
         L.a2d_fix_bwd.restype = ctypes.c_int
         L.a2d_fix_bwd.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(vp),
                                   vp, vp]
@@ -377,6 +380,31 @@ def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None
     _check(lib().a2d_partial_bwd(ctypes.byref(d), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO),
                                  _ptr(lse), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream()))
+    return dQ, dK, dV
+
+
+STATIC_MAX_ROWS = 1 << 20
+
+
+def partial_bwd_static(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None, out=None):
+    """a2d_partial_bwd_static: a2d_partial_bwd without a workspace argument (the library's own static
+    scratch holds delta; heads * nq <= STATIC_MAX_ROWS).  `out` = (dQ_part, dK_part, dV_part) fp32;
+    with out given this function allocates nothing either."""
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _dev3(t, n)
+    if O.shape != Q.shape or dO.shape != Q.shape or O.dtype != Q.dtype or dO.dtype != Q.dtype or \
+            lse.shape != Q.shape[:2] or lse.dtype != torch.float32 or K.shape != V.shape or \
+            K.shape[0] != Q.shape[0] or not lse.is_contiguous():
+        raise A2DError(-1, "O, dO, lse do not match Q (lse: plain fp32 [heads][nq]); K, V need Q's head count")
+    d = tile_desc(Q, K, q_off, kv_off, causal, scale, V, O, dO)
+    if out is None:
+        out = (torch.empty(Q.shape, dtype=torch.float32, device=Q.device),
+               torch.empty(K.shape, dtype=torch.float32, device=Q.device),
+               torch.empty(K.shape, dtype=torch.float32, device=Q.device))
+    _plain(out, "out=(dQ_part, dK_part, dV_part)")
+    dQ, dK, dV = out
+    _check(lib().a2d_partial_bwd_static(ctypes.byref(d), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(lse),
+                                        _ptr(dQ), _ptr(dK), _ptr(dV), _stream()))
     return dQ, dK, dV
 
 

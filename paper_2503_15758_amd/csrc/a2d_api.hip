@@ -1,5 +1,6 @@
 // C-ABI layer of liba2d: argument validation, kernel selection, error reporting.
 // No arithmetic happens here; see include/a2d.h for the contract of every call.
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -243,9 +244,55 @@ a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
                                             dV_part, s), who);
 }
 
+// ---- scratch of the entry point that allocates nothing (a2d_partial_bwd_static): the per-row
+// sums delta of one backward call, at most A2D_STATIC_MAX_ROWS of them, in a file-scope device
+// array.  Every GPU the library runs on holds its own copy at its own address until the process
+// ends; host code only ever uses the address hipGetSymbolAddress returned for the current device.
+__device__ __align__(256) float scratch[A2D_STATIC_MAX_ROWS];
+constexpr int kMaxDevices = 64;
+std::atomic<float*> g_scratch_ptr[kMaxDevices];
+
+a2d_status static_scratch(float** out, const char* who) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_result(e, who);
+  if (dev < 0 || dev >= kMaxDevices)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: device index %d outside 0..%d", who, dev, kMaxDevices - 1);
+  float* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {                                     // first call on this device (it is the current one)
+    void* sym = nullptr;
+    e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_result(e, who);
+    if (!sym) return fail(A2D_ERR_HIP, "%s: hipGetSymbolAddress returned NULL", who);
+    p = static_cast<float*>(sym);
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // (two first calls at once store the same address)
+  }
+  *out = p;
+  return A2D_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+a2d_status a2d_partial_bwd_static(const a2d_tile_desc* desc, const void* Q, const void* K, const void* V,
+                                  const void* O, const void* dO, const float* lse, float* dQ_part,
+                                  float* dK_part, float* dV_part, void* stream) {
+  const char* who = "a2d_partial_bwd_static";
+  A2D_TRY(check_desc(desc, who));
+  if ((desc->flags & A2D_DESC_KEEP_DS) != 0)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: A2D_DESC_KEEP_DS needs a caller workspace (use a2d_partial_bwd)", who);
+  const int64_t rows = (int64_t)desc->heads * desc->nq;
+  if (rows > (int64_t)A2D_STATIC_MAX_ROWS)
+    return fail(A2D_ERR_WORKSPACE, "%s: heads * nq = %lld rows exceed the static scratch of %d rows (use a2d_partial_bwd)",
+                who, (long long)rows, A2D_STATIC_MAX_ROWS);
+  float* ptr = nullptr;
+  A2D_TRY(static_scratch(&ptr, who));
+  // delta is written in full by the call's first kernel before the others read it: nothing in
+  // the array has to start at zero
+  return partial_bwd_impl(desc, one_segment(desc), Q, K, V, O, dO, lse, dQ_part, dK_part, dV_part, ptr,
+                          sizeof(float) * (size_t)A2D_STATIC_MAX_ROWS, stream, who);
+}
 
 size_t a2d_workspace_bytes(const a2d_tile_desc* desc, int op, int k) {
   if (!desc || desc->heads < 1 || desc->nq < 1) return 0;
