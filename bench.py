@@ -30,23 +30,6 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
-# HBM bytes per launch of each call, from rocprofv3 PMC runs of this script (FETCH_SIZE and WRITE_SIZE,
-# each scaled by the reading of a 1 GiB copy: profiles/bench_c3_hbm_traffic.txt).  The tile calls sum
-# their kernels (partial_bwd = delta + dK/dV + dQ kernels).  Only the default workload was counted.
-# The default backward hands dS (bf16, 2 bytes per visible score) from the dK/dV kernel to the dQ
-# kernel through the workspace: bytes traded for the dQ kernel's recomputation of S and dP; the
-# "_recompute" entries are the --recompute-bwd path (traffic = the algorithmic minimum for the unmasked
-# tile; the diagonal tiles order their workgroups by size and share their inputs in L2 less).
-MIB = float(1 << 20)
-TRAFFIC_BYTES = {"c3": {
-    "partial_fwd_diag": (465.7 + 214.9) * MIB, "partial_fwd_full": (288.2 + 224.6) * MIB,
-    "partial_bwd_diag": (192.0 + 676.3 + 1873.8 + 1.5 + 1932.1 + 192.8) * MIB,
-    "partial_bwd_full": (192.0 + 387.6 + 3269.9 + 1.5 + 3456.1 + 194.1) * MIB,
-    "partial_bwd_diag_recompute": (192.0 + 666.0 + 621.9 + 1.5 + 384.2 + 192.8) * MIB,
-    "partial_bwd_full_recompute": (192.0 + 388.4 + 387.2 + 1.5 + 384.0 + 193.3) * MIB,
-    "fix": (1632.1 + 97.5) * MIB, "fix_bwd_dq": (1536.0 + 96.0) * MIB,
-    "fix_bwd_dk": (1536.0 + 96.0) * MIB, "fix_bwd_dv": (1536.0 + 96.0) * MIB}}
-
 
 def tile_flops(w, nq, nkv, causal_diag):
     """Algorithmic FLOPs of one tile, all heads: fwd 4 Nq Nkv H, bwd 10 Nq Nkv H per head; a
@@ -54,6 +37,23 @@ def tile_flops(w, nq, nkv, causal_diag):
     frac = (nq + 1) / (2.0 * nq) if causal_diag else 1.0
     base = w.heads * nq * nkv * w.hdim * frac
     return 4.0 * base, 10.0 * base
+
+
+def call_kernels(call, w, recompute):
+    """The library kernels one call of the step launches, in launch order."""
+    if call.startswith("partial_fwd"):
+        return ["fwd_mfma_kernel" if w.dtype == "bf16" else "fwd_generic_kernel"]
+    if call.startswith("partial_bwd"):
+        if w.dtype != "bf16":
+            return ["delta_kernel", "bwd_dkdv_generic_kernel", "bwd_dq_generic_kernel"]
+        return ["delta_kernel", "bwd_dkdv_kernel", "bwd_dq_kernel" if recompute else "bwd_dq_ds_kernel"]
+    if call == "fix":
+        return ["fix_kernel"]
+    if call.startswith("fix_bwd"):
+        return ["sum_kernel"]
+    if call == "copy_probe":
+        return ["copy_probe_kernel"]
+    raise KeyError(call)
 
 
 def main():
@@ -66,23 +66,29 @@ def main():
     ap.add_argument("--no-mfma-probe", action="store_true")
     ap.add_argument("--no-gathered", action="store_true",
                     help="skip the extra measurements appended after the timed steps (gathered key row, "
-                         "normalised partials, grouped-query heads)")
+                         "normalised partials, grouped-query heads, small and rectangular tiles)")
+    ap.add_argument("--no-extras", action="store_true", help="--no-gathered and --no-mfma-probe together")
     ap.add_argument("--recompute-bwd", action="store_true",
-                    help="give a2d_partial_bwd only its minimum workspace: the dQ kernel then recomputes S and dP "
-                         "instead of reading the dS the dK/dV kernel left in the larger workspace")
+                    help="do not set A2D_DESC_KEEP_DS: the dQ kernel then recomputes S and dP instead of reading "
+                         "the dS the dK/dV kernel left in the (larger) workspace")
     ap.add_argument("--grid-emulation", action="store_true",
                     help="also time Alg. 1 + Alg. 3 over all P tiles of the c2 sequence (8192 tokens, 4 x 4 grid)")
     ap.add_argument("--copy-probe", action="store_true",
-                    help="after the timed steps run one plain 1 GiB device copy (torch copy_), so that a "
+                    help="after the timed steps launch the library's plain copy kernel once on 1 GiB, so that a "
                          "rocprofv3 --pmc run of this command also holds the counter reading of a copy of "
                          "known size (the scale factor for FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--launch-log", default=None,
+                    help="write, as JSON, which call every library kernel launch of this process belongs to, in "
+                         "launch order (paper_2503_15758_amd.rocprof_summary matches profiler rows against it)")
     args = ap.parse_args()
+    if args.no_extras:
+        args.no_gathered = args.no_mfma_probe = True
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the sqrt(P) x sqrt(P) grid is emulated as "
                  "independent tiles on one device); --gpus %d is not supported" % args.gpus)
 
     import torch
-    from paper_2503_15758_amd import binding as a2d, synth
+    from paper_2503_15758_amd import binding as a2d, synth, rocprof_summary
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -94,6 +100,11 @@ def main():
     r = G - 1                                   # the query block with every partial non-empty
     # tiles of the step: (key block c, is_diagonal)
     tiles = [(r, True), (0, False)] if w.causal else [(0, False)]
+    launch_log = []                             # (kernel, call, phase) of every library launch, in order
+
+    def log_call(call, phase):
+        for k in call_kernels(call, w, args.recompute_bwd):
+            launch_log.append({"kernel": k, "call": call, "phase": phase})
 
     dev = lambda t: t.to("cuda")
     Q = dev(synth.q_block(w, r))
@@ -111,10 +122,11 @@ def main():
         if c not in timed_cols:
             a2d.partial_fwd(Q, dev(synth.k_block(w, c)), dev(synth.v_block(w, c)), r * T, c * T, w.causal,
                             scale, out=parts[c])
+            log_call("partial_fwd_full", "setup")
     O = torch.empty(w.heads, T, H, dtype=dt, device="cuda")
     lse = torch.empty(w.heads, T, **f32)
     if w.backward:
-        # the larger workspace (delta + dS, 2 T^2 bytes per head more) selects the dS hand-over
+        # with the dS hand-over (A2D_DESC_KEEP_DS) the workspace holds delta + dS: 2 T^2 bytes per head more
         ws_op = a2d.OP_PARTIAL_BWD if args.recompute_bwd else a2d.OP_PARTIAL_BWD_DS
         ws = torch.empty(a2d.workspace_bytes(a2d.tile_desc(Q, Kc[tiles[0][0]], 0, 0, w.causal, scale), ws_op),
                          dtype=torch.uint8, device="cuda")
@@ -129,7 +141,6 @@ def main():
         dV = torch.empty(w.heads, T, H, dtype=dt, device="cuda")
     torch.cuda.synchronize()
 
-    names = []
     calls = []      # (name, fn)
     for i, (c, diag) in enumerate(tiles):
         tag = "diag" if diag else "full"
@@ -147,77 +158,136 @@ def main():
         calls.append(("fix_bwd_dk", lambda: a2d.fix_bwd(dk_parts, out=dK)))
         calls.append(("fix_bwd_dv", lambda: a2d.fix_bwd(dv_parts, out=dV)))
     names = [n for n, _ in calls]
+    kernel_seq = [(n, k) for n in names for k in call_kernels(n, w, args.recompute_bwd)]   # launches of one step
+    events_per_step = len(kernel_seq) + len(calls)          # one event before every call, one after every kernel
 
-    def step(events=None):
-        for i, (_, fn) in enumerate(calls):
+    def step(events=None, phase=None):
+        for i, (name, fn) in enumerate(calls):
             if events is not None:
                 events[i][0].record()
             fn()
             if events is not None:
                 events[i][1].record()
+            if phase:
+                log_call(name, phase)
 
     for _ in range(args.warmup):
-        step()
+        step(phase="warmup")
     torch.cuda.synchronize()
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
            for _ in calls] for _ in range(args.steps)]
+    # per-kernel times: HIP events recorded by the library on the launch stream around every kernel
+    trace = a2d.KernelTrace(args.steps * events_per_step)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        step(ev[s])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    with trace:
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            step(ev[s], phase="timed")
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+    assert trace.count == args.steps * events_per_step, (trace.count, args.steps, events_per_step)
+    iv = trace.intervals_ms()
+    trace.close()
+    kern_ms = {}                                # (call, kernel) -> average duration over the timed steps
+    for s in range(args.steps):
+        pos = s * events_per_step               # index of the call's "before" event
+        for name in names:
+            for k in call_kernels(name, w, args.recompute_bwd):
+                kern_ms[(name, k)] = kern_ms.get((name, k), 0.0) + iv[pos] / args.steps
+                pos += 1
+            pos += 1
     if args.copy_probe:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        dst.copy_(src)
+        a2d.copy_probe(dst, src)
+        log_call("copy_probe", "probe")
         torch.cuda.synchronize()
+        del src, dst
+    if args.launch_log:
+        with open(args.launch_log, "w") as f:
+            json.dump(launch_log, f)
 
     avg_ms = {n: sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)) / args.steps
               for i, n in enumerate(names)}
 
-    # ---- algorithmic work of each call
-    flops = {}
+    # ---- algorithmic work of each call and of each kernel
+    esz = 2 if w.dtype == "bf16" else 4
+    rows = w.heads * T
+    flops, bytes_ = {}, {}
+    kflops, kbytes, knote = {}, {}, {}
     for c, diag in tiles:
         tag = "diag" if diag else "full"
         f, b = tile_flops(w, T, T, diag)
+        vis = (T + 1) / (2.0 * T) if diag else 1.0
         flops["partial_fwd_" + tag] = f
+        kflops[("partial_fwd_" + tag, call_kernels("partial_fwd_" + tag, w, False)[0])] = f
         if w.backward:
-            flops["partial_bwd_" + tag] = b
-    out_b = 2 if w.dtype == "bf16" else 4
-    rows = w.heads * T
-    bytes_ = {"fix": rows * (G * (H + 2) * 4 + H * out_b + 4)}
+            n = "partial_bwd_" + tag
+            flops[n] = b
+            ks = call_kernels(n, w, args.recompute_bwd)
+            kbytes[(n, ks[0])] = rows * (2 * H * esz + 4)
+            kflops[(n, ks[1])] = 0.8 * b                      # four of the five counted contractions: S, dP, dV, dK
+            if ks[2] == "bwd_dq_ds_kernel":
+                # one contraction over the stored dS: dS (2 bytes per visible score) + K read, dQ written
+                kbytes[(n, ks[2])] = w.heads * (2.0 * T * T * vis + T * H * esz + T * H * 4)
+                knote[(n, ks[2])] = "bytes = dS read back (2 per visible score) + K + the fp32 dQ partial; " \
+                                    "mfma_frac = its one contraction against the MFMA peak"
+            kflops[(n, ks[2])] = 0.2 * b                      # dQ = scale dS K (recomputation of S and dP not counted)
+    bytes_["fix"] = rows * (G * (H + 2) * 4 + H * esz + 4)
+    kbytes[("fix", "fix_kernel")] = bytes_["fix"]
     if w.backward:
         for n in ("fix_bwd_dq", "fix_bwd_dk", "fix_bwd_dv"):
-            bytes_[n] = rows * (G * H * 4 + H * out_b)
+            bytes_[n] = rows * (G * H * 4 + H * esz)
+            kbytes[(n, "sum_kernel")] = bytes_[n]
     total_flops = sum(flops.values())
     value = total_flops / (ms_per_step * 1e-3) / 1e12
 
-    kernels = {}
-    for n in names:
-        if n in flops:
-            ach = flops[n] / (avg_ms[n] * 1e-3) / 1e12
-            kernels[n] = {"avg_ms": round(avg_ms[n], 4), "bound": "mfma", "achieved": round(ach, 2),
-                          "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4)}
+    traffic_name = w.name + ("_recompute" if args.recompute_bwd else "")
+    traffic, traffic_sha = rocprof_summary.read_traffic(traffic_name)
+    src_sha = rocprof_summary.source_hash()
+
+    def entry(ms, fl=None, by=None, note=None):
+        if by is not None and (fl is None or note):           # HBM-bound
+            ach = by / (ms * 1e-3) / 1e9
+            e = {"avg_ms": round(ms, 4), "bound": "hbm", "achieved": round(ach, 1), "unit": "GB/s",
+                 "frac": round(ach / PEAK_HBM_GBS, 4), "peak": PEAK_HBM_GBS}
+            if fl is not None:
+                e["mfma_frac"] = round(fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)
         else:
-            ach = bytes_[n] / (avg_ms[n] * 1e-3) / 1e9
-            kernels[n] = {"avg_ms": round(avg_ms[n], 4), "bound": "hbm", "achieved": round(ach, 1),
-                          "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4)}
-    dom = max((n for n in names if n in flops), key=lambda n: avg_ms[n])
-    roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["achieved"],
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": kernels[dom]["frac"],
-                "avg_ms": kernels[dom]["avg_ms"],
-                "traffic": TRAFFIC_BYTES.get(w.name, {}).get(dom + ("_recompute" if args.recompute_bwd else ""),
-                                                             TRAFFIC_BYTES.get(w.name, {}).get(dom))}
+            ach = fl / (ms * 1e-3) / 1e12
+            e = {"avg_ms": round(ms, 4), "bound": "mfma", "achieved": round(ach, 2), "unit": "TFLOP/s",
+                 "frac": round(ach / PEAK_BF16_TFLOPS, 4), "peak": PEAK_BF16_TFLOPS}
+        if note:
+            e["note"] = note
+        return e
+
+    kernels = {n: entry(avg_ms[n], flops.get(n), bytes_.get(n)) for n in names}
+    per_kernel = {}
+    for (n, k), ms in kern_ms.items():
+        e = entry(ms, kflops.get((n, k)), kbytes.get((n, k)), knote.get((n, k)))
+        e["traffic"] = traffic.get("%s/%s" % (n, k))
+        per_kernel["%s/%s" % (n, k)] = e
+    for n in names:
+        kernels[n]["traffic"] = traffic.get(n)
+    # the dominant kernel: the longest single launch of the step
+    dom = max(kern_ms, key=lambda nk: kern_ms[nk])
+    de = per_kernel["%s/%s" % dom]
+    roofline = {"kernel": dom[1], "call": dom[0], "bound": de["bound"], "achieved": de["achieved"], "peak": de["peak"],
+                "unit": de["unit"], "frac": de["frac"], "avg_ms": de["avg_ms"], "traffic": de["traffic"],
+                "algorithmic": ("4 of the call's 5 counted contractions (S, dP, dV, dK): 8 Nq Nkv H per head"
+                                if dom[1] == "bwd_dkdv_kernel" else "the call's counted work"),
+                "traffic_source": {"file": "profiles/%s_hbm_traffic.txt" % traffic_name if traffic else None,
+                                   "measured_on_sources": traffic_sha, "current_sources": src_sha,
+                                   "current": bool(traffic) and traffic_sha == src_sha}}
     if w.backward:
         roofline["bwd_path"] = "recompute" if args.recompute_bwd else "dS hand-over"
         # the call's inputs and outputs read / written once (Q, K, V, O, dO in the model's dtype, three fp32
-        # gradient partials, lse): what `traffic` is to be held against.  The dS hand-over adds 2 bytes per
-        # visible score written and read back (an intermediate traded for two contractions).
-        esz = 2 if w.dtype == "bf16" else 4
-        roofline["algorithmic_bytes"] = w.heads * (5 * T * H * esz + 3 * T * H * 4 + T * 4)
+        # gradient partials, lse): what the call's `traffic` is to be held against.  The dS hand-over adds 2
+        # bytes per visible score written and read back (an intermediate traded for two contractions).
+        roofline["call_algorithmic_bytes"] = w.heads * (5 * T * H * esz + 3 * T * H * 4 + T * 4)
+        roofline["call_traffic"] = traffic.get(dom[0])
 
     result = {
         "metric": "fwd+bwd attention TFLOP/s per tile + % bf16 MFMA peak; AttnFix GB/s",
@@ -230,7 +300,7 @@ def main():
             "tiles_per_step": [("diagonal" if d else "unmasked") for _, d in tiles], "fix_k": G},
         "frac_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "attnfix_gbs": kernels["fix"]["achieved"], "attnfix_frac_hbm": kernels["fix"]["frac"],
-        "roofline": roofline, "kernels": kernels,
+        "roofline": roofline, "kernels": kernels, "per_kernel": per_kernel,
     }
     # ---- extra measurements after the timed steps; none of them may cost the line above
     def extra(key, fn):

@@ -374,6 +374,28 @@ a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t sc
  */
 void a2d_debug_force_generic(int on);
 
+/*
+ * Diagnostic, not part of the method: per-kernel timing of the calls above.  events: a HOST array
+ * of n hipEvent_t handles the caller created with timing enabled (it owns them and the array,
+ * which must stay valid until the trace is switched off), or NULL / n = 0 to switch the trace
+ * off.  While a trace is set - per host thread - every call of this library made by that thread
+ * records the next unused event on the call's stream once before its first kernel and once
+ * after each kernel it launches; consecutive events of one call then bracket one kernel each
+ * (a tile forward: 2 events; a2d_partial_bwd: 4 - delta, dK/dV, dQ kernels; a merge: 2).  Events
+ * beyond n are not recorded.  a2d_debug_trace_count: events recorded since the trace was set.
+ */
+void a2d_debug_trace(void** events, int n);
+int a2d_debug_trace_count(void);
+
+/*
+ * Diagnostic, not part of the method: a plain device-to-device copy of `bytes` bytes (a positive
+ * multiple of 16; both pointers 16-byte aligned, buffers must not overlap) with 128-bit
+ * non-temporal loads and stores, enqueued on `stream`.  It gives the streaming calls (a2d_fix,
+ * a2d_fix_bwd) the copy rate this chip reaches as context for their HBM fraction, and a kernel of
+ * known traffic for calibrating the HBM byte counters of a profiler run.
+ */
+a2d_status a2d_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+
 /* Static string for a status code. */
 const char* a2d_status_str(a2d_status status);
 /* Detail of the calling thread's last failed call ("" if none). */

@@ -23,6 +23,7 @@ EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd
            "a2d_partial_fwd_norm", "a2d_fix_norm", "a2d_partial_fwd_gqa", "a2d_partial_bwd_gqa",
            "a2d_fix_strided", "a2d_fix_bwd_strided", "a2d_fix_norm_strided",
            "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling", "a2d_debug_force_generic",
+           "a2d_debug_trace", "a2d_debug_trace_count", "a2d_copy_probe",
            "a2d_status_str", "a2d_last_error", "a2d_version")
 
 
@@ -127,6 +128,12 @@ def lib():
                                        ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.a2d_debug_force_generic.restype = None
         L.a2d_debug_force_generic.argtypes = [ctypes.c_int]
+        L.a2d_debug_trace.restype = None
+        L.a2d_debug_trace.argtypes = [ctypes.POINTER(vp), ctypes.c_int]
+        L.a2d_debug_trace_count.restype = ctypes.c_int
+        L.a2d_debug_trace_count.argtypes = []
+        L.a2d_copy_probe.restype = ctypes.c_int
+        L.a2d_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.a2d_status_str.restype = ctypes.c_char_p
         L.a2d_status_str.argtypes = [ctypes.c_int]
         L.a2d_last_error.restype = ctypes.c_char_p
@@ -440,6 +447,72 @@ def mfma_ceiling(iters=20000, random_data=True):
 def force_generic(on):
     """a2d_debug_force_generic: route every tile call to the vector-ALU kernels (debugging aid)."""
     lib().a2d_debug_force_generic(int(bool(on)))
+
+
+def copy_probe(dst, src):
+    """a2d_copy_probe: plain device copy of src into dst (contiguous device tensors of equal byte size)."""
+    _plain([dst, src], "dst, src")
+    n = src.numel() * src.element_size()
+    if n != dst.numel() * dst.element_size():
+        raise A2DError(-1, "dst and src differ in size")
+    _check(lib().a2d_copy_probe(_ptr(dst), _ptr(src), n, _stream()))
+    return dst
+
+
+def _loaded_hip_runtime():
+    """Path of the HIP runtime ALREADY mapped into this process (the one liba2d.so and torch use):
+    events must come from that copy, not from a second one a search by name might load."""
+    with open("/proc/self/maps") as f:
+        for line in f:
+            if "libamdhip64.so" in line:
+                return line.split()[-1]
+    raise RuntimeError("no HIP runtime is loaded in this process")
+
+
+class KernelTrace:
+    """a2d_debug_trace on the calling thread: `with KernelTrace(n) as tr:` records up to n HIP events
+    (created here through the HIP runtime the library is linked against); after a device
+    synchronisation tr.intervals_ms() gives the time between consecutive recorded events."""
+
+    def __init__(self, n):
+        self.n = int(n)
+        lib()
+        self._hip = ctypes.CDLL(_loaded_hip_runtime())
+        self._hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self._hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self._hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self._ev = (ctypes.c_void_p * self.n)()
+        for i in range(self.n):
+            e = ctypes.c_void_p()
+            if self._hip.hipEventCreate(ctypes.byref(e)) != 0:
+                raise A2DError(-5, "hipEventCreate failed")
+            self._ev[i] = e
+        self.count = 0
+
+    def __enter__(self):
+        lib().a2d_debug_trace(self._ev, self.n)
+        return self
+
+    def __exit__(self, *exc):
+        self.count = int(lib().a2d_debug_trace_count())
+        lib().a2d_debug_trace(None, 0)
+        return False
+
+    def intervals_ms(self):
+        """[t(event i+1) - t(event i)] for the recorded events; call after the device has finished them."""
+        out = []
+        for i in range(self.count - 1):
+            ms = ctypes.c_float()
+            if self._hip.hipEventElapsedTime(ctypes.byref(ms), self._ev[i], self._ev[i + 1]) != 0:
+                raise A2DError(-5, "hipEventElapsedTime failed")
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for i in range(self.n):
+            if self._ev[i]:
+                self._hip.hipEventDestroy(self._ev[i])
+                self._ev[i] = None
 
 
 def version():

@@ -178,9 +178,11 @@ a2d_status partial_fwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
     a2d::SegList go = g;
     go.by_size = blocks_differ(desc, g);
     A2D_TRY(hip_result(a2d::launch_fwd_mfma(a2d::PREPARE, dd, go, Q, K, V, O_part, m, l, s), who));
+    a2d::trace_mark(s);
     return hip_result(a2d::launch_fwd_mfma(a2d::LAUNCH, dd, go, Q, K, V, O_part, m, l, s), who);
   }
   A2D_TRY(hip_result(a2d::launch_fwd_generic(a2d::PREPARE, dd, g, Q, K, V, O_part, m, l, s), who));
+  a2d::trace_mark(s);
   return hip_result(a2d::launch_fwd_generic(a2d::LAUNCH, dd, g, Q, K, V, O_part, m, l, s), who);
 }
 
@@ -233,12 +235,14 @@ a2d_status partial_bwd_impl(const a2d_tile_desc* desc, const a2d::SegList& g, co
     go.by_size = blocks_differ(desc, g);
     A2D_TRY(hip_result(a2d::launch_bwd_mfma(a2d::PREPARE, dd, go, Q, K, V, dO, lse, delta, dQ_part, dK_part,
                                             dV_part, ds_ws, split_ws, s), who));
+    a2d::trace_mark(s);
     A2D_TRY(hip_result(a2d::launch_delta(dd, O, dO, delta, s), who));
     return hip_result(a2d::launch_bwd_mfma(a2d::LAUNCH, dd, go, Q, K, V, dO, lse, delta, dQ_part, dK_part,
                                            dV_part, ds_ws, split_ws, s), who);
   }
   A2D_TRY(hip_result(a2d::launch_bwd_generic(a2d::PREPARE, dd, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
                                              dV_part, s), who));
+  a2d::trace_mark(s);
   A2D_TRY(hip_result(a2d::launch_delta(dd, O, dO, delta, s), who));
   return hip_result(a2d::launch_bwd_generic(a2d::LAUNCH, dd, g, Q, K, V, dO, lse, delta, dQ_part, dK_part,
                                             dV_part, s), who);
@@ -362,6 +366,7 @@ a2d_status fix_norm_impl(int k, int64_t rows, int32_t hdim, int32_t in_dtype, in
     A2D_TRY(check_ptr(lse_parts[x], who, "lse_parts[x]"));
     p.o[x] = O_norm_parts[x]; p.lse[x] = lse_parts[x];
   }
+  a2d::trace_mark(static_cast<hipStream_t>(stream));
   return hip_result(a2d::launch_fix_norm(k, rows, hdim, in_dtype, out_dtype, p, om, O, lse,
                                          static_cast<hipStream_t>(stream)), who);
 }
@@ -497,6 +502,7 @@ a2d_status fix_impl(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
     A2D_TRY(check_ptr(l[x], who, "l[x]"));
     p.o[x] = O_parts[x]; p.m[x] = m[x]; p.l[x] = l[x];
   }
+  a2d::trace_mark(static_cast<hipStream_t>(stream));
   return hip_result(a2d::launch_fix(k, rows, hdim, out_dtype, p, om, O, lse,
                                     static_cast<hipStream_t>(stream)), who);
 }
@@ -518,6 +524,7 @@ a2d_status fix_bwd_impl(int k, int64_t n, int32_t hdim, int32_t out_dtype, const
     A2D_TRY(check_ptr(parts[x], who, "parts[x]"));
     p.p[x] = parts[x];
   }
+  a2d::trace_mark(static_cast<hipStream_t>(stream));
   return hip_result(a2d::launch_fix_bwd(k, n, hdim / 4, out_dtype, p, om, out, static_cast<hipStream_t>(stream)), who);
 }
 
@@ -652,6 +659,19 @@ a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t sc
 }
 
 void a2d_debug_force_generic(int on) { a2d::set_force_generic(on != 0); }
+
+void a2d_debug_trace(void** events, int n) { a2d::trace_set(reinterpret_cast<hipEvent_t*>(events), n); }
+
+int a2d_debug_trace_count(void) { return a2d::trace_count(); }
+
+a2d_status a2d_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
+  const char* who = "a2d_copy_probe";
+  A2D_TRY(check_ptr(dst, who, "dst"));
+  A2D_TRY(check_ptr(src, who, "src"));
+  if (bytes < 16 || bytes % 16 != 0)
+    return fail(A2D_ERR_INVALID_ARG, "%s: bytes=%zu must be a positive multiple of 16", who, bytes);
+  return hip_result(a2d::launch_copy_probe(dst, src, bytes / 16, static_cast<hipStream_t>(stream)), who);
+}
 
 const char* a2d_last_error(void) { return g_err; }
 

@@ -1081,20 +1081,20 @@ hipError_t bwd_launch_ds(Phase ph, const a2d_tile_desc& d, const SegList& g, con
   const int per_unit = g.group / g.split;
   dim3 grid_q(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + dq_rows - 1) / dq_rows)));
   if (grouped)
-    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, true, true>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g,
+    A2D_LAUNCH((bwd_dkdv_kernel<HR, true, true>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g,
                        (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV,
                        (bf16_t*)ds_ws);
   else
-    hipLaunchKernelGGL((bwd_dkdv_kernel<HR, false, true>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g,
+    A2D_LAUNCH((bwd_dkdv_kernel<HR, false, true>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g,
                        (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV,
                        (bf16_t*)ds_ws);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (big)
-    hipLaunchKernelGGL((bwd_dq_ds_kernel<8, HR>), grid_q, dim3(512), DSQ_LDS, s, d, g, (const bf16_t*)K,
+    A2D_LAUNCH((bwd_dq_ds_kernel<8, HR>), grid_q, dim3(512), DSQ_LDS, s, d, g, (const bf16_t*)K,
                        (const bf16_t*)ds_ws, dQ);
   else
-    hipLaunchKernelGGL((bwd_dq_ds_kernel<4, HR>), grid_q, dim3(256), DSQ_LDS, s, d, g, (const bf16_t*)K,
+    A2D_LAUNCH((bwd_dq_ds_kernel<4, HR>), grid_q, dim3(256), DSQ_LDS, s, d, g, (const bf16_t*)K,
                        (const bf16_t*)ds_ws, dQ);
   return hipGetLastError();
 }
@@ -1128,7 +1128,7 @@ hipError_t bwd_launch_hd(Phase ph, const a2d_tile_desc& d, const SegList& g, con
   const int per_unit = g.group / g.split;
   dim3 grid_q(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + dq_rows - 1) / dq_rows)));
 #define A2D_DKDV(GR, PL)                                                                                          \
-  hipLaunchKernelGGL((bwd_dkdv_kernel<HR, GR, false, PL>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q, \
+  A2D_LAUNCH((bwd_dkdv_kernel<HR, GR, false, PL>), grid_kv, dim3(DK_THREADS), DK_LDS, s, d, g, (const bf16_t*)Q, \
                      (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dK, dV, (bf16_t*)nullptr)
   if (grouped && plain) A2D_DKDV(true, true);
   else if (grouped) A2D_DKDV(true, false);
@@ -1138,10 +1138,10 @@ hipError_t bwd_launch_hd(Phase ph, const a2d_tile_desc& d, const SegList& g, con
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (big)
-    hipLaunchKernelGGL((bwd_dq_kernel<8, HR>), grid_q, dim3(512), DQ_LDS, s, d, g, (const bf16_t*)Q,
+    A2D_LAUNCH((bwd_dq_kernel<8, HR>), grid_q, dim3(512), DQ_LDS, s, d, g, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
   else
-    hipLaunchKernelGGL((bwd_dq_kernel<4, HR>), grid_q, dim3(256), DQ_LDS, s, d, g, (const bf16_t*)Q,
+    A2D_LAUNCH((bwd_dq_kernel<4, HR>), grid_q, dim3(256), DQ_LDS, s, d, g, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
   return hipGetLastError();
 }

@@ -89,6 +89,17 @@ hipError_t ensure_dynamic_lds(const void* kernel, int bytes);
 // A2D_FORCE_GENERIC=1 in the environment, read once per process; a2d_debug_force_generic() sets it.
 bool force_generic();
 void set_force_generic(bool on);
+// Kernel trace of the calling host thread (diagnostic, see a2d_debug_trace): trace_mark records
+// the next caller-supplied event on the stream; a no-op (one thread-local test) when no trace is set.
+void trace_set(hipEvent_t* events, int n);
+int trace_count();
+void trace_mark(hipStream_t s);
+// every kernel launch of the method goes through this: the launch, then the trace mark
+#define A2D_LAUNCH(kernel, grid, block, lds, stream, ...)               \
+  do {                                                                  \
+    hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);  \
+    ::a2d::trace_mark(stream);                                          \
+  } while (0)
 
 // ---- launchers (none synchronises) ----
 // Every tile launcher runs in two phases so that a call can finish everything that may fail on the
@@ -152,6 +163,8 @@ struct NormPtrs {
 hipError_t launch_fix_norm(int k, int64_t rows, int hdim, int in_dtype, int out_dtype, const NormPtrs& p,
                            const OutMap& om, void* O, float* lse, hipStream_t s);
 
+// plain device copy of n16 16-byte pieces (diagnostic: HBM ceiling and counter calibration)
+hipError_t launch_copy_probe(void* dst, const void* src, size_t n16, hipStream_t s);
 // MFMA-only ceiling probe (diagnostic)
 hipError_t launch_mfma_probe(int blocks, int iters, int random_data, float* scratch, hipStream_t s);
 int mfma_probe_threads();

@@ -19,6 +19,11 @@ std::mutex g_mu;
 std::vector<std::pair<int, const void*>> g_prepared;       // (device, kernel): limit already raised
 std::atomic<int> g_force_generic{-1};                      // -1 = environment not read yet
 
+// kernel trace of the calling host thread (a2d_debug_trace)
+thread_local hipEvent_t* t_trace_events = nullptr;
+thread_local int t_trace_cap = 0;
+thread_local int t_trace_used = 0;
+
 }  // namespace
 
 hipError_t device_cus(int* cus) {
@@ -67,5 +72,16 @@ bool force_generic() {
 }
 
 void set_force_generic(bool on) { g_force_generic.store(on ? 1 : 0); }
+
+void trace_set(hipEvent_t* events, int n) {
+  t_trace_events = (events && n > 0) ? events : nullptr;
+  t_trace_cap = t_trace_events ? n : 0;
+  t_trace_used = 0;
+}
+int trace_count() { return t_trace_used; }
+void trace_mark(hipStream_t s) {
+  if (!t_trace_events || t_trace_used >= t_trace_cap) return;
+  if (hipEventRecord(t_trace_events[t_trace_used], s) == hipSuccess) ++t_trace_used;
+}
 
 }  // namespace a2d

@@ -172,7 +172,7 @@ void fix_launch(int k, int64_t rows, int hv, const FixPtrs& p, const OutMap& om,
   constexpr int CPT = chunks_per_thread(KMAX);
   const int64_t per_block = 256 * CPT;
   const dim3 grid((unsigned)((rows * hv + per_block - 1) / per_block)), block(256);
-  hipLaunchKernelGGL((fix_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, rows, hv, om, O, lse);
+  A2D_LAUNCH((fix_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, rows, hv, om, O, lse);
 }
 
 template <typename OutT, int KMAX>
@@ -180,7 +180,7 @@ void sum_launch(int k, int64_t n4, int hv, const SumPtrs& p, const OutMap& om, O
   constexpr int CPT = chunks_per_thread(KMAX);
   const int64_t per_block = 256 * CPT;
   const dim3 grid((unsigned)((n4 + per_block - 1) / per_block)), block(256);
-  hipLaunchKernelGGL((sum_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, n4, hv, om, out);
+  A2D_LAUNCH((sum_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, n4, hv, om, out);
 }
 
 template <typename OutT>
@@ -212,7 +212,7 @@ void fix_norm_launch(int k, int64_t rows, int hv, const NormPtrs& p, const OutMa
   constexpr int CPT = chunks_per_thread(KMAX);
   const int64_t per_block = 256 * CPT;
   const dim3 grid((unsigned)((rows * hv + per_block - 1) / per_block)), block(256);
-  hipLaunchKernelGGL((fix_norm_kernel<InT, OutT, KMAX, CPT>), grid, block, 0, s, p, k, rows, hv, om, O, lse);
+  A2D_LAUNCH((fix_norm_kernel<InT, OutT, KMAX, CPT>), grid, block, 0, s, p, k, rows, hv, om, O, lse);
 }
 
 template <typename InT, typename OutT>

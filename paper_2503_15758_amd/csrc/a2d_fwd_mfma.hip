@@ -120,6 +120,19 @@ __device__ __forceinline__ void fwd_block(FwdState<HD>& st, const bf16x8 (&qf)[H
   __builtin_amdgcn_sched_barrier(0);
   float psum = 0.f;
   bf16x8 pb[4];
+#ifdef A2D_FWD_DOT2
+  // the row sum is taken over the ROUNDED probabilities, two per instruction (v_dot2c_f32_bf16
+  // against a pair of ones, fp32 accumulation): the weights of N and their sum l then agree exactly
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pb[u][e] = (bf16_t)fast_exp2(fmaf(s[u >> 1][8 * (u & 1) + e], c, -mc));
+    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
+#pragma unroll
+    for (int e = 0; e < 8; e += 2)
+      psum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pb[u][e], pb[u][e + 1]}, ones, psum, false);
+  }
+#else
 #pragma unroll
   for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -128,6 +141,7 @@ __device__ __forceinline__ void fwd_block(FwdState<HD>& st, const bf16x8 (&qf)[H
       psum += p;
       pb[u][e] = (bf16_t)p;
     }
+#endif
   st.l_run += psum;
   __builtin_amdgcn_sched_barrier(0);
   static_for<0, 4 * CT>([&](auto I) {
@@ -401,7 +415,7 @@ hipError_t fwd_launch(Phase ph, const a2d_tile_desc& d, const SegList& g, const 
     return ensure_dynamic_lds(reinterpret_cast<const void*>(fwd_mfma_kernel<WAVES, HR>), bytes);
   const int per_unit = g.group / g.split;
   dim3 grid(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + 32 * WAVES - 1) / (32 * WAVES)))), block(64 * WAVES);
-  hipLaunchKernelGGL((fwd_mfma_kernel<WAVES, HR>), grid, block, bytes, s, d, g, (const bf16_t*)Q,
+  A2D_LAUNCH((fwd_mfma_kernel<WAVES, HR>), grid, block, bytes, s, d, g, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, O_part, m, l);
   return hipGetLastError();
 }

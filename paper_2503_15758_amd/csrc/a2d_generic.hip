@@ -440,7 +440,7 @@ hipError_t fwd_launch(Phase ph, const a2d_tile_desc& d, const SegList& g, const 
   constexpr size_t lds = sizeof(float) * (64 * (H + 1) * 2 + 64 * H + 64 * 65);
   if (ph == PREPARE) return set_lds(fwd_generic_kernel<T, H>, lds);
   dim3 grid((d.nq + 63) / 64, d.heads), block(kThreads);
-  hipLaunchKernelGGL((fwd_generic_kernel<T, H>), grid, block, lds, s, d, g, (const T*)Q, (const T*)K,
+  A2D_LAUNCH((fwd_generic_kernel<T, H>), grid, block, lds, s, d, g, (const T*)Q, (const T*)K,
                      (const T*)V, O_part, m, l);
   return hipGetLastError();
 }
@@ -457,11 +457,11 @@ hipError_t bwd_launch(Phase ph, const a2d_tile_desc& d, const SegList& g, const 
   }
   dim3 block(kThreads);
   dim3 grid_kv((d.nkv + 63) / 64, d.heads / g.group), grid_q((d.nq + 63) / 64, d.heads);
-  hipLaunchKernelGGL((bwd_dkdv_generic_kernel<T, H>), grid_kv, block, lds_kv, s, d, g, (const T*)Q,
+  A2D_LAUNCH((bwd_dkdv_generic_kernel<T, H>), grid_kv, block, lds_kv, s, d, g, (const T*)Q,
                      (const T*)K, (const T*)V, (const T*)dO, lse, delta, dK, dV);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((bwd_dq_generic_kernel<T, H>), grid_q, block, lds_q, s, d, g, (const T*)Q,
+  A2D_LAUNCH((bwd_dq_generic_kernel<T, H>), grid_q, block, lds_q, s, d, g, (const T*)Q,
                      (const T*)K, (const T*)V, (const T*)dO, lse, delta, dQ);
   return hipGetLastError();
 }
@@ -500,10 +500,10 @@ hipError_t launch_delta(const a2d_tile_desc& d, const void* O, const void* dO, f
   const int64_t threads = rows * lpr;
   dim3 grid((unsigned)((threads + kThreads - 1) / kThreads)), block(kThreads);
   if (dtype == A2D_BF16)
-    hipLaunchKernelGGL((delta_kernel<bf16_t>), grid, block, 0, s, rows, d.nq, hdim, lpr, d.lo, d.ldo,
+    A2D_LAUNCH((delta_kernel<bf16_t>), grid, block, 0, s, rows, d.nq, hdim, lpr, d.lo, d.ldo,
                        (const bf16_t*)O, (const bf16_t*)dO, delta);
   else
-    hipLaunchKernelGGL((delta_kernel<float>), grid, block, 0, s, rows, d.nq, hdim, lpr, d.lo, d.ldo,
+    A2D_LAUNCH((delta_kernel<float>), grid, block, 0, s, rows, d.nq, hdim, lpr, d.lo, d.ldo,
                        (const float*)O, (const float*)dO, delta);
   return hipGetLastError();
 }

@@ -54,7 +54,34 @@ __global__ __launch_bounds__(PROBE_THREADS) void mfma_probe_kernel(float* __rest
   if (tid == 0 && blockIdx.x == 0) { clocks[0] = c1 - c0; clocks[1] = w1 - w0; }
 }
 
+// Plain copy: every thread moves 16-byte pieces one grid-sized stride apart, four loads in flight.
+__global__ __launch_bounds__(256) void copy_probe_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
+                                                         size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
+    const u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
+    __builtin_nontemporal_store(a, dst + i);
+    __builtin_nontemporal_store(b, dst + i + stride);
+    __builtin_nontemporal_store(c, dst + i + 2 * stride);
+    __builtin_nontemporal_store(d, dst + i + 3 * stride);
+  }
+  for (; i < n16; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
 }  // namespace
+
+hipError_t launch_copy_probe(void* dst, const void* src, size_t n16, hipStream_t s) {
+  int cus = 0;
+  const hipError_t e = device_cus(&cus);
+  if (e != hipSuccess) return e;
+  // eight workgroups per compute unit, each thread walking the buffer in grid-sized strides
+  const size_t want = (n16 + 255) / 256;
+  const unsigned blocks = (unsigned)(want < (size_t)cus * 8 ? (want ? want : 1) : (size_t)cus * 8);
+  hipLaunchKernelGGL(copy_probe_kernel, dim3(blocks), dim3(256), 0, s, (u32x4*)dst, (const u32x4*)src, n16);
+  return hipGetLastError();
+}
 
 // scratch: (blocks * PROBE_THREADS) floats of results followed by two 64-bit counters
 hipError_t launch_mfma_probe(int blocks, int iters, int random_data, float* scratch, hipStream_t s) {
