@@ -120,19 +120,6 @@ __device__ __forceinline__ void fwd_block(FwdState<HD>& st, const bf16x8 (&qf)[H
   __builtin_amdgcn_sched_barrier(0);
   float psum = 0.f;
   bf16x8 pb[4];
-#ifdef A2D_FWD_DOT2
-  // the row sum is taken over the ROUNDED probabilities, two per instruction (v_dot2c_f32_bf16
-  // against a pair of ones, fp32 accumulation): the weights of N and their sum l then agree exactly
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) pb[u][e] = (bf16_t)fast_exp2(fmaf(s[u >> 1][8 * (u & 1) + e], c, -mc));
-    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
-#pragma unroll
-    for (int e = 0; e < 8; e += 2)
-      psum = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{pb[u][e], pb[u][e + 1]}, ones, psum, false);
-  }
-#else
 #pragma unroll
   for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -141,7 +128,6 @@ __device__ __forceinline__ void fwd_block(FwdState<HD>& st, const bf16x8 (&qf)[H
       psum += p;
       pb[u][e] = (bf16_t)p;
     }
-#endif
   st.l_run += psum;
   __builtin_amdgcn_sched_barrier(0);
   static_for<0, 4 * CT>([&](auto I) {
