@@ -8,9 +8,13 @@ workload (default: the GPT-3-like causal workload, 4096 x 4096 x H128 tiles, 96 
 All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
   value            = algorithmic tile FLOPs of the step / wall time of the step (TFLOP/s)
-  roofline         = the dominant kernel (the backward tile kernel) against the bf16 MFMA peak,
-                     its duration measured with events on the launch stream inside the timed region
-  kernels          = the same for every call of the step (fix / fix_bwd against the HBM peak)
+  roofline         = the dominant kernel (the longest single launch of the step: the dK/dV kernel of the
+                     unmasked backward tile) against the roofline that bounds it, its duration measured with
+                     HIP events the library records on the launch stream around every kernel, inside the
+                     timed region (a2d_debug_trace); traffic = HBM bytes per launch from profiles/
+  per_kernel       = the same object for every kernel of the step (MFMA kernels against the bf16 MFMA peak,
+                     streaming kernels and the dQ-from-dS kernel against the HBM peak)
+  kernels          = per call of the step (a backward call = delta + dK/dV + dQ kernels)
   cpu_baseline     = the fp64 oracle timed on the host cores on a bounded sample
   mfma_ceiling     = what the bf16 MFMA units sustain on their own on this chip (diagnostic probe of the
                      library: register operands, no other work), with random and with constant operands,
@@ -161,28 +165,23 @@ def main():
     kernel_seq = [(n, k) for n in names for k in call_kernels(n, w, args.recompute_bwd)]   # launches of one step
     events_per_step = len(kernel_seq) + len(calls)          # one event before every call, one after every kernel
 
-    def step(events=None, phase=None):
-        for i, (name, fn) in enumerate(calls):
-            if events is not None:
-                events[i][0].record()
+    def step(phase=None):
+        for name, fn in calls:
             fn()
-            if events is not None:
-                events[i][1].record()
             if phase:
                 log_call(name, phase)
 
     for _ in range(args.warmup):
         step(phase="warmup")
     torch.cuda.synchronize()
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in calls] for _ in range(args.steps)]
-    # per-kernel times: HIP events recorded by the library on the launch stream around every kernel
+    # per-kernel times: HIP events recorded by the library on the launch stream, one before every call
+    # and one after every kernel (the only events inside the timed region)
     trace = a2d.KernelTrace(args.steps * events_per_step)
     torch.cuda.synchronize()
     with trace:
         t0 = time.perf_counter()
         for s in range(args.steps):
-            step(ev[s], phase="timed")
+            step(phase="timed")
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
@@ -209,8 +208,8 @@ def main():
         with open(args.launch_log, "w") as f:
             json.dump(launch_log, f)
 
-    avg_ms = {n: sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)) / args.steps
-              for i, n in enumerate(names)}
+    # a call's time: from the event before it to the event after its last kernel
+    avg_ms = {n: sum(kern_ms[(n, k)] for k in call_kernels(n, w, args.recompute_bwd)) for n in names}
 
     # ---- algorithmic work of each call and of each kernel
     esz = 2 if w.dtype == "bf16" else 4
@@ -332,6 +331,20 @@ def main():
                 "launches_per_step": len(calls) + (2 * len(tiles) if w.backward else 0),
                 "what": "the timed step captured once into a HIP graph and replayed"}
 
+    def plain_step():
+        # the same eager step with nothing between the calls: no per-call events, no kernel trace
+        # (they cost a short step more than a long one: every event is a packet of its own in the queue)
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        msp = (time.perf_counter() - t0) * 1e3 / args.steps
+        return {"ms_per_step": round(msp, 4), "tflops": round(total_flops / (msp * 1e-3) / 1e12, 2),
+                "what": "the timed step, eager, without the per-call events and the kernel trace of the timed region"}
+
     def two_stream_step():
         # the same step with the two backward tile calls on two streams (their own workspaces): the
         # HBM-bound dQ-from-dS kernel of one tile then runs beside the MFMA-bound dK/dV kernel of the other
@@ -375,6 +388,7 @@ def main():
                 "unit": "TFLOP/s", "kind": "MFMA-only probe, register operands"}
 
     if not args.no_gathered:
+        extra("plain_step", plain_step)
         extra("hip_graph_step", graph_step)
         if w.backward and len(tiles) == 2:
             extra("two_stream_step", two_stream_step)
@@ -384,6 +398,8 @@ def main():
             extra("normalised_partials", lambda: normalised_format(a2d, synth, w, scale, kernels))
             extra("grouped_query", lambda: grouped_query(a2d, synth, w, scale, kernels))
             extra("strided_inputs", lambda: strided_inputs(a2d, synth, w, scale, kernels))
+            extra("rectangular_tiles", lambda: rectangular_tiles(a2d, synth, w, scale))
+            extra("small_tiles", lambda: small_tiles(a2d, synth))
     if args.grid_emulation:
         extra("grid_emulation", lambda: grid_emulation(synth))
     if not args.no_mfma_probe:
@@ -601,6 +617,111 @@ def grouped_query(a2d, synth, w, scale, kernels):
                              "bwd_ms": round(t_b, 4), "bwd_tflops": round(b_fl / t_b / 1e9, 1),
                              "bwd_split_groups_ms": round(t_s, 4), "bwd_split_groups_tflops": round(b_fl / t_s / 1e9, 1)})
     return res
+
+
+def _timeit(torch, fn, n=10):
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(3):      # median of three loops: the first one after an idle stretch runs at lower clocks
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) / n)
+    return sorted(ts)[1]
+
+
+def rectangular_tiles(a2d, synth, w, scale):
+    """Tiles with Nq != Nkv (Sec. 3.2 allows rectangular device grids; 8 GPUs of a node are a 2 x 4
+    grid): the workload's heads on unmasked tiles of the same area as the square one, both
+    orientations, forward and backward on both backward paths, with the launch shape each kernel took."""
+    import torch
+    H, heads = w.hdim, w.heads
+    gen = torch.Generator(device="cuda"); gen.manual_seed(11)
+    mk = lambda rows: torch.randn(heads, rows, H, device="cuda", generator=gen).to(torch.bfloat16)
+    out = {"what": "%d heads, unmasked tiles of equal area, Nq x Nkv; fwd_wg / dq_wg = query rows per workgroup of the "
+                   "forward / dQ kernels (256: eight wavefronts; 128: four), dkdv_wgs = workgroups of 128 keys" % heads,
+           "cases": []}
+    for nq, nkv in ((4096, 4096), (2048, 8192), (8192, 2048), (1024, 16384), (16384, 1024)):
+        Q, dO, K, V = mk(nq), mk(nq), mk(nkv), mk(nkv)
+        o = a2d.partial_fwd(Q, K, V, 0, 0, False, scale)
+        O, lse = a2d.fix([o[0]], [o[1]], [o[2]])
+        d = a2d.tile_desc(Q, K, 0, 0, False, scale)
+        ws = torch.empty(a2d.workspace_bytes(d, a2d.OP_PARTIAL_BWD_DS), dtype=torch.uint8, device="cuda")
+        g3 = a2d.partial_bwd(Q, K, V, O, dO, lse, 0, 0, False, scale, workspace=ws, ds_handover=True)
+        t_f = _timeit(torch, lambda: a2d.partial_fwd(Q, K, V, 0, 0, False, scale, out=o))
+        t_b = _timeit(torch, lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, 0, 0, False, scale, out=g3, workspace=ws,
+                                                     ds_handover=True), 5)
+        t_r = _timeit(torch, lambda: a2d.partial_bwd(Q, K, V, O, dO, lse, 0, 0, False, scale, out=g3, workspace=ws), 5)
+        base = float(heads) * nq * nkv * H
+        big = heads * ((nq + 255) // 256) >= 256
+        out["cases"].append({"nq": nq, "nkv": nkv, "fwd_ms": round(t_f, 4), "fwd_tflops": round(4 * base / t_f / 1e9, 1),
+                             "bwd_ds_ms": round(t_b, 4), "bwd_ds_tflops": round(10 * base / t_b / 1e9, 1),
+                             "bwd_recompute_ms": round(t_r, 4), "bwd_recompute_tflops": round(10 * base / t_r / 1e9, 1),
+                             "fwd_wg": 256 if big else 128, "dq_wg": 256 if big else 128,
+                             "dkdv_wgs": heads * ((nkv + 127) // 128)})
+        del Q, dO, K, V, o, O, lse, ws, g3
+    return out
+
+
+def small_tiles(a2d, synth):
+    """The c2 workload (2048 x 2048 tiles, 16 heads: too few workgroups to fill 256 compute units with
+    256-row blocks) as a whole eager step with nothing between the calls, beside its replay from a
+    HIP graph: what launch overhead costs on tiles this small."""
+    import torch
+    w = synth.WORKLOADS["c2"]
+    T, G, H = w.tile, w.grid, w.hdim
+    scale = 1.0 / math.sqrt(H)
+    dev = lambda t: t.to("cuda")
+    Q, dO, K, V = dev(synth.q_block(w, 0)), dev(synth.do_block(w, 0)), dev(synth.k_block(w, 0)), dev(synth.v_block(w, 0))
+    f32 = dict(dtype=torch.float32, device="cuda")
+    parts = [a2d.partial_fwd(Q, K, V, 0, 0, False, scale) for _ in range(G)]
+    O, lse = a2d.fix([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts])
+    ws = torch.empty(a2d.workspace_bytes(a2d.tile_desc(Q, K, 0, 0, False, scale), a2d.OP_PARTIAL_BWD_DS),
+                     dtype=torch.uint8, device="cuda")
+    gq, gk, gv = ([torch.randn(w.heads, T, H, **f32) for _ in range(G)] for _ in range(3))
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+
+    def step():
+        a2d.partial_fwd(Q, K, V, 0, 0, False, scale, out=parts[0])
+        a2d.fix([p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts], out=(O, lse))
+        a2d.partial_bwd(Q, K, V, O, dO, lse, 0, 0, False, scale, out=(gq[0], gk[0], gv[0]), workspace=ws, ds_handover=True)
+        a2d.fix_bwd(gq, out=dQ); a2d.fix_bwd(gk, out=dK); a2d.fix_bwd(gv, out=dV)
+
+    def wall(fn, n=200):
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            t = (time.perf_counter() - t0) * 1e3 / n
+            best = t if best is None or t < best else best
+        return best
+
+    eager = wall(step)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    replay = wall(graph.replay)
+    fl = 14.0 * w.heads * T * T * H
+    return {"workload": "c2: non-causal tile %dx%dxH%d, %d heads, fwd + fix (k=%d) + bwd + 3 fix_bwd" % (T, T, H, w.heads, G),
+            "eager_ms": round(eager, 4), "eager_tflops": round(fl / eager / 1e9, 1),
+            "graph_ms": round(replay, 4), "graph_tflops": round(fl / replay / 1e9, 1),
+            "eager_over_graph": round(eager / replay, 3)}
 
 
 def grid_emulation(synth):

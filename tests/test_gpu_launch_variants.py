@@ -218,3 +218,51 @@ def test_strided_inputs_eight_wavefront_kernels(a2d):
         torch.cuda.synchronize()
         for x, y in zip(g3, r3):
             assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("name", ["c3", "c5"])
+def test_partial_formats_accuracy_side_by_side(a2d, name):
+    """The two partial formats at full size, merged over all sqrt(P) partials of a query block and
+    compared with the oracle on sampled rows: the fp32 unnormalised triple (N, m, l) merged by
+    a2d_fix, and the normalised pair (O' in bf16, lse') merged by a2d_fix_norm (footnote of
+    Sec. 3.2).  Both merges write fp32 here, so that the figures show the formats themselves and not
+    the final rounding of O.  Prints max-abs and relative-Frobenius errors side by side (the numbers
+    quoted in the design notes) and holds both to the bf16 bar."""
+    from helpers import max_abs, rel_fro
+    w = synth.WORKLOADS[name]
+    T, scale, G = w.tile, 1.0 / math.sqrt(w.hdim), w.grid
+    r = G - 1 if w.causal else 0
+    Qr = synth.q_block(w, r)
+    Qd = dev(Qr)
+    step = max(1, T // 96)
+    rows = np.array(sorted(set(list(range(0, T, step)) + [T - 1])))
+    hs = [0, w.heads // 2 - 1 if w.heads > 2 else w.heads - 1]
+    trip, norm, ref = [], [], []
+    for c in range(G):
+        Kc, Vc = synth.k_block(w, c), synth.v_block(w, c)
+        trip.append(a2d.partial_fwd(Qd, dev(Kc), dev(Vc), r * T, c * T, w.causal, scale))
+        norm.append(a2d.partial_fwd_norm(Qd, dev(Kc), dev(Vc), r * T, c * T, w.causal, scale))
+        if w.causal and c == r:
+            # the diagonal block needs the rows' own offsets: one row at a time
+            N = np.empty((len(hs), len(rows), w.hdim)); m = np.empty((len(hs), len(rows))); l = np.empty((len(hs), len(rows)))
+            for i, row in enumerate(rows):
+                a, b, c_ = oracle.partial_fwd(np64(Qr[hs][:, row:row + 1]), np64(Kc[hs]), np64(Vc[hs]), r * T + row, c * T,
+                                              True, scale)
+                N[:, i], m[:, i], l[:, i] = a[:, 0], b[:, 0], c_[:, 0]
+            ref.append((N, m, l))
+        else:
+            ref.append(oracle.partial_fwd(np64(Qr[hs][:, rows]), np64(Kc[hs]), np64(Vc[hs]), 0, 0, False, scale))
+    O_t, lse_t = a2d.fix([p[0] for p in trip], [p[1] for p in trip], [p[2] for p in trip], torch.float32)
+    O_n, lse_n = a2d.fix_norm([p[0] for p in norm], [p[1] for p in norm], torch.float32)
+    torch.cuda.synchronize()
+    Or, lr = oracle.fix([t[0] for t in ref], [t[1] for t in ref], [t[2] for t in ref])
+    print("\n%s: %d partials, %d sampled rows of heads %s, merged O in fp32" % (name, G, len(rows), hs))
+    print("%-34s %12s %12s %12s" % ("partial format", "max|dO|", "relFro(O)", "max|dlse|"))
+    res = {}
+    for tag, O, lse in (("fp32 triple (N, m, l) + a2d_fix", O_t, lse_t), ("bf16 O' + lse' + a2d_fix_norm", O_n, lse_n)):
+        eo, _ = max_abs(np64(O[hs][:, rows]), Or)
+        el, _ = max_abs(np64(lse[hs][:, rows]), lr)
+        rf = rel_fro(np64(O[hs][:, rows]), Or)
+        res[tag] = (eo, rf, el)
+        print("%-34s %12.3e %12.3e %12.3e" % (tag, eo, rf, el), flush=True)
+        assert eo <= 2e-2 and el <= 2e-2 and rf <= 1.5e-2, (name, tag, eo, rf, el)
