@@ -44,7 +44,15 @@ PASSES = {
     "util2": ["--pmc", "SQ_VALU_MFMA_BUSY_CYCLES", "SQ_VALU_MFMA_COEXEC_CYCLES", "SQ_ACTIVE_INST_VALU",
               "SQ_ACTIVE_INST_LDS", "SQ_WAIT_INST_LDS", "SQ_WAIT_INST_ANY", "SQ_WAVE_CYCLES", "GRBM_GUI_ACTIVE"],
 }
-BENCH_STEPS = {"kt": ("10", "3"), "fetch": ("2", "1"), "write": ("2", "1"), "util1": ("2", "1"), "util2": ("2", "1")}
+# optional passes (collect --memory-path): where vector-memory instructions wait
+MEMORY_PASSES = {
+    "vmem": ["--pmc", "SQ_INSTS_VMEM_WR", "SQ_INST_CYCLES_VMEM_WR", "SQ_VMEM_WR_TA_DATA_FIFO_FULL",
+             "SQ_VMEM_TA_ADDR_FIFO_FULL", "SQ_INSTS_VMEM_RD", "SQ_INST_CYCLES_VMEM_RD", "SQ_WAVE_CYCLES", "GRBM_GUI_ACTIVE"],
+    "tc": ["--pmc", "TCP_TCC_WRITE_REQ_LATENCY_sum", "TCP_TCC_WRITE_REQ_sum", "TCP_PENDING_STALL_CYCLES_sum",
+           "TCC_EA0_WRREQ_STALL_sum", "TCC_EA0_WRREQ_sum", "TCC_TOO_MANY_EA_WRREQS_STALL_sum", "GRBM_GUI_ACTIVE"],
+}
+BENCH_STEPS = {"kt": ("10", "3"), "fetch": ("2", "1"), "write": ("2", "1"), "util1": ("2", "1"), "util2": ("2", "1"),
+               "vmem": ("2", "1"), "tc": ("2", "1")}
 
 
 def source_hash():
@@ -68,7 +76,7 @@ def git_head():
 
 def pass_command(workload, name, out_dir, extra):
     steps, warm = BENCH_STEPS[name]
-    cmd = ["rocprofv3"] + PASSES[name] + ["--output-format", "csv", "-d", out_dir, "-o", "bench", "--",
+    cmd = ["rocprofv3"] + (PASSES.get(name) or MEMORY_PASSES[name]) + ["--output-format", "csv", "-d", out_dir, "-o", "bench", "--",
                                           "python3", "bench.py", "--workload", workload, "--steps", steps,
                                           "--warmup", warm, "--no-cpu-baseline", "--no-extras", "--copy-probe",
                                           "--launch-log", os.path.join(out_dir, "launches.json")] + list(extra)
@@ -78,7 +86,7 @@ def pass_command(workload, name, out_dir, extra):
 def collect(args):
     os.makedirs(args.dir, exist_ok=True)
     env = dict(os.environ, TMPDIR="/tmp")
-    for name in PASSES:
+    for name in list(PASSES) + (list(MEMORY_PASSES) if args.memory_path else []):
         out_dir = os.path.join(args.dir, name)
         os.makedirs(out_dir, exist_ok=True)
         cmd = pass_command(args.workload, name, out_dir, args.bench_args.split())
@@ -265,7 +273,25 @@ def tables(args):
             100 * g(m2, "SQ_WAIT_INST_LDS") / g(m2, "SQ_WAVE_CYCLES") if g(m2, "SQ_WAVE_CYCLES") else 0.0,
             512 * g(m1, "SQ_INSTS_VALU_MFMA_MOPS_BF16") / 1e12))
     open(os.path.join(args.out, "%s_utilisation.txt" % name), "w").write("\n".join(out) + "\n")
-    for n in ("kernel_trace", "hbm_traffic", "utilisation"):
+    shown = ["kernel_trace", "hbm_traffic", "utilisation"]
+    # ---- optional: the vector-memory path (raw counter means per launch)
+    if os.path.isdir(os.path.join(args.dir, "vmem")) and os.path.isdir(os.path.join(args.dir, "tc")):
+        mm = {}
+        for pname in MEMORY_PASSES:
+            for ctr, rws in counter_rows(os.path.join(args.dir, pname)).items():
+                if ctr != "GRBM_GUI_ACTIVE" or pname == "vmem":
+                    mm[ctr] = mean_of(rws)
+        cols = [c for c in mm if c != "GRBM_GUI_ACTIVE"]
+        out = ["Vector-memory path per launch from rocprofv3 PMC counters over bench.py (raw counter values, mean per launch;"] + \
+              ["SQ_* summed over the chip's SIMDs / wavefronts, TCP_* / TCC_* over their instances; cycles = GRBM_GUI_ACTIVE / 8)"] + head + \
+              ["commands:", cmd("vmem"), cmd("tc"), ""]
+        out.append("%-18s %-20s %12s " % ("call", "kernel", "cycles") + " ".join("%14s" % c.replace("SQ_", "").replace("_sum", "")[:14] for c in cols))
+        for key in mm.get("GRBM_GUI_ACTIVE", {}):
+            out.append("%-18s %-20s %12.0f " % (key[0], key[1], mm["GRBM_GUI_ACTIVE"][key] / 8.0) +
+                       " ".join("%14.4g" % mm[c].get(key, float("nan")) for c in cols))
+        open(os.path.join(args.out, "%s_memory_path.txt" % name), "w").write("\n".join(out) + "\n")
+        shown.append("memory_path")
+    for n in shown:
         print(open(os.path.join(args.out, "%s_%s.txt" % (name, n))).read())
 
 
@@ -297,6 +323,8 @@ def main():
             p.add_argument("--name", default=None, help="prefix of the files written (default: the workload; "
                                                         "bench.py --recompute-bwd reads <workload>_recompute)")
         else:
+            p.add_argument("--memory-path", action="store_true", help="two more passes: vector-memory instruction and "
+                                                                      "write-path counters")
             p.add_argument("--bench-args", default="", help="further bench.py flags for every pass, as one string "
                                                             "(e.g. --bench-args=--recompute-bwd)")
     args = ap.parse_args()
