@@ -383,8 +383,12 @@ def main():
     def mfma_ceiling():
         tf_r, mhz_r = a2d.mfma_ceiling(20000, True)
         tf_c, mhz_c = a2d.mfma_ceiling(20000, False)
+        tf_m, mhz_m = a2d.forward_mix_ceiling(6000)
         return {"random_operands": {"tflops": round(tf_r, 1), "shader_mhz": round(mhz_r)},
                 "constant_operands": {"tflops": round(tf_c, 1), "shader_mhz": round(mhz_c)},
+                "forward_loop_model": {"tflops": round(tf_m, 1), "shader_mhz": round(mhz_m),
+                                       "what": "MFMA + one LDS fragment + softmax arithmetic per MFMA, random operands, "
+                                               "nothing else of the kernel"},
                 "unit": "TFLOP/s", "kind": "MFMA-only probe, register operands"}
 
     if not args.no_gathered:

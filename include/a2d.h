@@ -368,6 +368,17 @@ a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t sc
                             double* tflops, double* shader_mhz);
 
 /*
+ * Diagnostic like a2d_mfma_ceiling, one step closer to the forward tile kernel: the same MFMAs on
+ * pseudo-random operands, but every MFMA takes a fresh A fragment from LDS and is followed by the
+ * softmax arithmetic of one score per lane (fma, exp2, max, add), two wavefronts per SIMD - and
+ * nothing else of the kernel (no global traffic, barriers, masks, prologue or epilogue).  What it
+ * sustains is what this loop structure can reach on the chip.  Arguments and results as for
+ * a2d_mfma_ceiling (same scratch size); synchronous.
+ */
+a2d_status a2d_forward_mix_ceiling(int iters, void* scratch, size_t scratch_bytes, double* tflops,
+                                   double* shader_mhz);
+
+/*
  * Debugging aid, not part of the method: on != 0 routes every tile call of the process to the
  * fp32 vector-ALU kernels (also for bf16 inputs), 0 back to the default choice.  The initial
  * value is 1 when A2D_FORCE_GENERIC=1 is in the environment at the first tile call, else 0.

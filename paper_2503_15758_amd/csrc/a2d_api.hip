@@ -621,9 +621,10 @@ size_t a2d_mfma_ceiling_scratch_bytes(void) {
   return (size_t)4 * cus * a2d::mfma_probe_threads() * sizeof(float) + 16;
 }
 
-a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t scratch_bytes,
-                            double* tflops, double* shader_mhz) {
-  const char* who = "a2d_mfma_ceiling";
+namespace {
+// runs one of the two probes twice (the first run settles the clocks) and converts its counters
+a2d_status run_probe(const char* who, int iters, int mode, void* scratch, size_t scratch_bytes, double* tflops,
+                     double* shader_mhz) {
   if (iters < 1 || iters > (1 << 22)) return fail(A2D_ERR_INVALID_ARG, "%s: iters=%d outside 1..2^22", who, iters);
   if (!tflops || !shader_mhz) return fail(A2D_ERR_INVALID_ARG, "%s: result pointer is NULL", who);
   A2D_TRY(check_ptr(scratch, who, "scratch"));
@@ -631,15 +632,21 @@ a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t sc
   if (need == 0) return fail(A2D_ERR_HIP, "%s: cannot query the device", who);
   if (scratch_bytes < need)
     return fail(A2D_ERR_WORKSPACE, "%s: scratch of %zu bytes, %zu needed", who, scratch_bytes, need);
-  const int blocks = (int)((need - 16) / (a2d::mfma_probe_threads() * sizeof(float)));
+  // MFMA-only probe: four workgroups per compute unit; forward-mix model: one (64 KiB of LDS each)
+  const int all = (int)((need - 16) / (a2d::mfma_probe_threads() * sizeof(float)));
+  const int blocks = mode == 2 ? all / 4 : all;
+  float* sc = static_cast<float*>(scratch);
+  auto launch = [&]() {
+    return mode == 2 ? a2d::launch_mix_probe(blocks, iters, sc, nullptr)
+                     : a2d::launch_mfma_probe(blocks, iters, mode, sc, nullptr);
+  };
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
     return fail(A2D_ERR_HIP, "%s: hipEventCreate failed", who);
-  float* sc = static_cast<float*>(scratch);
-  hipError_t e = a2d::launch_mfma_probe(blocks, iters, random_data, sc, nullptr);   // warm-up, clocks settle
+  hipError_t e = launch();   // warm-up, clocks settle
   if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
   if (e == hipSuccess) e = hipEventRecord(e0, nullptr);
-  if (e == hipSuccess) e = a2d::launch_mfma_probe(blocks, iters, random_data, sc, nullptr);
+  if (e == hipSuccess) e = launch();
   if (e == hipSuccess) e = hipEventRecord(e1, nullptr);
   if (e == hipSuccess) e = hipEventSynchronize(e1);
   float ms = 0.f;
@@ -656,6 +663,17 @@ a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t sc
   *tflops = flop / (ms * 1e-3) / 1e12;
   *shader_mhz = clocks[1] ? (double)clocks[0] / ((double)clocks[1] / 100.0) : 0.0;   // 100 MHz wall counter
   return A2D_OK;
+}
+}  // namespace
+
+a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t scratch_bytes,
+                            double* tflops, double* shader_mhz) {
+  return run_probe("a2d_mfma_ceiling", iters, random_data ? 1 : 0, scratch, scratch_bytes, tflops, shader_mhz);
+}
+
+a2d_status a2d_forward_mix_ceiling(int iters, void* scratch, size_t scratch_bytes, double* tflops,
+                                   double* shader_mhz) {
+  return run_probe("a2d_forward_mix_ceiling", iters, 2, scratch, scratch_bytes, tflops, shader_mhz);
 }
 
 void a2d_debug_force_generic(int on) { a2d::set_force_generic(on != 0); }

@@ -54,6 +54,69 @@ __global__ __launch_bounds__(PROBE_THREADS) void mfma_probe_kernel(float* __rest
   if (tid == 0 && blockIdx.x == 0) { clocks[0] = c1 - c0; clocks[1] = w1 - w0; }
 }
 
+// Model of the forward tile kernel's inner loop with everything but its three pipes taken away: per
+// MFMA one fresh 1 KiB A fragment from LDS (128-bit reads, the K tile's row stride) and the softmax
+// arithmetic of one score per lane (fma, exp2, max, add, plus a conversion every other one), finely
+// interleaved, two wavefronts per SIMD, pseudo-random operands; no global traffic, no barriers, no
+// masks, no prologue or epilogue.  What it sustains is what this loop STRUCTURE can reach on the
+// chip (it is power limited like the MFMA-only probe), a yardstick beside the data-sheet peak.
+constexpr int MIX_LDS_BYTES = 65536;
+__global__ __launch_bounds__(PROBE_THREADS) void mix_probe_kernel(float* __restrict__ out, int iters,
+                                                                  unsigned long long* __restrict__ clocks) {
+  extern __shared__ __attribute__((aligned(16))) char mix_lds[];
+  const unsigned base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)mix_lds;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // 64 KiB of pseudo-random bf16 of unit scale
+  for (int i = tid; i < MIX_LDS_BYTES / 2; i += PROBE_THREADS) {
+    unsigned h = (blockIdx.x * 32768u + i + 1) * 2654435761u;
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    reinterpret_cast<unsigned short*>(mix_lds)[i] = (unsigned short)((h & 0x807Fu) | ((125u + ((h >> 9) & 3u)) << 7));
+  }
+  __syncthreads();
+  bf16x8 q[8], a[4];
+#pragma unroll
+  for (int f = 0; f < 8; ++f) q[f] = lds_load_b128(base + ((lane * 16 + f * 1024 + (tid >> 6) * 8192) & (MIX_LDS_BYTES - 1)));
+  f32x16 acc[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) acc[t] = zero16();
+  float sv[16], mx = -1e30f, sum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) sv[r] = (float)(lane + r) * 0.01f;
+  // fragment reads like the K tile's: row (lane & 31) of 272 bytes, 16-byte half (lane >> 5); every
+  // address below stays under 8448 + 32767 + 224 + 16 < 64 KiB
+  const unsigned rd = base + (lane & 31) * 272 + (lane >> 5) * 16;
+#pragma unroll
+  for (int f = 0; f < 4; ++f) a[f] = lds_load_b128(rd + f * 32);
+  const unsigned long long c0 = __builtin_readcyclecounter();
+  const unsigned long long w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int x = 0; x < PROBE_MFMA_PER_ITER; ++x) {
+      acc[x & 3] = mma(a[x & 3], q[x & 7], acc[x & 3]);
+      a[x & 3] = lds_load_b128(rd + ((x * 32 + it * 8704) & 0x7FFF) + (x & 7) * 32);
+      const float s = sv[x];
+      mx = fmaxf(mx, s);
+      const float p = fast_exp2(fmaf(s, 0.127f, -3.0f));
+      sum += p;
+      sv[x] = p * 1.001f + 0.5f;                  // keeps the chain alive and bounded
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA,
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read,
+      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);   // five vector-ALU instructions
+    }
+  }
+  const unsigned long long c1 = __builtin_readcyclecounter();
+  const unsigned long long w1 = wall_clock64();
+  float r = sum + mx;
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) r += acc[t][e];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) r += sv[e];
+  out[blockIdx.x * PROBE_THREADS + tid] = r;
+  if (tid == 0 && blockIdx.x == 0) { clocks[0] = c1 - c0; clocks[1] = w1 - w0; }
+}
+
 // Plain copy: every thread moves 16-byte pieces one grid-sized stride apart, four loads in flight.
 __global__ __launch_bounds__(256) void copy_probe_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
                                                          size_t n16) {
@@ -87,6 +150,15 @@ hipError_t launch_copy_probe(void* dst, const void* src, size_t n16, hipStream_t
 hipError_t launch_mfma_probe(int blocks, int iters, int random_data, float* scratch, hipStream_t s) {
   unsigned long long* clocks = reinterpret_cast<unsigned long long*>(scratch + (size_t)blocks * PROBE_THREADS);
   hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(PROBE_THREADS), 0, s, scratch, iters, random_data, clocks);
+  return hipGetLastError();
+}
+
+// one workgroup per compute unit (64 KiB of LDS each); scratch as for launch_mfma_probe
+hipError_t launch_mix_probe(int blocks, int iters, float* scratch, hipStream_t s) {
+  hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(mix_probe_kernel), MIX_LDS_BYTES);
+  if (e != hipSuccess) return e;
+  unsigned long long* clocks = reinterpret_cast<unsigned long long*>(scratch + (size_t)blocks * PROBE_THREADS);
+  hipLaunchKernelGGL(mix_probe_kernel, dim3(blocks), dim3(PROBE_THREADS), MIX_LDS_BYTES, s, scratch, iters, clocks);
   return hipGetLastError();
 }
 

@@ -483,6 +483,17 @@ def test_mfma_ceiling_probe_runs(a2d):
     """The diagnostic MFMA-only probe returns a plausible rate and clock, and rejects a short scratch."""
     tf, mhz = a2d.mfma_ceiling(2000, True)
     assert 100.0 < tf < 20000.0 and 300.0 < mhz < 4000.0
+    tf_m, mhz_m = a2d.forward_mix_ceiling(500)          # the forward loop's model: below the MFMA-only rate
+    assert 100.0 < tf_m < 1.05 * max(tf, a2d.mfma_ceiling(2000, False)[0]) and 300.0 < mhz_m < 4000.0
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    a2d.copy_probe(dst, src)                            # the plain copy kernel copies
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    tail = torch.zeros(1000 * 4 + 4, dtype=torch.int32, device="cuda")   # a size that is not a multiple of the stride
+    a2d.copy_probe(tail, src[:tail.numel()].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(tail, src[:tail.numel()])
     import ctypes
     scratch = torch.empty(1024, dtype=torch.uint8, device="cuda")
     t, m = ctypes.c_double(), ctypes.c_double()
