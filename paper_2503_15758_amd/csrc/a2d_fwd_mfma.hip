@@ -138,23 +138,32 @@ __device__ __forceinline__ void fwd_block(FwdState<HD>& st, const bf16x8 (&qf)[H
   });
 }
 
-// WAVES wavefronts (32 query rows each) per workgroup: 8 fill a compute unit with one workgroup;
-// 4 (two workgroups per compute unit) are used when there are too few 256-row blocks to give
-// every compute unit one.
+// WAVES wavefronts per workgroup, in KL key lanes of WAVES / KL wavefronts (32 query rows each):
+//   <8, 1>  256 rows: one workgroup fills a compute unit;
+//   <4, 1>  128 rows, two workgroups per compute unit: when there are too few 256-row blocks to
+//           give every compute unit one;
+//   <8, 2>  128 rows walked by two key lanes: when even the 128-row blocks come to at most one per
+//           compute unit, so that a SIMD still holds two wavefronts.  The lanes take alternate key
+//           blocks of the walk, each staging its own tiles into its own pair of LDS buffers, and
+//           their (N, m, l) are merged through LDS at the end exactly as two partials of one
+//           query block are (Alg. 2).
 // HR: head size = row length in memory (80, 96 or 128); the LDS tiles and fragments are laid out
 // for the padded head size HD = padded_head(HR) (96 or 128).
-template <int WAVES, int HR>
+template <int WAVES, int HR, int KL>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
     a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, float* __restrict__ O_part, float* __restrict__ m_out,
     float* __restrict__ l_out) {
-  constexpr int BM = 32 * WAVES;          // query rows per workgroup
-  constexpr int kThreads = 64 * WAVES;
+  constexpr int RW = WAVES / KL;          // wavefronts of one key lane
+  constexpr int BM = 32 * RW;             // query rows per workgroup
+  constexpr int kThreads = 64 * RW;       // threads of one key lane (they stage its tiles)
   constexpr int HD = padded_head(HR), H = HR;
   constexpr int KS = HD / 16, CT = HD / 32, KLD = kld(HD), K_BYTES = BN * KLD, BUF_BYTES = buf_bytes(HD);
   constexpr int kLdsBytes = lds_bytes(HD);
-  extern __shared__ __attribute__((aligned(16))) char lds[];
-  // [buf]{ K tile (BN x KLD), V tile (BN x VLD) }
+  extern __shared__ __attribute__((aligned(16))) char lds_all[];
+  // per key lane: [buf]{ K tile (BN x KLD), V tile (BN x VLD) }
+  const int kl = KL == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x / kThreads);   // key lane of this wavefront
+  char* const lds = lds_all + kl * kLdsBytes;
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
   const int nqb = (d.nq + BM - 1) / BM;
@@ -168,7 +177,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   blk = g.by_size ? blk / per_unit : blk % nqb;
   // heavy (late) query blocks first: under a causal mask they walk more key blocks
   const int q0 = (nqb - 1 - blk) * BM;
-  const int tid = threadIdx.x;
+  const int tid = (int)threadIdx.x - kl * kThreads;     // within the key lane
   const int wave = tid >> 6, lane = tid & 63;
   const int half = lane >> 5, l32 = lane & 31;
   Q += (int64_t)head * d.lq.head;
@@ -194,6 +203,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   const float c = d.scale * kLog2e;
   float m_in = -INFINITY;
   if (g.acc) {
+    // (key lane 0 continues the stored partial; the barriers are the whole workgroup's)
     // Continue from the (N, m, l) already in the output buffers: N into the accumulators (same
     // element mapping as the epilogue's stores), m as the exponent reference, l into one of the two
     // lanes of the row.  A lane's share of N is 16 scattered 16-byte pieces of its row, so the
@@ -201,7 +211,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
     // coalesced loads into a private, padded LDS area and the owning lanes pick their pieces.
     constexpr int ALD = HD * 4 + 16;                          // padded row stride, bytes
     static_assert(16 * ALD * (kThreads / 64) <= kLdsBytes, "accumulator staging must fit the tile buffers");
-    char* area = lds + wave * 16 * ALD;
+    char* area = lds_all + wave * 16 * ALD;
     const int64_t wrow0 = (int64_t)head * d.nq + q0 + wave * 32;   // first row of the wavefront
     const int64_t last_row = (int64_t)head * d.nq + d.nq - 1;
     const bool col_ok = 4 * (lane & 31) < H;                 // this lane's 16-byte piece exists in the row
@@ -212,16 +222,16 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
       for (int i = 0; i < 8; ++i) {                          // two whole rows per load instruction
         const int64_t r = wrow0 + 16 * pass + 2 * i + (lane >> 5);
         t[i] = u32x4{0, 0, 0, 0};
-        if (col_ok)
+        if (col_ok && kl == 0)
           t[i] = *reinterpret_cast<const u32x4*>(O_part + (r < last_row ? r : last_row) * H + 4 * (lane & 31));
       }
-      if (4 * (lane & 31) < HD) {
+      if (4 * (lane & 31) < HD && kl == 0) {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
           *reinterpret_cast<u32x4*>(area + (2 * i + (lane >> 5)) * ALD + 16 * (lane & 31)) = t[i];
       }
       __syncthreads();
-      if ((l32 >> 4) == pass) {
+      if ((l32 >> 4) == pass && kl == 0) {
         const char* mine = area + (l32 & 15) * ALD + 16 * half;
 #pragma unroll
         for (int ht = 0; ht < CT; ++ht)
@@ -233,7 +243,9 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
       }
       __syncthreads();
     }
-    if (q_row < d.nq) {
+    if (kl != 0) {
+      // the other key lane starts from nothing
+    } else if (q_row < d.nq) {
       const int64_t row = (int64_t)head * d.nq + q_row;
       m_in = m_out[row];
       st.l_run = half == 0 ? l_out[row] : 0.f;
@@ -312,46 +324,91 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   const unsigned v_rd0 =
       lds_base + K_BYTES + (4 * (g16 >> 1) + (j16 >> 2)) * VLD + (16 * (g16 & 1) + 4 * (j16 & 3)) * 2;
 
-  // Walk over (sub-block, key block).  The sub-block table lives in kernel-argument memory, and
-  // scalar loads share a wait counter with the LDS reads in flight, so it is only touched when
-  // the walk moves to another sub-block; in between its values sit in registers.
-  int sb = 0, j = 0;                               // current sub-block and key block within it
-  while (sb < g.n && seg_blocks(sb) == 0) ++sb;    // first sub-block with visible keys
-  int nblk = 0, nx_start = 0, nx_rows = 0, nx_nblk = 0;   // blocks of sb; start / rows / blocks of the next block's sub-block
+  // Walk over the entries (sub-block, key block); key lane kl takes entries kl, kl + KL, ...  The
+  // sub-block table lives in kernel-argument memory, and scalar loads share a wait counter with the
+  // LDS reads in flight, so it is only touched when a walk moves to another sub-block; in between
+  // its values sit in registers.
+  // An entry is (sub-block sb, block j of its nblk); sb == g.n: past the end.
+  auto open_segment = [&](int s, int& sb, int& j, int& nblk) {   // first sub-block after s with visible keys
+    do { ++s; } while (s < g.n && seg_blocks(s) == 0);
+    sb = s; j = 0;
+    if (s < g.n) nblk = seg_blocks(s);
+  };
+  auto advance = [&](int& sb, int& j, int& nblk) {
+    if (sb < g.n && ++j >= nblk) open_segment(sb, sb, j, nblk);
+  };
+  int sb, j, nblk = 0;                             // this key lane's current entry
+  open_segment(-1, sb, j, nblk);
+  int lead_sb = sb, lead_j = j, lead_nblk = nblk;  // key lane 0's: every lane loops while it exists
+  if (KL > 1) {
+    for (int x = 0; x < kl; ++x) advance(sb, j, nblk);
+  }
+  int nx_start = 0, nx_rows = 0;                   // start / rows of the next entry's sub-block
   if (sb < g.n) {
     enter_segment(sb);
-    nblk = nx_nblk = seg_blocks(sb); nx_start = g.start[sb]; nx_rows = g.rows[sb];
-    load_tile(nx_start, nx_rows, 0);
+    nx_start = g.start[sb]; nx_rows = g.rows[sb];
+    load_tile(nx_start, nx_rows, j);
     store_tile(0);
   }
   __syncthreads();
 
   int boff = 0;
-  while (sb < g.n) {
-    int nsb = sb, nj = j + 1;
-    if (nj >= nblk) {                              // the next block opens another sub-block
-      nj = 0;
-      do { ++nsb; } while (nsb < g.n && seg_blocks(nsb) == 0);
-      if (nsb < g.n) { nx_start = g.start[nsb]; nx_rows = g.rows[nsb]; nx_nblk = seg_blocks(nsb); }
-    }
+  while ((KL == 1 ? sb : lead_sb) < g.n) {
+    int nsb = sb, nj = j, nnblk = nblk;
+#pragma unroll
+    for (int x = 0; x < KL; ++x) advance(nsb, nj, nnblk);
     const bool more = nsb < g.n;
+    if (more && nsb != sb) { nx_start = g.start[nsb]; nx_rows = g.rows[nsb]; }
     if (more) load_tile(nx_start, nx_rows, nj);
     const int k0 = j * BN;                         // local to the sub-block
-    if (k0 < nvis_wave) {
+    if ((KL == 1 || sb < g.n) && k0 < nvis_wave) {
       if (k0 + BN > nfull_wave) fwd_block<HD, true>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
       else fwd_block<HD, false>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
     }
     if (more) store_tile(BUF_BYTES - boff);
     __syncthreads();
-    if (more && nsb != sb) { enter_segment(nsb); nblk = nx_nblk; }
-    sb = nsb; j = nj;
+    if (more && nsb != sb) enter_segment(nsb);
+    if (KL > 1) {
+#pragma unroll
+      for (int x = 0; x < KL; ++x) advance(lead_sb, lead_j, lead_nblk);
+    }
+    sb = nsb; j = nj; nblk = nnblk;
     boff = BUF_BYTES - boff;
   }
 
   // ---- epilogue: bring N and l to the true row maximum, store N, m (scaled units), l
-  const float m_row = fmaxf(st.m_lane, __shfl_xor(st.m_lane, 32, 64));
-  const float f = (m_row == -INFINITY) ? 0.f : fast_exp2((st.m_ref - m_row) * c);
-  const float l_tot = (st.l_run + __shfl_xor(st.l_run, 32, 64)) * f;
+  float m_row = fmaxf(st.m_lane, __shfl_xor(st.m_lane, 32, 64));
+  float f = (m_row == -INFINITY) ? 0.f : fast_exp2((st.m_ref - m_row) * c);
+  float l_tot = (st.l_run + __shfl_xor(st.l_run, 32, 64)) * f;
+  if constexpr (KL == 2) {
+    // Key lane 1 hands its (N, m, l) to lane 0 through LDS (the tiles are no longer read: every
+    // wavefront has passed the walk's last barrier), which merges the two as Alg. 2 does.
+    // Layout: [row wavefront][value index][lane], one float each, so every access is conflict free.
+    constexpr int NV = CT * 16 + 2;
+    static_assert(RW * NV * 256 <= KL * kLdsBytes, "the exchange area must fit the tile buffers");
+    float* xch = reinterpret_cast<float*>(lds_all) + wave * NV * 64 + lane;
+    if (kl == 1) {
+#pragma unroll
+      for (int t = 0; t < CT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) xch[(16 * t + r) * 64] = st.o[t][r] * f;
+      xch[(CT * 16) * 64] = m_row;
+      xch[(CT * 16 + 1) * 64] = l_tot;
+    }
+    __syncthreads();
+    if (kl == 1) return;
+    const float m1 = xch[(CT * 16) * 64], l1 = xch[(CT * 16 + 1) * 64];
+    const float m_new = fmaxf(m_row, m1);
+    const float a0 = (m_row == -INFINITY) ? 0.f : f * fast_exp2((m_row - m_new) * c);
+    const float a1 = (m1 == -INFINITY) ? 0.f : fast_exp2((m1 - m_new) * c);
+#pragma unroll
+    for (int t = 0; t < CT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.o[t][r] = st.o[t][r] * a0 + xch[(16 * t + r) * 64] * a1;
+    l_tot = (m_row == -INFINITY ? 0.f : l_tot * fast_exp2((m_row - m_new) * c)) + l1 * a1;
+    m_row = m_new;
+    f = 1.f;
+  }
   // a lane's piece (column tile ht, group gq) covers columns 32 ht + 8 gq + 4 half + 0..3
   if (q_row < d.nq && g.norm) {
     // normalised partial: O' = N / l rounded to bf16, lse' = m + ln l (Sec. 3.2, footnote)
@@ -393,15 +450,15 @@ bool fwd_mfma_supported(const a2d_tile_desc& d) {
 }
 
 namespace {
-template <int WAVES, int HR>
+template <int WAVES, int HR, int KL>
 hipError_t fwd_launch(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K, const void* V,
                       float* O_part, float* m, float* l, hipStream_t s) {
-  constexpr int bytes = lds_bytes(padded_head(HR));
+  constexpr int bytes = KL * lds_bytes(padded_head(HR)), BM = 32 * WAVES / KL;
   if (ph == PREPARE)
-    return ensure_dynamic_lds(reinterpret_cast<const void*>(fwd_mfma_kernel<WAVES, HR>), bytes);
+    return ensure_dynamic_lds(reinterpret_cast<const void*>(fwd_mfma_kernel<WAVES, HR, KL>), bytes);
   const int per_unit = g.group / g.split;
-  dim3 grid(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + 32 * WAVES - 1) / (32 * WAVES)))), block(64 * WAVES);
-  A2D_LAUNCH((fwd_mfma_kernel<WAVES, HR>), grid, block, bytes, s, d, g, (const bf16_t*)Q,
+  dim3 grid(xcd_grid(d.heads / per_unit, per_unit * ((d.nq + BM - 1) / BM))), block(64 * WAVES);
+  A2D_LAUNCH((fwd_mfma_kernel<WAVES, HR, KL>), grid, block, bytes, s, d, g, (const bf16_t*)Q,
                      (const bf16_t*)K, (const bf16_t*)V, O_part, m, l);
   return hipGetLastError();
 }
@@ -409,13 +466,17 @@ hipError_t fwd_launch(Phase ph, const a2d_tile_desc& d, const SegList& g, const 
 
 hipError_t launch_fwd_mfma(Phase ph, const a2d_tile_desc& d, const SegList& g, const void* Q, const void* K,
                            const void* V, float* O_part, float* m, float* l, hipStream_t s) {
-  // eight wavefronts per workgroup unless that leaves compute units without a workgroup
+  // 256-row workgroups unless that leaves compute units without one; then 128-row workgroups, with
+  // two key lanes when at most one of those comes to a compute unit either
   int cus = 0;
   const hipError_t e = device_cus(&cus);
   if (e != hipSuccess) return e;
   const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
-#define A2D_FWD(HR) \
-  return big ? fwd_launch<8, HR>(ph, d, g, Q, K, V, O_part, m, l, s) : fwd_launch<4, HR>(ph, d, g, Q, K, V, O_part, m, l, s)
+  const bool lanes = !big && (int64_t)d.heads * ((d.nq + 127) / 128) <= cus;
+#define A2D_FWD(HR)                                                                      \
+  return big     ? fwd_launch<8, HR, 1>(ph, d, g, Q, K, V, O_part, m, l, s)              \
+         : lanes ? fwd_launch<8, HR, 2>(ph, d, g, Q, K, V, O_part, m, l, s)              \
+                 : fwd_launch<4, HR, 1>(ph, d, g, Q, K, V, O_part, m, l, s)
   if (d.hdim == 128) { A2D_FWD(128); }
   if (d.hdim == 96) { A2D_FWD(96); }
   if (d.hdim == 80) { A2D_FWD(80); }

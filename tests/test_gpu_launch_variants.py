@@ -1,14 +1,18 @@
-"""GPU parity at the launch shapes of the FULL-SIZE kernels, on sizes the oracle still finishes.
+"""GPU parity at every launch shape of the tile kernels, on sizes the oracle still finishes.
 
-The forward, dQ and dQ-from-dS kernels exist in two instantiations: workgroups of four wavefronts
-for tiles with few query blocks, and workgroups of eight wavefronts (256 query rows) once
-heads * ceil(nq / 256) reaches the number of compute units (256 on MI355X) - the one every
-paper-sized workload runs.  The small cases of test_gpu_parity.py all take the first.  The cases
-here have many heads and short, RAGGED tiles, so that they take the eight-wavefront kernels (and
-their by-size workgroup order under a causal mask, with head counts that leave a partial last
-chunk of heads per XCD) for every head size, in every form of the calls: plain, accumulating,
-normalised, gathered, grouped heads, both backward paths.  The oracle checks whole heads: the
-first, the last, and heads whose index is 1..6 modulo the 8 XCDs.
+The forward, dQ and dQ-from-dS kernels exist in several instantiations, chosen from the number of
+query blocks against the number of compute units (256 on MI355X):
+  * workgroups of eight wavefronts (256 query rows) once heads * ceil(nq / 256) reaches the number
+    of compute units - the one every paper-sized workload runs;
+  * workgroups of four wavefronts (128 rows) below that;
+  * for the forward kernel, when even heads * ceil(nq / 128) is at most the number of compute
+    units, 128-row workgroups of eight wavefronts in two key lanes whose partials are merged
+    inside the kernel (the small cases of test_gpu_parity.py all take this one).
+The cases here have many heads and short, RAGGED tiles, so that each regime is reached (with the
+by-size workgroup order under a causal mask, and head counts that leave a partial last chunk of
+heads per XCD) for every head size, in every form of the calls: plain, accumulating, normalised,
+gathered, grouped heads, both backward paths.  The oracle checks whole heads: the first, the last,
+and heads whose index is 1..6 modulo the 8 XCDs.
 """
 import math
 
@@ -80,11 +84,46 @@ def _fwd_close(got, ref, what):
         assert_close(Ng[ok], Nr[ok], BF, what + " N (per-row scaled)", rel=False, scale_rows=True)
 
 
+# between the two thresholds: 128-row workgroups of four wavefronts, two per compute unit
+CASES_FOUR = [
+    (30, 30, 1100, 700, 96, True, 200, 0),      # 150 blocks of 256 rows, 270 of 128
+    (36, 36, 1000, 400, 64, True, 300, 0),
+    (24, 24, 1400, 500, 128, True, 0, 700),     # the first rows see no key
+    (24, 6, 1400, 600, 80, False, 0, 0),        # grouped heads, no mask
+]
+
+# at most one 128-row block per compute unit: the forward kernel walks the keys in two lanes
+CASES_LANES = [
+    (8, 8, 700, 900, 128, True, 400, 0),        # diagonal through the tile: the lanes' shares differ
+    (12, 12, 300, 1000, 80, True, 900, 0),      # an odd number of visible key blocks for most workgroups
+    (16, 16, 130, 260, 64, False, 0, 0),        # a second, nearly empty query block per head
+    (4, 2, 1000, 330, 96, True, 0, 0),          # grouped heads; short rows whose second lane has no block
+    (3, 3, 200, 200, 128, True, 0, 150),        # most rows see nothing; the workgroup has at most one block
+]
+
+
 @pytest.mark.parametrize("case", CASES, ids=_ids)
 def test_eight_wavefront_kernels_every_call_form(a2d, case):
+    assert case[0] * ((case[2] + 255) // 256) >= CUS, "the case must take the eight-wavefront kernels"
+    _every_call_form(a2d, case, "8w")
+
+
+@pytest.mark.parametrize("case", CASES_FOUR, ids=_ids)
+def test_four_wavefront_kernels_every_call_form(a2d, case):
+    assert case[0] * ((case[2] + 255) // 256) < CUS < case[0] * ((case[2] + 127) // 128), \
+        "the case must take the four-wavefront kernels with one key lane"
+    _every_call_form(a2d, case, "4w")
+
+
+@pytest.mark.parametrize("case", CASES_LANES, ids=_ids)
+def test_two_key_lane_forward_every_call_form(a2d, case):
+    assert case[0] * ((case[2] + 127) // 128) <= CUS, "the case must take the forward kernel with two key lanes"
+    _every_call_form(a2d, case, "2 lanes")
+
+
+def _every_call_form(a2d, case, regime):
     heads, kvh, nq, nkv, H, causal, q_off, kv_off = case
-    assert heads * ((nq + 255) // 256) >= CUS, "the case must take the eight-wavefront kernels"
-    print("launch-variant case", case, flush=True)
+    print("launch-variant case", regime, case, flush=True)
     grp = heads // kvh
     scale = 1.0 / math.sqrt(H)
     Q = synth.normal((heads, nq, H), 97, 0, 1.0, "bf16")
@@ -101,7 +140,7 @@ def test_eight_wavefront_kernels_every_call_form(a2d, case):
     kh = [h // grp for h in hs]
     Qh, dOh = np64(Q[hs]), np64(dO[hs])
     Kh, Vh, K2h, V2h = np64(K[kh]), np64(V[kh]), np64(K2[kh]), np64(V2[kh])
-    what = "8w %s" % (case,)
+    what = "%s %s" % (regime, case)
     Qd, Kd, Vd, dOd = dev(Q), dev(K), dev(V), dev(dO)
 
     # ---- forward: plain, twice (bitwise), normalised
