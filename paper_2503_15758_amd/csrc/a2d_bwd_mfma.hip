@@ -665,18 +665,25 @@ __device__ __forceinline__ void dq_piece(DqCtx<HD>& cx, int key0) {
 // WAVES wavefronts (32 query rows each) per workgroup: 8 fill a compute unit with one workgroup;
 // 4 (two workgroups per compute unit) are used when there are too few 256-row blocks to give
 // every compute unit one.
+// KL key lanes of WAVES / KL wavefronts: with KL = 2 a 128-row workgroup of eight wavefronts walks
+// the key blocks in two lanes (alternate blocks, own tile buffers) whose dQ sums are added through
+// LDS at the end - for tiles with at most one 128-row block per compute unit, so that a SIMD still
+// holds two wavefronts.
 // HR: head size (80, 96 or 128), HD its padded size, as in the dK/dV kernel.
-template <int WAVES, int HR>
+template <int WAVES, int HR, int KL>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
     a2d_tile_desc d, SegList g, const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
     const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
     const float* __restrict__ delta, float* __restrict__ dQ) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
-  constexpr int DQ_ROWS = 32 * WAVES;      // query rows per workgroup
-  constexpr int DQ_THREADS = 64 * WAVES;
+  extern __shared__ __attribute__((aligned(1024))) char lds_all[];
+  constexpr int RW = WAVES / KL;           // wavefronts of one key lane
+  constexpr int DQ_ROWS = 32 * RW;         // query rows per workgroup
+  constexpr int DQ_THREADS = 64 * RW;      // threads of one key lane (they stage its tiles)
   constexpr int HD = padded_head(HR), H = HR;
   constexpr int KS = HD / 16, CT = HD / 32, VT_LD = vt_ld(HD), DQ_BUF = dq_buf(HD);
+  const int kl = KL == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x / DQ_THREADS);
+  char* const lds = lds_all + kl * (2 * DQ_BUF);
+  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
   const int nqb = (d.nq + DQ_ROWS - 1) / DQ_ROWS;
   // the query blocks of the query heads that share a key/value head go to one XCD (to g.split
   // XCDs, an equal share of the heads each, when that is what spreads the load evenly)
@@ -687,7 +694,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   const int head = unit * per_unit + (g.by_size ? blk % per_unit : blk / nqb), kvh = head / g.group;
   blk = g.by_size ? blk / per_unit : blk % nqb;
   const int q0 = (nqb - 1 - blk) * DQ_ROWS;            // heavy blocks first under a causal mask
-  const int tid = threadIdx.x;
+  const int tid = (int)threadIdx.x - kl * DQ_THREADS;  // within the key lane
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31;
   Q += (int64_t)head * d.lq.head;
@@ -783,36 +790,49 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
     }
   };
 
-  // Walk over (sub-block, key block).  The sub-block table lives in kernel-argument memory, and
-  // scalar loads share a wait counter with the LDS reads in flight, so it is only touched when
-  // the walk moves to another sub-block; in between its values sit in registers.
-  int sb = 0, j = 0;                               // current sub-block and key block within it
-  while (sb < g.n && seg_blocks(sb) == 0) ++sb;
-  int nblk = 0, nx_start = 0, nx_rows = 0, nx_nblk = 0;   // blocks of sb; start / rows / blocks of the next block's sub-block
+  // Walk over the entries (sub-block, key block); key lane kl takes entries kl, kl + KL, ...  The
+  // sub-block table lives in kernel-argument memory, and scalar loads share a wait counter with the
+  // LDS reads in flight, so it is only touched when a walk moves to another sub-block; in between
+  // its values sit in registers.  An entry is (sub-block sb, block j of its nblk); sb == g.n: past
+  // the end.
+  auto open_segment = [&](int s, int& sb, int& j, int& nblk) {   // first sub-block after s with visible keys
+    do { ++s; } while (s < g.n && seg_blocks(s) == 0);
+    sb = s; j = 0;
+    if (s < g.n) nblk = seg_blocks(s);
+  };
+  auto advance = [&](int& sb, int& j, int& nblk) {
+    if (sb < g.n && ++j >= nblk) open_segment(sb, sb, j, nblk);
+  };
+  int sb, j, nblk = 0;                             // this key lane's current entry
+  open_segment(-1, sb, j, nblk);
+  int lead_sb = sb, lead_j = j, lead_nblk = nblk;  // key lane 0's: every lane loops while it exists
+  if (KL > 1) {
+    for (int x = 0; x < kl; ++x) advance(sb, j, nblk);
+  }
+  int nx_start = 0, nx_rows = 0;                   // start / rows of the next entry's sub-block
   if (sb < g.n) {
     enter_segment(sb);
-    nblk = nx_nblk = seg_blocks(sb); nx_start = g.start[sb]; nx_rows = g.rows[sb];
-    load_half(nx_start, nx_rows, 0, 0); store_half(0, 0);
-    load_half(nx_start, nx_rows, 0, 1); store_half(0, 1);
+    nx_start = g.start[sb]; nx_rows = g.rows[sb];
+    load_half(nx_start, nx_rows, j, 0); store_half(0, 0);
+    load_half(nx_start, nx_rows, j, 1); store_half(0, 1);
   }
   __syncthreads();
 
   int buf = 0;
-  while (sb < g.n) {
-    int nsb = sb, nj = j + 1;
-    if (nj >= nblk) {                              // the next block opens another sub-block
-      nj = 0;
-      do { ++nsb; } while (nsb < g.n && seg_blocks(nsb) == 0);
-      if (nsb < g.n) { nx_start = g.start[nsb]; nx_rows = g.rows[nsb]; nx_nblk = seg_blocks(nsb); }
-    }
+  while ((KL == 1 ? sb : lead_sb) < g.n) {
+    int nsb = sb, nj = j, nnblk = nblk;
+#pragma unroll
+    for (int x = 0; x < KL; ++x) advance(nsb, nj, nnblk);
     const bool more = nsb < g.n;
+    if (more && nsb != sb) { nx_start = g.start[nsb]; nx_rows = g.rows[nsb]; }
+    const bool here = KL == 1 || sb < g.n;         // this lane has a block in this round
     const int k0 = j * BKS;                        // local to the sub-block
     if (more) load_half(nx_start, nx_rows, nj, 0);
-    if (k0 < nvis_wave) {
+    if (here && k0 < nvis_wave) {
       if (k0 + 32 > nfull_wave) dq_piece<0, true>(cx, k0); else dq_piece<0, false>(cx, k0);
     }
     if (more) { store_half(buf ^ 1, 0); load_half(nx_start, nx_rows, nj, 1); }
-    if (k0 + 32 < nvis_wave) {
+    if (here && k0 + 32 < nvis_wave) {
       if (k0 + 64 > nfull_wave) dq_piece<1, true>(cx, k0 + 32); else dq_piece<1, false>(cx, k0 + 32);
     }
     if (more) store_half(buf ^ 1, 1);
@@ -820,9 +840,31 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
     cx.ka.shift(tog);
     cx.vnat += tog;
     __syncthreads();
-    if (more && nsb != sb) { enter_segment(nsb); nblk = nx_nblk; }
-    sb = nsb; j = nj;
+    if (more && nsb != sb) enter_segment(nsb);
+    if (KL > 1) {
+#pragma unroll
+      for (int x = 0; x < KL; ++x) advance(lead_sb, lead_j, lead_nblk);
+    }
+    sb = nsb; j = nj; nblk = nnblk;
     buf ^= 1;
+  }
+  if constexpr (KL == 2) {
+    // lane 1 hands its sums to lane 0 through LDS (the tiles are no longer read: every wavefront
+    // has passed the walk's last barrier); layout [row wavefront][value][lane]: conflict free
+    static_assert(RW * CT * 16 * 256 <= KL * 2 * DQ_BUF, "the exchange area must fit the tile buffers");
+    float* xch = reinterpret_cast<float*>(lds_all) + wave * (CT * 16 * 64) + lane;
+    if (kl == 1) {
+#pragma unroll
+      for (int t = 0; t < CT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) xch[(16 * t + r) * 64] = cx.dq[t][r];
+    }
+    __syncthreads();
+    if (kl == 1) return;
+#pragma unroll
+    for (int t = 0; t < CT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) cx.dq[t][r] += xch[(16 * t + r) * 64];
   }
   if (q_ok) store_acc_t<CT>(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, d.scale, H, g.acc != 0);
 }
@@ -881,13 +923,20 @@ __device__ __forceinline__ void dsq_piece(DsqCtx<HD>& cx, const u32x4 (&ds)[4], 
   });
 }
 
-template <int WAVES, int HR>
+// KL key lanes of WAVES / KL wavefronts: with KL = 2 a 128-row workgroup of eight wavefronts walks
+// the key blocks in two lanes (alternate blocks, own K buffers) whose dQ sums are added through LDS
+// at the end - for tiles with at most one 128-row block per compute unit, so that a SIMD still
+// holds two wavefronts and twice the dS requests are in flight.
+template <int WAVES, int HR, int KL>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
     a2d_tile_desc d, SegList g, const bf16_t* __restrict__ K, const bf16_t* __restrict__ dS,
     float* __restrict__ dQ) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  extern __shared__ __attribute__((aligned(1024))) char lds_all[];
+  constexpr int RW = WAVES / KL;                       // wavefronts of one key lane
+  constexpr int DQ_ROWS = 32 * RW, DQ_THREADS = 64 * RW;   // rows of the workgroup, threads of one key lane
+  const int kl = KL == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x / DQ_THREADS);
+  char* const lds = lds_all + kl * (2 * DUAL64_BYTES);
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
-  constexpr int DQ_ROWS = 32 * WAVES, DQ_THREADS = 64 * WAVES;
   constexpr int HD = padded_head(HR), H = HR, CT = HD / 32;
   const int nqb = (d.nq + DQ_ROWS - 1) / DQ_ROWS;
   // placement as in bwd_dq_kernel (grouped heads: the query heads of a key/value head share an XCD)
@@ -898,7 +947,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
   const int head = unit * per_unit + (g.by_size ? blk % per_unit : blk / nqb), kvh = head / g.group;
   blk = g.by_size ? blk / per_unit : blk % nqb;
   const int q0 = (nqb - 1 - blk) * DQ_ROWS;            // heavy blocks first under a causal mask
-  const int tid = threadIdx.x;
+  const int tid = (int)threadIdx.x - kl * DQ_THREADS;  // within the key lane
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31;
   K += (int64_t)kvh * d.lk.head;
@@ -935,16 +984,21 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
   // Walk over the visible blocks, as global block numbers (start of the sub-block / 64 + block
   // inside it).  The fetch walker runs ahead of the compute walker; once it has run out it keeps
   // returning its last block (loads stay unconditional).
+  // (a key lane takes every KL-th block: each walker moves KL blocks per call, after kl at the start)
   int f_sb = -1, f_j = 0, f_nblk = 0, f_base = 0, f_id = 0;
-  auto fetch_next = [&]() {
+  auto fetch_one = [&]() {
     if (f_j + 1 < f_nblk) { ++f_j; f_id = f_base + f_j; return; }
     int s = f_sb + 1;
     while (s < g.n && seg_blocks(s) == 0) ++s;
     if (s < g.n) { f_sb = s; f_j = 0; f_nblk = seg_blocks(s); f_base = g.start[s] / BKS; f_id = f_base; }
   };
+  auto fetch_next = [&]() {
+#pragma unroll
+    for (int x = 0; x < KL; ++x) fetch_one();
+  };
   int c_sb = -1, c_j = 0, c_nblk = 0;              // compute walker: sub-block, block inside it
   int nvis_wave = 0, nfull_wave = 0;
-  auto compute_next = [&]() {
+  auto compute_one = [&]() {
     if (c_j + 1 < c_nblk) { ++c_j; return; }
     int s = c_sb + 1;
     while (s < g.n && seg_blocks(s) == 0) ++s;
@@ -956,6 +1010,10 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
     } else {
       nvis_wave = 0;                               // past the last block: nothing to compute
     }
+  };
+  auto compute_next = [&]() {
+#pragma unroll
+    for (int x = 0; x < KL; ++x) compute_one();
   };
 
   // ---- K staging: thread moves chunk (tid & 15) of rows (tid >> 4) + ST_ROWS p of the 64-row tile
@@ -995,10 +1053,15 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
   };
 
   if (count == 0) {                                // no visible key: dQ share is zero
-    if (q_ok && !g.acc) store_acc_t<CT>(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, 0.f, H, false);
+    if (q_ok && !g.acc && kl == 0) store_acc_t<CT>(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, 0.f, H, false);
     return;
   }
-  fetch_next();                                    // block 0
+  if (KL > 1) {
+    for (int x = 0; x < kl; ++x) { fetch_one(); compute_one(); }
+    fetch_one();                                   // this lane's first block (the last one, if it has none)
+  } else {
+    fetch_next();                                  // block 0
+  }
   load_k(f_id);
   load_ds(f_id, std::integral_constant<int, 0>{});
   store_k(0);
@@ -1008,7 +1071,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
     idq[decltype(S)::value - 1] = f_id;
     load_ds(f_id, S);
   });
-  compute_next();
+  if (KL > 1) compute_one(); else compute_next();
   __syncthreads();
 
   int buf = 0;
@@ -1036,8 +1099,26 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_ds_kernel(
     compute_next();
     __syncthreads();
   };
-  for (int t = 0; t < count; t += DSQ_SETS)        // blocks past the last find nvis_wave = 0
+  for (int t = 0; t < (count + KL - 1) / KL; t += DSQ_SETS)   // blocks past the last find nvis_wave = 0
     static_for<0, DSQ_SETS>([&](auto S) { iteration(S); });
+  if constexpr (KL == 2) {
+    // lane 1 hands its sums to lane 0 through LDS (the K tiles are no longer read: every wavefront
+    // has passed the walk's last barrier); layout [row wavefront][value][lane]: conflict free
+    static_assert(RW * CT * 16 * 256 <= KL * 2 * DUAL64_BYTES, "the exchange area must fit the K buffers");
+    float* xch = reinterpret_cast<float*>(lds_all) + wave * (CT * 16 * 64) + lane;
+    if (kl == 1) {
+#pragma unroll
+      for (int t = 0; t < CT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) xch[(16 * t + r) * 64] = cx.dq[t][r];
+    }
+    __syncthreads();
+    if (kl == 1) return;
+#pragma unroll
+    for (int t = 0; t < CT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) cx.dq[t][r] += xch[(16 * t + r) * 64];
+  }
   if (q_ok) store_acc_t<CT>(dQ + ((int64_t)head * d.nq + q_row) * H, cx.dq, cx.half, d.scale, H, g.acc != 0);
 }
 
@@ -1069,12 +1150,15 @@ hipError_t bwd_launch_ds(Phase ph, const a2d_tile_desc& d, const SegList& g, con
   hipError_t e = device_cus(&cus);
   if (e != hipSuccess) return e;
   const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
+  // the dQ kernel walks the keys in two lanes when at most one 128-row block comes to a compute unit
+  const bool lanes = !big && (int64_t)d.heads * ((d.nq + 127) / 128) <= cus;
   if (ph == PREPARE) {
     e = ensure_dynamic_lds(grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, true>)
                                    : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, true>), DK_LDS);
     if (e != hipSuccess) return e;
-    return ensure_dynamic_lds(big ? reinterpret_cast<const void*>(bwd_dq_ds_kernel<8, HR>)
-                                  : reinterpret_cast<const void*>(bwd_dq_ds_kernel<4, HR>), DSQ_LDS);
+    return lanes ? ensure_dynamic_lds(reinterpret_cast<const void*>(bwd_dq_ds_kernel<8, HR, 2>), 2 * DSQ_LDS)
+                 : ensure_dynamic_lds(big ? reinterpret_cast<const void*>(bwd_dq_ds_kernel<8, HR, 1>)
+                                          : reinterpret_cast<const void*>(bwd_dq_ds_kernel<4, HR, 1>), DSQ_LDS);
   }
   dim3 grid_kv(xcd_grid(d.heads / g.group * g.qsplit, (d.nkv + DK_KEYS - 1) / DK_KEYS));
   const int dq_rows = big ? 256 : 128;
@@ -1091,10 +1175,13 @@ hipError_t bwd_launch_ds(Phase ph, const a2d_tile_desc& d, const SegList& g, con
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (big)
-    A2D_LAUNCH((bwd_dq_ds_kernel<8, HR>), grid_q, dim3(512), DSQ_LDS, s, d, g, (const bf16_t*)K,
+    A2D_LAUNCH((bwd_dq_ds_kernel<8, HR, 1>), grid_q, dim3(512), DSQ_LDS, s, d, g, (const bf16_t*)K,
+                       (const bf16_t*)ds_ws, dQ);
+  else if (lanes)
+    A2D_LAUNCH((bwd_dq_ds_kernel<8, HR, 2>), grid_q, dim3(512), 2 * DSQ_LDS, s, d, g, (const bf16_t*)K,
                        (const bf16_t*)ds_ws, dQ);
   else
-    A2D_LAUNCH((bwd_dq_ds_kernel<4, HR>), grid_q, dim3(256), DSQ_LDS, s, d, g, (const bf16_t*)K,
+    A2D_LAUNCH((bwd_dq_ds_kernel<4, HR, 1>), grid_q, dim3(256), DSQ_LDS, s, d, g, (const bf16_t*)K,
                        (const bf16_t*)ds_ws, dQ);
   return hipGetLastError();
 }
@@ -1113,6 +1200,8 @@ hipError_t bwd_launch_hd(Phase ph, const a2d_tile_desc& d, const SegList& g, con
   hipError_t e = device_cus(&cus);
   if (e != hipSuccess) return e;
   const bool big = (int64_t)d.heads * ((d.nq + 255) / 256) >= cus;
+  // two key lanes when at most one 128-row block comes to a compute unit
+  const bool lanes = !big && (int64_t)d.heads * ((d.nq + 127) / 128) <= cus;
   if (ph == PREPARE) {
     const void* dkdv = plain ? (grouped ? reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, true, false, true>)
                                         : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, false, true>))
@@ -1120,8 +1209,9 @@ hipError_t bwd_launch_hd(Phase ph, const a2d_tile_desc& d, const SegList& g, con
                                         : reinterpret_cast<const void*>(bwd_dkdv_kernel<HR, false, false, false>));
     e = ensure_dynamic_lds(dkdv, DK_LDS);
     if (e != hipSuccess) return e;
-    return ensure_dynamic_lds(big ? reinterpret_cast<const void*>(bwd_dq_kernel<8, HR>)
-                                  : reinterpret_cast<const void*>(bwd_dq_kernel<4, HR>), DQ_LDS);
+    return lanes ? ensure_dynamic_lds(reinterpret_cast<const void*>(bwd_dq_kernel<8, HR, 2>), 2 * DQ_LDS)
+                 : ensure_dynamic_lds(big ? reinterpret_cast<const void*>(bwd_dq_kernel<8, HR, 1>)
+                                          : reinterpret_cast<const void*>(bwd_dq_kernel<4, HR, 1>), DQ_LDS);
   }
   dim3 grid_kv(xcd_grid(d.heads / g.group * g.qsplit, (d.nkv + DK_KEYS - 1) / DK_KEYS));
   const int dq_rows = big ? 256 : 128;
@@ -1138,10 +1228,13 @@ hipError_t bwd_launch_hd(Phase ph, const a2d_tile_desc& d, const SegList& g, con
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (big)
-    A2D_LAUNCH((bwd_dq_kernel<8, HR>), grid_q, dim3(512), DQ_LDS, s, d, g, (const bf16_t*)Q,
+    A2D_LAUNCH((bwd_dq_kernel<8, HR, 1>), grid_q, dim3(512), DQ_LDS, s, d, g, (const bf16_t*)Q,
+                       (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
+  else if (lanes)
+    A2D_LAUNCH((bwd_dq_kernel<8, HR, 2>), grid_q, dim3(512), 2 * DQ_LDS, s, d, g, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
   else
-    A2D_LAUNCH((bwd_dq_kernel<4, HR>), grid_q, dim3(256), DQ_LDS, s, d, g, (const bf16_t*)Q,
+    A2D_LAUNCH((bwd_dq_kernel<4, HR, 1>), grid_q, dim3(256), DQ_LDS, s, d, g, (const bf16_t*)Q,
                        (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)dO, lse, delta, dQ);
   return hipGetLastError();
 }
