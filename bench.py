@@ -384,11 +384,16 @@ def main():
         tf_r, mhz_r = a2d.mfma_ceiling(20000, True)
         tf_c, mhz_c = a2d.mfma_ceiling(20000, False)
         tf_m, mhz_m = a2d.forward_mix_ceiling(6000)
+        tf_b, mhz_b = a2d.backward_mix_ceiling(6000)
         return {"random_operands": {"tflops": round(tf_r, 1), "shader_mhz": round(mhz_r)},
                 "constant_operands": {"tflops": round(tf_c, 1), "shader_mhz": round(mhz_c)},
                 "forward_loop_model": {"tflops": round(tf_m, 1), "shader_mhz": round(mhz_m),
                                        "what": "MFMA + one LDS fragment + softmax arithmetic per MFMA, random operands, "
                                                "nothing else of the kernel"},
+                "dkdv_loop_model": {"tflops": round(tf_b, 1), "shader_mhz": round(mhz_b),
+                                    "what": "paired score / gradient wavefronts, natural and transposing LDS fragments, "
+                                            "fp32 mailbox, one barrier per 32-row step, random operands, nothing else "
+                                            "of the kernel"},
                 "unit": "TFLOP/s", "kind": "MFMA-only probe, register operands"}
 
     if not args.no_gathered:
@@ -648,7 +653,8 @@ def rectangular_tiles(a2d, synth, w, scale):
     gen = torch.Generator(device="cuda"); gen.manual_seed(11)
     mk = lambda rows: torch.randn(heads, rows, H, device="cuda", generator=gen).to(torch.bfloat16)
     out = {"what": "%d heads, unmasked tiles of equal area, Nq x Nkv; fwd_wg / dq_wg = query rows per workgroup of the "
-                   "forward / dQ kernels (256: eight wavefronts; 128: four), dkdv_wgs = workgroups of 128 keys" % heads,
+                   "forward / dQ kernels (256: eight wavefronts; 128: four, or eight in two key lanes when at most one block "
+                   "comes to a compute unit), dkdv_wgs = workgroups of 128 keys" % heads,
            "cases": []}
     for nq, nkv in ((4096, 4096), (2048, 8192), (8192, 2048), (1024, 16384), (16384, 1024)):
         Q, dO, K, V = mk(nq), mk(nq), mk(nkv), mk(nkv)

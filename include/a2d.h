@@ -379,6 +379,18 @@ a2d_status a2d_forward_mix_ceiling(int iters, void* scratch, size_t scratch_byte
                                    double* shader_mhz);
 
 /*
+ * The same for the dK/dV kernel of the backward tile call: eight wavefronts in four pairs of a
+ * score and a gradient role, per step of 32 query rows 8 MFMAs on natural LDS fragments, the
+ * arithmetic that turns their results into the next operand (fma + exp2, or a multiplication with
+ * the partner's probabilities, which travel through an LDS mailbox in fp32), 8 MFMAs on
+ * transposing LDS reads, one barrier - and nothing else of the kernel (no global traffic, masks,
+ * staging, dS hand-over, prologue or epilogue).  Arguments and results as for a2d_mfma_ceiling
+ * (same scratch size); synchronous.
+ */
+a2d_status a2d_backward_mix_ceiling(int iters, void* scratch, size_t scratch_bytes, double* tflops,
+                                    double* shader_mhz);
+
+/*
  * Debugging aid, not part of the method: on != 0 routes every tile call of the process to the
  * fp32 vector-ALU kernels (also for bf16 inputs), 0 back to the default choice.  The initial
  * value is 1 when A2D_FORCE_GENERIC=1 is in the environment at the first tile call, else 0.

@@ -622,7 +622,7 @@ size_t a2d_mfma_ceiling_scratch_bytes(void) {
 }
 
 namespace {
-// runs one of the two probes twice (the first run settles the clocks) and converts its counters
+// runs one of the probes twice (the first run settles the clocks) and converts its counters
 a2d_status run_probe(const char* who, int iters, int mode, void* scratch, size_t scratch_bytes, double* tflops,
                      double* shader_mhz) {
   if (iters < 1 || iters > (1 << 22)) return fail(A2D_ERR_INVALID_ARG, "%s: iters=%d outside 1..2^22", who, iters);
@@ -632,13 +632,14 @@ a2d_status run_probe(const char* who, int iters, int mode, void* scratch, size_t
   if (need == 0) return fail(A2D_ERR_HIP, "%s: cannot query the device", who);
   if (scratch_bytes < need)
     return fail(A2D_ERR_WORKSPACE, "%s: scratch of %zu bytes, %zu needed", who, scratch_bytes, need);
-  // MFMA-only probe: four workgroups per compute unit; forward-mix model: one (64 KiB of LDS each)
+  // MFMA-only probe: four workgroups per compute unit; the loop models: one (64 / 96 KiB of LDS each)
   const int all = (int)((need - 16) / (a2d::mfma_probe_threads() * sizeof(float)));
-  const int blocks = mode == 2 ? all / 4 : all;
+  const int blocks = mode >= 2 ? all / 4 : all;
   float* sc = static_cast<float*>(scratch);
   auto launch = [&]() {
-    return mode == 2 ? a2d::launch_mix_probe(blocks, iters, sc, nullptr)
-                     : a2d::launch_mfma_probe(blocks, iters, mode, sc, nullptr);
+    return mode == 3   ? a2d::launch_bwd_mix_probe(blocks, iters, sc, nullptr)
+           : mode == 2 ? a2d::launch_mix_probe(blocks, iters, sc, nullptr)
+                       : a2d::launch_mfma_probe(blocks, iters, mode, sc, nullptr);
   };
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
@@ -674,6 +675,11 @@ a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t sc
 a2d_status a2d_forward_mix_ceiling(int iters, void* scratch, size_t scratch_bytes, double* tflops,
                                    double* shader_mhz) {
   return run_probe("a2d_forward_mix_ceiling", iters, 2, scratch, scratch_bytes, tflops, shader_mhz);
+}
+
+a2d_status a2d_backward_mix_ceiling(int iters, void* scratch, size_t scratch_bytes, double* tflops,
+                                    double* shader_mhz) {
+  return run_probe("a2d_backward_mix_ceiling", iters, 3, scratch, scratch_bytes, tflops, shader_mhz);
 }
 
 void a2d_debug_force_generic(int on) { a2d::set_force_generic(on != 0); }

@@ -1195,7 +1195,7 @@ hipError_t bwd_launch_hd(Phase ph, const a2d_tile_desc& d, const SegList& g, con
   const bool grouped = g.group > 1;
   // Q and dO in the plain layout: the variant with compile-time staging offsets
   const bool plain = d.lq.row == HR && d.ldo.row == HR && d.lq.head == (int64_t)d.nq * HR && d.ldo.head == d.lq.head;
-  // dQ kernel: eight wavefronts per workgroup unless that leaves compute units without a workgroup
+  // dQ kernel: 256-row workgroups unless that leaves compute units without a workgroup
   int cus = 0;
   hipError_t e = device_cus(&cus);
   if (e != hipSuccess) return e;

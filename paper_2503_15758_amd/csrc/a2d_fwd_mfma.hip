@@ -3,7 +3,8 @@
 //
 // Work split: one workgroup = 8 wavefronts = 256 query rows of one head; each
 // wavefront owns 32 query rows for the whole kernel and walks the key blocks
-// (64 keys per step) that the workgroup stages through LDS.
+// (64 keys per step) that the workgroup stages through LDS.  (Tiles with too few
+// query blocks for that take 128-row workgroups: see the kernel's template parameters.)
 //
 // Both contractions are issued TRANSPOSED so that no cross-lane data movement is
 // needed between them (v_mfma_f32_32x32x16_bf16, D = A * B, A: 32 x 16, B: 16 x 32):

@@ -117,6 +117,110 @@ __global__ __launch_bounds__(PROBE_THREADS) void mix_probe_kernel(float* __restr
   if (tid == 0 && blockIdx.x == 0) { clocks[0] = c1 - c0; clocks[1] = w1 - w0; }
 }
 
+// Model of the dK/dV kernel's inner loop, in the same spirit: eight wavefronts in four pairs (w, w + 4:
+// one SIMD each).  Per step of 32 query rows a wavefront issues 8 MFMAs on fresh natural fragments
+// (128-bit LDS reads, rows of 320 bytes), turns the 16 results per lane into the B operand of the
+// second contraction - the score role by fma + exp2, handing its probabilities to the partner as
+// fp32 through a 4 KiB LDS mailbox, the gradient role by multiplying with the partner's
+// probabilities of the step before - and issues 8 MFMAs whose A fragments come from the LDS
+// transpose read; one barrier per step.  Pseudo-random operands; no global traffic, masks,
+// staging, statistics, dS hand-over, prologue or epilogue.
+constexpr int BMIX_MBOX = MIX_LDS_BYTES;                       // mailboxes behind the 64 KiB of operands
+constexpr int BMIX_LDS_BYTES = MIX_LDS_BYTES + 4 * 2 * 4096;   // four pairs x two slots x 4 KiB
+__global__ __launch_bounds__(PROBE_THREADS) void bwd_mix_probe_kernel(float* __restrict__ out, int iters,
+                                                                      unsigned long long* __restrict__ clocks) {
+  extern __shared__ __attribute__((aligned(16))) char mix_lds[];
+  const unsigned base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)mix_lds;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int role = wave >> 2, pair = wave & 3;
+  for (int i = tid; i < MIX_LDS_BYTES / 2; i += PROBE_THREADS) {
+    unsigned h = (blockIdx.x * 32768u + i + 1) * 2654435761u;
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    reinterpret_cast<unsigned short*>(mix_lds)[i] = (unsigned short)((h & 0x807Fu) | ((125u + ((h >> 9) & 3u)) << 7));
+  }
+  for (int i = tid; i < (BMIX_LDS_BYTES - MIX_LDS_BYTES) / 4; i += PROBE_THREADS)
+    reinterpret_cast<float*>(mix_lds + BMIX_MBOX)[i] = 0.25f;
+  __syncthreads();
+  bf16x8 kf[8];                                   // the register-resident fragments (K^T or V^T)
+#pragma unroll
+  for (int f = 0; f < 8; ++f) kf[f] = lds_load_b128(base + ((lane * 16 + f * 1024 + wave * 8192) & (MIX_LDS_BYTES - 1)));
+  f32x16 acc[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) acc[t] = zero16();
+  // natural reads: row (lane & 31) of 320 bytes, 16-byte half (lane >> 5); transposing reads: the
+  // 8-byte pieces of rows 4 * (g16 >> 1) + (j16 >> 2) and + 8.  Every address stays below
+  // 32767 + 31 * 320 + 16 + 7 * 32 + 16 < 64 KiB.
+  const int g16 = lane >> 4, j16 = lane & 15;
+  const unsigned nat = base + (lane & 31) * 320 + (lane >> 5) * 16;
+  const unsigned tr = base + (4 * (g16 >> 1) + (j16 >> 2)) * 320 + (16 * (g16 & 1) + 4 * (j16 & 3)) * 2;
+  const unsigned mbox = base + BMIX_MBOX + pair * 8192 + lane * 16;
+  const unsigned long long c0 = __builtin_readcyclecounter();
+  const unsigned long long w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+    const unsigned mv = (unsigned)(it * 2560) & 0x7FFF;       // the tiles move through the 64 KiB
+    const unsigned slot = (it & 1) * 4096;
+    bf16x8 a[4];
+#pragma unroll
+    for (int f = 0; f < 4; ++f) a[f] = lds_load_b128(nat + mv + f * 32);
+    f32x4 pm[4];
+    if (role == 1) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        pm[g] = *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>((uintptr_t)(mbox + (slot ^ 4096) + g * 1024));
+    }
+    f32x16 s0 = zero16(), s1 = zero16();
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      if (x & 1) s1 = mma(a[x & 3], kf[x], s1); else s0 = mma(a[x & 3], kf[x], s0);
+      if (x + 4 < 8) a[x & 3] = lds_load_b128(nat + mv + (x + 4) * 32);
+    }
+    bf16x8 t[4];
+#pragma unroll
+    for (int ht = 0; ht < 4; ++ht) t[ht] = lds_load_tr(tr + mv + 64 * ht, tr + mv + 64 * ht + 8 * 320);
+    f32x16 s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = s0[r] + s1[r];
+    if (role == 0) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f32x4 p4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float p = fast_exp2(fmaf(s[4 * g + e], 0.1f, -8.0f));
+          s[4 * g + e] = p;
+          p4[e] = p;
+        }
+        *reinterpret_cast<__attribute__((address_space(3))) f32x4*>((uintptr_t)(mbox + slot + g * 1024)) = p4;
+      }
+    } else {
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[4 * g + e] = pm[g][e] * s[4 * g + e] * 0.01f;
+    }
+    bf16x8 bf[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) bf[u] = pack8(s, 8 * u);
+#pragma unroll
+    for (int ht = 0; ht < 4; ++ht) {
+      acc[ht] = mma(t[ht], bf[0], acc[ht]);
+      t[ht] = lds_load_tr(tr + mv + 64 * ht + 16 * 320, tr + mv + 64 * ht + 24 * 320);
+    }
+#pragma unroll
+    for (int ht = 0; ht < 4; ++ht) acc[ht] = mma(t[ht], bf[1], acc[ht]);
+    __syncthreads();
+  }
+  const unsigned long long c1 = __builtin_readcyclecounter();
+  const unsigned long long w1 = wall_clock64();
+  float r = 0.f;
+#pragma unroll
+  for (int t4 = 0; t4 < 4; ++t4)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) r += acc[t4][e];
+  out[blockIdx.x * PROBE_THREADS + tid] = r;
+  if (tid == 0 && blockIdx.x == 0) { clocks[0] = c1 - c0; clocks[1] = w1 - w0; }
+}
+
 // Plain copy: every thread moves 16-byte pieces one grid-sized stride apart, four loads in flight.
 __global__ __launch_bounds__(256) void copy_probe_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
                                                          size_t n16) {
@@ -159,6 +263,15 @@ hipError_t launch_mix_probe(int blocks, int iters, float* scratch, hipStream_t s
   if (e != hipSuccess) return e;
   unsigned long long* clocks = reinterpret_cast<unsigned long long*>(scratch + (size_t)blocks * PROBE_THREADS);
   hipLaunchKernelGGL(mix_probe_kernel, dim3(blocks), dim3(PROBE_THREADS), MIX_LDS_BYTES, s, scratch, iters, clocks);
+  return hipGetLastError();
+}
+
+// one workgroup per compute unit (96 KiB of LDS each); scratch as for launch_mfma_probe
+hipError_t launch_bwd_mix_probe(int blocks, int iters, float* scratch, hipStream_t s) {
+  hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(bwd_mix_probe_kernel), BMIX_LDS_BYTES);
+  if (e != hipSuccess) return e;
+  unsigned long long* clocks = reinterpret_cast<unsigned long long*>(scratch + (size_t)blocks * PROBE_THREADS);
+  hipLaunchKernelGGL(bwd_mix_probe_kernel, dim3(blocks), dim3(PROBE_THREADS), BMIX_LDS_BYTES, s, scratch, iters, clocks);
   return hipGetLastError();
 }
 

@@ -5,9 +5,9 @@ query blocks against the number of compute units (256 on MI355X):
   * workgroups of eight wavefronts (256 query rows) once heads * ceil(nq / 256) reaches the number
     of compute units - the one every paper-sized workload runs;
   * workgroups of four wavefronts (128 rows) below that;
-  * for the forward kernel, when even heads * ceil(nq / 128) is at most the number of compute
-    units, 128-row workgroups of eight wavefronts in two key lanes whose partials are merged
-    inside the kernel (the small cases of test_gpu_parity.py all take this one).
+  * when even heads * ceil(nq / 128) is at most the number of compute units, 128-row workgroups of
+    eight wavefronts in two key lanes whose partials (forward) or sums (dQ) are merged inside the
+    kernel (the small cases of test_gpu_parity.py all take this one).
 The cases here have many heads and short, RAGGED tiles, so that each regime is reached (with the
 by-size workgroup order under a causal mask, and head counts that leave a partial last chunk of
 heads per XCD) for every head size, in every form of the calls: plain, accumulating, normalised,
@@ -92,7 +92,7 @@ CASES_FOUR = [
     (24, 6, 1400, 600, 80, False, 0, 0),        # grouped heads, no mask
 ]
 
-# at most one 128-row block per compute unit: the forward kernel walks the keys in two lanes
+# at most one 128-row block per compute unit: the forward and dQ kernels walk the keys in two lanes
 CASES_LANES = [
     (8, 8, 700, 900, 128, True, 400, 0),        # diagonal through the tile: the lanes' shares differ
     (12, 12, 300, 1000, 80, True, 900, 0),      # an odd number of visible key blocks for most workgroups
@@ -116,8 +116,8 @@ def test_four_wavefront_kernels_every_call_form(a2d, case):
 
 
 @pytest.mark.parametrize("case", CASES_LANES, ids=_ids)
-def test_two_key_lane_forward_every_call_form(a2d, case):
-    assert case[0] * ((case[2] + 127) // 128) <= CUS, "the case must take the forward kernel with two key lanes"
+def test_two_key_lane_kernels_every_call_form(a2d, case):
+    assert case[0] * ((case[2] + 127) // 128) <= CUS, "the case must take the kernels with two key lanes"
     _every_call_form(a2d, case, "2 lanes")
 
 

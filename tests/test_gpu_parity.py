@@ -485,6 +485,8 @@ def test_mfma_ceiling_probe_runs(a2d):
     assert 100.0 < tf < 20000.0 and 300.0 < mhz < 4000.0
     tf_m, mhz_m = a2d.forward_mix_ceiling(500)          # the forward loop's model: below the MFMA-only rate
     assert 100.0 < tf_m < 1.05 * max(tf, a2d.mfma_ceiling(2000, False)[0]) and 300.0 < mhz_m < 4000.0
+    tf_b, mhz_b = a2d.backward_mix_ceiling(500)         # the dK/dV loop's model
+    assert 100.0 < tf_b < 1.05 * max(tf, a2d.mfma_ceiling(2000, False)[0]) and 300.0 < mhz_b < 4000.0
     src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
     dst = torch.zeros_like(src)
     a2d.copy_probe(dst, src)                            # the plain copy kernel copies
