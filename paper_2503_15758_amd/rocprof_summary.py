@@ -2,12 +2,12 @@
 
 Two commands (run from the repository root, on the MI355X machine):
 
-  python -m paper_2503_15758_amd.rocprof_summary collect --workload c3 --dir gpurun_out/prof_c3
+  python -m paper_2503_15758_amd.rocprof_summary collect --workload c3 --dir raw/prof_c3
       runs bench.py five times under rocprofv3 (kernel trace; FETCH_SIZE; WRITE_SIZE; two passes of
       SQ activity counters), each pass in a run of its own, and leaves the raw CSV output, bench.py's
       JSON line and its launch log in <dir>/<pass>/.
 
-  python -m paper_2503_15758_amd.rocprof_summary tables --workload c3 --dir gpurun_out/prof_c3 --out profiles
+  python -m paper_2503_15758_amd.rocprof_summary tables --workload c3 --dir raw/prof_c3 --out profiles
       turns that raw output into profiles/<workload>_kernel_trace.txt, _hbm_traffic.txt and
       _utilisation.txt.  The traffic file ends with machine-readable lines that bench.py reads
       (`traffic_bytes <call> <bytes>`), stamped with the hash of the kernel sources they were
@@ -317,7 +317,7 @@ def main():
     for name in ("collect", "tables"):
         p = sub.add_parser(name)
         p.add_argument("--workload", default="c3")
-        p.add_argument("--dir", required=True, help="raw output of the passes (under gpurun_out/)")
+        p.add_argument("--dir", required=True, help="raw output of the passes (a scratch folder, not committed)")
         if name == "tables":
             p.add_argument("--out", default=os.path.join(ROOT, "profiles"))
             p.add_argument("--name", default=None, help="prefix of the files written (default: the workload; "
