@@ -385,6 +385,11 @@ def main():
         tf_c, mhz_c = a2d.mfma_ceiling(20000, False)
         tf_m, mhz_m = a2d.forward_mix_ceiling(6000)
         tf_b, mhz_b = a2d.backward_mix_ceiling(6000)
+        without = {name: round(a2d.backward_mix_ceiling(6000, bits)[0], 1)
+                   for name, bits in (("mailbox", a2d.LEAVE_MAILBOX), ("arithmetic", a2d.LEAVE_ARITHMETIC),
+                                      ("mailbox_barrier", a2d.LEAVE_MAILBOX | a2d.LEAVE_BARRIER),
+                                      ("mailbox_barrier_arithmetic", 7))}
+        lds_n, lds_t = a2d.lds_read_ceiling(20000, False)[0], a2d.lds_read_ceiling(20000, True)[0]
         return {"random_operands": {"tflops": round(tf_r, 1), "shader_mhz": round(mhz_r)},
                 "constant_operands": {"tflops": round(tf_c, 1), "shader_mhz": round(mhz_c)},
                 "forward_loop_model": {"tflops": round(tf_m, 1), "shader_mhz": round(mhz_m),
@@ -393,7 +398,10 @@ def main():
                 "dkdv_loop_model": {"tflops": round(tf_b, 1), "shader_mhz": round(mhz_b),
                                     "what": "paired score / gradient wavefronts, natural and transposing LDS fragments, "
                                             "fp32 mailbox, one barrier per 32-row step, random operands, nothing else "
-                                            "of the kernel"},
+                                            "of the kernel",
+                                    "tflops_without": without},
+                "lds_read_tbytes_per_s": {"b128": round(lds_n, 1), "b64_transposing": round(lds_t, 1),
+                                          "what": "eight wavefronts per compute unit that only read LDS"},
                 "unit": "TFLOP/s", "kind": "MFMA-only probe, register operands"}
 
     if not args.no_gathered:

@@ -384,11 +384,26 @@ a2d_status a2d_forward_mix_ceiling(int iters, void* scratch, size_t scratch_byte
  * arithmetic that turns their results into the next operand (fma + exp2, or a multiplication with
  * the partner's probabilities, which travel through an LDS mailbox in fp32), 8 MFMAs on
  * transposing LDS reads, one barrier - and nothing else of the kernel (no global traffic, masks,
- * staging, dS hand-over, prologue or epilogue).  Arguments and results as for a2d_mfma_ceiling
- * (same scratch size); synchronous.
+ * staging, dS hand-over, prologue or epilogue).
+ * leave_out: parts of the model to leave out, to see what each costs: bit 0 the mailbox, bit 1
+ * the element-wise arithmetic, bit 2 the barrier (accepted only together with bit 0: without the
+ * barrier nothing passes between wavefronts); 0 is the whole model.  Other values:
+ * A2D_ERR_INVALID_ARG.  Other arguments and results as for a2d_mfma_ceiling (same scratch size);
+ * synchronous.
  */
-a2d_status a2d_backward_mix_ceiling(int iters, void* scratch, size_t scratch_bytes, double* tflops,
-                                    double* shader_mhz);
+a2d_status a2d_backward_mix_ceiling(int iters, int leave_out, void* scratch, size_t scratch_bytes,
+                                    double* tflops, double* shader_mhz);
+
+/*
+ * Diagnostic: what the LDS of the chip delivers to eight wavefronts per compute unit that only
+ * read it, with the tile kernels' two kinds of fragment reads - 128-bit reads of padded rows
+ * (transposing = 0) or 64-bit transposing reads (transposing != 0).  *tbytes_per_s: 10^12 bytes
+ * per second over the whole chip.  Against it the kernels' own LDS traffic shows whether LDS
+ * bandwidth bounds them.  Other arguments as for a2d_mfma_ceiling (same scratch size; iters:
+ * groups of 16 reads per wavefront); synchronous.
+ */
+a2d_status a2d_lds_read_ceiling(int iters, int transposing, void* scratch, size_t scratch_bytes,
+                                double* tbytes_per_s, double* shader_mhz);
 
 /*
  * Debugging aid, not part of the method: on != 0 routes every tile call of the process to the

@@ -22,7 +22,7 @@ EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd
            "a2d_partial_fwd_seg", "a2d_partial_bwd_seg", "a2d_partial_fwd_acc", "a2d_partial_bwd_acc",
            "a2d_partial_fwd_norm", "a2d_fix_norm", "a2d_partial_fwd_gqa", "a2d_partial_bwd_gqa",
            "a2d_fix_strided", "a2d_fix_bwd_strided", "a2d_fix_norm_strided",
-           "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling", "a2d_forward_mix_ceiling", "a2d_backward_mix_ceiling", "a2d_debug_force_generic",
+           "a2d_mfma_ceiling_scratch_bytes", "a2d_mfma_ceiling", "a2d_forward_mix_ceiling", "a2d_backward_mix_ceiling", "a2d_lds_read_ceiling", "a2d_debug_force_generic",
            "a2d_debug_trace", "a2d_debug_trace_count", "a2d_copy_probe",
            "a2d_status_str", "a2d_last_error", "a2d_version")
 
@@ -127,8 +127,11 @@ def lib():
         L.a2d_mfma_ceiling.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t,
                                        ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.a2d_backward_mix_ceiling.restype = ctypes.c_int
-        L.a2d_backward_mix_ceiling.argtypes = [ctypes.c_int, vp, ctypes.c_size_t,
+        L.a2d_backward_mix_ceiling.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t,
                                                ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+        L.a2d_lds_read_ceiling.restype = ctypes.c_int
+        L.a2d_lds_read_ceiling.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t,
+                                           ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.a2d_forward_mix_ceiling.restype = ctypes.c_int
         L.a2d_forward_mix_ceiling.argtypes = [ctypes.c_int, vp, ctypes.c_size_t,
                                               ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -460,14 +463,29 @@ def forward_mix_ceiling(iters=6000):
     return tf.value, mhz.value
 
 
-def backward_mix_ceiling(iters=6000):
+LEAVE_MAILBOX, LEAVE_ARITHMETIC, LEAVE_BARRIER = 1, 2, 4
+
+
+def backward_mix_ceiling(iters=6000, leave_out=0):
     """Diagnostic (a2d_backward_mix_ceiling): (TFLOP/s of the dK/dV loop's model - paired roles, natural and
-    transposing LDS fragments, mailbox, one barrier per step -, shader MHz)."""
+    transposing LDS fragments, mailbox, one barrier per step -, shader MHz); leave_out: LEAVE_* bits."""
     n = int(lib().a2d_mfma_ceiling_scratch_bytes())
     scratch = torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
     tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
-    _check(lib().a2d_backward_mix_ceiling(int(iters), _ptr(scratch), scratch.numel(), ctypes.byref(tf), ctypes.byref(mhz)))
+    _check(lib().a2d_backward_mix_ceiling(int(iters), int(leave_out), _ptr(scratch), scratch.numel(),
+                                          ctypes.byref(tf), ctypes.byref(mhz)))
     return tf.value, mhz.value
+
+
+def lds_read_ceiling(iters=20000, transposing=False):
+    """Diagnostic (a2d_lds_read_ceiling): (10^12 bytes per second the chip's LDS delivers to wavefronts that
+    only read it, shader MHz)."""
+    n = int(lib().a2d_mfma_ceiling_scratch_bytes())
+    scratch = torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
+    tb, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(lib().a2d_lds_read_ceiling(int(iters), int(bool(transposing)), _ptr(scratch), scratch.numel(),
+                                      ctypes.byref(tb), ctypes.byref(mhz)))
+    return tb.value, mhz.value
 
 
 def force_generic(on):

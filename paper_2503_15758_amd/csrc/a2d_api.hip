@@ -622,22 +622,25 @@ size_t a2d_mfma_ceiling_scratch_bytes(void) {
 }
 
 namespace {
-// runs one of the probes twice (the first run settles the clocks) and converts its counters
-a2d_status run_probe(const char* who, int iters, int mode, void* scratch, size_t scratch_bytes, double* tflops,
+// runs one of the probes twice (the first run settles the clocks) and converts its counters.
+// mode 0 / 1: MFMA only, constant / random operands; 2: forward loop model; 3: dK/dV loop model
+// (arg = parts left out); 4: LDS reads (arg = kind).  *rate: TFLOP/s, or TB/s for mode 4.
+a2d_status run_probe(const char* who, int iters, int mode, int arg, void* scratch, size_t scratch_bytes, double* rate,
                      double* shader_mhz) {
   if (iters < 1 || iters > (1 << 22)) return fail(A2D_ERR_INVALID_ARG, "%s: iters=%d outside 1..2^22", who, iters);
-  if (!tflops || !shader_mhz) return fail(A2D_ERR_INVALID_ARG, "%s: result pointer is NULL", who);
+  if (!rate || !shader_mhz) return fail(A2D_ERR_INVALID_ARG, "%s: result pointer is NULL", who);
   A2D_TRY(check_ptr(scratch, who, "scratch"));
   const size_t need = a2d_mfma_ceiling_scratch_bytes();
   if (need == 0) return fail(A2D_ERR_HIP, "%s: cannot query the device", who);
   if (scratch_bytes < need)
     return fail(A2D_ERR_WORKSPACE, "%s: scratch of %zu bytes, %zu needed", who, scratch_bytes, need);
-  // MFMA-only probe: four workgroups per compute unit; the loop models: one (64 / 96 KiB of LDS each)
+  // MFMA-only probe: four workgroups per compute unit; the others: one (64 / 96 KiB of LDS each)
   const int all = (int)((need - 16) / (a2d::mfma_probe_threads() * sizeof(float)));
   const int blocks = mode >= 2 ? all / 4 : all;
   float* sc = static_cast<float*>(scratch);
   auto launch = [&]() {
-    return mode == 3   ? a2d::launch_bwd_mix_probe(blocks, iters, sc, nullptr)
+    return mode == 4   ? a2d::launch_lds_read_probe(blocks, iters, arg, sc, nullptr)
+           : mode == 3 ? a2d::launch_bwd_mix_probe(blocks, iters, arg, sc, nullptr)
            : mode == 2 ? a2d::launch_mix_probe(blocks, iters, sc, nullptr)
                        : a2d::launch_mfma_probe(blocks, iters, mode, sc, nullptr);
   };
@@ -658,10 +661,10 @@ a2d_status run_probe(const char* who, int iters, int mode, void* scratch, size_t
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
   if (e != hipSuccess) return hip_result(e, who);
-  // every wavefront issues iters * 16 MFMAs of 2 * 32 * 32 * 16 flop; 8 wavefronts per workgroup
-  const double flop = (double)blocks * (a2d::mfma_probe_threads() / 64) * iters *
-                      a2d::mfma_probe_mfma_per_iter() * 2.0 * 32 * 32 * 16;
-  *tflops = flop / (ms * 1e-3) / 1e12;
+  // every wavefront issues iters * 16 MFMAs of 2 * 32 * 32 * 16 flop - or 16 LDS reads of 1 KiB
+  // (a transposing read counts as its two 512-byte halves); 8 wavefronts per workgroup
+  const double units = (double)blocks * (a2d::mfma_probe_threads() / 64) * iters * a2d::mfma_probe_mfma_per_iter();
+  *rate = units * (mode == 4 ? 1024.0 : 2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12;
   *shader_mhz = clocks[1] ? (double)clocks[0] / ((double)clocks[1] / 100.0) : 0.0;   // 100 MHz wall counter
   return A2D_OK;
 }
@@ -669,17 +672,28 @@ a2d_status run_probe(const char* who, int iters, int mode, void* scratch, size_t
 
 a2d_status a2d_mfma_ceiling(int iters, int random_data, void* scratch, size_t scratch_bytes,
                             double* tflops, double* shader_mhz) {
-  return run_probe("a2d_mfma_ceiling", iters, random_data ? 1 : 0, scratch, scratch_bytes, tflops, shader_mhz);
+  return run_probe("a2d_mfma_ceiling", iters, random_data ? 1 : 0, 0, scratch, scratch_bytes, tflops, shader_mhz);
 }
 
 a2d_status a2d_forward_mix_ceiling(int iters, void* scratch, size_t scratch_bytes, double* tflops,
                                    double* shader_mhz) {
-  return run_probe("a2d_forward_mix_ceiling", iters, 2, scratch, scratch_bytes, tflops, shader_mhz);
+  return run_probe("a2d_forward_mix_ceiling", iters, 2, 0, scratch, scratch_bytes, tflops, shader_mhz);
 }
 
-a2d_status a2d_backward_mix_ceiling(int iters, void* scratch, size_t scratch_bytes, double* tflops,
+a2d_status a2d_backward_mix_ceiling(int iters, int leave_out, void* scratch, size_t scratch_bytes, double* tflops,
                                     double* shader_mhz) {
-  return run_probe("a2d_backward_mix_ceiling", iters, 3, scratch, scratch_bytes, tflops, shader_mhz);
+  const char* who = "a2d_backward_mix_ceiling";
+  if (leave_out < 0 || leave_out > 7 || ((leave_out & 4) && !(leave_out & 1)))
+    return fail(A2D_ERR_INVALID_ARG, "%s: leave_out=%d (bits 0..2; the barrier only together with the mailbox)", who,
+                leave_out);
+  if (leave_out == 4 || leave_out == 6) return fail(A2D_ERR_INVALID_ARG, "%s: leave_out=%d", who, leave_out);
+  return run_probe(who, iters, 3, leave_out, scratch, scratch_bytes, tflops, shader_mhz);
+}
+
+a2d_status a2d_lds_read_ceiling(int iters, int transposing, void* scratch, size_t scratch_bytes, double* tbytes_per_s,
+                                double* shader_mhz) {
+  return run_probe("a2d_lds_read_ceiling", iters, 4, transposing ? 1 : 0, scratch, scratch_bytes, tbytes_per_s,
+                   shader_mhz);
 }
 
 void a2d_debug_force_generic(int on) { a2d::set_force_generic(on != 0); }

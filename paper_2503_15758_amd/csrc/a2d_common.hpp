@@ -169,7 +169,8 @@ hipError_t launch_copy_probe(void* dst, const void* src, size_t n16, hipStream_t
 hipError_t launch_mfma_probe(int blocks, int iters, int random_data, float* scratch, hipStream_t s);
 // model of the forward loop: MFMA + one LDS fragment per MFMA + softmax arithmetic (diagnostic)
 hipError_t launch_mix_probe(int blocks, int iters, float* scratch, hipStream_t s);
-hipError_t launch_bwd_mix_probe(int blocks, int iters, float* scratch, hipStream_t s);
+hipError_t launch_bwd_mix_probe(int blocks, int iters, int leave_out, float* scratch, hipStream_t s);
+hipError_t launch_lds_read_probe(int blocks, int iters, int kind, float* scratch, hipStream_t s);
 int mfma_probe_threads();
 int mfma_probe_mfma_per_iter();
 

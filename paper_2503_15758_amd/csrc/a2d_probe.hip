@@ -125,10 +125,16 @@ __global__ __launch_bounds__(PROBE_THREADS) void mix_probe_kernel(float* __restr
 // probabilities of the step before - and issues 8 MFMAs whose A fragments come from the LDS
 // transpose read; one barrier per step.  Pseudo-random operands; no global traffic, masks,
 // staging, statistics, dS hand-over, prologue or epilogue.
+// LEAVE: parts of the model left out, to see what each costs - bit 0 the mailbox (the gradient
+// role multiplies with constants), bit 1 the element-wise arithmetic (the first contraction's
+// results are only rounded), bit 2 the barrier (only together with bit 0: without the barrier
+// nothing may pass between wavefronts).
 constexpr int BMIX_MBOX = MIX_LDS_BYTES;                       // mailboxes behind the 64 KiB of operands
 constexpr int BMIX_LDS_BYTES = MIX_LDS_BYTES + 4 * 2 * 4096;   // four pairs x two slots x 4 KiB
+template <int LEAVE>
 __global__ __launch_bounds__(PROBE_THREADS) void bwd_mix_probe_kernel(float* __restrict__ out, int iters,
                                                                       unsigned long long* __restrict__ clocks) {
+  static_assert(!(LEAVE & 4) || (LEAVE & 1), "no barrier only without the mailbox");
   extern __shared__ __attribute__((aligned(16))) char mix_lds[];
   const unsigned base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)mix_lds;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -166,7 +172,9 @@ __global__ __launch_bounds__(PROBE_THREADS) void bwd_mix_probe_kernel(float* __r
     if (role == 1) {
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        pm[g] = *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>((uintptr_t)(mbox + (slot ^ 4096) + g * 1024));
+        pm[g] = (LEAVE & 1) ? f32x4{0.3f, 0.2f, 0.1f, 0.4f}
+                            : *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(
+                                  (uintptr_t)(mbox + (slot ^ 4096) + g * 1024));
     }
     f32x16 s0 = zero16(), s1 = zero16();
 #pragma unroll
@@ -186,17 +194,18 @@ __global__ __launch_bounds__(PROBE_THREADS) void bwd_mix_probe_kernel(float* __r
         f32x4 p4;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float p = fast_exp2(fmaf(s[4 * g + e], 0.1f, -8.0f));
+          const float p = (LEAVE & 2) ? s[4 * g + e] : fast_exp2(fmaf(s[4 * g + e], 0.1f, -8.0f));
           s[4 * g + e] = p;
           p4[e] = p;
         }
-        *reinterpret_cast<__attribute__((address_space(3))) f32x4*>((uintptr_t)(mbox + slot + g * 1024)) = p4;
+        if (!(LEAVE & 1))
+          *reinterpret_cast<__attribute__((address_space(3))) f32x4*>((uintptr_t)(mbox + slot + g * 1024)) = p4;
       }
     } else {
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) s[4 * g + e] = pm[g][e] * s[4 * g + e] * 0.01f;
+        for (int e = 0; e < 4; ++e) s[4 * g + e] = (LEAVE & 2) ? s[4 * g + e] : pm[g][e] * s[4 * g + e] * 0.01f;
     }
     bf16x8 bf[2];
 #pragma unroll
@@ -208,7 +217,7 @@ __global__ __launch_bounds__(PROBE_THREADS) void bwd_mix_probe_kernel(float* __r
     }
 #pragma unroll
     for (int ht = 0; ht < 4; ++ht) acc[ht] = mma(t[ht], bf[1], acc[ht]);
-    __syncthreads();
+    if (!(LEAVE & 4)) __syncthreads();
   }
   const unsigned long long c1 = __builtin_readcyclecounter();
   const unsigned long long w1 = wall_clock64();
@@ -218,6 +227,44 @@ __global__ __launch_bounds__(PROBE_THREADS) void bwd_mix_probe_kernel(float* __r
 #pragma unroll
     for (int e = 0; e < 16; ++e) r += acc[t4][e];
   out[blockIdx.x * PROBE_THREADS + tid] = r;
+  if (tid == 0 && blockIdx.x == 0) { clocks[0] = c1 - c0; clocks[1] = w1 - w0; }
+}
+
+// What the LDS of a compute unit delivers to eight wavefronts that do nothing but read it, with the
+// two kinds of fragment reads the tile kernels use: KIND 0 128-bit reads (rows of 272 bytes, the K
+// tile's pattern), KIND 1 64-bit transposing reads (rows of 320 bytes, the V tile's pattern).  16 reads
+// per wavefront and iteration; the values are folded into one word so that no read can be dropped.
+template <int KIND>
+__global__ __launch_bounds__(PROBE_THREADS) void lds_read_probe_kernel(float* __restrict__ out, int iters,
+                                                                       unsigned long long* __restrict__ clocks) {
+  extern __shared__ __attribute__((aligned(16))) char mix_lds[];
+  const unsigned base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)mix_lds;
+  const int tid = threadIdx.x, lane = tid & 63;
+  for (int i = tid; i < MIX_LDS_BYTES / 4; i += PROBE_THREADS) reinterpret_cast<unsigned*>(mix_lds)[i] = i * 2654435761u;
+  __syncthreads();
+  const int g16 = lane >> 4, j16 = lane & 15;
+  // every address stays below 32767 + 31 * 272 + 16 + 15 * 32 + 16 (KIND 0) or
+  // 32767 + 7 * 320 + 56 + 192 + 28 * 320 + 8 (KIND 1), both < 64 KiB
+  const unsigned addr = KIND == 0 ? base + (lane & 31) * 272 + (lane >> 5) * 16
+                                  : base + (4 * (g16 >> 1) + (j16 >> 2)) * 320 + (16 * (g16 & 1) + 4 * (j16 & 3)) * 2;
+  u32x4 acc = {0, 0, 0, 0};
+  const unsigned long long c0 = __builtin_readcyclecounter();
+  const unsigned long long w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+    const unsigned mv = (unsigned)(it * 2560) & 0x7FFF;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      if (KIND == 0) {
+        acc ^= __builtin_bit_cast(u32x4, lds_load_b128(addr + mv + x * 32));
+      } else {
+        const unsigned a = addr + mv + (x & 3) * 64 + (x >> 2) * 8 * 320;
+        acc ^= __builtin_bit_cast(u32x4, lds_load_tr(a, a + 4 * 320));   // two 64-bit transposing reads
+      }
+    }
+  }
+  const unsigned long long c1 = __builtin_readcyclecounter();
+  const unsigned long long w1 = wall_clock64();
+  out[blockIdx.x * PROBE_THREADS + tid] = __builtin_bit_cast(float, (acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) & 0x3FFFFFFFu);
   if (tid == 0 && blockIdx.x == 0) { clocks[0] = c1 - c0; clocks[1] = w1 - w0; }
 }
 
@@ -266,13 +313,42 @@ hipError_t launch_mix_probe(int blocks, int iters, float* scratch, hipStream_t s
   return hipGetLastError();
 }
 
-// one workgroup per compute unit (96 KiB of LDS each); scratch as for launch_mfma_probe
-hipError_t launch_bwd_mix_probe(int blocks, int iters, float* scratch, hipStream_t s) {
-  hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(bwd_mix_probe_kernel), BMIX_LDS_BYTES);
+// one workgroup per compute unit (96 KiB of LDS each); scratch as for launch_mfma_probe;
+// leave_out: 0, 1, 2, 3, 5 or 7 (the kernel's LEAVE)
+namespace {
+template <int LEAVE>
+hipError_t bwd_mix_launch(int blocks, int iters, float* scratch, hipStream_t s) {
+  hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(bwd_mix_probe_kernel<LEAVE>), BMIX_LDS_BYTES);
   if (e != hipSuccess) return e;
   unsigned long long* clocks = reinterpret_cast<unsigned long long*>(scratch + (size_t)blocks * PROBE_THREADS);
-  hipLaunchKernelGGL(bwd_mix_probe_kernel, dim3(blocks), dim3(PROBE_THREADS), BMIX_LDS_BYTES, s, scratch, iters, clocks);
+  hipLaunchKernelGGL(bwd_mix_probe_kernel<LEAVE>, dim3(blocks), dim3(PROBE_THREADS), BMIX_LDS_BYTES, s, scratch, iters,
+                     clocks);
   return hipGetLastError();
+}
+template <int KIND>
+hipError_t lds_read_launch(int blocks, int iters, float* scratch, hipStream_t s) {
+  hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(lds_read_probe_kernel<KIND>), MIX_LDS_BYTES);
+  if (e != hipSuccess) return e;
+  unsigned long long* clocks = reinterpret_cast<unsigned long long*>(scratch + (size_t)blocks * PROBE_THREADS);
+  hipLaunchKernelGGL(lds_read_probe_kernel<KIND>, dim3(blocks), dim3(PROBE_THREADS), MIX_LDS_BYTES, s, scratch, iters,
+                     clocks);
+  return hipGetLastError();
+}
+}  // namespace
+hipError_t launch_bwd_mix_probe(int blocks, int iters, int leave_out, float* scratch, hipStream_t s) {
+  switch (leave_out) {
+    case 0: return bwd_mix_launch<0>(blocks, iters, scratch, s);
+    case 1: return bwd_mix_launch<1>(blocks, iters, scratch, s);
+    case 2: return bwd_mix_launch<2>(blocks, iters, scratch, s);
+    case 3: return bwd_mix_launch<3>(blocks, iters, scratch, s);
+    case 5: return bwd_mix_launch<5>(blocks, iters, scratch, s);
+    case 7: return bwd_mix_launch<7>(blocks, iters, scratch, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+// one workgroup of eight wavefronts per compute unit; kind 0: 128-bit reads, 1: transposing 64-bit reads
+hipError_t launch_lds_read_probe(int blocks, int iters, int kind, float* scratch, hipStream_t s) {
+  return kind == 0 ? lds_read_launch<0>(blocks, iters, scratch, s) : lds_read_launch<1>(blocks, iters, scratch, s);
 }
 
 int mfma_probe_threads() { return PROBE_THREADS; }

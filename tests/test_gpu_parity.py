@@ -487,6 +487,14 @@ def test_mfma_ceiling_probe_runs(a2d):
     assert 100.0 < tf_m < 1.05 * max(tf, a2d.mfma_ceiling(2000, False)[0]) and 300.0 < mhz_m < 4000.0
     tf_b, mhz_b = a2d.backward_mix_ceiling(500)         # the dK/dV loop's model
     assert 100.0 < tf_b < 1.05 * max(tf, a2d.mfma_ceiling(2000, False)[0]) and 300.0 < mhz_b < 4000.0
+    for leave in (1, 2, 3, 5, 7):                       # with parts left out it still runs
+        assert a2d.backward_mix_ceiling(200, leave)[0] > 100.0
+    for leave in (4, 6, 8, -1):                         # the barrier only goes together with the mailbox
+        with pytest.raises(a2d.A2DError):
+            a2d.backward_mix_ceiling(200, leave)
+    for tr in (False, True):                            # LDS read rate: tens of TB/s over the chip
+        tb, mhz_l = a2d.lds_read_ceiling(500, tr)
+        assert 5.0 < tb < 1000.0 and 300.0 < mhz_l < 4000.0
     src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
     dst = torch.zeros_like(src)
     a2d.copy_probe(dst, src)                            # the plain copy kernel copies
