@@ -121,9 +121,9 @@ __device__ __forceinline__ void dk_first_pre(const DkCtx<HD>& cx, bf16x8 (&n)[4]
 // `init` is the starting value of the sum (zero for S, -delta for dP - delta).  Two accumulators
 // (even / odd 16-wide slices of H): an MFMA that accumulates onto the result of the one issued
 // just before it would wait for that result.
-template <int HD>
+// KS: the slices that hold data (a head size of 80 fills five of the padded six)
+template <int HD, int KS = HD / 16>
 __device__ __forceinline__ f32x16 dk_first(const DkCtx<HD>& cx, bf16x8 (&n)[4], f32x16 init) {
-  constexpr int KS = HD / 16;
   f32x16 sa = init, sb = zero16();
   static_for<0, KS>([&](auto X) {
     constexpr int x = decltype(X)::value;
@@ -298,6 +298,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
     }
   }
   constexpr int HD = padded_head(HR), H = HR, KS = HD / 16, CT = HD / 32;
+  constexpr int KSR = (HR + 15) / 16;       // slices of H that hold data
   const int k0 = blk * DK_KEYS;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -513,7 +514,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
       if (active(j, cs)) {
         const int i0 = i_start + cs * BQ;
         bf16x8 t[CT], bf[2];
-        f32x16 s = dk_first(cx, n, zero16());
+        f32x16 s = dk_first<HD, KSR>(cx, n, zero16());
         dk_second_pre(cx, t);
         if (i0 >= w_all && i0 + BQ <= d.nq) dk_probs<false>(cx, st, s, bf, i0);
         else dk_probs<true>(cx, st, s, bf, i0);
@@ -576,7 +577,7 @@ __global__ __launch_bounds__(DK_THREADS) void bwd_dkdv_kernel(
         f32x16 init;
 #pragma unroll
         for (int r = 0; r < 16; ++r) init[r] = -st[r >> 2][r & 3];
-        dp = dk_first(cx, n, init);
+        dp = dk_first<HD, KSR>(cx, n, init);
       }
       __syncthreads();
     };
@@ -616,9 +617,10 @@ struct DqCtx {
 // one 32-key x 32-query piece: T selects the half of the 64-key step.  HD / 16 slices of H in the
 // two first contractions (S^T and dP^T, alternating), 2 * HD / 32 MFMAs in dQ^T += K^T dS^T
 // (step I: 16-key group I / CT, column tile I % CT); fragments run two steps ahead of their use.
-template <int T, bool MASK, int HD>
+// (KS: the slices that hold data - a head size of 80 fills five of the padded six)
+template <int T, bool MASK, int HD, int KS = HD / 16>
 __device__ __forceinline__ void dq_piece(DqCtx<HD>& cx, int key0) {
-  constexpr int KS = HD / 16, CT = HD / 32, VT_LD = vt_ld(HD);
+  constexpr int CT = HD / 32, VT_LD = vt_ld(HD);
   constexpr int RB = T * 32 * DUAL_LD;
   constexpr int VB = T * 32 * VT_LD;
   bf16x8 kr[DQ_RING], vr[DQ_RING], kt[DQ_RING];
@@ -681,6 +683,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
   constexpr int DQ_THREADS = 64 * RW;      // threads of one key lane (they stage its tiles)
   constexpr int HD = padded_head(HR), H = HR;
   constexpr int KS = HD / 16, CT = HD / 32, VT_LD = vt_ld(HD), DQ_BUF = dq_buf(HD);
+  constexpr int KSR = (HR + 15) / 16;      // slices of H that hold data
   const int kl = KL == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x / DQ_THREADS);
   char* const lds = lds_all + kl * (2 * DQ_BUF);
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
@@ -829,11 +832,11 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void bwd_dq_kernel(
     const int k0 = j * BKS;                        // local to the sub-block
     if (more) load_half(nx_start, nx_rows, nj, 0);
     if (here && k0 < nvis_wave) {
-      if (k0 + 32 > nfull_wave) dq_piece<0, true>(cx, k0); else dq_piece<0, false>(cx, k0);
+      if (k0 + 32 > nfull_wave) dq_piece<0, true, HD, KSR>(cx, k0); else dq_piece<0, false, HD, KSR>(cx, k0);
     }
     if (more) { store_half(buf ^ 1, 0); load_half(nx_start, nx_rows, nj, 1); }
     if (here && k0 + 32 < nvis_wave) {
-      if (k0 + 64 > nfull_wave) dq_piece<1, true>(cx, k0 + 32); else dq_piece<1, false>(cx, k0 + 32);
+      if (k0 + 64 > nfull_wave) dq_piece<1, true, HD, KSR>(cx, k0 + 32); else dq_piece<1, false, HD, KSR>(cx, k0 + 32);
     }
     if (more) store_half(buf ^ 1, 1);
     const int tog = buf ? -DQ_BUF : DQ_BUF;

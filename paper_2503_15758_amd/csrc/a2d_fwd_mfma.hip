@@ -54,11 +54,12 @@ struct FwdState {
 
 // One 64-key block for one wavefront.  k_rd / v_rd: per-lane LDS byte addresses of the
 // natural K fragment (t = 0, st = 0) and of the transposing V read (u = 0, ht = 0, low rows).
-// HD / 16 slices of H in the score contraction, HD / 32 column tiles in the output contraction.
-template <int HD, bool MASK>
+// KS slices of H in the score contraction (those that hold data: a head size of 80 fills five of
+// the padded six), HD / 32 column tiles in the output contraction.
+template <int HD, bool MASK, int KS = HD / 16>
 __device__ __forceinline__ void fwd_block(FwdState<HD>& st, const bf16x8 (&qf)[HD / 16], unsigned k_rd, unsigned v_rd,
                                           int k0, int my_vis, int half, float c) {
-  constexpr int KS = HD / 16, CT = HD / 32, KLD = kld(HD);
+  constexpr int CT = HD / 32, KLD = kld(HD);
   // K fragments go through a ring four deep: each is requested four MFMAs before its use (the
   // scheduling fences keep the compiler from sinking the requests back to their uses)
   f32x16 s[2];
@@ -160,6 +161,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
   constexpr int kThreads = 64 * RW;       // threads of one key lane (they stage its tiles)
   constexpr int HD = padded_head(HR), H = HR;
   constexpr int KS = HD / 16, CT = HD / 32, KLD = kld(HD), K_BYTES = BN * KLD, BUF_BYTES = buf_bytes(HD);
+  constexpr int KSR = (HR + 15) / 16;     // slices of H that hold data
   constexpr int kLdsBytes = lds_bytes(HD);
   extern __shared__ __attribute__((aligned(16))) char lds_all[];
   // per key lane: [buf]{ K tile (BN x KLD), V tile (BN x VLD) }
@@ -363,8 +365,8 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void fwd_mfma_kernel(
     if (more) load_tile(nx_start, nx_rows, nj);
     const int k0 = j * BN;                         // local to the sub-block
     if ((KL == 1 || sb < g.n) && k0 < nvis_wave) {
-      if (k0 + BN > nfull_wave) fwd_block<HD, true>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
-      else fwd_block<HD, false>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
+      if (k0 + BN > nfull_wave) fwd_block<HD, true, KSR>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
+      else fwd_block<HD, false, KSR>(st, qf, k_rd0 + boff, v_rd0 + boff, k0, my_vis, half, c);
     }
     if (more) store_tile(BUF_BYTES - boff);
     __syncthreads();
