@@ -283,3 +283,14 @@ def test_every_export_has_typed_arguments(binding):
                 assert fn.argtypes[i] is ctypes.c_size_t, "%s: argument %d must be c_size_t" % (name, i)
             if p_.startswith("int64_t"):
                 assert fn.argtypes[i] is ctypes.c_int64, "%s: argument %d must be c_int64" % (name, i)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stderr + r.stdout)
