@@ -32,6 +32,10 @@ __device__ __forceinline__ int64_t out_offset(const OutMap& om, int64_t idx, int
 #define A2D_LD(p) __builtin_nontemporal_load(p)
 constexpr int kLoadsInFlight = 32;
 constexpr int chunks_per_thread(int kmax) { return kmax >= kLoadsInFlight ? 1 : kLoadsInFlight / kmax > 4 ? 4 : kLoadsInFlight / kmax; }
+// (AttnFix carries m and l besides N: with 8 partials two chunks per thread - 16 loads of N in
+// flight - leave room for more wavefronts and measured 3 % faster than four; 2, 4 and 16 partials
+// are fastest with the common rule)
+constexpr int chunks_per_thread_fix(int kmax) { return kmax == 8 ? 2 : chunks_per_thread(kmax); }
 
 // Which column groups a thread owns: its wavefront owns CPT * 64 CONSECUTIVE groups and lane l takes
 // the groups l, l + 64, ... of that run, so that every load instruction of a wavefront reads 1 KiB
@@ -177,7 +181,7 @@ __global__ __launch_bounds__(256) void fix_norm_kernel(NormPtrs p, int k, int64_
 
 template <typename OutT, int KMAX>
 void fix_launch(int k, int64_t rows, int hv, const FixPtrs& p, const OutMap& om, OutT* O, float* lse, hipStream_t s) {
-  constexpr int CPT = chunks_per_thread(KMAX);
+  constexpr int CPT = chunks_per_thread_fix(KMAX);
   const int64_t per_block = 256 * CPT;
   const dim3 grid((unsigned)((rows * hv + per_block - 1) / per_block)), block(256);
   A2D_LAUNCH((fix_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, rows, hv, om, O, lse);
