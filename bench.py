@@ -413,6 +413,7 @@ def main():
             if w.causal:
                 extra("gathered", lambda: gathered_tile(a2d, synth, w, scale, kernels))
             extra("normalised_partials", lambda: normalised_format(a2d, synth, w, scale, kernels))
+            extra("attnfix_hops", lambda: attnfix_hops(a2d, w))
             extra("grouped_query", lambda: grouped_query(a2d, synth, w, scale, kernels))
             extra("strided_inputs", lambda: strided_inputs(a2d, synth, w, scale, kernels))
             extra("rectangular_tiles", lambda: rectangular_tiles(a2d, synth, w, scale))
@@ -526,6 +527,26 @@ def normalised_format(a2d, synth, w, scale, kernels):
     return {"fix_norm_ms": round(t_fix, 4), "fix_norm_gbs": round(nbytes / t_fix / 1e6, 1),
             "fix_norm_frac_hbm": round(nbytes / t_fix / 1e6 / PEAK_HBM_GBS, 4), "fix_norm_bytes": nbytes,
             "fix_fp32_ms": kernels["fix"]["avg_ms"], "partial_fwd_norm_unmasked_tile_ms": round(t_fwd, 4)}
+
+
+def attnfix_hops(a2d, w):
+    """a2d_attnfix on its own: one hop of a pairwise reduce-scatter (two partials of a query block
+    merged into one, still unnormalised) and the whole k-way merge left unnormalised."""
+    import torch
+    T, G, H = w.tile, w.grid, w.hdim
+    gen = torch.Generator(device="cuda"); gen.manual_seed(5)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    Ns = [torch.randn(w.heads, T, H, generator=gen, **f32) for _ in range(G)]
+    ms = [torch.randn(w.heads, T, generator=gen, **f32) for _ in range(G)]
+    ls = [torch.rand(w.heads, T, generator=gen, **f32) + 1.0 for _ in range(G)]
+    out = a2d.attnfix(Ns[:2], ms[:2], ls[:2])
+    rows = w.heads * T
+    t2 = _timeit(torch, lambda: a2d.attnfix(Ns[:2], ms[:2], ls[:2], out=out), n=20)
+    tk = _timeit(torch, lambda: a2d.attnfix(Ns, ms, ls, out=out), n=20)
+    b2, bk = rows * 3 * (H + 2) * 4, rows * (G + 1) * (H + 2) * 4
+    return {"what": "two partials -> one (a hop of the reduce-scatter of Alg. 1 line 5), and all %d -> one" % G,
+            "pair_ms": round(t2, 4), "pair_gbs": round(b2 / t2 / 1e6, 1), "pair_frac_hbm": round(b2 / t2 / 1e6 / PEAK_HBM_GBS, 4),
+            "kway_ms": round(tk, 4), "kway_gbs": round(bk / tk / 1e6, 1), "kway_frac_hbm": round(bk / tk / 1e6 / PEAK_HBM_GBS, 4)}
 
 
 def strided_inputs(a2d, synth, w, scale, kernels):

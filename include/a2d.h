@@ -164,6 +164,22 @@ a2d_status a2d_fix(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
                    const float* const* l, void* O, float* lse, void* stream);
 
 /*
+ * AttnFix alone (Alg. 2, folded over k inputs): merges k partials of the same query block into
+ * ONE partial of the same unnormalised form - the operator of the reduce-scatter of Alg. 1
+ * line 5, one hop of it for k = 2; a2d_fix is this followed by the division of line 6.
+ *   in : O_parts, m, l: HOST arrays of k device pointers, each a partial (N, m, l) as written by
+ *        a2d_partial_fwd (or by this call) for `rows` rows of head size hdim
+ *   out: N_out [rows][hdim], m_out [rows], l_out [rows], fp32:
+ *        m_out = max_k m_k, N_out = sum_k exp(m_k - m_out) N_k, l_out = sum_k exp(m_k - m_out) l_k
+ *        (sums in index order 0..k-1); a row empty in every input stays empty (0, -inf, 0).
+ * The outputs must not be any of the inputs (A2D_ERR_INVALID_ARG).  1 <= k <= A2D_MAX_PARTS;
+ * hdim a multiple of 4.
+ */
+a2d_status a2d_attnfix(int k, int64_t rows, int32_t hdim, const float* const* O_parts,
+                       const float* const* m, const float* const* l, float* N_out, float* m_out,
+                       float* l_out, void* stream);
+
+/*
  * Gradient share of one tile (the BwdFlashAttn call of Alg. 3 line 3).
  *   in : Q, K, V as for the forward; O [heads][nq][H] and lse [heads][nq]: the
  *        FINAL merged output and log-sum-exp of the query block (what Alg. 1

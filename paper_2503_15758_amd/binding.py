@@ -17,7 +17,7 @@ A2D_F32, A2D_BF16 = 0, 1
 OP_PARTIAL_FWD, OP_FIX, OP_PARTIAL_BWD, OP_FIX_BWD, OP_PARTIAL_BWD_DS, OP_PARTIAL_BWD_SPLIT = 0, 1, 2, 3, 4, 5
 MAX_PARTS = 32
 
-EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_partial_bwd", "a2d_fix_bwd",
+EXPORTS = ("a2d_workspace_bytes", "a2d_partial_fwd", "a2d_fix", "a2d_attnfix", "a2d_partial_bwd", "a2d_fix_bwd",
            "a2d_partial_bwd_static",
            "a2d_partial_fwd_seg", "a2d_partial_bwd_seg", "a2d_partial_fwd_acc", "a2d_partial_bwd_acc",
            "a2d_partial_fwd_norm", "a2d_fix_norm", "a2d_partial_fwd_gqa", "a2d_partial_bwd_gqa",
@@ -102,6 +102,9 @@ def lib():
         L.a2d_fix.restype = ctypes.c_int
         L.a2d_fix.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                               ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, fp, vp]
+        L.a2d_attnfix.restype = ctypes.c_int
+        L.a2d_attnfix.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32,
+                                  ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), fp, fp, fp, vp]
         L.a2d_partial_bwd.restype = ctypes.c_int
         L.a2d_partial_bwd.argtypes = [ctypes.POINTER(TileDesc), vp, vp, vp, vp, vp, fp, fp, fp, fp,
                                       vp, ctypes.c_size_t, vp]
@@ -338,6 +341,27 @@ def fix(O_parts, ms, ls, out_dtype=torch.bfloat16, out=None):
     _check(lib().a2d_fix(k, rows, shape[-1], _dtype_code(O.dtype), _ptr_array(O_parts),
                          _ptr_array(ms), _ptr_array(ls), _ptr(O), _ptr(lse), _stream()))
     return O, lse
+
+
+def attnfix(O_parts, ms, ls, out=None):
+    """a2d_attnfix: AttnFix alone over k partial triples. Returns one partial (N, m, l), fp32, not normalised."""
+    k = len(O_parts)
+    if k < 1 or len(ms) != k or len(ls) != k:
+        raise A2DError(-1, "need k >= 1 partial triples")
+    shape = O_parts[0].shape
+    rows = 1
+    for s in shape[:-1]:
+        rows *= s
+    if out is None:
+        N = torch.empty(shape, dtype=torch.float32, device=O_parts[0].device)
+        m = torch.empty(shape[:-1], dtype=torch.float32, device=O_parts[0].device)
+        l = torch.empty(shape[:-1], dtype=torch.float32, device=O_parts[0].device)
+    else:
+        N, m, l = out
+    _plain(list(O_parts) + list(ms) + list(ls) + [N, m, l], "the partials")
+    _check(lib().a2d_attnfix(k, rows, shape[-1], _ptr_array(O_parts), _ptr_array(ms), _ptr_array(ls),
+                             _ptr(N), _ptr(m), _ptr(l), _stream()))
+    return N, m, l
 
 
 def partial_bwd(Q, K, V, O, dO, lse, q_off=0, kv_off=0, causal=False, scale=None, out=None,

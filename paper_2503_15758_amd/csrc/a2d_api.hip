@@ -538,6 +538,35 @@ a2d_status a2d_fix(int k, int64_t rows, int32_t hdim, int32_t out_dtype,
   return fix_impl(k, rows, hdim, out_dtype, O_parts, m, l, O, a2d::plain_out(), lse, stream, "a2d_fix");
 }
 
+a2d_status a2d_attnfix(int k, int64_t rows, int32_t hdim, const float* const* O_parts, const float* const* m,
+                       const float* const* l, float* N_out, float* m_out, float* l_out, void* stream) {
+  const char* who = "a2d_attnfix";
+  if (k < 1 || k > A2D_MAX_PARTS)
+    return fail(A2D_ERR_INVALID_ARG, "%s: k=%d outside 1..%d", who, k, A2D_MAX_PARTS);
+  if (rows < 1) return fail(A2D_ERR_INVALID_ARG, "%s: rows=%lld must be >= 1", who, (long long)rows);
+  if (hdim < 4 || hdim % 4 != 0 || hdim > 1024)
+    return fail(A2D_ERR_UNSUPPORTED, "%s: hdim=%d must be a multiple of 4 in 4..1024", who, hdim);
+  if (rows * (int64_t)(hdim / 4) > ((int64_t)1 << 39))
+    return fail(A2D_ERR_INVALID_ARG, "%s: rows * hdim too large", who);
+  if (!O_parts || !m || !l) return fail(A2D_ERR_INVALID_ARG, "%s: pointer array is NULL", who);
+  A2D_TRY(check_ptr(N_out, who, "N_out"));
+  A2D_TRY(check_ptr(m_out, who, "m_out"));
+  A2D_TRY(check_ptr(l_out, who, "l_out"));
+  a2d::FixPtrs p;
+  memset(&p, 0, sizeof(p));
+  for (int x = 0; x < k; ++x) {
+    A2D_TRY(check_ptr(O_parts[x], who, "O_parts[x]"));
+    A2D_TRY(check_ptr(m[x], who, "m[x]"));
+    A2D_TRY(check_ptr(l[x], who, "l[x]"));
+    // a row's column groups are read by several lanes and written by others: no output may be an input
+    if (O_parts[x] == N_out || m[x] == m_out || l[x] == l_out)
+      return fail(A2D_ERR_INVALID_ARG, "%s: output %d aliases an input (the merge is not in place)", who, x);
+    p.o[x] = O_parts[x]; p.m[x] = m[x]; p.l[x] = l[x];
+  }
+  a2d::trace_mark(static_cast<hipStream_t>(stream));
+  return hip_result(a2d::launch_attnfix(k, rows, hdim, p, N_out, m_out, l_out, static_cast<hipStream_t>(stream)), who);
+}
+
 a2d_status a2d_fix_strided(int k, int32_t heads, int32_t nq, int32_t hdim, int32_t out_dtype,
                            const float* const* O_parts, const float* const* m, const float* const* l,
                            void* O, const a2d_layout* lo, float* lse, void* stream) {

@@ -152,6 +152,8 @@ struct OutMap {
 inline OutMap plain_out() { return OutMap{0, 0, 1, 1}; }
 hipError_t launch_fix(int k, int64_t rows, int hdim, int out_dtype, const FixPtrs& p, const OutMap& om, void* O,
                       float* lse, hipStream_t s);
+hipError_t launch_attnfix(int k, int64_t rows, int hdim, const FixPtrs& p, float* N, float* m, float* l,
+                          hipStream_t s);
 // (hv = 4-column groups per row, used only when the output is not plain)
 hipError_t launch_fix_bwd(int k, int64_t n, int hv, int out_dtype, const SumPtrs& p, const OutMap& om, void* out,
                           hipStream_t s);

@@ -50,9 +50,12 @@ __device__ __forceinline__ int64_t group_index(int c) {
 
 // A column group = 4 consecutive columns of one row; hv = H / 4 groups per row.
 // KMAX is the unroll bound (k <= KMAX); loads of absent partials are predicated off.
-template <typename OutT, int KMAX, int CPT>
+// TRIPLE: the merge alone (Alg. 2 over k inputs): the result stays an unnormalised partial
+// (N, m, l) - O receives N in fp32, lse receives m, l_out receives l.
+template <typename OutT, int KMAX, int CPT, bool TRIPLE = false>
 __global__ __launch_bounds__(256) void fix_kernel(FixPtrs p, int k, int64_t rows, int hv, OutMap om,
-                                                  OutT* __restrict__ O, float* __restrict__ lse) {
+                                                  OutT* __restrict__ O, float* __restrict__ lse,
+                                                  float* __restrict__ l_out) {
   const int64_t total = rows * hv;
 
   f32x4 n[CPT][KMAX];
@@ -94,10 +97,18 @@ __global__ __launch_bounds__(256) void fix_kernel(FixPtrs p, int k, int64_t rows
       acc[2] = fmaf(w, n[c][x][2], acc[2]);
       acc[3] = fmaf(w, n[c][x][3], acc[3]);
     }
-    const float inv = (D > 0.f) ? 1.0f / D : 0.f;
-    acc[0] *= inv; acc[1] *= inv; acc[2] *= inv; acc[3] *= inv;
-    store_out4(O, out_offset(om, idx, hv), acc);
-    if (idx == row * hv) lse[row] = (D > 0.f) ? M + logf(D) : -INFINITY;
+    if constexpr (TRIPLE) {
+      store_out4(O, out_offset(om, idx, hv), acc);
+      if (idx == row * hv) {
+        lse[row] = M;
+        l_out[row] = D;
+      }
+    } else {
+      const float inv = (D > 0.f) ? 1.0f / D : 0.f;
+      acc[0] *= inv; acc[1] *= inv; acc[2] *= inv; acc[3] *= inv;
+      store_out4(O, out_offset(om, idx, hv), acc);
+      if (idx == row * hv) lse[row] = (D > 0.f) ? M + logf(D) : -INFINITY;
+    }
   }
 }
 
@@ -179,12 +190,13 @@ __global__ __launch_bounds__(256) void fix_norm_kernel(NormPtrs p, int k, int64_
   }
 }
 
-template <typename OutT, int KMAX>
-void fix_launch(int k, int64_t rows, int hv, const FixPtrs& p, const OutMap& om, OutT* O, float* lse, hipStream_t s) {
+template <typename OutT, int KMAX, bool TRIPLE = false>
+void fix_launch(int k, int64_t rows, int hv, const FixPtrs& p, const OutMap& om, OutT* O, float* lse, float* l_out,
+                hipStream_t s) {
   constexpr int CPT = chunks_per_thread_fix(KMAX);
   const int64_t per_block = 256 * CPT;
   const dim3 grid((unsigned)((rows * hv + per_block - 1) / per_block)), block(256);
-  A2D_LAUNCH((fix_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, rows, hv, om, O, lse);
+  A2D_LAUNCH((fix_kernel<OutT, KMAX, CPT, TRIPLE>), grid, block, 0, s, p, k, rows, hv, om, O, lse, l_out);
 }
 
 template <typename OutT, int KMAX>
@@ -195,15 +207,15 @@ void sum_launch(int k, int64_t n4, int hv, const SumPtrs& p, const OutMap& om, O
   A2D_LAUNCH((sum_kernel<OutT, KMAX, CPT>), grid, block, 0, s, p, k, n4, hv, om, out);
 }
 
-template <typename OutT>
+template <typename OutT, bool TRIPLE = false>
 hipError_t fix_dispatch(int k, int64_t rows, int hdim, const FixPtrs& p, const OutMap& om, OutT* O, float* lse,
-                        hipStream_t s) {
+                        float* l_out, hipStream_t s) {
   const int hv = hdim / 4;
-  if (k <= 2) fix_launch<OutT, 2>(k, rows, hv, p, om, O, lse, s);
-  else if (k <= 4) fix_launch<OutT, 4>(k, rows, hv, p, om, O, lse, s);
-  else if (k <= 8) fix_launch<OutT, 8>(k, rows, hv, p, om, O, lse, s);
-  else if (k <= 16) fix_launch<OutT, 16>(k, rows, hv, p, om, O, lse, s);
-  else fix_launch<OutT, 32>(k, rows, hv, p, om, O, lse, s);
+  if (k <= 2) fix_launch<OutT, 2, TRIPLE>(k, rows, hv, p, om, O, lse, l_out, s);
+  else if (k <= 4) fix_launch<OutT, 4, TRIPLE>(k, rows, hv, p, om, O, lse, l_out, s);
+  else if (k <= 8) fix_launch<OutT, 8, TRIPLE>(k, rows, hv, p, om, O, lse, l_out, s);
+  else if (k <= 16) fix_launch<OutT, 16, TRIPLE>(k, rows, hv, p, om, O, lse, l_out, s);
+  else fix_launch<OutT, 32, TRIPLE>(k, rows, hv, p, om, O, lse, l_out, s);
   return hipGetLastError();
 }
 
@@ -253,8 +265,14 @@ hipError_t launch_fix_norm(int k, int64_t rows, int hdim, int in_dtype, int out_
 
 hipError_t launch_fix(int k, int64_t rows, int hdim, int out_dtype, const FixPtrs& p, const OutMap& om, void* O,
                       float* lse, hipStream_t s) {
-  if (out_dtype == A2D_BF16) return fix_dispatch<bf16_t>(k, rows, hdim, p, om, (bf16_t*)O, lse, s);
-  return fix_dispatch<float>(k, rows, hdim, p, om, (float*)O, lse, s);
+  if (out_dtype == A2D_BF16) return fix_dispatch<bf16_t>(k, rows, hdim, p, om, (bf16_t*)O, lse, nullptr, s);
+  return fix_dispatch<float>(k, rows, hdim, p, om, (float*)O, lse, nullptr, s);
+}
+
+// the merge alone: k partials in, one unnormalised partial (N, m, l) out
+hipError_t launch_attnfix(int k, int64_t rows, int hdim, const FixPtrs& p, float* N, float* m, float* l,
+                          hipStream_t s) {
+  return fix_dispatch<float, true>(k, rows, hdim, p, plain_out(), N, m, l, s);
 }
 
 // hv = column groups per row (only used when the output is not plain)

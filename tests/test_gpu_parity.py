@@ -116,6 +116,49 @@ def test_fix_vs_oracle(a2d, k, H, out):
     assert np64(lse)[7] == -np.inf and np.all(np64(O)[7] == 0.0)
 
 
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 32])
+@pytest.mark.parametrize("H", [128, 80, 64])
+def test_attnfix_alone_vs_oracle(a2d, k, H):
+    """a2d_attnfix (Alg. 2 over k inputs, result left unnormalised) against the oracle's pairwise
+    AttnFix folded over the inputs: m exactly (a maximum), N and l per row relative to their size;
+    merging in two stages and dividing equals a2d_fix of all inputs; aliasing is refused."""
+    rows = 517
+    g = torch.Generator().manual_seed(300 + 7 * k + H)
+    Ns = [torch.randn(rows, H, generator=g) * 3 for _ in range(k)]
+    ms = [torch.randn(rows, generator=g) * 20 for _ in range(k)]
+    ls = [torch.rand(rows, generator=g) * 50 + 1 for _ in range(k)]
+    for x in range(k):                      # empty partials here and there, one row empty everywhere
+        emp = torch.rand(rows, generator=g) < 0.2
+        emp[11] = True
+        ms[x][emp] = -float("inf"); ls[x][emp] = 0.0; Ns[x][emp] = 0.0
+    dN, dm, dl = [dev(n) for n in Ns], [dev(m) for m in ms], [dev(l) for l in ls]
+    N, m, l = a2d.attnfix(dN, dm, dl)
+    torch.cuda.synchronize()
+    Mr, Nr, Dr = np64(ms[0]), np64(Ns[0]), np64(ls[0])
+    for x in range(1, k):
+        Mr, Nr, Dr = oracle.attnfix_pair(Mr, Nr, Dr, np64(ms[x]), np64(Ns[x]), np64(ls[x]))
+    assert np.array_equal(np64(m), Mr.astype(np.float32).astype(np.float64)), "attnfix m k=%d" % k
+    assert_close(N, Nr, torch.float32, "attnfix N k=%d" % k, rel=False, scale_rows=True)
+    assert_close(np64(l) / np.maximum(1.0, Dr), Dr / np.maximum(1.0, Dr), torch.float32, "attnfix l k=%d" % k, rel=False)
+    assert np64(m)[11] == -np.inf and np64(l)[11] == 0.0 and np.all(np64(N)[11] == 0.0)
+    # two stages (the hops of a reduce-scatter), then the division, against one k-way a2d_fix
+    if k >= 2:
+        h = k // 2
+        A = a2d.attnfix(dN[:h], dm[:h], dl[:h])
+        B = a2d.attnfix(dN[h:], dm[h:], dl[h:])
+        O2, lse2 = a2d.fix([A[0], B[0]], [A[1], B[1]], [A[2], B[2]], torch.float32)
+        O1, lse1 = a2d.fix(dN, dm, dl, torch.float32)
+        torch.cuda.synchronize()
+        assert_close(O2, np64(O1), torch.float32, "two-stage merge O k=%d" % k)
+        fin = np.isfinite(np64(lse1))
+        assert np.array_equal(np.isfinite(np64(lse2)), fin)
+        assert_close(np64(lse2)[fin], np64(lse1)[fin], torch.float32, "two-stage merge lse k=%d" % k, rel=False)
+    with pytest.raises(a2d.A2DError):
+        a2d.attnfix(dN, dm, dl, out=(dN[0], m, l))
+    with pytest.raises(a2d.A2DError):
+        a2d.attnfix(dN, dm, dl, out=(N, dm[k - 1], l))
+
+
 @pytest.mark.parametrize("k", [1, 2, 5, 8, 32])
 @pytest.mark.parametrize("out", ["bf16", "f32"])
 def test_fix_bwd_vs_oracle(a2d, k, out):
