@@ -66,8 +66,11 @@ class _Streams:
             self.main.wait_event(e)
 
 
-def forward(Q, K, V, grid, causal=True, layout="cyclic", scale=None, streams=4):
-    """Alg. 1: O [heads][n][H] in the input dtype and lse [heads][n] (what the forward saves)."""
+def forward(Q, K, V, grid, causal=True, layout="cyclic", scale=None, streams=4, merge="kway"):
+    """Alg. 1: O [heads][n][H] in the input dtype and lse [heads][n] (what the forward saves).
+    merge: "kway" - the partials of a grid row in one a2d_fix pass; "ring" - folded pairwise by
+    a2d_attnfix, one hop per partial as a ring reduce-scatter with AttnFix as its operator does
+    (Alg. 1 line 5), then the division of line 6 (a2d_fix of the one remaining partial)."""
     heads, n, H = Q.shape
     scale = float(scale if scale is not None else 1.0 / math.sqrt(H))
     idx = block_indices(n, grid, layout, Q.device)
@@ -89,6 +92,13 @@ def forward(Q, K, V, grid, causal=True, layout="cyclic", scale=None, streams=4):
     st.join()
     for r in range(grid):                              # Alg. 1 lines 5-6: AttnFix over the grid row, then 1 / D
         row = [parts[t] for t in tiles if t[0] == r]
+        if merge == "ring":
+            acc = row[0]
+            for p in row[1:]:
+                acc = a2d.attnfix([acc[0], p[0]], [acc[1], p[1]], [acc[2], p[2]])
+            row = [acc]
+        elif merge != "kway":
+            raise ValueError("merge must be 'kway' or 'ring'")
         Or, lr = a2d.fix([p[0] for p in row], [p[1] for p in row], [p[2] for p in row], Q.dtype)
         O.index_copy_(1, idx[r], Or)
         lse.index_copy_(1, idx[r], lr)

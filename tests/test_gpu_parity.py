@@ -877,6 +877,13 @@ def test_grid_emulation_matches_full_attention(a2d, layout, dt, H, grid):
     O1, lse1 = g2d.forward(dev(Q), dev(K), dev(V), grid, True, layout, scale, streams=1)
     torch.cuda.synchronize()
     assert torch.equal(O, O1) and torch.equal(lse, lse1)
+    # merging a grid row hop by hop (a ring reduce-scatter with AttnFix as its operator) is the
+    # same attention: against the oracle, and within fp32 rounding of the one-pass merge
+    O2, lse2 = g2d.forward(dev(Q), dev(K), dev(V), grid, True, layout, scale, streams=2, merge="ring")
+    torch.cuda.synchronize()
+    assert_close(O2, Or, DT[dt], "grid O, ring merge")
+    assert_close(lse2, lr, DT[dt], "grid lse, ring merge", rel=False)
+    assert_close(lse2, np64(lse), torch.float32, "ring against one-pass lse", rel=False)
 
 
 @pytest.mark.gpu
